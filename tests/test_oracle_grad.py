@@ -1,0 +1,137 @@
+"""Pins for the oracle's gradient routines (paper Section 4, Algorithm 3)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import givens_oracle as O
+from paper_2106_00003_amd import inputs
+
+
+def _case(n, b, seed):
+    rng = np.random.default_rng(seed)
+    th = rng.uniform(-math.pi, math.pi, n * (n - 1) // 2)
+    x = rng.standard_normal((n, b))
+    g = rng.standard_normal((n, b))
+    return th, x, g
+
+
+def test_n2_gradient_closed_form():
+    th, x, g = _case(2, 3, 1)
+    c, s = math.cos(th[0]), math.sin(th[0])
+    # L = sum_b g0 (c x0 - s x1) + g1 (s x0 + c x1)
+    want = float(np.sum(g[0] * (-s * x[0] - c * x[1]) + g[1] * (c * x[0] - s * x[1])))
+    y = O.forward_block_parallel(th, x)
+    d1, dx, xr = O.reverse_sweep(th, y, g)
+    d2 = O.grad_theta_alg3(th, O.build_u(th, 2), g @ x.T)
+    assert abs(d1[0] - want) < 1e-13
+    assert abs(d2[0] - want) < 1e-13
+    u = np.array([[c, -s], [s, c]])
+    assert np.allclose(dx, u.T @ g, atol=1e-14)
+    assert np.allclose(xr, x, atol=1e-14)
+
+
+def test_q_e_structure_and_rank_two_jacobian():
+    """dU/dtheta_e = U^{1:k-1} Q_e U^{k:n-1} = u_j v_i^T - u_i v_j^T (Section 4.1),
+    checked against central differences of the explicit product for every angle, n = 6."""
+    n = 6
+    th, _, _ = _case(n, 1, 2)
+    blocks = O.circle_method_schedule(n)
+    half = n // 2
+    eps = 1e-6
+    for k in range(n - 1):
+        # U^{1:k-1} and U^{k:n-1} from explicit factors (blocks are 0-based here: k = block k+1)
+        left = np.eye(n)
+        for kk in range(k):
+            for p in range(half):
+                left = left @ O.givens_matrix(n, *blocks[kk, p], th[kk * half + p])
+        right = np.eye(n)
+        for kk in range(k, n - 1):
+            for p in range(half):
+                right = right @ O.givens_matrix(n, *blocks[kk, p], th[kk * half + p])
+        for p in range(half):
+            e = k * half + p
+            i, j = blocks[k, p]
+            q = np.zeros((n, n))
+            q[i, j] = -1.0
+            q[j, i] = 1.0
+            analytic = left @ q @ right
+            rank2 = np.outer(left[:, j], right[i]) - np.outer(left[:, i], right[j])
+            tp, tm = th.copy(), th.copy()
+            tp[e] += eps
+            tm[e] -= eps
+            fd = (O.dense_product(n, tp) - O.dense_product(n, tm)) / (2 * eps)
+            assert np.allclose(analytic, rank2, atol=1e-14)
+            assert np.allclose(analytic, fd, atol=1e-8)
+            assert np.linalg.matrix_rank(analytic, tol=1e-10) == 2
+
+
+@pytest.mark.parametrize("n,b,seed", [(4, 3, 3), (6, 2, 4), (8, 4, 5), (12, 7, 6), (16, 16, 7)])
+def test_both_gradient_forms_match_central_differences(n, b, seed):
+    th, x, g = _case(n, b, seed)
+    fd = O.finite_difference_grad_theta(
+        th, x, g, forward=lambda t: O.dense_product(n, t) @ x if n <= 8 else
+        O.forward_sequential(t, x))
+    u = O.build_u(th, n)
+    alg3 = O.grad_theta_alg3(th, u, g @ x.T)
+    sweep, dx, xr = O.reverse_sweep(th, u @ x, g)
+    scale = np.linalg.norm(fd)
+    assert np.linalg.norm(alg3 - fd) < 2e-8 * scale
+    assert np.linalg.norm(sweep - fd) < 2e-8 * scale
+    assert np.linalg.norm(alg3 - sweep) < 1e-12 * scale
+    assert np.allclose(dx, u.T @ g, atol=1e-12)
+    assert np.allclose(dx, O.grad_operand(th, g), atol=1e-13)
+    assert np.allclose(xr, x, atol=1e-12)
+
+
+def test_config1_gradient_against_finite_differences_of_the_explicit_product():
+    data = inputs.make_inputs(1)
+    th, x, g = data["theta"], data["X"], data["G"]
+    fd = O.finite_difference_grad_theta(th, x, g, forward=lambda t: O.dense_product(8, t) @ x)
+    u = O.dense_product(8, th)
+    alg3 = O.grad_theta_alg3(th, u, g @ x.T)
+    sweep, dx, _ = O.reverse_sweep(th, u @ x, g)
+    assert np.linalg.norm(alg3 - fd) < 1e-8 * np.linalg.norm(fd)
+    assert np.linalg.norm(sweep - fd) < 1e-8 * np.linalg.norm(fd)
+    assert np.allclose(dx, u.T @ g, atol=1e-13)
+    # build case (X = I): Gamma = G, an 8 x 8 upstream gradient
+    g8 = np.random.default_rng(1).standard_normal((8, 8))
+    fd_u = O.finite_difference_grad_theta(th, np.eye(8), g8, forward=lambda t: O.dense_product(8, t))
+    assert np.linalg.norm(O.grad_theta_alg3(th, u, g8) - fd_u) < 1e-8 * np.linalg.norm(fd_u)
+
+
+@pytest.mark.parametrize("n,b", [(8, 8), (32, 5), (64, 64)])
+def test_upstream_equal_to_output_gives_zero_gradient(n, b):
+    """L = 1/2 ||U X||_F^2 = 1/2 ||X||_F^2 does not depend on theta, and G = Y is its upstream
+    gradient; every term of the sweep then cancels exactly."""
+    th, x, _ = _case(n, b, n + b)
+    y = O.forward_block_parallel(th, x)
+    d, dx, xr = O.reverse_sweep(th, y, y)
+    assert np.array_equal(d, np.zeros_like(d))
+    assert np.allclose(dx, x, atol=1e-12)
+    u = O.build_u(th, n)
+    d3 = O.grad_theta_alg3(th, u, u)          # X = I, Gamma = U
+    assert np.max(np.abs(d3)) < 1e-12
+
+
+@pytest.mark.parametrize("n,b", [(16, 9), (64, 40)])
+def test_adjoint_identity_for_the_operand_gradient(n, b):
+    th, x, g = _case(n, b, 3 * n + b)
+    xp = np.random.default_rng(9).standard_normal((n, b))
+    lhs = float(np.sum(g * O.forward_block_parallel(th, xp)))
+    rhs = float(np.sum(O.grad_operand(th, g) * xp))
+    assert abs(lhs - rhs) < 1e-11 * abs(lhs)
+
+
+def test_directional_finite_difference_at_a_medium_size():
+    n, b = 64, 48
+    th, x, g = _case(n, b, 77)
+    y = O.forward_block_parallel(th, x)
+    d, _, _ = O.reverse_sweep(th, y, g)
+    rng = np.random.default_rng(5)
+    for _ in range(3):
+        v = rng.standard_normal(th.size)
+        v /= np.linalg.norm(v)
+        eps = 1e-5
+        fd = (O.loss(th + eps * v, x, g) - O.loss(th - eps * v, x, g)) / (2 * eps)
+        assert abs(fd - float(d @ v)) < 1e-6 * max(1.0, abs(fd))
