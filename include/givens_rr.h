@@ -1,0 +1,127 @@
+/*
+ * givens_rr.h -- C ABI of the round-robin Givens library for MI355X (gfx950).
+ *
+ * The library applies an angle-parametrised special orthogonal matrix
+ *
+ *     U(theta) = G^{e_1}(theta_{e_1}) G^{e_2}(theta_{e_2}) ... G^{e_N}(theta_{e_N}),   N = n(n-1)/2,
+ *
+ * (paper Section 2, Eq. (2); G^{e_N} is applied first) to an n x B operand, where the pair
+ * sequence E is the round-robin sequence produced by the circle method (Section 3, Figure 1):
+ * n-1 blocks b_1..b_{n-1} of n/2 disjoint pairs, so that each block is one parallel step
+ * (Algorithm 2).  It also runs the reverse sweep that yields dL/dtheta (the quantity
+ * Algorithm 3 computes) and dL/dX without stored activations.
+ *
+ * Conventions shared by every entry point
+ *   - n is even, n >= 2.  Coordinates are 0..n-1.  A pair is written (i, j) with i < j and
+ *     G^e has G_ii = G_jj = cos, G_ij = -sin, G_ji = +sin (Section 2).
+ *   - theta and dtheta have N entries in E order: entry k*(n/2)+p belongs to arc p of block
+ *     b_{k+1}, i.e. to rr_schedule's pairs[k][p].
+ *   - Matrices are row-major n x B with leading dimension B: a row is a coordinate that gets
+ *     rotated, a column is one vector of the batch.
+ *   - Unless marked "host", pointers are DEVICE pointers owned by the caller; the library
+ *     neither frees nor retains them.  `stream` is a hipStream_t passed as void* (NULL = the
+ *     default stream).  Calls are asynchronous on that stream.
+ *   - The library owns a per-device workspace (cos/sin table, partial gradients), grown on
+ *     demand with hipMalloc and released by givens_release().  Calls that use the same device
+ *     share it: they must be ordered on one stream (or otherwise not overlap).
+ *   - Return value: 0 on success, a negative GIVENS_ERR_* code otherwise.  Nothing is launched
+ *     when an argument check fails.  No exceptions, no aborts.
+ */
+#ifndef GIVENS_RR_H
+#define GIVENS_RR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GIVENS_OK 0
+#define GIVENS_ERR_BAD_N (-1)       /* n < 2 or n odd                                   */
+#define GIVENS_ERR_BAD_B (-2)       /* B < 1                                            */
+#define GIVENS_ERR_NULL (-3)        /* a required pointer is NULL                       */
+#define GIVENS_ERR_HIP (-4)         /* a HIP call failed; see givens_last_hip_error()   */
+#define GIVENS_ERR_UNSUPPORTED (-5) /* shape not supported by the requested kernel      */
+#define GIVENS_ERR_ALIAS (-6)       /* forbidden aliasing between arguments             */
+
+/* Kernel families (givens_set_kernel). */
+#define GIVENS_KERNEL_AUTO 0     /* register carousel where the shape allows, else LDS strip */
+#define GIVENS_KERNEL_LDS 1      /* strip of the operand held in LDS; any even n that fits   */
+#define GIVENS_KERNEL_CAROUSEL 2 /* strip held in VGPRs in circle-method position order      */
+
+/*
+ * rr_schedule -- the round-robin sequence by the circle method (Section 3; the worked n = 6
+ * example is Eq. (3), the dimension sequences are the left column of Figure 1).
+ * Start from (0, 1, ..., n-1); block k pairs the elements at equal distance from the two ends,
+ * outermost arc first; then element 0 is held and the last element moves to position 1.
+ *   pairs : HOST buffer of (n-1)*(n/2)*2 int32, written as pairs[k][p][0] = i, pairs[k][p][1] = j.
+ * Pure host integer work; bit-exact by definition.
+ */
+int rr_schedule(int n, int32_t *pairs);
+
+/*
+ * givens_forward -- Y = U(theta) X  (Algorithm 2 started from X instead of I_n).
+ *   theta : N floats.   X : n x B.   Y : n x B, may be the same buffer as X (in place).
+ *   Partial overlap of X and Y is not checked and not allowed.
+ */
+int givens_forward(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream);
+
+/*
+ * givens_build -- U = U(theta), n x n  (Algorithm 2 as printed: the operand is I_n, which is
+ * generated on chip and never read from memory).
+ */
+int givens_build(int n, const float *theta, float *U, void *stream);
+
+/*
+ * givens_backward -- reverse sweep for L with upstream gradient G = dL/dY.
+ * Takes the forward OUTPUT Y (not X): the state before each block is recovered by applying the
+ * block's transposed rotations, so no activation is stored.  For block k = 1..n-1 in order and
+ * every pair e = (i, j) of the block:
+ *     dtheta_e = sum_b ( gbar_{j,b} z_{i,b} - gbar_{i,b} z_{j,b} ),
+ * then z <- G^{b_k}^T z and gbar <- G^{b_k}^T gbar, with z = Y and gbar = G at the start
+ * (Section 4.1: dU/dtheta_e = U^{1:k-1} Q_e U^{k:n-1}; this is the quantity of Algorithm 3
+ * with dL/dU = G X^T).  At the end gbar = dL/dX = U^T G.
+ *   Y, G : n x B.   dX : n x B, may be the same buffer as G.   dtheta : N floats, overwritten.
+ *   dX may be NULL (only dtheta is wanted).
+ */
+int givens_backward(int n, int64_t B, const float *theta, const float *Y, const float *G,
+                    float *dX, float *dtheta, void *stream);
+
+/* float64 variants: same semantics, all arrays double. */
+int givens_forward_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream);
+int givens_build_f64(int n, const double *theta, double *U, void *stream);
+int givens_backward_f64(int n, int64_t B, const double *theta, const double *Y, const double *G,
+                        double *dX, double *dtheta, void *stream);
+
+/* Frees every workspace the library holds (all devices).  Synchronises the devices it touches. */
+int givens_release(void);
+
+/* hipError_t value of the last failed HIP call made by the library on this thread (0 if none). */
+int givens_last_hip_error(void);
+
+/* Static, human-readable text for a GIVENS_ERR_* code. */
+const char *givens_error_string(int code);
+
+/* Selects the kernel family for subsequent calls (process-wide).  Returns the previous value,
+ * or GIVENS_ERR_UNSUPPORTED for an unknown value.  With GIVENS_KERNEL_CAROUSEL a call whose
+ * shape the carousel kernels do not cover returns GIVENS_ERR_UNSUPPORTED instead of falling back. */
+int givens_set_kernel(int which);
+
+/* Which family the last successful forward/build/backward call on this thread used
+ * (GIVENS_KERNEL_LDS or GIVENS_KERNEL_CAROUSEL; 0 before any call). */
+int givens_last_kernel(void);
+
+/*
+ * Per-kernel timing.  givens_set_timing(1) makes every subsequent call record HIP events on the
+ * caller's stream around each kernel it launches.  givens_last_timing() waits for the events of
+ * the last call on this thread and writes milliseconds: ms[0] = coefficient table kernel,
+ * ms[1] = sweep kernel(s), ms[2] = dtheta second-stage reduction (0 for forward/build).
+ * Returns GIVENS_ERR_UNSUPPORTED if timing was off for that call.
+ */
+int givens_set_timing(int on);
+int givens_last_timing(float ms[3]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GIVENS_RR_H */

@@ -1,0 +1,175 @@
+"""Thin ctypes binding to libgivens_rr.so (the C ABI of include/givens_rr.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+PyTorch tensors are used as device buffers (data_ptr) and for the current HIP stream.
+There is no CPU fallback: if the library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgivens_rr.so")
+
+KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL = 0, 1, 2
+
+EXPORTS = [
+    "rr_schedule", "givens_forward", "givens_build", "givens_backward",
+    "givens_forward_f64", "givens_build_f64", "givens_backward_f64",
+    "givens_release", "givens_last_hip_error", "givens_error_string",
+    "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
+]
+
+_lib = None
+
+
+class GivensError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        L = _lib
+        text = L.givens_error_string(code).decode() if L is not None else "?"
+        hip = L.givens_last_hip_error() if L is not None else 0
+        super().__init__(f"{where}: error {code} ({text}); last HIP error {hip}")
+
+
+def lib():
+    """Load the library once.  Raises if it has not been built (python -m ... build or __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python paper_2106_00003_amd/build.py` "
+            "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    L.rr_schedule.argtypes = [i32, vp]
+    for name in ("givens_forward", "givens_forward_f64"):
+        getattr(L, name).argtypes = [i32, i64, vp, vp, vp, vp]
+    for name in ("givens_build", "givens_build_f64"):
+        getattr(L, name).argtypes = [i32, vp, vp, vp]
+    for name in ("givens_backward", "givens_backward_f64"):
+        getattr(L, name).argtypes = [i32, i64, vp, vp, vp, vp, vp, vp]
+    L.givens_error_string.argtypes = [i32]
+    L.givens_error_string.restype = ctypes.c_char_p
+    L.givens_set_kernel.argtypes = [i32]
+    L.givens_set_timing.argtypes = [i32]
+    L.givens_last_timing.argtypes = [ctypes.POINTER(ctypes.c_float)]
+    for name in EXPORTS:
+        if name != "givens_error_string":
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise GivensError(rc, where)
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _suffix(t) -> str:
+    import torch
+    if t.dtype == torch.float32:
+        return ""
+    if t.dtype == torch.float64:
+        return "_f64"
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(t, name, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} has dtype {t.dtype}, expected {dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def rr_schedule(n: int) -> np.ndarray:
+    """Host call: (n-1, n/2, 2) int32 array of pairs (i < j) in block order."""
+    if n < 2 or n % 2:
+        _check(lib().rr_schedule(n, None), "rr_schedule")
+    out = np.empty((n - 1, n // 2, 2), dtype=np.int32)
+    _check(lib().rr_schedule(n, out.ctypes.data_as(ctypes.c_void_p)), "rr_schedule")
+    return out
+
+
+def givens_forward(theta, X, Y=None, stream=None):
+    """Y = U(theta) X on the device.  Y=None allocates; Y may be X (in place)."""
+    import torch
+    n, B = X.shape
+    if theta.numel() != n * (n - 1) // 2:
+        raise ValueError("theta must have n(n-1)/2 entries")
+    if Y is None:
+        Y = torch.empty_like(X)
+    fn = getattr(lib(), "givens_forward" + _suffix(X))
+    _check(fn(n, B, _dev(theta, "theta", X.dtype), _dev(X, "X"), _dev(Y, "Y", X.dtype), _stream_ptr(stream)),
+           "givens_forward")
+    return Y
+
+
+def givens_build(theta, n: int, U=None, stream=None):
+    """U = U(theta), n x n."""
+    import torch
+    if theta.numel() != n * (n - 1) // 2:
+        raise ValueError("theta must have n(n-1)/2 entries")
+    if U is None:
+        U = torch.empty((n, n), dtype=theta.dtype, device=theta.device)
+    fn = getattr(lib(), "givens_build" + _suffix(theta))
+    _check(fn(n, _dev(theta, "theta"), _dev(U, "U", theta.dtype), _stream_ptr(stream)), "givens_build")
+    return U
+
+
+def givens_backward(theta, Y, G, dX=None, dtheta=None, want_dx: bool = True, stream=None):
+    """Reverse sweep from the forward output Y and the upstream gradient G.  Returns (dX, dtheta)."""
+    import torch
+    n, B = Y.shape
+    if theta.numel() != n * (n - 1) // 2:
+        raise ValueError("theta must have n(n-1)/2 entries")
+    if G.shape != Y.shape:
+        raise ValueError("G must have the shape of Y")
+    if dX is None and want_dx:
+        dX = torch.empty_like(G)
+    if dtheta is None:
+        dtheta = torch.empty_like(theta)
+    fn = getattr(lib(), "givens_backward" + _suffix(Y))
+    _check(fn(n, B, _dev(theta, "theta", Y.dtype), _dev(Y, "Y"), _dev(G, "G", Y.dtype),
+              _dev(dX, "dX", Y.dtype), _dev(dtheta, "dtheta", Y.dtype), _stream_ptr(stream)),
+           "givens_backward")
+    return dX, dtheta
+
+
+def set_kernel(which: int) -> int:
+    rc = lib().givens_set_kernel(which)
+    if rc < 0:
+        raise GivensError(rc, "givens_set_kernel")
+    return rc
+
+
+def last_kernel() -> int:
+    return lib().givens_last_kernel()
+
+
+def set_timing(on: bool) -> int:
+    return lib().givens_set_timing(1 if on else 0)
+
+
+def last_timing():
+    """(table_ms, sweep_ms, reduce_ms) of the last call on this thread; waits for its events."""
+    buf = (ctypes.c_float * 3)()
+    _check(lib().givens_last_timing(buf), "givens_last_timing")
+    return float(buf[0]), float(buf[1]), float(buf[2])
+
+
+def release():
+    _check(lib().givens_release(), "givens_release")

@@ -1,0 +1,350 @@
+// Register-carousel kernels (float): the fast family for n = 128 * WAVES * M.
+//
+// Idea.  The circle method (paper Section 3, Figure 1) keeps a line of n positions; block k
+// pairs position p with position n-1-p, and between blocks the labels move one position along
+// a ring of n-1 positions while position 0 is held.  So instead of moving pairings around, the
+// kernel keeps the strip of the operand *in position order* and folded in two:
+//
+//     top[p] = row sitting at position p,      bot[p] = row sitting at position n-1-p,
+//
+// p = 0..n/2-1.  Every block then rotates (top[p], bot[p]) for all p -- the partner is always in
+// the same lane -- and the step to the next block is a carousel move: the top line shifts by one
+// slot in one direction, the bottom line by one slot in the other direction, with a turn-around at
+// the far end (top[n/2-1] <-> bot[n/2-1]) and at the near end (top[1] <-> bot[0]); top[0] stays.
+//
+// Mapping.  A workgroup of L = 64*WAVES lanes owns W columns of the operand for all n-1 blocks
+// (one HBM read, one HBM write).  Lane l holds slots p = l*M .. l*M+M-1 of both lines, W columns
+// each, in VGPRs: 2*M*W floats.  The carousel move only changes one slot per lane per line: the
+// slot that leaves goes to the neighbouring lane (DPP wave shift inside a wavefront, a few floats
+// through LDS between wavefronts), and the other M-1 slots are "moved" by renaming: the round loop
+// is unrolled M times so that the slot <-> register map is static in every copy of the body.
+// cos/sin come from the table written by coef_table_kernel, M pairs per lane per block, reused
+// for the W columns the lane holds and prefetched one block ahead.
+//
+// Forward (Algorithm 2 from operand X) walks blocks k = n-2 .. 0, so the strip is loaded in the
+// position order of block n-1 and ends in the order of block 1, which is the identity order.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+#include <utility>
+
+#include "../../include/givens_rr.h"
+#include "lds_kernels.hpp"
+#include "rr_index.h"
+
+namespace givens {
+
+// lane l receives the value of lane l+1; lane 63 (no source) keeps `incoming`
+__device__ __forceinline__ float lane_from_next(float incoming, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(incoming), __float_as_int(v),
+                                                      0x130 /* wave_shl:1 */, 0xf, 0xf, false));
+}
+// lane l receives the value of lane l-1; lane 0 (no source) keeps `incoming`
+__device__ __forceinline__ float lane_from_prev(float incoming, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(incoming), __float_as_int(v),
+                                                      0x138 /* wave_shr:1 */, 0xf, 0xf, false));
+}
+
+// Slots that cross a wavefront boundary in one carousel move, double-buffered by block parity.
+template <int W, int WAVES>
+struct CarouselExchange {
+    float first_top[2][WAVES][W]; // lane 0's leaving top slot, per wavefront
+    float last_bot[2][WAVES][W];  // lane 63's leaving bottom slot, per wavefront
+    float near_turn[2][W];        // wavefront 0, lane 0: top[1], which turns round into bot[0]
+};
+
+template <int M, int W, int WAVES>
+struct CarouselFwd {
+    static constexpr int kLanes = 64 * WAVES;
+    static constexpr int kN = 2 * kLanes * M;
+    static constexpr int kLastU = (kN - 2) % M; // register rotation after the n-2 moves
+
+    float top[M][W];
+    float bot[M][W];
+    float2 cs[2][M];
+    int n, H, lane, wave, tid;
+    const float2 *tab_lane; // table + tid*M
+    CarouselExchange<W, WAVES> *sh;
+
+    __device__ __forceinline__ void load_coefs(int k, float2 (&dst)[M])
+    {
+        const float2 *src = tab_lane + (long long)k * H;
+        if constexpr (M % 2 == 0) {
+            const float4 *s4 = reinterpret_cast<const float4 *>(src);
+#pragma unroll
+            for (int r = 0; r < M / 2; ++r) {
+                const float4 v = s4[r];
+                dst[2 * r] = make_float2(v.x, v.y);
+                dst[2 * r + 1] = make_float2(v.z, v.w);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < M; ++r) dst[r] = src[r];
+        }
+    }
+
+    // Empty asm with every strip register as an in/out operand: emits nothing, but the compiler
+    // must have all of this block's rotations finished here.  Without it, rotations whose results
+    // are not needed for the exchange are sunk into later blocks and drag their cos/sin registers
+    // along, which multiplies the live table registers by the unroll factor.
+    __device__ __forceinline__ void pin_strip()
+    {
+#pragma unroll
+        for (int r = 0; r < M; ++r) {
+#pragma unroll
+            for (int x = 0; x < W; ++x) {
+                asm volatile("" : "+v"(top[r][x]));
+                asm volatile("" : "+v"(bot[r][x]));
+            }
+        }
+    }
+
+    // One block of Algorithm 2 with the slot <-> register map of unrolled copy U, then the move.
+    // LAST marks the very last block (k = 0): nothing to prefetch and no move after it.
+    template <int U, bool LAST>
+    __device__ __forceinline__ void step(int k)
+    {
+        float2(&cur)[M] = cs[U & 1];
+        if constexpr (!LAST) load_coefs(k - 1, cs[(U + 1) & 1]);
+
+#pragma unroll
+        for (int r = 0; r < M; ++r) {
+            const int it = (r + U) % M, ib = (r - U + M) % M;
+            const float c = cur[r].x, s = cur[r].y;
+#pragma unroll
+            for (int x = 0; x < W; ++x) {
+                const float a = top[it][x], b = bot[ib][x];
+                top[it][x] = fmaf(c, a, -(s * b)); // r_i = cos U_i - sin U_j
+                bot[ib][x] = fmaf(c, b, s * a);    // r_j = sin U_i + cos U_j
+            }
+        }
+        pin_strip();
+
+        if constexpr (!LAST) {
+            constexpr int q = U % M;                // top slot 0: leaves towards the previous lane
+            constexpr int qb = (M - 1 - U + M) % M; // bottom slot M-1: leaves towards the next lane
+            constexpr int q1 = (1 + U) % M;         // top slot 1 (matters in lane 0 of wavefront 0)
+            constexpr int par = U & 1;
+            if (lane == 0) {
+#pragma unroll
+                for (int x = 0; x < W; ++x) sh->first_top[par][wave][x] = top[q][x];
+            }
+            if (lane == 63) {
+#pragma unroll
+                for (int x = 0; x < W; ++x) sh->last_bot[par][wave][x] = bot[qb][x];
+            }
+            if (wave == 0) {
+                if (lane == 0) {
+#pragma unroll
+                    for (int x = 0; x < W; ++x) sh->near_turn[par][x] = top[q1][x];
+                }
+                // position 0 is held: in lane 0 its row hops to the register that will be slot 0
+#pragma unroll
+                for (int x = 0; x < W; ++x) {
+                    const float held = top[q][x], other = top[q1][x];
+                    top[q1][x] = (lane == 0) ? held : other;
+                }
+            }
+            __syncthreads();
+            const float *in_top = (wave == WAVES - 1) ? sh->last_bot[par][WAVES - 1] : sh->first_top[par][wave + 1];
+            const float *in_bot = (wave == 0) ? sh->near_turn[par] : sh->last_bot[par][wave - 1];
+#pragma unroll
+            for (int x = 0; x < W; ++x) {
+                top[q][x] = lane_from_next(in_top[x], top[q][x]);
+                bot[qb][x] = lane_from_prev(in_bot[x], bot[qb][x]);
+            }
+        }
+    }
+
+    // M consecutive blocks starting at block index k_first (going down), none of them the last
+    template <int... Us>
+    __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Us...>)
+    {
+        (step<Us, false>(k_first - Us), ...);
+    }
+    // the closing M-1 blocks k = M-2 .. 0 (n-1 = -1 mod M, so the tail always has M-1 blocks)
+    template <int... Us>
+    __device__ __forceinline__ void tail_group(std::integer_sequence<int, Us...>)
+    {
+        (step<Us, Us == M - 2>(M - 2 - Us), ...);
+    }
+};
+
+template <int W>
+__device__ __forceinline__ void load_row(float (&dst)[W], const float *X, long long B, int row, long long b0,
+                                         int wv, bool vec, int identity)
+{
+    if (identity) {
+#pragma unroll
+        for (int x = 0; x < W; ++x) dst[x] = (x < wv && (long long)row == b0 + x) ? 1.f : 0.f;
+        return;
+    }
+    const float *src = X + (long long)row * B + b0;
+    if constexpr (W % 4 == 0) {
+        if (vec) {
+#pragma unroll
+            for (int x = 0; x < W / 4; ++x) {
+                const float4 v = reinterpret_cast<const float4 *>(src)[x];
+                dst[4 * x] = v.x; dst[4 * x + 1] = v.y; dst[4 * x + 2] = v.z; dst[4 * x + 3] = v.w;
+            }
+            return;
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < W; ++x) dst[x] = (x < wv) ? src[x] : 0.f;
+}
+
+template <int W>
+__device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long long B, int row, long long b0,
+                                          int wv, bool vec)
+{
+    float *dst = Y + (long long)row * B + b0;
+    if constexpr (W % 4 == 0) {
+        if (vec) {
+#pragma unroll
+            for (int x = 0; x < W / 4; ++x)
+                reinterpret_cast<float4 *>(dst)[x] = make_float4(src[4 * x], src[4 * x + 1], src[4 * x + 2], src[4 * x + 3]);
+            return;
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < W; ++x)
+        if (x < wv) dst[x] = src[x];
+}
+
+template <int M, int W, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
+    int n, long long B, const float2 *__restrict__ table, const float *X, float *Y, int identity, int vec_ok)
+{
+    using State = CarouselFwd<M, W, WAVES>;
+    __shared__ CarouselExchange<W, WAVES> sh;
+    State st;
+    st.n = n;
+    st.H = n >> 1;
+    st.tid = threadIdx.x;
+    st.lane = threadIdx.x & 63;
+    st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    st.tab_lane = table + (long long)threadIdx.x * M;
+    st.sh = &sh;
+
+    const long long b0 = (long long)blockIdx.x * W;
+    const int wv = (B - b0) < W ? (int)(B - b0) : W;
+    const bool vec = vec_ok && wv == W;
+
+    // strip in the position order of block n-1 (k = n-2)
+#pragma unroll
+    for (int r = 0; r < M; ++r) {
+        const int p = st.tid * M + r;
+        load_row<W>(st.top[r], X, B, rr_label(n, n - 2, p), b0, wv, vec, identity);
+        load_row<W>(st.bot[r], X, B, rr_label(n, n - 2, n - 1 - p), b0, wv, vec, identity);
+    }
+    st.load_coefs(n - 2, st.cs[0]);
+
+    // n - 1 = (n/M - 1) * M + (M - 1) blocks: full groups of M, then a tail of M - 1
+    for (int k = n - 2; k >= M - 1; k -= M) st.full_group(k, std::make_integer_sequence<int, M>{});
+    st.tail_group(std::make_integer_sequence<int, M - 1>{});
+
+    // after block 1 the position order is the identity: position p holds row p
+    constexpr int UL = State::kLastU;
+#pragma unroll
+    for (int r = 0; r < M; ++r) {
+        const int p = st.tid * M + r;
+        store_row<W>(st.top[(r + UL) % M], Y, B, p, b0, wv, vec);
+        store_row<W>(st.bot[(r - UL + M) % M], Y, B, n - 1 - p, b0, wv, vec);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct CarouselShape {
+    int M, WAVES;
+};
+
+// n = 128 * WAVES * M with one of the compiled (M, WAVES) pairs
+inline bool carousel_shape_for(int n, CarouselShape *out)
+{
+    switch (n) {
+    case 256: *out = {2, 1}; return true;
+    case 512: *out = {4, 1}; return true;
+    case 1024: *out = {8, 1}; return true;
+    case 2048: *out = {8, 2}; return true;
+    case 4096: *out = {8, 4}; return true;
+    case 8192: *out = {8, 8}; return true;
+    default: return false;
+    }
+}
+
+template <typename T>
+inline bool carousel_supported(int n, long long B)
+{
+    (void)B;
+    CarouselShape s;
+    return std::is_same<T, float>::value && carousel_shape_for(n, &s);
+}
+
+template <typename T>
+inline bool carousel_backward_supported(int n, long long B)
+{
+    (void)n; (void)B;
+    return false;
+}
+
+// Columns per lane: the widest of {8,4,2,1} that still gives the chip about two wavefronts per SIMD.
+inline int carousel_width(long long B, int waves)
+{
+    const long long want_waves = 2048; // 256 CUs x 4 SIMDs x 2
+    for (int w = 8; w > 1; w >>= 1)
+        if (((B + w - 1) / w) * waves >= want_waves) return w;
+    return 1;
+}
+
+template <int M, int W, int WAVES>
+inline void carousel_launch_fwd(int n, long long B, const float2 *table, const float *X, float *Y, int identity,
+                                int vec_ok, hipStream_t stream)
+{
+    const long long strips = (B + W - 1) / W;
+    hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES>), dim3((unsigned)strips), dim3(64 * WAVES), 0, stream,
+                       n, B, table, X, Y, identity, vec_ok);
+}
+
+template <int M, int WAVES>
+inline int carousel_dispatch_w(int W, int n, long long B, const float2 *table, const float *X, float *Y,
+                               int identity, int vec_ok, hipStream_t stream)
+{
+    switch (W) {
+    case 8: carousel_launch_fwd<M, 8, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
+    case 4: carousel_launch_fwd<M, 4, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
+    case 2: carousel_launch_fwd<M, 2, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
+    case 1: carousel_launch_fwd<M, 1, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+
+template <typename T>
+inline int carousel_forward(int n, long long B, const typename Pair2<T>::type *table, const T *X, T *Y,
+                            int identity, hipStream_t stream)
+{
+    if constexpr (!std::is_same<T, float>::value) {
+        return GIVENS_ERR_UNSUPPORTED;
+    } else {
+        CarouselShape s;
+        if (!carousel_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
+        const int W = carousel_width(B, s.WAVES);
+        const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
+                             (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
+        const int vec_ok = aligned ? 1 : 0;
+        if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_w<2, 1>(W, n, B, table, X, Y, identity, vec_ok, stream);
+        if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_w<4, 1>(W, n, B, table, X, Y, identity, vec_ok, stream);
+        if (s.M == 8 && s.WAVES == 1) return carousel_dispatch_w<8, 1>(W, n, B, table, X, Y, identity, vec_ok, stream);
+        if (s.M == 8 && s.WAVES == 2) return carousel_dispatch_w<8, 2>(W, n, B, table, X, Y, identity, vec_ok, stream);
+        if (s.M == 8 && s.WAVES == 4) return carousel_dispatch_w<8, 4>(W, n, B, table, X, Y, identity, vec_ok, stream);
+        if (s.M == 8 && s.WAVES == 8) return carousel_dispatch_w<8, 8>(W, n, B, table, X, Y, identity, vec_ok, stream);
+        return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+
+} // namespace givens

@@ -1,0 +1,387 @@
+// C ABI of the round-robin Givens library (see include/givens_rr.h for the contract).
+// Host side: argument checks, workspace, kernel selection, launches, optional event timing.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "../../include/givens_rr.h"
+#include "carousel_kernels.hpp"
+#include "lds_kernels.hpp"
+#include "rr_index.h"
+
+namespace givens {
+namespace {
+
+constexpr int kMaxDevices = 64;
+constexpr size_t kLdsBudgetBytes = 144 * 1024;                 // of the 160 KB per CU on gfx950
+constexpr size_t kPartialCapBytes = size_t(4) << 30;           // cap on one chunk of strip partials
+
+struct Workspace {
+    void *table = nullptr;
+    size_t table_bytes = 0;
+    void *partial = nullptr;
+    size_t partial_bytes = 0;
+};
+
+std::mutex g_mutex;
+Workspace g_ws[kMaxDevices];
+int g_kernel_choice = GIVENS_KERNEL_AUTO;
+int g_timing_on = 0;
+
+struct TimedSpan {
+    int category;
+    hipEvent_t start, stop;
+};
+struct ThreadState {
+    int last_hip_error = 0;
+    int last_kernel = 0;
+    bool timing_valid = false;
+    std::vector<TimedSpan> spans;
+    std::vector<hipEvent_t> pool;
+};
+thread_local ThreadState t_state;
+
+bool hip_ok(hipError_t e)
+{
+    if (e == hipSuccess) return true;
+    t_state.last_hip_error = (int)e;
+    return false;
+}
+
+#define GIVENS_HIP(call)                         \
+    do {                                         \
+        if (!hip_ok(call)) return GIVENS_ERR_HIP; \
+    } while (0)
+
+int grow(void **ptr, size_t *have, size_t want)
+{
+    if (*have >= want) return GIVENS_OK;
+    if (*ptr) {
+        GIVENS_HIP(hipFree(*ptr));                             // synchronises the device
+        *ptr = nullptr;
+        *have = 0;
+    }
+    GIVENS_HIP(hipMalloc(ptr, want));
+    *have = want;
+    return GIVENS_OK;
+}
+
+hipEvent_t take_event()
+{
+    ThreadState &ts = t_state;
+    if (!ts.pool.empty()) {
+        hipEvent_t e = ts.pool.back();
+        ts.pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (!hip_ok(hipEventCreate(&e))) return nullptr;
+    return e;
+}
+
+void timing_begin_call()
+{
+    ThreadState &ts = t_state;
+    for (auto &s : ts.spans) {
+        ts.pool.push_back(s.start);
+        ts.pool.push_back(s.stop);
+    }
+    ts.spans.clear();
+    ts.timing_valid = g_timing_on != 0;
+}
+
+// RAII: records an event pair around the launches made while it is alive.
+struct Span {
+    hipStream_t stream;
+    bool on;
+    TimedSpan rec{};
+    Span(int category, hipStream_t s) : stream(s), on(t_state.timing_valid)
+    {
+        if (!on) return;
+        rec.category = category;
+        rec.start = take_event();
+        rec.stop = take_event();
+        if (!rec.start || !rec.stop) { on = false; return; }
+        (void)hipEventRecord(rec.start, stream);
+    }
+    ~Span()
+    {
+        if (!on) return;
+        (void)hipEventRecord(rec.stop, stream);
+        t_state.spans.push_back(rec);
+    }
+};
+
+int check_n(int n) { return (n < 2 || (n & 1)) ? GIVENS_ERR_BAD_N : GIVENS_OK; }
+
+// Widest odd strip (<= 15 columns) whose `strips_in_lds` copies fit the LDS budget; narrower
+// when that is needed to give every CU a few workgroups.
+template <typename T>
+int lds_strip_width(int n, long long B, int strips_in_lds)
+{
+    int w = 15;
+    while (w > 1 && (size_t)n * lds_row_stride(w) * sizeof(T) * strips_in_lds > kLdsBudgetBytes) w -= 2;
+    if ((size_t)n * lds_row_stride(w) * sizeof(T) * strips_in_lds > kLdsBudgetBytes) return 0;
+    while (w > 1 && (B + w - 1) / w < 1024) w -= 2;
+    return w;
+}
+
+template <typename T>
+int launch_table(int dev, int n, const T *theta, hipStream_t stream, typename Pair2<T>::type **table)
+{
+    const long long N = (long long)n * (n - 1) / 2;
+    Workspace &ws = g_ws[dev];
+    int rc = grow(&ws.table, &ws.table_bytes, (size_t)N * sizeof(typename Pair2<T>::type));
+    if (rc) return rc;
+    *table = reinterpret_cast<typename Pair2<T>::type *>(ws.table);
+    Span span(0, stream);
+    const int threads = 256;
+    const unsigned blocks = (unsigned)((N + threads - 1) / threads);
+    hipLaunchKernelGGL(coef_table_kernel<T>, dim3(blocks), dim3(threads), 0, stream, n, theta, *table);
+    GIVENS_HIP(hipGetLastError());
+    return GIVENS_OK;
+}
+
+template <typename T>
+int lds_forward(int n, long long B, const typename Pair2<T>::type *table, const T *X, T *Y,
+                int identity, hipStream_t stream)
+{
+    const int w = lds_strip_width<T>(n, B, 1);
+    if (w == 0) return GIVENS_ERR_UNSUPPORTED;
+    const size_t smem = (size_t)n * lds_row_stride(w) * sizeof(T);
+    auto kern = lds_forward_kernel<T>;
+    GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    const long long strips = (B + w - 1) / w;
+    Span span(1, stream);
+    hipLaunchKernelGGL(kern, dim3((unsigned)strips), dim3(kLdsThreads), smem, stream, n, B, w, table, X, Y,
+                       identity);
+    GIVENS_HIP(hipGetLastError());
+    return GIVENS_OK;
+}
+
+template <typename T>
+int lds_backward(int dev, int n, long long B, const typename Pair2<T>::type *table, const T *Y, const T *G,
+                 T *dX, T *dtheta, hipStream_t stream)
+{
+    const int w = lds_strip_width<T>(n, B, 2);
+    if (w == 0) return GIVENS_ERR_UNSUPPORTED;
+    const long long N = (long long)n * (n - 1) / 2;
+    const size_t smem = (size_t)2 * n * lds_row_stride(w) * sizeof(T);
+    auto kern = lds_backward_kernel<T>;
+    GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    const long long strips = (B + w - 1) / w;
+    long long chunk = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
+    chunk = std::max<long long>(1, std::min(chunk, strips));
+    Workspace &ws = g_ws[dev];
+    int rc = grow(&ws.partial, &ws.partial_bytes, (size_t)chunk * N * sizeof(T));
+    if (rc) return rc;
+    T *partial = reinterpret_cast<T *>(ws.partial);
+    for (long long s0 = 0; s0 < strips; s0 += chunk) {
+        const long long ns = std::min(chunk, strips - s0);
+        {
+            Span span(1, stream);
+            hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, B, w, s0, table,
+                               Y, G, dX, partial);
+            GIVENS_HIP(hipGetLastError());
+        }
+        {
+            Span span(2, stream);
+            const int threads = 256;
+            hipLaunchKernelGGL(reduce_partials_kernel<T>, dim3((unsigned)((N + threads - 1) / threads)),
+                               dim3(threads), 0, stream, N, ns, partial, dtheta, s0 > 0 ? 1 : 0);
+            GIVENS_HIP(hipGetLastError());
+        }
+    }
+    return GIVENS_OK;
+}
+
+int current_device(int *dev)
+{
+    GIVENS_HIP(hipGetDevice(dev));
+    if (*dev < 0 || *dev >= kMaxDevices) return GIVENS_ERR_UNSUPPORTED;
+    return GIVENS_OK;
+}
+
+template <typename T>
+int forward_impl(int n, long long B, const T *theta, const T *X, T *Y, int identity, void *stream_v)
+{
+    if (int rc = check_n(n)) return rc;
+    if (B < 1) return GIVENS_ERR_BAD_B;
+    if (!theta || !Y || (!identity && !X)) return GIVENS_ERR_NULL;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    if (int rc = current_device(&dev)) return rc;
+    timing_begin_call();
+    const int choice = g_kernel_choice;
+    const bool can_carousel = carousel_supported<T>(n, B);
+    if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
+    typename Pair2<T>::type *table = nullptr;
+    if (int rc = launch_table<T>(dev, n, theta, stream, &table)) return rc;
+    int rc;
+    if (can_carousel && choice != GIVENS_KERNEL_LDS) {
+        Span span(1, stream);
+        rc = carousel_forward<T>(n, B, table, X, Y, identity, stream);
+        if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+        t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
+    } else {
+        rc = lds_forward<T>(n, B, table, X, Y, identity, stream);
+        t_state.last_kernel = GIVENS_KERNEL_LDS;
+    }
+    return rc;
+}
+
+template <typename T>
+int backward_impl(int n, long long B, const T *theta, const T *Y, const T *G, T *dX, T *dtheta,
+                  void *stream_v)
+{
+    if (int rc = check_n(n)) return rc;
+    if (B < 1) return GIVENS_ERR_BAD_B;
+    if (!theta || !Y || !G || !dtheta) return GIVENS_ERR_NULL;
+    if (dX && (const void *)dX == (const void *)Y) return GIVENS_ERR_ALIAS;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    if (int rc = current_device(&dev)) return rc;
+    timing_begin_call();
+    const int choice = g_kernel_choice;
+    const bool can_carousel = carousel_backward_supported<T>(n, B);
+    if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
+    typename Pair2<T>::type *table = nullptr;
+    if (int rc = launch_table<T>(dev, n, theta, stream, &table)) return rc;
+    int rc;
+    if (can_carousel && choice != GIVENS_KERNEL_LDS) {
+        rc = GIVENS_ERR_UNSUPPORTED;                            // (carousel reverse sweep: see carousel_kernels.hpp)
+        t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
+    } else {
+        rc = lds_backward<T>(dev, n, B, table, Y, G, dX, dtheta, stream);
+        t_state.last_kernel = GIVENS_KERNEL_LDS;
+    }
+    return rc;
+}
+
+} // namespace
+} // namespace givens
+
+extern "C" {
+
+int rr_schedule(int n, int32_t *pairs)
+{
+    if (n < 2 || (n & 1)) return GIVENS_ERR_BAD_N;
+    if (!pairs) return GIVENS_ERR_NULL;
+    const int H = n / 2;
+    for (int k = 0; k < n - 1; ++k) {
+        for (int p = 0; p < H; ++p) {
+            const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+            int32_t *out = pairs + ((size_t)k * H + p) * 2;
+            out[0] = a < b ? a : b;
+            out[1] = a < b ? b : a;
+        }
+    }
+    return GIVENS_OK;
+}
+
+int givens_forward(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream)
+{
+    return givens::forward_impl<float>(n, B, theta, X, Y, 0, stream);
+}
+int givens_build(int n, const float *theta, float *U, void *stream)
+{
+    return givens::forward_impl<float>(n, n, theta, nullptr, U, 1, stream);
+}
+int givens_backward(int n, int64_t B, const float *theta, const float *Y, const float *G, float *dX,
+                    float *dtheta, void *stream)
+{
+    return givens::backward_impl<float>(n, B, theta, Y, G, dX, dtheta, stream);
+}
+int givens_forward_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream)
+{
+    return givens::forward_impl<double>(n, B, theta, X, Y, 0, stream);
+}
+int givens_build_f64(int n, const double *theta, double *U, void *stream)
+{
+    return givens::forward_impl<double>(n, n, theta, nullptr, U, 1, stream);
+}
+int givens_backward_f64(int n, int64_t B, const double *theta, const double *Y, const double *G,
+                        double *dX, double *dtheta, void *stream)
+{
+    return givens::backward_impl<double>(n, B, theta, Y, G, dX, dtheta, stream);
+}
+
+int givens_release(void)
+{
+    using namespace givens;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int keep = 0;
+    if (!hip_ok(hipGetDevice(&keep))) return GIVENS_ERR_HIP;
+    int rc = GIVENS_OK;
+    for (int d = 0; d < kMaxDevices; ++d) {
+        Workspace &ws = g_ws[d];
+        if (!ws.table && !ws.partial) continue;
+        if (!hip_ok(hipSetDevice(d))) { rc = GIVENS_ERR_HIP; continue; }
+        if (ws.table && !hip_ok(hipFree(ws.table))) rc = GIVENS_ERR_HIP;
+        if (ws.partial && !hip_ok(hipFree(ws.partial))) rc = GIVENS_ERR_HIP;
+        ws = Workspace{};
+    }
+    (void)hipSetDevice(keep);
+    return rc;
+}
+
+int givens_last_hip_error(void) { return givens::t_state.last_hip_error; }
+
+const char *givens_error_string(int code)
+{
+    switch (code) {
+    case GIVENS_OK: return "success";
+    case GIVENS_ERR_BAD_N: return "n must be even and at least 2";
+    case GIVENS_ERR_BAD_B: return "B must be at least 1";
+    case GIVENS_ERR_NULL: return "a required pointer is NULL";
+    case GIVENS_ERR_HIP: return "a HIP call failed (see givens_last_hip_error)";
+    case GIVENS_ERR_UNSUPPORTED: return "shape or option not supported by the requested kernel";
+    case GIVENS_ERR_ALIAS: return "forbidden aliasing between arguments";
+    default: return "unknown error code";
+    }
+}
+
+int givens_set_kernel(int which)
+{
+    if (which != GIVENS_KERNEL_AUTO && which != GIVENS_KERNEL_LDS && which != GIVENS_KERNEL_CAROUSEL)
+        return GIVENS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(givens::g_mutex);
+    const int prev = givens::g_kernel_choice;
+    givens::g_kernel_choice = which;
+    return prev;
+}
+
+int givens_last_kernel(void) { return givens::t_state.last_kernel; }
+
+int givens_set_timing(int on)
+{
+    std::lock_guard<std::mutex> lock(givens::g_mutex);
+    const int prev = givens::g_timing_on;
+    givens::g_timing_on = on ? 1 : 0;
+    return prev;
+}
+
+int givens_last_timing(float ms[3])
+{
+    using namespace givens;
+    if (!ms) return GIVENS_ERR_NULL;
+    ThreadState &ts = t_state;
+    if (!ts.timing_valid) return GIVENS_ERR_UNSUPPORTED;
+    ms[0] = ms[1] = ms[2] = 0.f;
+    for (auto &s : ts.spans) {
+        if (!hip_ok(hipEventSynchronize(s.stop))) return GIVENS_ERR_HIP;
+        float t = 0.f;
+        if (!hip_ok(hipEventElapsedTime(&t, s.start, s.stop))) return GIVENS_ERR_HIP;
+        if (s.category >= 0 && s.category < 3) ms[s.category] += t;
+    }
+    return GIVENS_OK;
+}
+
+} // extern "C"

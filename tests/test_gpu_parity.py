@@ -1,0 +1,190 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Tolerances (relative Frobenius error against the oracle):
+    Y, U          <= 1e-5   (fp32 kernels)
+    dtheta, dX    <= 1e-4   (fp32 kernels)
+    everything    <= 1e-12  (fp64 kernels)
+The schedule is compared bit for bit in tests/test_library_host.py.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import c_oracle as C
+from oracle import givens_oracle as O
+from paper_2106_00003_amd import binding, inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL_Y, TOL_G, TOL_64 = 1e-5, 1e-4, 1e-12
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    binding.lib()          # fails loudly if the library is not built
+    yield
+    binding.set_kernel(binding.KERNEL_AUTO)
+    binding.release()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def check_forward_backward(theta, X, G, kernel, tol_y, tol_g, expect_kernel=None):
+    """Full comparison against the oracle (sizes the oracle finishes in seconds)."""
+    n, B = X.shape
+    binding.set_kernel(kernel)
+    th_d, x_d, g_d = dev(theta), dev(X), dev(G)
+    y_d = binding.givens_forward(th_d, x_d)
+    if expect_kernel is not None:
+        assert binding.last_kernel() == expect_kernel
+    want_y = C.forward(theta, X)
+    err_y = O.rel_fro(host(y_d), want_y)
+    assert err_y <= tol_y, f"Y: {err_y}"
+    # backward from the library's own forward output
+    dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+    want_dth, want_dx, _ = C.reverse_sweep(theta, want_y, G)
+    err_dx = O.rel_fro(host(dx_d), want_dx)
+    err_dth = O.rel_fro(host(dth_d), want_dth)
+    assert err_dx <= tol_g, f"dX: {err_dx}"
+    assert err_dth <= tol_g, f"dtheta: {err_dth}"
+    return err_y, err_dx, err_dth
+
+
+# ---------------------------------------------------------------- config 1 (fp64)
+def test_config1_fp64_forward_build_backward():
+    data = inputs.make_inputs(1)
+    th, X, G = data["theta"], data["X"], data["G"]
+    check_forward_backward(th, X, G, binding.KERNEL_AUTO, TOL_64, TOL_64, binding.KERNEL_LDS)
+    # against the explicit product of Givens matrices and per-angle central differences
+    u = O.dense_product(8, th)
+    u_d = binding.givens_build(dev(th), 8)
+    assert O.rel_fro(host(u_d), u) <= TOL_64
+    y_d = binding.givens_forward(dev(th), dev(X))
+    assert O.rel_fro(host(y_d), u @ X) <= TOL_64
+    _, dth_d = binding.givens_backward(dev(th), y_d, dev(G))
+    fd = O.finite_difference_grad_theta(th, X, G, forward=lambda t: O.dense_product(8, t) @ X)
+    assert O.rel_fro(host(dth_d), fd) <= 1e-7
+
+
+# ---------------------------------------------------------------- config 2
+@pytest.mark.parametrize("kernel,expect", [(binding.KERNEL_LDS, binding.KERNEL_LDS),
+                                           (binding.KERNEL_AUTO, binding.KERNEL_CAROUSEL)])
+def test_config2_n256_forward_backward(kernel, expect):
+    data = inputs.make_inputs(2)
+    check_forward_backward(data["theta"], data["X"], data["G"], kernel, TOL_Y, TOL_G)
+    binding.set_kernel(kernel)
+    binding.givens_forward(dev(data["theta"]), dev(data["X"]))
+    assert binding.last_kernel() == expect
+
+
+# ---------------------------------------------------------------- config 3 (build U, X = I)
+def test_config3_n1024_build_and_gradient():
+    data = inputs.make_inputs(3)
+    th, G = data["theta"], data["G"]
+    n = 1024
+    binding.set_kernel(binding.KERNEL_AUTO)
+    th_d = dev(th)
+    u_d = binding.givens_build(th_d, n)
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+    want_u = C.forward(th, None, n=n)
+    u = host(u_d)
+    assert O.rel_fro(u, want_u) <= TOL_Y
+    assert O.rel_fro(u.astype(np.float64).T @ u.astype(np.float64), np.eye(n)) <= 1e-5
+    # gradient of L = sum(G * U): Algorithm 3 with Gamma = G, and the reverse sweep, in the oracle
+    want_dth = C.grad_theta_alg3(th, want_u, G)
+    _, dth_d = binding.givens_backward(th_d, u_d, dev(G), want_dx=False)
+    assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
+    # same build through the LDS family
+    binding.set_kernel(binding.KERNEL_LDS)
+    u2_d = binding.givens_build(th_d, n)
+    assert binding.last_kernel() == binding.KERNEL_LDS
+    assert O.rel_fro(host(u2_d), want_u) <= TOL_Y
+
+
+# ---------------------------------------------------------------- ragged / odd shapes, both families
+@pytest.mark.parametrize("n,B,seed", [(2, 1, 1), (4, 3, 2), (6, 5, 3), (34, 19, 4), (130, 77, 5), (300, 41, 6)])
+def test_lds_family_small_and_ragged_shapes(n, B, seed):
+    data = inputs.make_custom(n, B, seed=seed)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_LDS, TOL_Y, TOL_G,
+                           binding.KERNEL_LDS)
+
+
+@pytest.mark.parametrize("n,B,seed", [(256, 1, 11), (256, 37, 12), (512, 100, 13), (1024, 67, 14),
+                                      (2048, 130, 15), (256, 4100, 16)])
+def test_carousel_family_ragged_batches(n, B, seed):
+    data = inputs.make_custom(n, B, seed=seed)
+    binding.set_kernel(binding.KERNEL_CAROUSEL)
+    th_d, x_d = dev(data["theta"]), dev(data["X"])
+    y_d = binding.givens_forward(th_d, x_d)
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+    want = C.forward(data["theta"], data["X"])
+    assert O.rel_fro(host(y_d), want) <= TOL_Y
+
+
+def test_carousel_rejects_shapes_it_does_not_cover():
+    data = inputs.make_custom(34, 8, seed=1)
+    binding.set_kernel(binding.KERNEL_CAROUSEL)
+    with pytest.raises(binding.GivensError) as err:
+        binding.givens_forward(dev(data["theta"]), dev(data["X"]))
+    assert err.value.code == -5
+    binding.set_kernel(binding.KERNEL_AUTO)
+
+
+def test_fp64_ragged():
+    data = inputs.make_custom(34, 19, seed=21, dtype=np.float64)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_64, TOL_64)
+
+
+@pytest.mark.parametrize("kernel", [binding.KERNEL_LDS, binding.KERNEL_AUTO])
+def test_in_place_forward_and_backward(kernel):
+    data = inputs.make_custom(256, 64, seed=31)
+    binding.set_kernel(kernel)
+    th_d = dev(data["theta"])
+    buf = dev(data["X"])
+    binding.givens_forward(th_d, buf, Y=buf)
+    want_y = C.forward(data["theta"], data["X"])
+    assert O.rel_fro(host(buf), want_y) <= TOL_Y
+    g_buf = dev(data["G"])
+    dx_d, dth_d = binding.givens_backward(th_d, buf, g_buf, dX=g_buf)
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
+    assert O.rel_fro(host(g_buf), want_dx) <= TOL_G
+    assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
+
+
+def test_zero_angles_and_single_angle():
+    n, B = 256, 16
+    data = inputs.make_custom(n, B, seed=41)
+    binding.set_kernel(binding.KERNEL_AUTO)
+    th = np.zeros(n * (n - 1) // 2, dtype=np.float32)
+    y = host(binding.givens_forward(dev(th), dev(data["X"])))
+    assert np.array_equal(y, data["X"])
+    e = 12345
+    th[e] = 0.625
+    i, j = binding.rr_schedule(n).reshape(-1, 2)[e]
+    want = data["X"].astype(np.float64).copy()
+    c, s = math.cos(0.625), math.sin(0.625)
+    want[i], want[j] = c * want[i] - s * want[j], s * data["X"][i].astype(np.float64) + c * want[j]
+    y = host(binding.givens_forward(dev(th), dev(data["X"])))
+    assert O.rel_fro(y, want) <= 1e-7
+
+
+def test_upstream_equal_to_output_gives_tiny_gradient():
+    data = inputs.make_inputs(2)
+    binding.set_kernel(binding.KERNEL_AUTO)
+    th_d = dev(data["theta"])
+    y_d = binding.givens_forward(th_d, dev(data["X"]))
+    dx_d, dth_d = binding.givens_backward(th_d, y_d, y_d.clone())
+    # gradient of a constant: every term cancels up to rounding; dX recovers X
+    scale = float(np.linalg.norm(data["X"])) ** 2
+    assert float(np.max(np.abs(host(dth_d)))) <= 1e-5 * scale / 256
+    assert O.rel_fro(host(dx_d), data["X"]) <= TOL_G
