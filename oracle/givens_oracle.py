@@ -18,6 +18,9 @@ that each function can be compared with the paper by eye:
   reverse_sweep            the operand-side form of the same gradient (Section 4.1,
                            dU/dtheta_e = U^{1:k-1} Q_e U^{k:n-1}, contracted with the
                            upstream gradient on the operand's side)
+  apply_block_range        partial products U^{a:b} of Section 4.1 applied to an operand
+  grad_theta_single        one component of the gradient from the rank-2 Jacobian
+                           dU/dtheta_e = u_j v_i^T - u_i v_j^T (Section 4.1), O(n^2 + nB)
   loss / finite_difference_grad_theta   L = sum(G * (U X)) and its central differences
 
 Readings of the paper taken here (each is also listed in the design notes):
@@ -228,6 +231,63 @@ def reverse_sweep(theta, y, upstream, pairs=None):
         gbar[i] = c * gi + s * gj
         gbar[j] = -s * gi + c * gj
     return grad.reshape(-1), gbar, z
+
+
+def apply_block_range(theta, operand, k_lo: int, k_hi: int, transpose: bool = False, pairs=None):
+    """U^{k_lo+1 : k_hi} . operand (0-based block indices k_lo..k_hi-1 are used), or its transpose.
+
+    U^{a:b} = G^{b_a} ... G^{b_b} (Section 4.1); the rightmost block applies first, so the plain
+    product sweeps the blocks downwards and the transposed one upwards with transposed rotations.
+    """
+    state = np.array(operand, dtype=np.float64, copy=True)
+    n = state.shape[0]
+    blocks = _as_blocks(n, pairs)
+    theta = np.asarray(theta, dtype=np.float64).reshape(n - 1, n // 2)
+    order = range(k_lo, k_hi) if transpose else range(k_hi - 1, k_lo - 1, -1)
+    for k in order:
+        i = blocks[k, :, 0]
+        j = blocks[k, :, 1]
+        c = np.cos(theta[k])
+        s = np.sin(theta[k])
+        if state.ndim == 2:
+            c, s = c[:, None], s[:, None]
+        rows_i = state[i]
+        rows_j = state[j]
+        if transpose:
+            state[i] = c * rows_i + s * rows_j
+            state[j] = -s * rows_i + c * rows_j
+        else:
+            state[i] = c * rows_i - s * rows_j
+            state[j] = s * rows_i + c * rows_j
+    return state
+
+
+def grad_theta_single(theta, operand, upstream, e: int, pairs=None) -> float:
+    """dL/dtheta_e for one angle, straight from the rank-2 form of Section 4.1:
+
+        dU/dtheta_e = u_j v_i^T - u_i v_j^T,   u = columns of U^fwd = U^{1:k-1},
+                                                v^T = rows of U^bck = U^{k:n-1},  e in b_k,
+
+    contracted with dL/dU = G X^T:  dL/dtheta_e = u_j^T G (v_i^T X)^T - u_i^T G (v_j^T X)^T.
+    Cost O(n^2 + nB): this is what full-size tests use for sampled angles.
+    """
+    x = np.asarray(operand)
+    g = np.asarray(upstream)
+    n = x.shape[0]
+    half = n // 2
+    blocks = _as_blocks(n, pairs)
+    k, p = divmod(int(e), half)
+    i, j = int(blocks[k, p, 0]), int(blocks[k, p, 1])
+    unit = np.zeros((n, 2), dtype=np.float64)
+    unit[i, 0] = 1.0
+    unit[j, 1] = 1.0
+    u_cols = apply_block_range(theta, unit, 0, k, transpose=False, pairs=pairs)          # U^{1:k-1} e_i, e_j
+    v_rows = apply_block_range(theta, unit, k, n - 1, transpose=True, pairs=pairs)       # (U^{k:n-1})^T e_i, e_j
+    z_i = v_rows[:, 0] @ x.astype(np.float64, copy=False)                                # row i of U^bck X
+    z_j = v_rows[:, 1] @ x.astype(np.float64, copy=False)
+    g_i = u_cols[:, 0] @ g.astype(np.float64, copy=False)                                # row i of U^fwd^T G
+    g_j = u_cols[:, 1] @ g.astype(np.float64, copy=False)
+    return float(g_j @ z_i - g_i @ z_j)
 
 
 def loss(theta, operand, upstream, pairs=None) -> float:

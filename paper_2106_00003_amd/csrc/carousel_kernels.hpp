@@ -258,6 +258,223 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// Reverse sweep (dtheta and dX from the forward output Y and the upstream gradient G).
+//
+// Two strips are carried, z (starts as Y) and g (starts as G), both in position order.  Blocks are
+// taken in the order b_1, b_2, ..., so the strips start in the identity order, the carousel turns
+// the other way (top line towards higher slots, bottom line towards lower slots), and the strips
+// end in the order of block n-1.  Per block and slot, first
+//     sum_x ( g_bot[x] * z_top[x] - g_top[x] * z_bot[x] )
+// over the lane's W columns -- the strip's share of dL/dtheta for that pair, up to the orientation
+// sign, which the second-stage reduction applies (top holds the larger label <=> negate) -- and
+// then the transposed rotation on both strips.
+// ---------------------------------------------------------------------------------------------
+template <int W, int WAVES>
+struct CarouselExchangeBwd {
+    // [parity][strip z/g][wavefront][column]
+    float top_in[2][2][WAVES][W]; // what lane 0 of each wavefront receives into its top line
+    float bot_in[2][2][WAVES][W]; // what lane 63 of each wavefront receives into its bottom line
+};
+
+template <int M, int W, int WAVES>
+struct CarouselBwd {
+    static constexpr int kLanes = 64 * WAVES;
+    static constexpr int kN = 2 * kLanes * M;
+    static constexpr int kLastU = (kN - 2) % M;
+
+    float zt[M][W], zb[M][W], gt[M][W], gb[M][W];
+    float2 cs[2][M];
+    int n, H, lane, wave, tid;
+    const float2 *tab_lane;  // table + tid*M
+    float *part_lane;        // this strip's partial sums + tid*M
+    CarouselExchangeBwd<W, WAVES> *sh;
+
+    __device__ __forceinline__ void load_coefs(int k, float2 (&dst)[M])
+    {
+        const float2 *src = tab_lane + (long long)k * H;
+        if constexpr (M % 2 == 0) {
+            const float4 *s4 = reinterpret_cast<const float4 *>(src);
+#pragma unroll
+            for (int r = 0; r < M / 2; ++r) {
+                const float4 v = s4[r];
+                dst[2 * r] = make_float2(v.x, v.y);
+                dst[2 * r + 1] = make_float2(v.z, v.w);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < M; ++r) dst[r] = src[r];
+        }
+    }
+
+    __device__ __forceinline__ void pin_strips()
+    {
+#pragma unroll
+        for (int r = 0; r < M; ++r) {
+#pragma unroll
+            for (int x = 0; x < W; ++x) {
+                asm volatile("" : "+v"(zt[r][x]));
+                asm volatile("" : "+v"(zb[r][x]));
+                asm volatile("" : "+v"(gt[r][x]));
+                asm volatile("" : "+v"(gb[r][x]));
+            }
+        }
+    }
+
+    // carousel move of one strip (top line `t`, bottom line `b`), reverse direction
+    template <int U, int WHICH>
+    __device__ __forceinline__ void publish(float (&t)[M][W], float (&b)[M][W])
+    {
+        constexpr int qt = (M - 1 - U + M) % M; // top slot M-1: leaves towards the next lane
+        constexpr int qb = U % M;               // bottom slot 0: leaves towards the previous lane
+        constexpr int pf = (M - U) % M;         // top slot 0 (the held position, in lane 0 of wavefront 0)
+        constexpr int par = U & 1;
+        if (lane == 63) {
+            float *dst = (wave < WAVES - 1) ? sh->top_in[par][WHICH][wave + 1] : sh->bot_in[par][WHICH][WAVES - 1];
+#pragma unroll
+            for (int x = 0; x < W; ++x) dst[x] = t[qt][x];
+        }
+        if (lane == 0) {
+            if (wave > 0) {
+#pragma unroll
+                for (int x = 0; x < W; ++x) sh->bot_in[par][WHICH][wave - 1][x] = b[qb][x];
+            } else {
+#pragma unroll
+                for (int x = 0; x < W; ++x) sh->top_in[par][WHICH][0][x] = t[pf][x];
+            }
+        }
+    }
+    template <int U, int WHICH>
+    __device__ __forceinline__ void receive(float (&t)[M][W], float (&b)[M][W])
+    {
+        constexpr int qt = (M - 1 - U + M) % M;
+        constexpr int qb = U % M;
+        constexpr int pf = (M - U) % M;
+        constexpr int par = U & 1;
+        const float *in_top = sh->top_in[par][WHICH][wave];
+        const float *in_bot = sh->bot_in[par][WHICH][wave];
+#pragma unroll
+        for (int x = 0; x < W; ++x) {
+            const float turn = b[qb][x]; // lane 0 of wavefront 0: bot[0] turns round into top[1]
+            t[qt][x] = lane_from_prev(in_top[x], t[qt][x]);
+            b[qb][x] = lane_from_next(in_bot[x], b[qb][x]);
+            if (wave == 0) {
+                const float keep = t[pf][x];
+                t[pf][x] = (lane == 0) ? turn : keep;
+            }
+        }
+    }
+
+    template <int U, bool LAST>
+    __device__ __forceinline__ void step(int k)
+    {
+        float2(&cur)[M] = cs[U & 1];
+        if constexpr (!LAST) load_coefs(k + 1, cs[(U + 1) & 1]);
+
+        float sums[M];
+#pragma unroll
+        for (int r = 0; r < M; ++r) {
+            const int it = (r - U + M) % M, ib = (r + U) % M;
+            const float c = cur[r].x, s = cur[r].y;
+            float acc = 0.f;
+#pragma unroll
+            for (int x = 0; x < W; ++x) {
+                const float za = zt[it][x], zv = zb[ib][x], ga = gt[it][x], gv = gb[ib][x];
+                acc = fmaf(gv, za, acc);
+                acc = fmaf(-ga, zv, acc);
+                zt[it][x] = fmaf(c, za, s * zv);   // transposed rotation
+                zb[ib][x] = fmaf(c, zv, -(s * za));
+                gt[it][x] = fmaf(c, ga, s * gv);
+                gb[ib][x] = fmaf(c, gv, -(s * ga));
+            }
+            sums[r] = acc;
+        }
+        {
+            float *dst = part_lane + (long long)k * H;
+            if constexpr (M % 4 == 0) {
+#pragma unroll
+                for (int r = 0; r < M / 4; ++r)
+                    reinterpret_cast<float4 *>(dst)[r] =
+                        make_float4(sums[4 * r], sums[4 * r + 1], sums[4 * r + 2], sums[4 * r + 3]);
+            } else if constexpr (M % 2 == 0) {
+#pragma unroll
+                for (int r = 0; r < M / 2; ++r)
+                    reinterpret_cast<float2 *>(dst)[r] = make_float2(sums[2 * r], sums[2 * r + 1]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < M; ++r) dst[r] = sums[r];
+            }
+        }
+        pin_strips();
+
+        if constexpr (!LAST) {
+            publish<U, 0>(zt, zb);
+            publish<U, 1>(gt, gb);
+            __syncthreads();
+            receive<U, 0>(zt, zb);
+            receive<U, 1>(gt, gb);
+        }
+    }
+
+    template <int... Us>
+    __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Us...>)
+    {
+        (step<Us, false>(k_first + Us), ...);
+    }
+    template <int... Us>
+    __device__ __forceinline__ void tail_group(int k_first, std::integer_sequence<int, Us...>)
+    {
+        (step<Us, Us == M - 2>(k_first + Us), ...);
+    }
+};
+
+template <int M, int W, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
+    int n, long long B, long long strip0, const float2 *__restrict__ table, const float *Yin, const float *G,
+    float *dX, float *__restrict__ partial, int vec_ok)
+{
+    using State = CarouselBwd<M, W, WAVES>;
+    __shared__ CarouselExchangeBwd<W, WAVES> sh;
+    State st;
+    st.n = n;
+    st.H = n >> 1;
+    st.tid = threadIdx.x;
+    st.lane = threadIdx.x & 63;
+    st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    st.tab_lane = table + (long long)threadIdx.x * M;
+    st.part_lane = partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) + (long long)threadIdx.x * M;
+    st.sh = &sh;
+
+    const long long b0 = (strip0 + blockIdx.x) * W;
+    const int wv = (B - b0) < W ? (int)(B - b0) : W;
+    const bool vec = vec_ok && wv == W;
+
+    // block 1 is processed first: identity position order
+#pragma unroll
+    for (int r = 0; r < M; ++r) {
+        const int p = st.tid * M + r;
+        load_row<W>(st.zt[r], Yin, B, p, b0, wv, vec, 0);
+        load_row<W>(st.zb[r], Yin, B, n - 1 - p, b0, wv, vec, 0);
+        load_row<W>(st.gt[r], G, B, p, b0, wv, vec, 0);
+        load_row<W>(st.gb[r], G, B, n - 1 - p, b0, wv, vec, 0);
+    }
+    st.load_coefs(0, st.cs[0]);
+
+    int k = 0;
+    for (; k + M <= n - 1; k += M) st.full_group(k, std::make_integer_sequence<int, M>{});
+    st.tail_group(k, std::make_integer_sequence<int, M - 1>{});
+
+    if (dX) {
+        constexpr int UL = State::kLastU;
+#pragma unroll
+        for (int r = 0; r < M; ++r) {
+            const int p = st.tid * M + r;
+            store_row<W>(st.gt[(r - UL + M) % M], dX, B, rr_label(n, n - 2, p), b0, wv, vec);
+            store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), b0, wv, vec);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 struct CarouselShape {
@@ -286,11 +503,25 @@ inline bool carousel_supported(int n, long long B)
     return std::is_same<T, float>::value && carousel_shape_for(n, &s);
 }
 
+// shapes of the reverse sweep: two strips per lane, so half the slots per lane of the forward
+inline bool carousel_bwd_shape_for(int n, CarouselShape *out)
+{
+    switch (n) {
+    case 256: *out = {2, 1}; return true;
+    case 512: *out = {4, 1}; return true;
+    case 1024: *out = {4, 2}; return true;
+    case 2048: *out = {4, 4}; return true;
+    case 4096: *out = {4, 8}; return true;
+    default: return false;
+    }
+}
+
 template <typename T>
 inline bool carousel_backward_supported(int n, long long B)
 {
-    (void)n; (void)B;
-    return false;
+    (void)B;
+    CarouselShape s;
+    return std::is_same<T, float>::value && carousel_bwd_shape_for(n, &s);
 }
 
 // Columns per lane: the widest of {8,4,2,1} that still gives the chip about two wavefronts per SIMD.
@@ -322,6 +553,56 @@ inline int carousel_dispatch_w(int W, int n, long long B, const float2 *table, c
     case 1: carousel_launch_fwd<M, 1, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
     default: return GIVENS_ERR_UNSUPPORTED;
     }
+}
+
+template <int M, int W, int WAVES>
+inline void carousel_launch_bwd(int n, long long B, long long strip0, long long nstrips, const float2 *table,
+                                const float *Y, const float *G, float *dX, float *partial, int vec_ok,
+                                hipStream_t stream)
+{
+    hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES>), dim3((unsigned)nstrips), dim3(64 * WAVES), 0,
+                       stream, n, B, strip0, table, Y, G, dX, partial, vec_ok);
+}
+
+template <int M, int WAVES>
+inline int carousel_dispatch_bwd_w(int W, int n, long long B, long long strip0, long long nstrips,
+                                   const float2 *table, const float *Y, const float *G, float *dX,
+                                   float *partial, int vec_ok, hipStream_t stream)
+{
+    switch (W) {
+    case 8: carousel_launch_bwd<M, 8, WAVES>(n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream); return GIVENS_OK;
+    case 4: carousel_launch_bwd<M, 4, WAVES>(n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream); return GIVENS_OK;
+    case 2: carousel_launch_bwd<M, 2, WAVES>(n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream); return GIVENS_OK;
+    case 1: carousel_launch_bwd<M, 1, WAVES>(n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream); return GIVENS_OK;
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+
+// Columns per workgroup of the reverse sweep.
+inline int carousel_bwd_width(int n, long long B)
+{
+    CarouselShape s;
+    if (!carousel_bwd_shape_for(n, &s)) return 0;
+    return carousel_width(B, s.WAVES);
+}
+
+// Launches the reverse sweep on strips [strip0, strip0 + nstrips); partial is [nstrips][N].
+inline int carousel_backward_strips(int n, long long B, int W, long long strip0, long long nstrips,
+                                    const float2 *table, const float *Y, const float *G, float *dX,
+                                    float *partial, hipStream_t stream)
+{
+    CarouselShape s;
+    if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
+    const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
+                         (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
+    const int vec_ok = aligned ? 1 : 0;
+    if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_bwd_w<2, 1>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
+    if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_bwd_w<4, 1>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
+    if (s.M == 4 && s.WAVES == 2) return carousel_dispatch_bwd_w<4, 2>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
+    if (s.M == 4 && s.WAVES == 4) return carousel_dispatch_bwd_w<4, 4>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
+    if (s.M == 4 && s.WAVES == 8) return carousel_dispatch_bwd_w<4, 8>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
+    return GIVENS_ERR_UNSUPPORTED;
 }
 
 template <typename T>

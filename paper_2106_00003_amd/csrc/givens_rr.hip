@@ -17,7 +17,7 @@ namespace {
 
 constexpr int kMaxDevices = 64;
 constexpr size_t kLdsBudgetBytes = 144 * 1024;                 // of the 160 KB per CU on gfx950
-constexpr size_t kPartialCapBytes = size_t(4) << 30;           // cap on one chunk of strip partials
+constexpr size_t kPartialCapBytes = size_t(24) << 30;          // cap on one chunk of strip partials
 
 struct Workspace {
     void *table = nullptr;
@@ -163,17 +163,26 @@ int lds_forward(int n, long long B, const typename Pair2<T>::type *table, const 
     return GIVENS_OK;
 }
 
+// Reverse sweep in chunks of strips: each chunk writes one partial sum per (strip, angle) and the
+// second stage folds the chunk into dtheta.  `family` picks the sweep kernel.
 template <typename T>
-int lds_backward(int dev, int n, long long B, const typename Pair2<T>::type *table, const T *Y, const T *G,
-                 T *dX, T *dtheta, hipStream_t stream)
+int backward_chunks(int dev, int family, int n, long long B, const typename Pair2<T>::type *table,
+                    const T *Y, const T *G, T *dX, T *dtheta, hipStream_t stream)
 {
-    const int w = lds_strip_width<T>(n, B, 2);
-    if (w == 0) return GIVENS_ERR_UNSUPPORTED;
     const long long N = (long long)n * (n - 1) / 2;
-    const size_t smem = (size_t)2 * n * lds_row_stride(w) * sizeof(T);
+    int w = 0;
+    size_t smem = 0;
     auto kern = lds_backward_kernel<T>;
-    GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    if (family == GIVENS_KERNEL_LDS) {
+        w = lds_strip_width<T>(n, B, 2);
+        if (w == 0) return GIVENS_ERR_UNSUPPORTED;
+        smem = (size_t)2 * n * lds_row_stride(w) * sizeof(T);
+        GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    } else {
+        w = carousel_bwd_width(n, B);
+        if (w == 0) return GIVENS_ERR_UNSUPPORTED;
+    }
     const long long strips = (B + w - 1) / w;
     long long chunk = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
     chunk = std::max<long long>(1, std::min(chunk, strips));
@@ -185,15 +194,22 @@ int lds_backward(int dev, int n, long long B, const typename Pair2<T>::type *tab
         const long long ns = std::min(chunk, strips - s0);
         {
             Span span(1, stream);
-            hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, B, w, s0, table,
-                               Y, G, dX, partial);
+            if (family == GIVENS_KERNEL_LDS) {
+                hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, B, w, s0,
+                                   table, Y, G, dX, partial);
+            } else if constexpr (std::is_same<T, float>::value) {
+                if (int rc2 = carousel_backward_strips(n, B, w, s0, ns, table, Y, G, dX, partial, stream))
+                    return rc2;
+            } else {
+                return GIVENS_ERR_UNSUPPORTED;
+            }
             GIVENS_HIP(hipGetLastError());
         }
         {
             Span span(2, stream);
             const int threads = 256;
             hipLaunchKernelGGL(reduce_partials_kernel<T>, dim3((unsigned)((N + threads - 1) / threads)),
-                               dim3(threads), 0, stream, N, ns, partial, dtheta, s0 > 0 ? 1 : 0);
+                               dim3(threads), 0, stream, n, ns, partial, dtheta, s0 > 0 ? 1 : 0);
             GIVENS_HIP(hipGetLastError());
         }
     }
@@ -255,13 +271,9 @@ int backward_impl(int n, long long B, const T *theta, const T *Y, const T *G, T 
     typename Pair2<T>::type *table = nullptr;
     if (int rc = launch_table<T>(dev, n, theta, stream, &table)) return rc;
     int rc;
-    if (can_carousel && choice != GIVENS_KERNEL_LDS) {
-        rc = GIVENS_ERR_UNSUPPORTED;                            // (carousel reverse sweep: see carousel_kernels.hpp)
-        t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
-    } else {
-        rc = lds_backward<T>(dev, n, B, table, Y, G, dX, dtheta, stream);
-        t_state.last_kernel = GIVENS_KERNEL_LDS;
-    }
+    const int family = (can_carousel && choice != GIVENS_KERNEL_LDS) ? GIVENS_KERNEL_CAROUSEL : GIVENS_KERNEL_LDS;
+    rc = backward_chunks<T>(dev, family, n, B, table, Y, G, dX, dtheta, stream);
+    t_state.last_kernel = family;
     return rc;
 }
 

@@ -108,8 +108,8 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
                 ga[c] = cs.x * ua + cs.y * ub;
                 gbb[c] = cs.x * ub - cs.y * ua;
             }
-            // with i < j the term is gbar_j z_i - gbar_i z_j: flip when top holds the larger label
-            mine[(long long)k * H + p] = (a < b) ? sum : -sum;
+            // orientation sign (top holds the larger label <=> negate) is applied by the reduction
+            mine[(long long)k * H + p] = sum;
         }
         __syncthreads();
     }
@@ -122,16 +122,31 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
     }
 }
 
-// dtheta[e] (+)= sum over s of partial[s][e], in strip order (fixed order: reproducible).
+// Second stage of the gradient reduction: dtheta[e] (+)= sign(e) * sum over strips s of
+// partial[s][e], in strip order (fixed order: reproducible).  The sweeps store
+// sum_b (gbar_bot z_top - gbar_top z_bot); with i < j the paper's term is gbar_j z_i - gbar_i z_j,
+// so the sum is negated for the pairs whose top position holds the larger label.
 template <typename T>
-__global__ void reduce_partials_kernel(long long N, long long nstrips, const T *__restrict__ partial,
+__global__ void reduce_partials_kernel(int n, long long nstrips, const T *__restrict__ partial,
                                        T *dtheta, int accumulate)
 {
+    const int H = n >> 1;
+    const long long N = (long long)(n - 1) * H;
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= N) return;
-    T acc = accumulate ? dtheta[e] : T(0);
-    for (long long s = 0; s < nstrips; ++s) acc += partial[s * N + e];
-    dtheta[e] = acc;
+    T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
+    long long s = 0;
+    for (; s + 4 <= nstrips; s += 4) {          // four loads in flight; the order of additions is fixed
+        a0 += partial[s * N + e];
+        a1 += partial[(s + 1) * N + e];
+        a2 += partial[(s + 2) * N + e];
+        a3 += partial[(s + 3) * N + e];
+    }
+    for (; s < nstrips; ++s) a0 += partial[s * N + e];
+    T acc = (a0 + a1) + (a2 + a3);
+    const int k = (int)(e / H), p = (int)(e % H);
+    if (rr_label(n, k, p) > rr_label(n, k, n - 1 - p)) acc = -acc;
+    dtheta[e] = accumulate ? dtheta[e] + acc : acc;
 }
 
 // cos/sin table in E order, evaluated in double whatever T is, with the orientation sign folded

@@ -123,12 +123,9 @@ def test_lds_family_small_and_ragged_shapes(n, B, seed):
                                       (2048, 130, 15), (256, 4100, 16)])
 def test_carousel_family_ragged_batches(n, B, seed):
     data = inputs.make_custom(n, B, seed=seed)
-    binding.set_kernel(binding.KERNEL_CAROUSEL)
-    th_d, x_d = dev(data["theta"]), dev(data["X"])
-    y_d = binding.givens_forward(th_d, x_d)
-    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
-    want = C.forward(data["theta"], data["X"])
-    assert O.rel_fro(host(y_d), want) <= TOL_Y
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G,
+                           binding.KERNEL_CAROUSEL)
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL      # the reverse sweep too
 
 
 def test_carousel_rejects_shapes_it_does_not_cover():

@@ -135,3 +135,25 @@ def test_directional_finite_difference_at_a_medium_size():
         eps = 1e-5
         fd = (O.loss(th + eps * v, x, g) - O.loss(th - eps * v, x, g)) / (2 * eps)
         assert abs(fd - float(d @ v)) < 1e-6 * max(1.0, abs(fd))
+
+
+@pytest.mark.parametrize("n,b,seed", [(2, 3, 1), (6, 4, 2), (8, 4, 3), (16, 9, 4)])
+def test_single_angle_gradient_matches_sweep_and_finite_differences(n, b, seed):
+    th, x, g = _case(n, b, seed)
+    full, _, _ = O.reverse_sweep(th, O.forward_block_parallel(th, x), g)
+    fd = O.finite_difference_grad_theta(th, x, g, forward=lambda t: O.forward_sequential(t, x))
+    for e in range(th.size):
+        one = O.grad_theta_single(th, x, g, e)
+        assert abs(one - full[e]) < 1e-12 * max(1.0, np.linalg.norm(full))
+        assert abs(one - fd[e]) < 2e-8 * max(1.0, np.linalg.norm(fd))
+
+
+def test_partial_products_compose_to_u():
+    n = 12
+    th, x, _ = _case(n, 5, 8)
+    u = O.dense_product(n, th)
+    for k in (0, 1, 5, n - 1):
+        left = O.apply_block_range(th, np.eye(n), 0, k)          # U^{1:k}
+        right = O.apply_block_range(th, np.eye(n), k, n - 1)     # U^{k+1:n-1}
+        assert np.allclose(left @ right, u, atol=1e-13)
+        assert np.allclose(O.apply_block_range(th, x, k, n - 1, transpose=True), right.T @ x, atol=1e-13)
