@@ -49,6 +49,11 @@ extern "C" {
 #define GIVENS_KERNEL_LDS 1      /* strip of the operand held in LDS; any even n that fits   */
 #define GIVENS_KERNEL_CAROUSEL 2 /* strip held in VGPRs in circle-method position order      */
 
+/* Rotation forms of the float carousel kernels (givens_set_rotation_form). */
+#define GIVENS_FORM_AUTO 0     /* scaled form when every |theta| <= pi/4 (decided on the device), else standard */
+#define GIVENS_FORM_STANDARD 1 /* r_i = c U_i - s U_j, r_j = s U_i + c U_j exactly as in Algorithm 1         */
+#define GIVENS_FORM_SCALED 2   /* same rotations on rows kept divided by their accumulated cosines (2 FMAs)  */
+
 /*
  * rr_schedule -- the round-robin sequence by the circle method (Section 3; the worked n = 6
  * example is Eq. (3), the dimension sequences are the left column of Figure 1).
@@ -112,9 +117,22 @@ int givens_set_kernel(int which);
 int givens_last_kernel(void);
 
 /*
+ * The float carousel kernels have two arithmetically equivalent forms of the same Givens update
+ * (Algorithm 1's loop body).  The scaled form keeps every row divided by the product of the cosines it
+ * has met, which turns an update into two FMAs, and multiplies the rows back every 64 blocks; it is
+ * used only when every |theta| <= pi/4, which a device-side check of theta decides per call.
+ * givens_set_rotation_form(GIVENS_FORM_STANDARD) switches the check and the scaled form off
+ * (process-wide); returns the previous setting.  givens_last_rotation_form() reports which form the
+ * last forward/build/backward call on this thread ran (it reads the device flag back and waits for
+ * that call's stream).  Other kernel families and the f64 entry points always use the standard form.
+ */
+int givens_set_rotation_form(int which);
+int givens_last_rotation_form(void);
+
+/*
  * Per-kernel timing.  givens_set_timing(1) makes every subsequent call record HIP events on the
  * caller's stream around each kernel it launches.  givens_last_timing() waits for the events of
- * the last call on this thread and writes milliseconds: ms[0] = coefficient table kernel,
+ * the last call on this thread and writes milliseconds: ms[0] = coefficient kernels (range check, tables),
  * ms[1] = sweep kernel(s), ms[2] = dtheta second-stage reduction (0 for forward/build).
  * Returns GIVENS_ERR_UNSUPPORTED if timing was off for that call.
  */

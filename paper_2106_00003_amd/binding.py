@@ -15,12 +15,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgivens_rr.so")
 
 KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL = 0, 1, 2
+FORM_AUTO, FORM_STANDARD, FORM_SCALED = 0, 1, 2
 
 EXPORTS = [
     "rr_schedule", "givens_forward", "givens_build", "givens_backward",
     "givens_forward_f64", "givens_build_f64", "givens_backward_f64",
     "givens_release", "givens_last_hip_error", "givens_error_string",
     "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
+    "givens_set_rotation_form", "givens_last_rotation_form",
 ]
 
 _lib = None
@@ -56,6 +58,7 @@ def lib():
     L.givens_error_string.argtypes = [i32]
     L.givens_error_string.restype = ctypes.c_char_p
     L.givens_set_kernel.argtypes = [i32]
+    L.givens_set_rotation_form.argtypes = [i32]
     L.givens_set_timing.argtypes = [i32]
     L.givens_last_timing.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for name in EXPORTS:
@@ -158,6 +161,20 @@ def set_kernel(which: int) -> int:
 
 def last_kernel() -> int:
     return lib().givens_last_kernel()
+
+
+def set_rotation_form(which: int) -> int:
+    rc = lib().givens_set_rotation_form(which)
+    if rc < 0:
+        raise GivensError(rc, "givens_set_rotation_form")
+    return rc
+
+
+def last_rotation_form() -> int:
+    rc = lib().givens_last_rotation_form()
+    if rc < 0:
+        raise GivensError(rc, "givens_last_rotation_form")
+    return rc
 
 
 def set_timing(on: bool) -> int:

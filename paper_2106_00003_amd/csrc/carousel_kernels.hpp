@@ -56,8 +56,12 @@ struct CarouselExchange {
     float near_turn[2][W];        // wavefront 0, lane 0: top[1], which turns round into bot[0]
 };
 
-template <int M, int W, int WAVES>
+// FORM 0: standard rotation (2 MUL + 2 FMA per update, table holds cos and sin).
+// FORM 1: scaled rotation (2 FMA per update on values kept divided by their accumulated cosines,
+//         table holds alpha and beta, renormalisation every kRenormPeriod blocks; coef_kernels.hpp).
+template <int M, int W, int WAVES, int FORM>
 struct CarouselFwd {
+    static_assert(kRenormPeriod % M == 0, "renormalisation must fall on the last copy of an unrolled group");
     static constexpr int kLanes = 64 * WAVES;
     static constexpr int kN = 2 * kLanes * M;
     static constexpr int kLastU = (kN - 2) % M; // register rotation after the n-2 moves
@@ -67,11 +71,14 @@ struct CarouselFwd {
     float2 cs[2][M];
     int n, H, lane, wave, tid;
     const float2 *tab_lane; // table + tid*M
+    const float2 *rn_lane;  // renormalisation factors + tid*M (scaled form)
     CarouselExchange<W, WAVES> *sh;
 
-    __device__ __forceinline__ void load_coefs(int k, float2 (&dst)[M])
+    __device__ __forceinline__ void load_coefs(int k, float2 (&dst)[M]) { load_row_of(tab_lane, k, dst); }
+
+    __device__ __forceinline__ void load_row_of(const float2 *base, int row, float2 (&dst)[M])
     {
-        const float2 *src = tab_lane + (long long)k * H;
+        const float2 *src = base + (long long)row * H;
         if constexpr (M % 2 == 0) {
             const float4 *s4 = reinterpret_cast<const float4 *>(src);
 #pragma unroll
@@ -86,48 +93,74 @@ struct CarouselFwd {
         }
     }
 
-    // Empty asm with every strip register as an in/out operand: emits nothing, but the compiler
-    // must have all of this block's rotations finished here.  Without it, rotations whose results
-    // are not needed for the exchange are sunk into later blocks and drag their cos/sin registers
-    // along, which multiplies the live table registers by the unroll factor.
-    __device__ __forceinline__ void pin_strip()
+    // Rotation of logical slot R under the register map of unrolled copy U (RN: then multiply the
+    // rows back by their renormalisation factors, scaled form).  Ends with an empty asm that has the
+    // slot's registers as in/out operands: it emits nothing, but pins the finished values here, so
+    // that the compiler cannot sink a rotation into a later block (which would keep that block's
+    // cos/sin registers alive and multiply the live table registers by the unroll factor).
+    template <int U, int R, bool RN>
+    __device__ __forceinline__ void rotate_slot(const float2 (&cur)[M], const float2 (&rn)[M])
     {
+        constexpr int it = (R + U) % M, ib = (R - U + M) % M;
+        const float c = cur[R].x, s = cur[R].y;
 #pragma unroll
-        for (int r = 0; r < M; ++r) {
-#pragma unroll
-            for (int x = 0; x < W; ++x) {
-                asm volatile("" : "+v"(top[r][x]));
-                asm volatile("" : "+v"(bot[r][x]));
+        for (int x = 0; x < W; ++x) {
+            const float a = top[it][x], b = bot[ib][x];
+            if constexpr (FORM == 0) {
+                top[it][x] = fmaf(c, a, -(s * b)); // r_i = cos U_i - sin U_j
+                bot[ib][x] = fmaf(c, b, s * a);    // r_j = sin U_i + cos U_j
+            } else {
+                top[it][x] = fmaf(-c, b, a);       // a~ - alpha b~
+                bot[ib][x] = fmaf(s, a, b);        // b~ + beta a~
+            }
+            if constexpr (RN) {
+                top[it][x] *= rn[R].x;
+                bot[ib][x] *= rn[R].y;
             }
         }
+#pragma unroll
+        for (int x = 0; x < W; ++x) asm volatile("" : "+v"(top[it][x]), "+v"(bot[ib][x]));
+    }
+    template <int U, bool RN, int... Rs>
+    __device__ __forceinline__ void rotate_slots(const float2 (&cur)[M], const float2 (&rn)[M],
+                                                 std::integer_sequence<int, Rs...>)
+    {
+        (rotate_slot<U, Rs, RN>(cur, rn), ...);
+    }
+    // slots 2 .. M-2, the ones that take no part in the exchange
+    template <int U, bool RN, int... Rs>
+    __device__ __forceinline__ void rotate_inner(const float2 (&cur)[M], const float2 (&rn)[M],
+                                                 std::integer_sequence<int, Rs...>)
+    {
+        (rotate_slot<U, Rs + 2, RN>(cur, rn), ...);
     }
 
     // One block of Algorithm 2 with the slot <-> register map of unrolled copy U, then the move.
     // LAST marks the very last block (k = 0): nothing to prefetch and no move after it.
-    template <int U, bool LAST>
+    // RENORM (scaled form): this block closes a renormalisation period; the rows are multiplied back
+    // by their factors (compile-time variant: a run-time branch around 2*M*W multiplies made the
+    // register allocator spill).
+    // Order inside the block: the slots whose results leave the lane (0, M-1 and, for the held
+    // position, 1) are rotated first and published to LDS; the other slots are rotated while those
+    // writes and the other wavefronts' arrival at the barrier are in flight.
+    template <int U, bool LAST, bool RENORM>
     __device__ __forceinline__ void step(int k)
     {
+        constexpr bool RN = FORM == 1 && (LAST || RENORM);
         float2(&cur)[M] = cs[U & 1];
         if constexpr (!LAST) load_coefs(k - 1, cs[(U + 1) & 1]);
+        float2 rn[M];
+        if constexpr (RN) load_row_of(rn_lane, (n - 2 - k) / kRenormPeriod, rn);
 
-#pragma unroll
-        for (int r = 0; r < M; ++r) {
-            const int it = (r + U) % M, ib = (r - U + M) % M;
-            const float c = cur[r].x, s = cur[r].y;
-#pragma unroll
-            for (int x = 0; x < W; ++x) {
-                const float a = top[it][x], b = bot[ib][x];
-                top[it][x] = fmaf(c, a, -(s * b)); // r_i = cos U_i - sin U_j
-                bot[ib][x] = fmaf(c, b, s * a);    // r_j = sin U_i + cos U_j
-            }
-        }
-        pin_strip();
+        rotate_slot<U, 0, RN>(cur, rn);
+        if constexpr (M > 1) rotate_slot<U, M - 1, RN>(cur, rn);
+        if constexpr (M > 2) rotate_slot<U, 1, RN>(cur, rn);
 
+        constexpr int q = U % M;                // top slot 0: leaves towards the previous lane
+        constexpr int qb = (M - 1 - U + M) % M; // bottom slot M-1: leaves towards the next lane
+        constexpr int q1 = (1 + U) % M;         // top slot 1 (matters in lane 0 of wavefront 0)
+        constexpr int par = U & 1;
         if constexpr (!LAST) {
-            constexpr int q = U % M;                // top slot 0: leaves towards the previous lane
-            constexpr int qb = (M - 1 - U + M) % M; // bottom slot M-1: leaves towards the next lane
-            constexpr int q1 = (1 + U) % M;         // top slot 1 (matters in lane 0 of wavefront 0)
-            constexpr int par = U & 1;
             if (lane == 0) {
 #pragma unroll
                 for (int x = 0; x < W; ++x) sh->first_top[par][wave][x] = top[q][x];
@@ -148,6 +181,11 @@ struct CarouselFwd {
                     top[q1][x] = (lane == 0) ? held : other;
                 }
             }
+        }
+
+        if constexpr (M > 3) rotate_inner<U, RN>(cur, rn, std::make_integer_sequence<int, M - 3>{});
+
+        if constexpr (!LAST) {
             __syncthreads();
             const float *in_top = (wave == WAVES - 1) ? sh->last_bot[par][WAVES - 1] : sh->first_top[par][wave + 1];
             const float *in_bot = (wave == 0) ? sh->near_turn[par] : sh->last_bot[par][wave - 1];
@@ -159,17 +197,38 @@ struct CarouselFwd {
         }
     }
 
-    // M consecutive blocks starting at block index k_first (going down), none of them the last
-    template <int... Us>
+    // M consecutive blocks starting at block index k_first (going down), none of them the last;
+    // RENORM: the group's last block closes a renormalisation period
+    template <bool RENORM, int... Us>
     __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Us...>)
     {
-        (step<Us, false>(k_first - Us), ...);
+        (step<Us, false, RENORM && Us == M - 1>(k_first - Us), ...);
     }
     // the closing M-1 blocks k = M-2 .. 0 (n-1 = -1 mod M, so the tail always has M-1 blocks)
     template <int... Us>
     __device__ __forceinline__ void tail_group(std::integer_sequence<int, Us...>)
     {
-        (step<Us, Us == M - 2>(M - 2 - Us), ...);
+        (step<Us, Us == M - 2, false>(M - 2 - Us), ...);
+    }
+
+    // all n-1 blocks: n/M - 1 full groups of M, then the tail of M - 1
+    __device__ __forceinline__ void sweep()
+    {
+        constexpr auto seq = std::make_integer_sequence<int, M>{};
+        int k = n - 2;
+        if constexpr (FORM == 0) {
+            for (; k >= M - 1; k -= M) full_group<false>(k, seq);
+        } else {
+            constexpr int per = kRenormPeriod / M;         // groups per renormalisation period
+            const int groups = n / M - 1;
+            for (int pd = 0; pd < groups / per; ++pd) {
+                for (int g = 0; g < per - 1; ++g, k -= M) full_group<false>(k, seq);
+                full_group<true>(k, seq);
+                k -= M;
+            }
+            for (int g = 0; g < groups % per; ++g, k -= M) full_group<false>(k, seq);
+        }
+        tail_group(std::make_integer_sequence<int, M - 1>{});
     }
 };
 
@@ -215,13 +274,16 @@ __device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long 
         if (x < wv) dst[x] = src[x];
 }
 
-template <int M, int W, int WAVES>
+template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
-    int n, long long B, const float2 *__restrict__ table, const float *X, float *Y, int identity, int vec_ok)
+    int n, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
+    const unsigned *flag, const float *X, float *Y, int identity, int vec_ok)
 {
-    using State = CarouselFwd<M, W, WAVES>;
+    if (!form_selected(flag, FORM == 1)) return;
+    using State = CarouselFwd<M, W, WAVES, FORM>;
     __shared__ CarouselExchange<W, WAVES> sh;
     State st;
+    st.rn_lane = renorm + (long long)threadIdx.x * M;
     st.n = n;
     st.H = n >> 1;
     st.tid = threadIdx.x;
@@ -243,9 +305,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
     }
     st.load_coefs(n - 2, st.cs[0]);
 
-    // n - 1 = (n/M - 1) * M + (M - 1) blocks: full groups of M, then a tail of M - 1
-    for (int k = n - 2; k >= M - 1; k -= M) st.full_group(k, std::make_integer_sequence<int, M>{});
-    st.tail_group(std::make_integer_sequence<int, M - 1>{});
+    st.sweep();
 
     // after block 1 the position order is the identity: position p holds row p
     constexpr int UL = State::kLastU;
@@ -276,8 +336,9 @@ struct CarouselExchangeBwd {
     float bot_in[2][2][WAVES][W]; // what lane 63 of each wavefront receives into its bottom line
 };
 
-template <int M, int W, int WAVES>
+template <int M, int W, int WAVES, int FORM>
 struct CarouselBwd {
+    static_assert(kRenormPeriod % M == 0, "renormalisation must fall on the last copy of an unrolled group");
     static constexpr int kLanes = 64 * WAVES;
     static constexpr int kN = 2 * kLanes * M;
     static constexpr int kLastU = (kN - 2) % M;
@@ -286,12 +347,15 @@ struct CarouselBwd {
     float2 cs[2][M];
     int n, H, lane, wave, tid;
     const float2 *tab_lane;  // table + tid*M
+    const float2 *rn_lane;   // renormalisation factors + tid*M (scaled form)
     float *part_lane;        // this strip's partial sums + tid*M
     CarouselExchangeBwd<W, WAVES> *sh;
 
-    __device__ __forceinline__ void load_coefs(int k, float2 (&dst)[M])
+    __device__ __forceinline__ void load_coefs(int k, float2 (&dst)[M]) { load_row_of(tab_lane, k, dst); }
+
+    __device__ __forceinline__ void load_row_of(const float2 *base, int row, float2 (&dst)[M])
     {
-        const float2 *src = tab_lane + (long long)k * H;
+        const float2 *src = base + (long long)row * H;
         if constexpr (M % 2 == 0) {
             const float4 *s4 = reinterpret_cast<const float4 *>(src);
 #pragma unroll
@@ -303,20 +367,6 @@ struct CarouselBwd {
         } else {
 #pragma unroll
             for (int r = 0; r < M; ++r) dst[r] = src[r];
-        }
-    }
-
-    __device__ __forceinline__ void pin_strips()
-    {
-#pragma unroll
-        for (int r = 0; r < M; ++r) {
-#pragma unroll
-            for (int x = 0; x < W; ++x) {
-                asm volatile("" : "+v"(zt[r][x]));
-                asm volatile("" : "+v"(zb[r][x]));
-                asm volatile("" : "+v"(gt[r][x]));
-                asm volatile("" : "+v"(gb[r][x]));
-            }
         }
     }
 
@@ -364,30 +414,70 @@ struct CarouselBwd {
         }
     }
 
-    template <int U, bool LAST>
-    __device__ __forceinline__ void step(int k)
+    // Logical slot R of one block: the strip's share of the pair's gradient, then the transposed
+    // rotation on both strips (RN: then the renormalisation multiply), then the pin (see the forward
+    // kernel's rotate_slot).
+    template <int U, int R, bool RN>
+    __device__ __forceinline__ float sweep_slot(const float2 (&cur)[M], const float2 (&rn)[M])
     {
-        float2(&cur)[M] = cs[U & 1];
-        if constexpr (!LAST) load_coefs(k + 1, cs[(U + 1) & 1]);
-
-        float sums[M];
+        constexpr int it = (R - U + M) % M, ib = (R + U) % M;
+        const float c = cur[R].x, s = cur[R].y;
+        float acc = 0.f;
 #pragma unroll
-        for (int r = 0; r < M; ++r) {
-            const int it = (r - U + M) % M, ib = (r + U) % M;
-            const float c = cur[r].x, s = cur[r].y;
-            float acc = 0.f;
-#pragma unroll
-            for (int x = 0; x < W; ++x) {
-                const float za = zt[it][x], zv = zb[ib][x], ga = gt[it][x], gv = gb[ib][x];
-                acc = fmaf(gv, za, acc);
-                acc = fmaf(-ga, zv, acc);
+        for (int x = 0; x < W; ++x) {
+            const float za = zt[it][x], zv = zb[ib][x], ga = gt[it][x], gv = gb[ib][x];
+            acc = fmaf(gv, za, acc);
+            acc = fmaf(-ga, zv, acc);
+            if constexpr (FORM == 0) {
                 zt[it][x] = fmaf(c, za, s * zv);   // transposed rotation
                 zb[ib][x] = fmaf(c, zv, -(s * za));
                 gt[it][x] = fmaf(c, ga, s * gv);
                 gb[ib][x] = fmaf(c, gv, -(s * ga));
+            } else {
+                zt[it][x] = fmaf(c, zv, za);       // a~ + alpha b~
+                zb[ib][x] = fmaf(-s, za, zv);      // b~ - beta a~
+                gt[it][x] = fmaf(c, gv, ga);
+                gb[ib][x] = fmaf(-s, ga, gv);
             }
-            sums[r] = acc;
+            if constexpr (RN) {
+                zt[it][x] *= rn[R].x;
+                zb[ib][x] *= rn[R].y;
+                gt[it][x] *= rn[R].x;
+                gb[ib][x] *= rn[R].y;
+            }
         }
+#pragma unroll
+        for (int x = 0; x < W; ++x)
+            asm volatile("" : "+v"(zt[it][x]), "+v"(zb[ib][x]), "+v"(gt[it][x]), "+v"(gb[ib][x]));
+        return acc;
+    }
+    // slots 1 .. M-2, the ones that take no part in the exchange
+    template <int U, bool RN, int... Rs>
+    __device__ __forceinline__ void sweep_inner(const float2 (&cur)[M], const float2 (&rn)[M], float (&sums)[M],
+                                                std::integer_sequence<int, Rs...>)
+    {
+        ((sums[Rs + 1] = sweep_slot<U, Rs + 1, RN>(cur, rn)), ...);
+    }
+
+    // One block of the reverse sweep.  The slots whose rows leave the lane (0 and M-1) go first and
+    // are published to LDS; the inner slots run while those writes and the barrier are in flight.
+    template <int U, bool LAST, bool RENORM>
+    __device__ __forceinline__ void step(int k)
+    {
+        constexpr bool RN = FORM == 1 && (LAST || RENORM);
+        float2(&cur)[M] = cs[U & 1];
+        if constexpr (!LAST) load_coefs(k + 1, cs[(U + 1) & 1]);
+        float2 rn[M];
+        if constexpr (RN) load_row_of(rn_lane, k / kRenormPeriod, rn);
+
+        float sums[M];
+        sums[0] = sweep_slot<U, 0, RN>(cur, rn);
+        if constexpr (M > 1) sums[M - 1] = sweep_slot<U, M - 1, RN>(cur, rn);
+        if constexpr (!LAST) {
+            publish<U, 0>(zt, zb);
+            publish<U, 1>(gt, gb);
+        }
+        if constexpr (M > 2) sweep_inner<U, RN>(cur, rn, sums, std::make_integer_sequence<int, M - 2>{});
         {
             float *dst = part_lane + (long long)k * H;
             if constexpr (M % 4 == 0) {
@@ -404,37 +494,55 @@ struct CarouselBwd {
                 for (int r = 0; r < M; ++r) dst[r] = sums[r];
             }
         }
-        pin_strips();
-
         if constexpr (!LAST) {
-            publish<U, 0>(zt, zb);
-            publish<U, 1>(gt, gb);
             __syncthreads();
             receive<U, 0>(zt, zb);
             receive<U, 1>(gt, gb);
         }
     }
 
-    template <int... Us>
+    template <bool RENORM, int... Us>
     __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Us...>)
     {
-        (step<Us, false>(k_first + Us), ...);
+        (step<Us, false, RENORM && Us == M - 1>(k_first + Us), ...);
     }
     template <int... Us>
     __device__ __forceinline__ void tail_group(int k_first, std::integer_sequence<int, Us...>)
     {
-        (step<Us, Us == M - 2>(k_first + Us), ...);
+        (step<Us, Us == M - 2, false>(k_first + Us), ...);
+    }
+
+    // all n-1 blocks in the order b_1, b_2, ...: n/M - 1 full groups of M, then the tail of M - 1
+    __device__ __forceinline__ void sweep()
+    {
+        constexpr auto seq = std::make_integer_sequence<int, M>{};
+        int k = 0;
+        if constexpr (FORM == 0) {
+            for (; k + M <= n - 1; k += M) full_group<false>(k, seq);
+        } else {
+            constexpr int per = kRenormPeriod / M;
+            const int groups = n / M - 1;
+            for (int pd = 0; pd < groups / per; ++pd) {
+                for (int g = 0; g < per - 1; ++g, k += M) full_group<false>(k, seq);
+                full_group<true>(k, seq);
+                k += M;
+            }
+            for (int g = 0; g < groups % per; ++g, k += M) full_group<false>(k, seq);
+        }
+        tail_group(k, std::make_integer_sequence<int, M - 1>{});
     }
 };
 
-template <int M, int W, int WAVES>
+template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
-    int n, long long B, long long strip0, const float2 *__restrict__ table, const float *Yin, const float *G,
-    float *dX, float *__restrict__ partial, int vec_ok)
+    int n, long long B, long long strip0, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
+    const unsigned *flag, const float *Yin, const float *G, float *dX, float *__restrict__ partial, int vec_ok)
 {
-    using State = CarouselBwd<M, W, WAVES>;
+    if (!form_selected(flag, FORM == 1)) return;
+    using State = CarouselBwd<M, W, WAVES, FORM>;
     __shared__ CarouselExchangeBwd<W, WAVES> sh;
     State st;
+    st.rn_lane = renorm + (long long)threadIdx.x * M;
     st.n = n;
     st.H = n >> 1;
     st.tid = threadIdx.x;
@@ -459,9 +567,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     }
     st.load_coefs(0, st.cs[0]);
 
-    int k = 0;
-    for (; k + M <= n - 1; k += M) st.full_group(k, std::make_integer_sequence<int, M>{});
-    st.tail_group(k, std::make_integer_sequence<int, M - 1>{});
+    st.sweep();
 
     if (dX) {
         constexpr int UL = State::kLastU;
@@ -479,6 +585,15 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
 // ---------------------------------------------------------------------------------------------
 struct CarouselShape {
     int M, WAVES;
+};
+
+// What a sweep of one rotation form reads: its table, its renormalisation rows (scaled form) and the
+// device flag that says which form is to run (nullptr: this launch always runs).
+struct CarouselCoefs {
+    int form; // 0 standard, 1 scaled
+    const float2 *table;
+    const float2 *renorm;
+    const unsigned *flag;
 };
 
 // n = 128 * WAVES * M with one of the compiled (M, WAVES) pairs
@@ -533,49 +648,95 @@ inline int carousel_width(long long B, int waves)
     return 1;
 }
 
-template <int M, int W, int WAVES>
-inline void carousel_launch_fwd(int n, long long B, const float2 *table, const float *X, float *Y, int identity,
-                                int vec_ok, hipStream_t stream)
+struct CarouselFwdArgs {
+    int n;
+    long long B;
+    CarouselCoefs coefs;
+    const float *X;
+    float *Y;
+    int identity, vec_ok;
+    hipStream_t stream;
+};
+
+template <int M, int W, int WAVES, int FORM>
+inline void carousel_launch_fwd(const CarouselFwdArgs &a)
 {
-    const long long strips = (B + W - 1) / W;
-    hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES>), dim3((unsigned)strips), dim3(64 * WAVES), 0, stream,
-                       n, B, table, X, Y, identity, vec_ok);
+    const long long strips = (a.B + W - 1) / W;
+    hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES, FORM>), dim3((unsigned)strips), dim3(64 * WAVES), 0,
+                       a.stream, a.n, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.X, a.Y, a.identity,
+                       a.vec_ok);
 }
 
 template <int M, int WAVES>
-inline int carousel_dispatch_w(int W, int n, long long B, const float2 *table, const float *X, float *Y,
-                               int identity, int vec_ok, hipStream_t stream)
+inline int carousel_dispatch_fwd(int W, const CarouselFwdArgs &a)
 {
+#define GIVENS_FWD_CASE(w)                                             \
+    case w:                                                            \
+        if (a.coefs.form == 1) carousel_launch_fwd<M, w, WAVES, 1>(a); \
+        else carousel_launch_fwd<M, w, WAVES, 0>(a);                   \
+        return GIVENS_OK;
     switch (W) {
-    case 8: carousel_launch_fwd<M, 8, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
-    case 4: carousel_launch_fwd<M, 4, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
-    case 2: carousel_launch_fwd<M, 2, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
-    case 1: carousel_launch_fwd<M, 1, WAVES>(n, B, table, X, Y, identity, vec_ok, stream); return GIVENS_OK;
+        GIVENS_FWD_CASE(8)
+        GIVENS_FWD_CASE(4)
+        GIVENS_FWD_CASE(2)
+        GIVENS_FWD_CASE(1)
     default: return GIVENS_ERR_UNSUPPORTED;
     }
+#undef GIVENS_FWD_CASE
 }
 
-template <int M, int W, int WAVES>
-inline void carousel_launch_bwd(int n, long long B, long long strip0, long long nstrips, const float2 *table,
-                                const float *Y, const float *G, float *dX, float *partial, int vec_ok,
-                                hipStream_t stream)
+inline int carousel_forward(int n, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
+                            int identity, hipStream_t stream)
 {
-    hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES>), dim3((unsigned)nstrips), dim3(64 * WAVES), 0,
-                       stream, n, B, strip0, table, Y, G, dX, partial, vec_ok);
+    CarouselShape s;
+    if (!carousel_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
+    const int W = carousel_width(B, s.WAVES);
+    const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
+                         (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
+    const CarouselFwdArgs a{n, B, coefs, X, Y, identity, aligned ? 1 : 0, stream};
+    if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_fwd<2, 1>(W, a);
+    if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_fwd<4, 1>(W, a);
+    if (s.M == 8 && s.WAVES == 1) return carousel_dispatch_fwd<8, 1>(W, a);
+    if (s.M == 8 && s.WAVES == 2) return carousel_dispatch_fwd<8, 2>(W, a);
+    if (s.M == 8 && s.WAVES == 4) return carousel_dispatch_fwd<8, 4>(W, a);
+    if (s.M == 8 && s.WAVES == 8) return carousel_dispatch_fwd<8, 8>(W, a);
+    return GIVENS_ERR_UNSUPPORTED;
+}
+
+struct CarouselBwdArgs {
+    int n;
+    long long B, strip0, nstrips;
+    CarouselCoefs coefs;
+    const float *Y, *G;
+    float *dX, *partial;
+    int vec_ok;
+    hipStream_t stream;
+};
+
+template <int M, int W, int WAVES, int FORM>
+inline void carousel_launch_bwd(const CarouselBwdArgs &a)
+{
+    hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.nstrips), dim3(64 * WAVES),
+                       0, a.stream, a.n, a.B, a.strip0, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.Y, a.G,
+                       a.dX, a.partial, a.vec_ok);
 }
 
 template <int M, int WAVES>
-inline int carousel_dispatch_bwd_w(int W, int n, long long B, long long strip0, long long nstrips,
-                                   const float2 *table, const float *Y, const float *G, float *dX,
-                                   float *partial, int vec_ok, hipStream_t stream)
+inline int carousel_dispatch_bwd(int W, const CarouselBwdArgs &a)
 {
+#define GIVENS_BWD_CASE(w)                                             \
+    case w:                                                            \
+        if (a.coefs.form == 1) carousel_launch_bwd<M, w, WAVES, 1>(a); \
+        else carousel_launch_bwd<M, w, WAVES, 0>(a);                   \
+        return GIVENS_OK;
     switch (W) {
-    case 8: carousel_launch_bwd<M, 8, WAVES>(n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream); return GIVENS_OK;
-    case 4: carousel_launch_bwd<M, 4, WAVES>(n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream); return GIVENS_OK;
-    case 2: carousel_launch_bwd<M, 2, WAVES>(n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream); return GIVENS_OK;
-    case 1: carousel_launch_bwd<M, 1, WAVES>(n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream); return GIVENS_OK;
+        GIVENS_BWD_CASE(8)
+        GIVENS_BWD_CASE(4)
+        GIVENS_BWD_CASE(2)
+        GIVENS_BWD_CASE(1)
     default: return GIVENS_ERR_UNSUPPORTED;
     }
+#undef GIVENS_BWD_CASE
 }
 
 // Columns per workgroup of the reverse sweep.
@@ -588,7 +749,7 @@ inline int carousel_bwd_width(int n, long long B)
 
 // Launches the reverse sweep on strips [strip0, strip0 + nstrips); partial is [nstrips][N].
 inline int carousel_backward_strips(int n, long long B, int W, long long strip0, long long nstrips,
-                                    const float2 *table, const float *Y, const float *G, float *dX,
+                                    const CarouselCoefs &coefs, const float *Y, const float *G, float *dX,
                                     float *partial, hipStream_t stream)
 {
     CarouselShape s;
@@ -596,36 +757,13 @@ inline int carousel_backward_strips(int n, long long B, int W, long long strip0,
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const int vec_ok = aligned ? 1 : 0;
-    if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_bwd_w<2, 1>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
-    if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_bwd_w<4, 1>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
-    if (s.M == 4 && s.WAVES == 2) return carousel_dispatch_bwd_w<4, 2>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
-    if (s.M == 4 && s.WAVES == 4) return carousel_dispatch_bwd_w<4, 4>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
-    if (s.M == 4 && s.WAVES == 8) return carousel_dispatch_bwd_w<4, 8>(W, n, B, strip0, nstrips, table, Y, G, dX, partial, vec_ok, stream);
+    const CarouselBwdArgs a{n, B, strip0, nstrips, coefs, Y, G, dX, partial, aligned ? 1 : 0, stream};
+    if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_bwd<2, 1>(W, a);
+    if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_bwd<4, 1>(W, a);
+    if (s.M == 4 && s.WAVES == 2) return carousel_dispatch_bwd<4, 2>(W, a);
+    if (s.M == 4 && s.WAVES == 4) return carousel_dispatch_bwd<4, 4>(W, a);
+    if (s.M == 4 && s.WAVES == 8) return carousel_dispatch_bwd<4, 8>(W, a);
     return GIVENS_ERR_UNSUPPORTED;
-}
-
-template <typename T>
-inline int carousel_forward(int n, long long B, const typename Pair2<T>::type *table, const T *X, T *Y,
-                            int identity, hipStream_t stream)
-{
-    if constexpr (!std::is_same<T, float>::value) {
-        return GIVENS_ERR_UNSUPPORTED;
-    } else {
-        CarouselShape s;
-        if (!carousel_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
-        const int W = carousel_width(B, s.WAVES);
-        const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
-                             (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
-        const int vec_ok = aligned ? 1 : 0;
-        if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_w<2, 1>(W, n, B, table, X, Y, identity, vec_ok, stream);
-        if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_w<4, 1>(W, n, B, table, X, Y, identity, vec_ok, stream);
-        if (s.M == 8 && s.WAVES == 1) return carousel_dispatch_w<8, 1>(W, n, B, table, X, Y, identity, vec_ok, stream);
-        if (s.M == 8 && s.WAVES == 2) return carousel_dispatch_w<8, 2>(W, n, B, table, X, Y, identity, vec_ok, stream);
-        if (s.M == 8 && s.WAVES == 4) return carousel_dispatch_w<8, 4>(W, n, B, table, X, Y, identity, vec_ok, stream);
-        if (s.M == 8 && s.WAVES == 8) return carousel_dispatch_w<8, 8>(W, n, B, table, X, Y, identity, vec_ok, stream);
-        return GIVENS_ERR_UNSUPPORTED;
-    }
 }
 
 } // namespace givens

@@ -1,0 +1,167 @@
+// Coefficient kernels: everything the sweeps need that depends on theta only.
+//
+// Standard form.  Per (block k, arc p): cos(theta) and the sine with the orientation folded in (the
+// sweeps address the strip by circle-method position: "top" = position p, "bottom" = position
+// n-1-p; the sine is negated when the top position holds the larger label), so that
+//     top' = c*top - s*bot,   bot' = s*top + c*bot
+// is Algorithm 2's update (r_i = c U_i - s U_j, r_j = s U_i + c U_j with i < j) either way.
+//
+// Scaled form (float, near-identity angles only: max |theta| <= kScaledMaxAbsTheta).  Each row r is
+// kept as a stored value y~_r = y_r / d_r, where d_r is the product of the cosines of the rotations
+// the row has been through since the last renormalisation.  Dividing a rotation of rows (a, b) by
+// its cosine turns it into two FMAs on the stored values,
+//     a~' = a~ - alpha * b~,   b~' = b~ + beta * a~,
+//     alpha = tan(theta) * d_b / d_a,   beta = tan(theta) * d_a / d_b,   d_a' = c d_a,  d_b' = c d_b,
+// and every kRenormPeriod blocks (and after the last one) the stored values are multiplied by d_r and
+// d_r restarts at 1.  The factors d depend on theta alone, so they are produced here, in float64: a
+// scan walks each row's trajectory through the circle-method positions for one renormalisation
+// period (scaled_scan_kernel), and the table kernel turns (theta, d_a, d_b) into (alpha, beta).
+// The result is the same product of Givens rotations (Eq. (2)); only the rounding differs (one
+// rounding per output instead of two).
+//
+// The choice between the two forms is made on the device: theta_range_kernel leaves the bit pattern
+// of max |theta| in a flag word, and every kernel of either form returns at once when the flag says
+// the other form is the one to run.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "rr_index.h"
+
+namespace givens {
+
+template <typename T> struct Pair2;
+template <> struct Pair2<float> { using type = float2; };
+template <> struct Pair2<double> { using type = double2; };
+
+constexpr int kRenormPeriod = 64;                 // blocks between renormalisations of the scaled form
+constexpr float kScaledMaxAbsTheta = 0.78539816f; // scaled form only when every |theta| <= pi/4
+
+// true when the form asked for is the one the flag selects (flag == nullptr: standard form, always)
+__device__ __forceinline__ bool form_selected(const unsigned *flag, bool want_scaled)
+{
+    if (!flag) return !want_scaled;
+    const bool scaled = __uint_as_float(*flag) <= kScaledMaxAbsTheta; // NaN compares false: standard form
+    return scaled == want_scaled;
+}
+
+__global__ void reset_flag_kernel(unsigned *flag) { *flag = 0u; }
+
+// flag <- bit pattern of max |theta| (non-negative floats order like unsigned integers; NaN sorts last)
+__global__ void theta_range_kernel(long long N, const float *__restrict__ theta, unsigned *flag)
+{
+    unsigned m = 0u;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < N;
+         e += (long long)gridDim.x * blockDim.x) {
+        const unsigned bits = __float_as_uint(theta[e]) & 0x7fffffffu;
+        m = bits > m ? bits : m;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned other = (unsigned)__shfl_xor((int)m, off, 64);
+        m = other > m ? other : m;
+    }
+    if ((threadIdx.x & 63) == 0) atomicMax(flag, m);
+}
+
+// Standard form table, in E order.  `factor` (optional) receives the orientation sign (+1 when the
+// top position holds the smaller label) that the dtheta reduction multiplies its sums by.
+template <typename T>
+__global__ void coef_table_kernel(int n, const T *__restrict__ theta, const unsigned *flag,
+                                  typename Pair2<T>::type *__restrict__ table, T *__restrict__ factor)
+{
+    if (!form_selected(flag, false)) return;
+    const int H = n >> 1;
+    const long long N = (long long)(n - 1) * H;
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= N) return;
+    const int k = (int)(e / H), p = (int)(e % H);
+    const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+    double s, c;
+    sincos((double)theta[e], &s, &c);
+    if (a > b) s = -s;
+    typename Pair2<T>::type out;
+    out.x = (T)c;
+    out.y = (T)s;
+    table[e] = out;
+    if (factor) factor[e] = (a < b) ? T(1) : T(-1);
+}
+
+// Scaled form, step 1.  One thread per (renormalisation period g, row r): walks the row through the
+// period's blocks in sweep order (FWD: k = n-2, n-3, ...; reverse sweep: k = 0, 1, ...), records the
+// row's factor d *before* each block at D[k][position], and leaves the factor after the period's last
+// block in renorm[g][slot] (.x for the top position of the slot, .y for the bottom one).
+template <bool FWD>
+__global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const unsigned *flag,
+                                   double *__restrict__ D, float *__restrict__ renorm)
+{
+    if (!form_selected(flag, true)) return;
+    const int H = n >> 1;
+    const int nseg = (n - 1 + kRenormPeriod - 1) / kRenormPeriod;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)nseg * n) return;
+    const int g = (int)(idx / n), r = (int)(idx % n);
+    const int t0 = g * kRenormPeriod;
+    const int t1 = (t0 + kRenormPeriod < n - 1) ? t0 + kRenormPeriod : n - 1;
+    double d = 1.0;
+    int q = 0, p = 0;
+    for (int t = t0; t < t1; ++t) {
+        const int k = FWD ? n - 2 - t : t;
+        q = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1); // position of label r in the sequence of block k
+        p = (q < H) ? q : n - 1 - q;
+        D[(long long)k * n + q] = d;
+        d *= cos((double)theta[(long long)k * H + p]);
+    }
+    renorm[2 * ((long long)g * H + p) + (q < H ? 0 : 1)] = (float)d;
+}
+
+// Scaled form, step 2: (alpha, beta) per (block, arc) in E order.  The same magnitudes serve both
+// sweeps; the sweeps apply the signs (forward: a - alpha b, b + beta a; reverse: a + alpha b, b - beta a),
+// but the factors d differ between the two directions, hence FWD.  For the reverse sweep `factor`
+// receives orientation sign * d_top * d_bot: the sweep sums stored values, and
+// gbar_j z_i - gbar_i z_j = d_i d_j (g~_j z~_i - g~_i z~_j).
+template <bool FWD>
+__global__ void scaled_table_kernel(int n, const float *__restrict__ theta, const unsigned *flag,
+                                    const double *__restrict__ D, float2 *__restrict__ table,
+                                    float *__restrict__ factor)
+{
+    if (!form_selected(flag, true)) return;
+    const int H = n >> 1;
+    const long long N = (long long)(n - 1) * H;
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= N) return;
+    const int k = (int)(e / H), p = (int)(e % H);
+    const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+    double s, c;
+    sincos((double)theta[e], &s, &c);
+    if (a > b) s = -s;
+    const double tn = s / c;
+    const double da = D[(long long)k * n + p], db = D[(long long)k * n + (n - 1 - p)];
+    table[e] = make_float2((float)(tn * db / da), (float)(tn * da / db));
+    if (!FWD && factor) factor[e] = (float)((a < b ? 1.0 : -1.0) * da * db);
+}
+
+// Second stage of the gradient reduction: dtheta[e] (+)= factor[e] * sum over strips s of
+// partial[s][e], in strip order (fixed order: reproducible).  The sweeps store
+// sum_b (g_bot z_top - g_top z_bot) of their stored values; `factor` carries the orientation sign
+// (with i < j the paper's term is gbar_j z_i - gbar_i z_j) and, in the scaled form, d_top * d_bot.
+template <typename T>
+__global__ void reduce_partials_kernel(int n, long long nstrips, const T *__restrict__ partial,
+                                       const T *__restrict__ factor, T *dtheta, int accumulate)
+{
+    const int H = n >> 1;
+    const long long N = (long long)(n - 1) * H;
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= N) return;
+    T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
+    long long s = 0;
+    for (; s + 4 <= nstrips; s += 4) {          // four loads in flight; the order of additions is fixed
+        a0 += partial[s * N + e];
+        a1 += partial[(s + 1) * N + e];
+        a2 += partial[(s + 2) * N + e];
+        a3 += partial[(s + 3) * N + e];
+    }
+    for (; s < nstrips; ++s) a0 += partial[s * N + e];
+    const T acc = ((a0 + a1) + (a2 + a3)) * factor[e];
+    dtheta[e] = accumulate ? dtheta[e] + acc : acc;
+}
+
+} // namespace givens

@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/givens_rr.h"
@@ -19,16 +20,25 @@ constexpr int kMaxDevices = 64;
 constexpr size_t kLdsBudgetBytes = 144 * 1024;                 // of the 160 KB per CU on gfx950
 constexpr size_t kPartialCapBytes = size_t(24) << 30;          // cap on one chunk of strip partials
 
+struct Buffer {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
 struct Workspace {
-    void *table = nullptr;
-    size_t table_bytes = 0;
-    void *partial = nullptr;
-    size_t partial_bytes = 0;
+    Buffer table;        // standard-form cos/sin table, E order
+    Buffer table_scaled; // scaled-form (alpha, beta) table, E order
+    Buffer scale;        // scaled form: float64 row factors d, [n-1][n]
+    Buffer renorm;       // scaled form: renormalisation rows, float2 [periods][n/2]
+    Buffer factor;       // per-angle factor of the dtheta reduction
+    Buffer flag;         // device word: bit pattern of max |theta|
+    Buffer partial;      // per-strip dtheta partial sums
+    Buffer *all[7] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial};
 };
 
 std::mutex g_mutex;
 Workspace g_ws[kMaxDevices];
 int g_kernel_choice = GIVENS_KERNEL_AUTO;
+int g_form_choice = GIVENS_FORM_AUTO;
 int g_timing_on = 0;
 
 struct TimedSpan {
@@ -38,6 +48,8 @@ struct TimedSpan {
 struct ThreadState {
     int last_hip_error = 0;
     int last_kernel = 0;
+    const unsigned *last_flag = nullptr; // device flag of the last call when both forms were launched
+    hipStream_t last_stream = nullptr;
     bool timing_valid = false;
     std::vector<TimedSpan> spans;
     std::vector<hipEvent_t> pool;
@@ -56,16 +68,16 @@ bool hip_ok(hipError_t e)
         if (!hip_ok(call)) return GIVENS_ERR_HIP; \
     } while (0)
 
-int grow(void **ptr, size_t *have, size_t want)
+int grow(Buffer &b, size_t want)
 {
-    if (*have >= want) return GIVENS_OK;
-    if (*ptr) {
-        GIVENS_HIP(hipFree(*ptr));                             // synchronises the device
-        *ptr = nullptr;
-        *have = 0;
+    if (b.bytes >= want) return GIVENS_OK;
+    if (b.ptr) {
+        GIVENS_HIP(hipFree(b.ptr));                            // synchronises the device
+        b.ptr = nullptr;
+        b.bytes = 0;
     }
-    GIVENS_HIP(hipMalloc(ptr, want));
-    *have = want;
+    GIVENS_HIP(hipMalloc(&b.ptr, want));
+    b.bytes = want;
     return GIVENS_OK;
 }
 
@@ -129,19 +141,72 @@ int lds_strip_width(int n, long long B, int strips_in_lds)
     return w;
 }
 
+// Everything the sweeps of one call read that depends on theta only.
 template <typename T>
-int launch_table(int dev, int n, const T *theta, hipStream_t stream, typename Pair2<T>::type **table)
+struct Coefs {
+    const typename Pair2<T>::type *table = nullptr; // standard form
+    const T *factor = nullptr;                      // reverse sweep only
+    CarouselCoefs standard{0, nullptr, nullptr, nullptr};
+    CarouselCoefs scaled{1, nullptr, nullptr, nullptr};
+    bool both_forms = false;                        // scaled-form kernels were launched too
+};
+
+// Launches the coefficient kernels.  `forward` picks the sweep direction of the scaled form's row
+// factors; `try_scaled` adds the range check and the scaled-form tables (float carousel path only).
+template <typename T>
+int prepare_coefs(int dev, int n, const T *theta, bool forward, bool try_scaled, hipStream_t stream,
+                  Coefs<T> *out)
 {
+    using P2 = typename Pair2<T>::type;
     const long long N = (long long)n * (n - 1) / 2;
     Workspace &ws = g_ws[dev];
-    int rc = grow(&ws.table, &ws.table_bytes, (size_t)N * sizeof(typename Pair2<T>::type));
-    if (rc) return rc;
-    *table = reinterpret_cast<typename Pair2<T>::type *>(ws.table);
-    Span span(0, stream);
+    if (int rc = grow(ws.table, (size_t)N * sizeof(P2))) return rc;
+    if (!forward)
+        if (int rc = grow(ws.factor, (size_t)N * sizeof(T))) return rc;
+    P2 *table = reinterpret_cast<P2 *>(ws.table.ptr);
+    T *factor = forward ? nullptr : reinterpret_cast<T *>(ws.factor.ptr);
+    unsigned *flag = nullptr;
     const int threads = 256;
     const unsigned blocks = (unsigned)((N + threads - 1) / threads);
-    hipLaunchKernelGGL(coef_table_kernel<T>, dim3(blocks), dim3(threads), 0, stream, n, theta, *table);
+    Span span(0, stream);
+    if constexpr (std::is_same<T, float>::value) {
+        if (try_scaled) {
+            const int periods = (n - 1 + kRenormPeriod - 1) / kRenormPeriod;
+            if (int rc = grow(ws.flag, 256)) return rc;
+            if (int rc = grow(ws.table_scaled, (size_t)N * sizeof(float2))) return rc;
+            if (int rc = grow(ws.scale, (size_t)(n - 1) * n * sizeof(double))) return rc;
+            if (int rc = grow(ws.renorm, (size_t)periods * (n / 2) * sizeof(float2))) return rc;
+            flag = reinterpret_cast<unsigned *>(ws.flag.ptr);
+            float2 *tab_s = reinterpret_cast<float2 *>(ws.table_scaled.ptr);
+            double *D = reinterpret_cast<double *>(ws.scale.ptr);
+            float *rn = reinterpret_cast<float *>(ws.renorm.ptr);
+            hipLaunchKernelGGL(reset_flag_kernel, dim3(1), dim3(1), 0, stream, flag);
+            hipLaunchKernelGGL(theta_range_kernel, dim3(1024), dim3(256), 0, stream, N, theta, flag);
+            const long long scan_threads = (long long)periods * n;
+            const unsigned scan_blocks = (unsigned)((scan_threads + threads - 1) / threads);
+            if (forward) {
+                hipLaunchKernelGGL(scaled_scan_kernel<true>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
+                                   flag, D, rn);
+                hipLaunchKernelGGL(scaled_table_kernel<true>, dim3(blocks), dim3(threads), 0, stream, n, theta,
+                                   flag, D, tab_s, factor);
+            } else {
+                hipLaunchKernelGGL(scaled_scan_kernel<false>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
+                                   flag, D, rn);
+                hipLaunchKernelGGL(scaled_table_kernel<false>, dim3(blocks), dim3(threads), 0, stream, n, theta,
+                                   flag, D, tab_s, factor);
+            }
+            out->scaled = CarouselCoefs{1, tab_s, reinterpret_cast<const float2 *>(rn), flag};
+            out->both_forms = true;
+        }
+        out->standard = CarouselCoefs{0, table, nullptr, flag};
+    }
+    hipLaunchKernelGGL(coef_table_kernel<T>, dim3(blocks), dim3(threads), 0, stream, n, theta,
+                       static_cast<const unsigned *>(flag), table, factor);
     GIVENS_HIP(hipGetLastError());
+    out->table = table;
+    out->factor = factor;
+    t_state.last_flag = flag;
+    t_state.last_stream = stream;
     return GIVENS_OK;
 }
 
@@ -166,8 +231,8 @@ int lds_forward(int n, long long B, const typename Pair2<T>::type *table, const 
 // Reverse sweep in chunks of strips: each chunk writes one partial sum per (strip, angle) and the
 // second stage folds the chunk into dtheta.  `family` picks the sweep kernel.
 template <typename T>
-int backward_chunks(int dev, int family, int n, long long B, const typename Pair2<T>::type *table,
-                    const T *Y, const T *G, T *dX, T *dtheta, hipStream_t stream)
+int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coefs, const T *Y, const T *G,
+                    T *dX, T *dtheta, hipStream_t stream)
 {
     const long long N = (long long)n * (n - 1) / 2;
     int w = 0;
@@ -187,19 +252,21 @@ int backward_chunks(int dev, int family, int n, long long B, const typename Pair
     long long chunk = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
     chunk = std::max<long long>(1, std::min(chunk, strips));
     Workspace &ws = g_ws[dev];
-    int rc = grow(&ws.partial, &ws.partial_bytes, (size_t)chunk * N * sizeof(T));
-    if (rc) return rc;
-    T *partial = reinterpret_cast<T *>(ws.partial);
+    if (int rc = grow(ws.partial, (size_t)chunk * N * sizeof(T))) return rc;
+    T *partial = reinterpret_cast<T *>(ws.partial.ptr);
     for (long long s0 = 0; s0 < strips; s0 += chunk) {
         const long long ns = std::min(chunk, strips - s0);
         {
             Span span(1, stream);
             if (family == GIVENS_KERNEL_LDS) {
                 hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, B, w, s0,
-                                   table, Y, G, dX, partial);
+                                   coefs.table, Y, G, dX, partial);
             } else if constexpr (std::is_same<T, float>::value) {
-                if (int rc2 = carousel_backward_strips(n, B, w, s0, ns, table, Y, G, dX, partial, stream))
-                    return rc2;
+                if (coefs.both_forms)
+                    if (int rc = carousel_backward_strips(n, B, w, s0, ns, coefs.scaled, Y, G, dX, partial, stream))
+                        return rc;
+                if (int rc = carousel_backward_strips(n, B, w, s0, ns, coefs.standard, Y, G, dX, partial, stream))
+                    return rc;
             } else {
                 return GIVENS_ERR_UNSUPPORTED;
             }
@@ -209,7 +276,7 @@ int backward_chunks(int dev, int family, int n, long long B, const typename Pair
             Span span(2, stream);
             const int threads = 256;
             hipLaunchKernelGGL(reduce_partials_kernel<T>, dim3((unsigned)((N + threads - 1) / threads)),
-                               dim3(threads), 0, stream, n, ns, partial, dtheta, s0 > 0 ? 1 : 0);
+                               dim3(threads), 0, stream, n, ns, partial, coefs.factor, dtheta, s0 > 0 ? 1 : 0);
             GIVENS_HIP(hipGetLastError());
         }
     }
@@ -237,16 +304,24 @@ int forward_impl(int n, long long B, const T *theta, const T *X, T *Y, int ident
     const int choice = g_kernel_choice;
     const bool can_carousel = carousel_supported<T>(n, B);
     if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
-    typename Pair2<T>::type *table = nullptr;
-    if (int rc = launch_table<T>(dev, n, theta, stream, &table)) return rc;
-    int rc;
-    if (can_carousel && choice != GIVENS_KERNEL_LDS) {
-        Span span(1, stream);
-        rc = carousel_forward<T>(n, B, table, X, Y, identity, stream);
-        if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+    const bool use_carousel = can_carousel && choice != GIVENS_KERNEL_LDS;
+    Coefs<T> coefs;
+    if (int rc = prepare_coefs<T>(dev, n, theta, true, use_carousel && g_form_choice == GIVENS_FORM_AUTO, stream,
+                                  &coefs))
+        return rc;
+    int rc = GIVENS_OK;
+    if (use_carousel) {
+        if constexpr (std::is_same<T, float>::value) {
+            Span span(1, stream);
+            if (coefs.both_forms) rc = carousel_forward(n, B, coefs.scaled, X, Y, identity, stream);
+            if (rc == GIVENS_OK) rc = carousel_forward(n, B, coefs.standard, X, Y, identity, stream);
+            if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+        } else {
+            rc = GIVENS_ERR_UNSUPPORTED;
+        }
         t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
     } else {
-        rc = lds_forward<T>(n, B, table, X, Y, identity, stream);
+        rc = lds_forward<T>(n, B, coefs.table, X, Y, identity, stream);
         t_state.last_kernel = GIVENS_KERNEL_LDS;
     }
     return rc;
@@ -268,11 +343,13 @@ int backward_impl(int n, long long B, const T *theta, const T *Y, const T *G, T 
     const int choice = g_kernel_choice;
     const bool can_carousel = carousel_backward_supported<T>(n, B);
     if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
-    typename Pair2<T>::type *table = nullptr;
-    if (int rc = launch_table<T>(dev, n, theta, stream, &table)) return rc;
-    int rc;
     const int family = (can_carousel && choice != GIVENS_KERNEL_LDS) ? GIVENS_KERNEL_CAROUSEL : GIVENS_KERNEL_LDS;
-    rc = backward_chunks<T>(dev, family, n, B, table, Y, G, dX, dtheta, stream);
+    Coefs<T> coefs;
+    if (int rc = prepare_coefs<T>(dev, n, theta, false,
+                                  family == GIVENS_KERNEL_CAROUSEL && g_form_choice == GIVENS_FORM_AUTO, stream,
+                                  &coefs))
+        return rc;
+    const int rc = backward_chunks<T>(dev, family, n, B, coefs, Y, G, dX, dtheta, stream);
     t_state.last_kernel = family;
     return rc;
 }
@@ -334,11 +411,14 @@ int givens_release(void)
     int rc = GIVENS_OK;
     for (int d = 0; d < kMaxDevices; ++d) {
         Workspace &ws = g_ws[d];
-        if (!ws.table && !ws.partial) continue;
+        bool any = false;
+        for (Buffer *b : ws.all) any = any || b->ptr;
+        if (!any) continue;
         if (!hip_ok(hipSetDevice(d))) { rc = GIVENS_ERR_HIP; continue; }
-        if (ws.table && !hip_ok(hipFree(ws.table))) rc = GIVENS_ERR_HIP;
-        if (ws.partial && !hip_ok(hipFree(ws.partial))) rc = GIVENS_ERR_HIP;
-        ws = Workspace{};
+        for (Buffer *b : ws.all) {
+            if (b->ptr && !hip_ok(hipFree(b->ptr))) rc = GIVENS_ERR_HIP;
+            *b = Buffer{};
+        }
     }
     (void)hipSetDevice(keep);
     return rc;
@@ -371,6 +451,30 @@ int givens_set_kernel(int which)
 }
 
 int givens_last_kernel(void) { return givens::t_state.last_kernel; }
+
+int givens_set_rotation_form(int which)
+{
+    if (which != GIVENS_FORM_AUTO && which != GIVENS_FORM_STANDARD) return GIVENS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(givens::g_mutex);
+    const int prev = givens::g_form_choice;
+    givens::g_form_choice = which;
+    return prev;
+}
+
+int givens_last_rotation_form(void)
+{
+    using namespace givens;
+    ThreadState &ts = t_state;
+    if (!ts.last_flag) return GIVENS_FORM_STANDARD;
+    unsigned bits = 0;
+    if (!hip_ok(hipMemcpyAsync(&bits, ts.last_flag, sizeof(bits), hipMemcpyDeviceToHost, ts.last_stream)))
+        return GIVENS_ERR_HIP;
+    if (!hip_ok(hipStreamSynchronize(ts.last_stream))) return GIVENS_ERR_HIP;
+    float max_abs;
+    static_assert(sizeof(max_abs) == sizeof(bits), "");
+    __builtin_memcpy(&max_abs, &bits, sizeof(bits));
+    return (max_abs <= kScaledMaxAbsTheta) ? GIVENS_FORM_SCALED : GIVENS_FORM_STANDARD;
+}
 
 int givens_set_timing(int on)
 {

@@ -4,20 +4,13 @@
 // Inside a block each thread owns whole pairs (arcs) and walks the strip's columns, so the
 // per-pair gradient sum of the reverse sweep needs no cross-thread reduction.
 //
-// The table holds, per (block k, arc p), cos(theta) and the sine with the orientation folded in:
-// the strip is addressed by the labels at positions p ("top") and n-1-p ("bottom") of the
-// circle-method sequence, and sin is negated when the top label is the larger one, so that
-//     top' = c*top - s*bot,   bot' = s*top + c*bot
-// is Algorithm 2's update (r_i = c U_i - s U_j, r_j = s U_i + c U_j with i < j) either way.
+// cos/sin come from the standard-form table of coef_kernels.hpp (orientation folded into the sine).
 #pragma once
 #include <hip/hip_runtime.h>
+#include "coef_kernels.hpp"
 #include "rr_index.h"
 
 namespace givens {
-
-template <typename T> struct Pair2;
-template <> struct Pair2<float> { using type = float2; };
-template <> struct Pair2<double> { using type = double2; };
 
 constexpr int kLdsThreads = 256;
 
@@ -108,7 +101,7 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
                 ga[c] = cs.x * ua + cs.y * ub;
                 gbb[c] = cs.x * ub - cs.y * ua;
             }
-            // orientation sign (top holds the larger label <=> negate) is applied by the reduction
+            // the orientation sign is applied by the second-stage reduction (factor array)
             mine[(long long)k * H + p] = sum;
         }
         __syncthreads();
@@ -120,54 +113,6 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
             if (c < wv) dX[(long long)r * B + b0 + c] = gb[r * ldw + c];
         }
     }
-}
-
-// Second stage of the gradient reduction: dtheta[e] (+)= sign(e) * sum over strips s of
-// partial[s][e], in strip order (fixed order: reproducible).  The sweeps store
-// sum_b (gbar_bot z_top - gbar_top z_bot); with i < j the paper's term is gbar_j z_i - gbar_i z_j,
-// so the sum is negated for the pairs whose top position holds the larger label.
-template <typename T>
-__global__ void reduce_partials_kernel(int n, long long nstrips, const T *__restrict__ partial,
-                                       T *dtheta, int accumulate)
-{
-    const int H = n >> 1;
-    const long long N = (long long)(n - 1) * H;
-    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= N) return;
-    T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
-    long long s = 0;
-    for (; s + 4 <= nstrips; s += 4) {          // four loads in flight; the order of additions is fixed
-        a0 += partial[s * N + e];
-        a1 += partial[(s + 1) * N + e];
-        a2 += partial[(s + 2) * N + e];
-        a3 += partial[(s + 3) * N + e];
-    }
-    for (; s < nstrips; ++s) a0 += partial[s * N + e];
-    T acc = (a0 + a1) + (a2 + a3);
-    const int k = (int)(e / H), p = (int)(e % H);
-    if (rr_label(n, k, p) > rr_label(n, k, n - 1 - p)) acc = -acc;
-    dtheta[e] = accumulate ? dtheta[e] + acc : acc;
-}
-
-// cos/sin table in E order, evaluated in double whatever T is, with the orientation sign folded
-// into the sine (see the header comment).
-template <typename T>
-__global__ void coef_table_kernel(int n, const T *__restrict__ theta,
-                                  typename Pair2<T>::type *__restrict__ table)
-{
-    const int H = n >> 1;
-    const long long N = (long long)(n - 1) * H;
-    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= N) return;
-    const int k = (int)(e / H), p = (int)(e % H);
-    const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-    double s, c;
-    sincos((double)theta[e], &s, &c);
-    if (a > b) s = -s;
-    typename Pair2<T>::type out;
-    out.x = (T)c;
-    out.y = (T)s;
-    table[e] = out;
 }
 
 } // namespace givens

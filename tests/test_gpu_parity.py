@@ -128,6 +128,38 @@ def test_carousel_family_ragged_batches(n, B, seed):
     assert binding.last_kernel() == binding.KERNEL_CAROUSEL      # the reverse sweep too
 
 
+# ---------------------------------------------------------------- scaled rotation form (near-identity angles)
+@pytest.mark.parametrize("n,B,seed", [(256, 64, 51), (512, 100, 52), (1024, 67, 53), (2048, 130, 54)])
+def test_scaled_form_is_used_for_small_angles_and_matches_the_oracle(n, B, seed):
+    data = inputs.make_custom(n, B, seed=seed, theta_dist="normal0.1")
+    assert float(np.abs(data["theta"]).max()) < 0.78
+    binding.set_rotation_form(binding.FORM_AUTO)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G,
+                           binding.KERNEL_CAROUSEL)
+    assert binding.last_rotation_form() == binding.FORM_SCALED
+    try:
+        binding.set_rotation_form(binding.FORM_STANDARD)
+        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G)
+        assert binding.last_rotation_form() == binding.FORM_STANDARD
+    finally:
+        binding.set_rotation_form(binding.FORM_AUTO)
+
+
+def test_rotation_form_switches_at_the_angle_threshold():
+    n, B = 512, 48
+    data = inputs.make_custom(n, B, seed=61)
+    theta = (data["theta"] * np.float32(0.245)).astype(np.float32)     # uniform in about +-0.77
+    assert float(np.abs(theta).max()) <= 0.78
+    check_forward_backward(theta, data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G)
+    assert binding.last_rotation_form() == binding.FORM_SCALED
+    theta[777] = np.float32(-0.80)                                     # one angle beyond pi/4
+    check_forward_backward(theta, data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G)
+    assert binding.last_rotation_form() == binding.FORM_STANDARD
+    theta[777] = np.float32("nan")                                     # NaN must not select the scaled form
+    binding.givens_forward(dev(theta), dev(data["X"]))
+    assert binding.last_rotation_form() == binding.FORM_STANDARD
+
+
 def test_carousel_rejects_shapes_it_does_not_cover():
     data = inputs.make_custom(34, 8, seed=1)
     binding.set_kernel(binding.KERNEL_CAROUSEL)
