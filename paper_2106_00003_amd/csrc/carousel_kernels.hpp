@@ -15,9 +15,9 @@
 // Mapping.  A workgroup of L = 64*WAVES lanes owns W columns of the operand for all n-1 blocks
 // (one HBM read, one HBM write).  Lane l holds slots p = l*M .. l*M+M-1 of both lines, W columns
 // each, in VGPRs: 2*M*W floats.  The carousel move only changes one slot per lane per line: the
-// slot that leaves goes to the neighbouring lane (DPP wave shift inside a wavefront, a few floats
-// through LDS between wavefronts), and the other M-1 slots are "moved" by renaming: the round loop
-// is unrolled M times so that the slot <-> register map is static in every copy of the body.
+// slot that leaves goes to the neighbouring lane through LDS, and the other M-1 slots are "moved"
+// by renaming: the round loop is unrolled M times so that the slot <-> register map is static in
+// every copy of the body.
 // cos/sin come from the table written by coef_table_kernel, M pairs per lane per block, reused
 // for the W columns the lane holds and prefetched one block ahead.
 //
@@ -48,13 +48,57 @@ __device__ __forceinline__ float lane_from_prev(float incoming, float v)
                                                       0x138 /* wave_shr:1 */, 0xf, 0xf, false));
 }
 
-// Slots that cross a wavefront boundary in one carousel move, double-buffered by block parity.
+// The carousel move goes through LDS for every lane: each lane writes the slot that leaves its top
+// line and the slot that leaves its bottom line, and after the barrier reads its neighbours'.  This
+// costs LDS bandwidth (2*W floats written and read per lane per block), which is otherwise idle,
+// instead of VALU issue slots (DPP moves), which are the bottleneck, and it needs no special case at
+// wavefront boundaries.  One buffer per block parity, so one barrier per block is enough.
 template <int W, int WAVES>
 struct CarouselExchange {
-    float first_top[2][WAVES][W]; // lane 0's leaving top slot, per wavefront
-    float last_bot[2][WAVES][W];  // lane 63's leaving bottom slot, per wavefront
-    float near_turn[2][W];        // wavefront 0, lane 0: top[1], which turns round into bot[0]
+    struct alignas(16) Buf {
+        float top_out[64 * WAVES][W];     // per lane: the top slot that leaves (towards the previous lane)
+        float bot_out[64 * WAVES][W];     // per lane: the bottom slot that leaves (towards the next lane)
+        float near_turn[(W + 3) / 4 * 4]; // lane 0: top[1], which turns round into bot[0]
+    };
+    Buf buf[2];
 };
+
+// W consecutive floats to / from LDS with the widest accesses W allows
+template <int W>
+__device__ __forceinline__ void lds_store_row(float *dst, const float (&src)[W])
+{
+    if constexpr (W % 4 == 0) {
+#pragma unroll
+        for (int x = 0; x < W / 4; ++x)
+            reinterpret_cast<float4 *>(dst)[x] = make_float4(src[4 * x], src[4 * x + 1], src[4 * x + 2], src[4 * x + 3]);
+    } else if constexpr (W % 2 == 0) {
+#pragma unroll
+        for (int x = 0; x < W / 2; ++x) reinterpret_cast<float2 *>(dst)[x] = make_float2(src[2 * x], src[2 * x + 1]);
+    } else {
+#pragma unroll
+        for (int x = 0; x < W; ++x) dst[x] = src[x];
+    }
+}
+template <int W>
+__device__ __forceinline__ void lds_load_row(float (&dst)[W], const float *src)
+{
+    if constexpr (W % 4 == 0) {
+#pragma unroll
+        for (int x = 0; x < W / 4; ++x) {
+            const float4 v = reinterpret_cast<const float4 *>(src)[x];
+            dst[4 * x] = v.x; dst[4 * x + 1] = v.y; dst[4 * x + 2] = v.z; dst[4 * x + 3] = v.w;
+        }
+    } else if constexpr (W % 2 == 0) {
+#pragma unroll
+        for (int x = 0; x < W / 2; ++x) {
+            const float2 v = reinterpret_cast<const float2 *>(src)[x];
+            dst[2 * x] = v.x; dst[2 * x + 1] = v.y;
+        }
+    } else {
+#pragma unroll
+        for (int x = 0; x < W; ++x) dst[x] = src[x];
+    }
+}
 
 // FORM 0: standard rotation (2 MUL + 2 FMA per update, table holds cos and sin).
 // FORM 1: scaled rotation (2 FMA per update on values kept divided by their accumulated cosines,
@@ -72,7 +116,10 @@ struct CarouselFwd {
     int n, H, lane, wave, tid;
     const float2 *tab_lane; // table + tid*M
     const float2 *rn_lane;  // renormalisation factors + tid*M (scaled form)
-    CarouselExchange<W, WAVES> *sh;
+    // this lane's LDS addresses in exchange buffer 0 (buffer 1 is at a compile-time offset)
+    float *out_top, *out_bot, *turn;
+    const float *in_top, *in_bot;
+    static constexpr int kBufFloats = (int)(sizeof(typename CarouselExchange<W, WAVES>::Buf) / sizeof(float));
 
     __device__ __forceinline__ void load_coefs(int k, float2 (&dst)[M]) { load_row_of(tab_lane, k, dst); }
 
@@ -161,19 +208,10 @@ struct CarouselFwd {
         constexpr int q1 = (1 + U) % M;         // top slot 1 (matters in lane 0 of wavefront 0)
         constexpr int par = U & 1;
         if constexpr (!LAST) {
-            if (lane == 0) {
-#pragma unroll
-                for (int x = 0; x < W; ++x) sh->first_top[par][wave][x] = top[q][x];
-            }
-            if (lane == 63) {
-#pragma unroll
-                for (int x = 0; x < W; ++x) sh->last_bot[par][wave][x] = bot[qb][x];
-            }
+            lds_store_row<W>(out_top + par * kBufFloats, top[q]);
+            lds_store_row<W>(out_bot + par * kBufFloats, bot[qb]);
             if (wave == 0) {
-                if (lane == 0) {
-#pragma unroll
-                    for (int x = 0; x < W; ++x) sh->near_turn[par][x] = top[q1][x];
-                }
+                if (lane == 0) lds_store_row<W>(turn + par * kBufFloats, top[q1]);
                 // position 0 is held: in lane 0 its row hops to the register that will be slot 0
 #pragma unroll
                 for (int x = 0; x < W; ++x) {
@@ -187,13 +225,8 @@ struct CarouselFwd {
 
         if constexpr (!LAST) {
             __syncthreads();
-            const float *in_top = (wave == WAVES - 1) ? sh->last_bot[par][WAVES - 1] : sh->first_top[par][wave + 1];
-            const float *in_bot = (wave == 0) ? sh->near_turn[par] : sh->last_bot[par][wave - 1];
-#pragma unroll
-            for (int x = 0; x < W; ++x) {
-                top[q][x] = lane_from_next(in_top[x], top[q][x]);
-                bot[qb][x] = lane_from_prev(in_bot[x], bot[qb][x]);
-            }
+            lds_load_row<W>(top[q], in_top + par * kBufFloats);
+            lds_load_row<W>(bot[qb], in_bot + par * kBufFloats);
         }
     }
 
@@ -290,7 +323,16 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
     st.lane = threadIdx.x & 63;
     st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     st.tab_lane = table + (long long)threadIdx.x * M;
-    st.sh = &sh;
+    {
+        constexpr int L = 64 * WAVES;
+        auto &b = sh.buf[0];
+        const int t = threadIdx.x;
+        st.out_top = b.top_out[t];
+        st.out_bot = b.bot_out[t];
+        st.turn = b.near_turn;
+        st.in_top = (t < L - 1) ? b.top_out[t + 1] : b.bot_out[L - 1]; // far end: bot[n/2-1] turns into top[n/2-1]
+        st.in_bot = (t > 0) ? b.bot_out[t - 1] : b.near_turn;          // near end: top[1] turns into bot[0]
+    }
 
     const long long b0 = (long long)blockIdx.x * W;
     const int wv = (B - b0) < W ? (int)(B - b0) : W;
