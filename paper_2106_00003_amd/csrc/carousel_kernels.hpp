@@ -35,19 +35,6 @@
 
 namespace givens {
 
-// lane l receives the value of lane l+1; lane 63 (no source) keeps `incoming`
-__device__ __forceinline__ float lane_from_next(float incoming, float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(incoming), __float_as_int(v),
-                                                      0x130 /* wave_shl:1 */, 0xf, 0xf, false));
-}
-// lane l receives the value of lane l-1; lane 0 (no source) keeps `incoming`
-__device__ __forceinline__ float lane_from_prev(float incoming, float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(incoming), __float_as_int(v),
-                                                      0x138 /* wave_shr:1 */, 0xf, 0xf, false));
-}
-
 // The carousel move goes through LDS for every lane: each lane writes the slot that leaves its top
 // line and the slot that leaves its bottom line, and after the barrier reads its neighbours'.  This
 // costs LDS bandwidth (2*W floats written and read per lane per block), which is otherwise idle,
@@ -371,11 +358,19 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 // sign, which the second-stage reduction applies (top holds the larger label <=> negate) -- and
 // then the transposed rotation on both strips.
 // ---------------------------------------------------------------------------------------------
+// Exchange buffers of the reverse sweep: as in the forward kernel every lane's leaving slots go
+// through LDS, here for two strips (z and g); one buffer per block parity.
 template <int W, int WAVES>
 struct CarouselExchangeBwd {
-    // [parity][strip z/g][wavefront][column]
-    float top_in[2][2][WAVES][W]; // what lane 0 of each wavefront receives into its top line
-    float bot_in[2][2][WAVES][W]; // what lane 63 of each wavefront receives into its bottom line
+    struct alignas(16) Strip {
+        float top_out[64 * WAVES][W]; // per lane: the top slot that leaves (towards the next lane)
+        float bot_out[64 * WAVES][W]; // per lane: the bottom slot that leaves (towards the previous lane)
+        float hold[(W + 3) / 4 * 4];  // lane 0: the row at the held position 0
+    };
+    struct Buf {
+        Strip strip[2]; // z, g
+    };
+    Buf buf[2];
 };
 
 template <int M, int W, int WAVES, int FORM>
@@ -391,7 +386,12 @@ struct CarouselBwd {
     const float2 *tab_lane;  // table + tid*M
     const float2 *rn_lane;   // renormalisation factors + tid*M (scaled form)
     float *part_lane;        // this strip's partial sums + tid*M
-    CarouselExchangeBwd<W, WAVES> *sh;
+    // this lane's LDS addresses for strip z in exchange buffer 0 (strip g and buffer 1 are at
+    // compile-time offsets)
+    float *out_top, *out_bot, *hold;
+    const float *in_top, *in_bot;
+    static constexpr int kStripFloats = (int)(sizeof(typename CarouselExchangeBwd<W, WAVES>::Strip) / sizeof(float));
+    static constexpr int kBufFloats = (int)(sizeof(typename CarouselExchangeBwd<W, WAVES>::Buf) / sizeof(float));
 
     __device__ __forceinline__ void load_coefs(int k, float2 (&dst)[M]) { load_row_of(tab_lane, k, dst); }
 
@@ -419,21 +419,10 @@ struct CarouselBwd {
         constexpr int qt = (M - 1 - U + M) % M; // top slot M-1: leaves towards the next lane
         constexpr int qb = U % M;               // bottom slot 0: leaves towards the previous lane
         constexpr int pf = (M - U) % M;         // top slot 0 (the held position, in lane 0 of wavefront 0)
-        constexpr int par = U & 1;
-        if (lane == 63) {
-            float *dst = (wave < WAVES - 1) ? sh->top_in[par][WHICH][wave + 1] : sh->bot_in[par][WHICH][WAVES - 1];
-#pragma unroll
-            for (int x = 0; x < W; ++x) dst[x] = t[qt][x];
-        }
-        if (lane == 0) {
-            if (wave > 0) {
-#pragma unroll
-                for (int x = 0; x < W; ++x) sh->bot_in[par][WHICH][wave - 1][x] = b[qb][x];
-            } else {
-#pragma unroll
-                for (int x = 0; x < W; ++x) sh->top_in[par][WHICH][0][x] = t[pf][x];
-            }
-        }
+        constexpr int off = (U & 1) * kBufFloats + WHICH * kStripFloats;
+        lds_store_row<W>(out_top + off, t[qt]);
+        lds_store_row<W>(out_bot + off, b[qb]);
+        if (wave == 0 && lane == 0) lds_store_row<W>(hold + off, t[pf]);
     }
     template <int U, int WHICH>
     __device__ __forceinline__ void receive(float (&t)[M][W], float (&b)[M][W])
@@ -441,19 +430,17 @@ struct CarouselBwd {
         constexpr int qt = (M - 1 - U + M) % M;
         constexpr int qb = U % M;
         constexpr int pf = (M - U) % M;
-        constexpr int par = U & 1;
-        const float *in_top = sh->top_in[par][WHICH][wave];
-        const float *in_bot = sh->bot_in[par][WHICH][wave];
+        constexpr int off = (U & 1) * kBufFloats + WHICH * kStripFloats;
+        if (wave == 0) {
+            // lane 0: bot[0] turns round into top[1], i.e. into the register the held row leaves
 #pragma unroll
-        for (int x = 0; x < W; ++x) {
-            const float turn = b[qb][x]; // lane 0 of wavefront 0: bot[0] turns round into top[1]
-            t[qt][x] = lane_from_prev(in_top[x], t[qt][x]);
-            b[qb][x] = lane_from_next(in_bot[x], b[qb][x]);
-            if (wave == 0) {
-                const float keep = t[pf][x];
+            for (int x = 0; x < W; ++x) {
+                const float turn = b[qb][x], keep = t[pf][x];
                 t[pf][x] = (lane == 0) ? turn : keep;
             }
         }
+        lds_load_row<W>(t[qt], in_top + off);
+        lds_load_row<W>(b[qb], in_bot + off);
     }
 
     // Logical slot R of one block: the strip's share of the pair's gradient, then the transposed
@@ -592,7 +579,16 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     st.tab_lane = table + (long long)threadIdx.x * M;
     st.part_lane = partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) + (long long)threadIdx.x * M;
-    st.sh = &sh;
+    {
+        constexpr int L = 64 * WAVES;
+        auto &z = sh.buf[0].strip[0];
+        const int t = threadIdx.x;
+        st.out_top = z.top_out[t];
+        st.out_bot = z.bot_out[t];
+        st.hold = z.hold;
+        st.in_top = (t > 0) ? z.top_out[t - 1] : z.hold;              // near end: the held row stays in slot 0
+        st.in_bot = (t < L - 1) ? z.bot_out[t + 1] : z.top_out[L - 1]; // far end: top[n/2-1] turns into bot[n/2-1]
+    }
 
     const long long b0 = (strip0 + blockIdx.x) * W;
     const int wv = (B - b0) < W ? (int)(B - b0) : W;
