@@ -40,24 +40,38 @@ namespace givens {
 // costs LDS bandwidth (2*W floats written and read per lane per block), which is otherwise idle,
 // instead of VALU issue slots (DPP moves), which are the bottleneck, and it needs no special case at
 // wavefront boundaries.  One buffer per block parity, so one barrier per block is enough.
+//
+// Layout of one exchange line (L lanes plus one extra row for the element that turns round at the
+// near end): when W is a multiple of 4 a lane's W floats are split into 16-byte chunks and chunk c of
+// lane l sits at float offset (c*(L+1) + l)*4, so that a wavefront's ds_*_b128 touches consecutive
+// 16-byte words (no bank conflicts; a [lane][W] layout with W = 8 had two-way conflicts on every
+// access).  Otherwise the W floats of a lane are contiguous.
+template <int W, int WAVES>
+struct CarouselLine {
+    static constexpr int kLanes = 64 * WAVES;
+    static constexpr int kLaneStride = (W % 4 == 0) ? 4 : W;   // floats between neighbouring lanes
+    static constexpr int kChunkStride = (kLanes + 1) * 4;      // floats between a lane's chunks
+    alignas(16) float data[(kLanes + 1) * W];
+    __device__ __forceinline__ float *lane(int l) { return data + l * kLaneStride; }
+};
 template <int W, int WAVES>
 struct CarouselExchange {
-    struct alignas(16) Buf {
-        float top_out[64 * WAVES][W];     // per lane: the top slot that leaves (towards the previous lane)
-        float bot_out[64 * WAVES][W];     // per lane: the bottom slot that leaves (towards the next lane)
-        float near_turn[(W + 3) / 4 * 4]; // lane 0: top[1], which turns round into bot[0]
+    struct Buf {
+        CarouselLine<W, WAVES> top_out; // per lane: the top slot that leaves; extra row: the near-end turn
+        CarouselLine<W, WAVES> bot_out; // per lane: the bottom slot that leaves
     };
     Buf buf[2];
 };
 
-// W consecutive floats to / from LDS with the widest accesses W allows
-template <int W>
+// a lane's W floats to / from its place in an exchange line
+template <int W, int WAVES>
 __device__ __forceinline__ void lds_store_row(float *dst, const float (&src)[W])
 {
     if constexpr (W % 4 == 0) {
 #pragma unroll
-        for (int x = 0; x < W / 4; ++x)
-            reinterpret_cast<float4 *>(dst)[x] = make_float4(src[4 * x], src[4 * x + 1], src[4 * x + 2], src[4 * x + 3]);
+        for (int c = 0; c < W / 4; ++c)
+            *reinterpret_cast<float4 *>(dst + c * CarouselLine<W, WAVES>::kChunkStride) =
+                make_float4(src[4 * c], src[4 * c + 1], src[4 * c + 2], src[4 * c + 3]);
     } else if constexpr (W % 2 == 0) {
 #pragma unroll
         for (int x = 0; x < W / 2; ++x) reinterpret_cast<float2 *>(dst)[x] = make_float2(src[2 * x], src[2 * x + 1]);
@@ -66,14 +80,14 @@ __device__ __forceinline__ void lds_store_row(float *dst, const float (&src)[W])
         for (int x = 0; x < W; ++x) dst[x] = src[x];
     }
 }
-template <int W>
+template <int W, int WAVES>
 __device__ __forceinline__ void lds_load_row(float (&dst)[W], const float *src)
 {
     if constexpr (W % 4 == 0) {
 #pragma unroll
-        for (int x = 0; x < W / 4; ++x) {
-            const float4 v = reinterpret_cast<const float4 *>(src)[x];
-            dst[4 * x] = v.x; dst[4 * x + 1] = v.y; dst[4 * x + 2] = v.z; dst[4 * x + 3] = v.w;
+        for (int c = 0; c < W / 4; ++c) {
+            const float4 v = *reinterpret_cast<const float4 *>(src + c * CarouselLine<W, WAVES>::kChunkStride);
+            dst[4 * c] = v.x; dst[4 * c + 1] = v.y; dst[4 * c + 2] = v.z; dst[4 * c + 3] = v.w;
         }
     } else if constexpr (W % 2 == 0) {
 #pragma unroll
@@ -195,10 +209,10 @@ struct CarouselFwd {
         constexpr int q1 = (1 + U) % M;         // top slot 1 (matters in lane 0 of wavefront 0)
         constexpr int par = U & 1;
         if constexpr (!LAST) {
-            lds_store_row<W>(out_top + par * kBufFloats, top[q]);
-            lds_store_row<W>(out_bot + par * kBufFloats, bot[qb]);
+            lds_store_row<W, WAVES>(out_top + par * kBufFloats, top[q]);
+            lds_store_row<W, WAVES>(out_bot + par * kBufFloats, bot[qb]);
             if (wave == 0) {
-                if (lane == 0) lds_store_row<W>(turn + par * kBufFloats, top[q1]);
+                if (lane == 0) lds_store_row<W, WAVES>(turn + par * kBufFloats, top[q1]);
                 // position 0 is held: in lane 0 its row hops to the register that will be slot 0
 #pragma unroll
                 for (int x = 0; x < W; ++x) {
@@ -212,8 +226,8 @@ struct CarouselFwd {
 
         if constexpr (!LAST) {
             __syncthreads();
-            lds_load_row<W>(top[q], in_top + par * kBufFloats);
-            lds_load_row<W>(bot[qb], in_bot + par * kBufFloats);
+            lds_load_row<W, WAVES>(top[q], in_top + par * kBufFloats);
+            lds_load_row<W, WAVES>(bot[qb], in_bot + par * kBufFloats);
         }
     }
 
@@ -314,11 +328,11 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
         constexpr int L = 64 * WAVES;
         auto &b = sh.buf[0];
         const int t = threadIdx.x;
-        st.out_top = b.top_out[t];
-        st.out_bot = b.bot_out[t];
-        st.turn = b.near_turn;
-        st.in_top = (t < L - 1) ? b.top_out[t + 1] : b.bot_out[L - 1]; // far end: bot[n/2-1] turns into top[n/2-1]
-        st.in_bot = (t > 0) ? b.bot_out[t - 1] : b.near_turn;          // near end: top[1] turns into bot[0]
+        st.out_top = b.top_out.lane(t);
+        st.out_bot = b.bot_out.lane(t);
+        st.turn = b.top_out.lane(L);                                              // the extra row
+        st.in_top = (t < L - 1) ? b.top_out.lane(t + 1) : b.bot_out.lane(L - 1); // far end: bot[n/2-1] -> top[n/2-1]
+        st.in_bot = (t > 0) ? b.bot_out.lane(t - 1) : b.top_out.lane(L);         // near end: top[1] -> bot[0]
     }
 
     const long long b0 = (long long)blockIdx.x * W;
@@ -362,10 +376,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 // through LDS, here for two strips (z and g); one buffer per block parity.
 template <int W, int WAVES>
 struct CarouselExchangeBwd {
-    struct alignas(16) Strip {
-        float top_out[64 * WAVES][W]; // per lane: the top slot that leaves (towards the next lane)
-        float bot_out[64 * WAVES][W]; // per lane: the bottom slot that leaves (towards the previous lane)
-        float hold[(W + 3) / 4 * 4];  // lane 0: the row at the held position 0
+    struct Strip {
+        CarouselLine<W, WAVES> top_out; // per lane: the top slot that leaves; extra row: the held position's row
+        CarouselLine<W, WAVES> bot_out; // per lane: the bottom slot that leaves
     };
     struct Buf {
         Strip strip[2]; // z, g
@@ -420,9 +433,9 @@ struct CarouselBwd {
         constexpr int qb = U % M;               // bottom slot 0: leaves towards the previous lane
         constexpr int pf = (M - U) % M;         // top slot 0 (the held position, in lane 0 of wavefront 0)
         constexpr int off = (U & 1) * kBufFloats + WHICH * kStripFloats;
-        lds_store_row<W>(out_top + off, t[qt]);
-        lds_store_row<W>(out_bot + off, b[qb]);
-        if (wave == 0 && lane == 0) lds_store_row<W>(hold + off, t[pf]);
+        lds_store_row<W, WAVES>(out_top + off, t[qt]);
+        lds_store_row<W, WAVES>(out_bot + off, b[qb]);
+        if (wave == 0 && lane == 0) lds_store_row<W, WAVES>(hold + off, t[pf]);
     }
     template <int U, int WHICH>
     __device__ __forceinline__ void receive(float (&t)[M][W], float (&b)[M][W])
@@ -439,8 +452,8 @@ struct CarouselBwd {
                 t[pf][x] = (lane == 0) ? turn : keep;
             }
         }
-        lds_load_row<W>(t[qt], in_top + off);
-        lds_load_row<W>(b[qb], in_bot + off);
+        lds_load_row<W, WAVES>(t[qt], in_top + off);
+        lds_load_row<W, WAVES>(b[qb], in_bot + off);
     }
 
     // Logical slot R of one block: the strip's share of the pair's gradient, then the transposed
@@ -583,11 +596,11 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
         constexpr int L = 64 * WAVES;
         auto &z = sh.buf[0].strip[0];
         const int t = threadIdx.x;
-        st.out_top = z.top_out[t];
-        st.out_bot = z.bot_out[t];
-        st.hold = z.hold;
-        st.in_top = (t > 0) ? z.top_out[t - 1] : z.hold;              // near end: the held row stays in slot 0
-        st.in_bot = (t < L - 1) ? z.bot_out[t + 1] : z.top_out[L - 1]; // far end: top[n/2-1] turns into bot[n/2-1]
+        st.out_top = z.top_out.lane(t);
+        st.out_bot = z.bot_out.lane(t);
+        st.hold = z.top_out.lane(L);                                              // the extra row
+        st.in_top = (t > 0) ? z.top_out.lane(t - 1) : z.top_out.lane(L);         // near end: the held row stays in slot 0
+        st.in_bot = (t < L - 1) ? z.bot_out.lane(t + 1) : z.top_out.lane(L - 1); // far end: top[n/2-1] -> bot[n/2-1]
     }
 
     const long long b0 = (strip0 + blockIdx.x) * W;
