@@ -175,12 +175,12 @@ struct CarouselFwd {
     {
         (rotate_slot<U, Rs, RN>(cur, rn), ...);
     }
-    // slots 2 .. M-2, the ones that take no part in the exchange
-    template <int U, bool RN, int... Rs>
+    // a run of inner slots (2 .. M-2 take no part in the exchange), starting at slot FIRST
+    template <int U, bool RN, int FIRST, int... Rs>
     __device__ __forceinline__ void rotate_inner(const float2 (&cur)[M], const float2 (&rn)[M],
                                                  std::integer_sequence<int, Rs...>)
     {
-        (rotate_slot<U, Rs + 2, RN>(cur, rn), ...);
+        (rotate_slot<U, FIRST + Rs, RN>(cur, rn), ...);
     }
 
     // One block of Algorithm 2 with the slot <-> register map of unrolled copy U, then the move.
@@ -189,8 +189,9 @@ struct CarouselFwd {
     // by their factors (compile-time variant: a run-time branch around 2*M*W multiplies made the
     // register allocator spill).
     // Order inside the block: the slots whose results leave the lane (0, M-1 and, for the held
-    // position, 1) are rotated first and published to LDS; the other slots are rotated while those
-    // writes and the other wavefronts' arrival at the barrier are in flight.
+    // position, 1) need what the previous block's exchange delivers and feed this block's exchange;
+    // the other slots are rotated around them, so that both LDS latencies and the barrier overlap
+    // with arithmetic.
     template <int U, bool LAST, bool RENORM>
     __device__ __forceinline__ void step(int k)
     {
@@ -199,6 +200,12 @@ struct CarouselFwd {
         if constexpr (!LAST) load_coefs(k - 1, cs[(U + 1) & 1]);
         float2 rn[M];
         if constexpr (RN) load_row_of(rn_lane, (n - 2 - k) / kRenormPeriod, rn);
+
+        // inner slots 2 .. M-2 are split in two runs: the first covers the latency of the LDS reads
+        // issued at the end of the previous block, the second the LDS writes and the barrier
+        constexpr int kInner = M > 3 ? M - 3 : 0;
+        constexpr int kInnerA = kInner / 2;
+        if constexpr (kInnerA > 0) rotate_inner<U, RN, 2>(cur, rn, std::make_integer_sequence<int, kInnerA>{});
 
         rotate_slot<U, 0, RN>(cur, rn);
         if constexpr (M > 1) rotate_slot<U, M - 1, RN>(cur, rn);
@@ -222,7 +229,8 @@ struct CarouselFwd {
             }
         }
 
-        if constexpr (M > 3) rotate_inner<U, RN>(cur, rn, std::make_integer_sequence<int, M - 3>{});
+        if constexpr (kInner - kInnerA > 0)
+            rotate_inner<U, RN, 2 + kInnerA>(cur, rn, std::make_integer_sequence<int, kInner - kInnerA>{});
 
         if constexpr (!LAST) {
             __syncthreads();
@@ -493,12 +501,12 @@ struct CarouselBwd {
             asm volatile("" : "+v"(zt[it][x]), "+v"(zb[ib][x]), "+v"(gt[it][x]), "+v"(gb[ib][x]));
         return acc;
     }
-    // slots 1 .. M-2, the ones that take no part in the exchange
-    template <int U, bool RN, int... Rs>
+    // a run of inner slots (1 .. M-2 take no part in the exchange), starting at slot FIRST
+    template <int U, bool RN, int FIRST, int... Rs>
     __device__ __forceinline__ void sweep_inner(const float2 (&cur)[M], const float2 (&rn)[M], float (&sums)[M],
                                                 std::integer_sequence<int, Rs...>)
     {
-        ((sums[Rs + 1] = sweep_slot<U, Rs + 1, RN>(cur, rn)), ...);
+        ((sums[FIRST + Rs] = sweep_slot<U, FIRST + Rs, RN>(cur, rn)), ...);
     }
 
     // One block of the reverse sweep.  The slots whose rows leave the lane (0 and M-1) go first and
@@ -513,13 +521,19 @@ struct CarouselBwd {
         if constexpr (RN) load_row_of(rn_lane, k / kRenormPeriod, rn);
 
         float sums[M];
+        // the inner slots all run after the exchange slots here: splitting them around the exchange as
+        // the forward kernel does costs registers this kernel does not have (it spills and gets slower)
+        constexpr int kInner = M > 2 ? M - 2 : 0;
+        constexpr int kInnerA = 0;
+        if constexpr (kInnerA > 0) sweep_inner<U, RN, 1>(cur, rn, sums, std::make_integer_sequence<int, kInnerA>{});
         sums[0] = sweep_slot<U, 0, RN>(cur, rn);
         if constexpr (M > 1) sums[M - 1] = sweep_slot<U, M - 1, RN>(cur, rn);
         if constexpr (!LAST) {
             publish<U, 0>(zt, zb);
             publish<U, 1>(gt, gb);
         }
-        if constexpr (M > 2) sweep_inner<U, RN>(cur, rn, sums, std::make_integer_sequence<int, M - 2>{});
+        if constexpr (kInner - kInnerA > 0)
+            sweep_inner<U, RN, 1 + kInnerA>(cur, rn, sums, std::make_integer_sequence<int, kInner - kInnerA>{});
         {
             float *dst = part_lane + (long long)k * H;
             if constexpr (M % 4 == 0) {
