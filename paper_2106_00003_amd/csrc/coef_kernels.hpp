@@ -25,6 +25,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
+
 #include "rr_index.h"
 
 namespace givens {
@@ -46,12 +48,25 @@ __device__ __forceinline__ bool form_selected(const unsigned *flag, bool want_sc
 
 __global__ void reset_flag_kernel(unsigned *flag) { *flag = 0u; }
 
-// flag <- bit pattern of max |theta| (non-negative floats order like unsigned integers; NaN sorts last)
+// flag <- bit pattern of max |theta| (non-negative floats order like unsigned integers; NaN sorts last).
+// theta is read as float4 where alignment allows; N is tiny next to the sweeps but this kernel sits
+// in front of every call, so it should run at memory speed.
 __global__ void theta_range_kernel(long long N, const float *__restrict__ theta, unsigned *flag)
 {
     unsigned m = 0u;
-    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < N;
-         e += (long long)gridDim.x * blockDim.x) {
+    const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long nthreads = (long long)gridDim.x * blockDim.x;
+    const bool aligned = (reinterpret_cast<uintptr_t>(theta) & 15u) == 0;
+    const long long n4 = aligned ? N / 4 : 0;
+    const uint4 *t4 = reinterpret_cast<const uint4 *>(theta);
+    for (long long i = tid; i < n4; i += nthreads) {
+        const uint4 v = t4[i];
+        const unsigned a = v.x & 0x7fffffffu, b = v.y & 0x7fffffffu, c = v.z & 0x7fffffffu, d = v.w & 0x7fffffffu;
+        const unsigned ab = a > b ? a : b, cd = c > d ? c : d;
+        const unsigned q = ab > cd ? ab : cd;
+        m = q > m ? q : m;
+    }
+    for (long long e = n4 * 4 + tid; e < N; e += nthreads) {
         const unsigned bits = __float_as_uint(theta[e]) & 0x7fffffffu;
         m = bits > m ? bits : m;
     }
@@ -59,7 +74,46 @@ __global__ void theta_range_kernel(long long N, const float *__restrict__ theta,
         const unsigned other = (unsigned)__shfl_xor((int)m, off, 64);
         m = other > m ? other : m;
     }
-    if ((threadIdx.x & 63) == 0) atomicMax(flag, m);
+    // Atomics on one word serialise (some 10 ns each: thousands of them cost more than reading theta),
+    // so the wavefronts of a workgroup combine through LDS first and send one atomic per workgroup.
+    __shared__ unsigned wave_max[16];
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) wave_max[wave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int waves = (blockDim.x + 63) >> 6;
+        for (int w = 1; w < waves; ++w) m = wave_max[w] > m ? wave_max[w] : m;
+        atomicMax(flag, m);
+    }
+}
+
+// sin and cos in float64 for |x| <= pi/4 (the only arguments the scaled form ever sees): plain
+// Taylor polynomials, no range reduction.  Truncation error below 1e-17 relative on that interval.
+__device__ __forceinline__ double cos_small(double x)
+{
+    const double z = x * x;
+    double p = 1.0 / 20922789888000.0;                 // 1/16!
+    p = fma(p, z, -1.0 / 87178291200.0);               // 1/14!
+    p = fma(p, z, 1.0 / 479001600.0);                  // 1/12!
+    p = fma(p, z, -1.0 / 3628800.0);                   // 1/10!
+    p = fma(p, z, 1.0 / 40320.0);                      // 1/8!
+    p = fma(p, z, -1.0 / 720.0);                       // 1/6!
+    p = fma(p, z, 1.0 / 24.0);                         // 1/4!
+    p = fma(p, z, -0.5);
+    return fma(p, z, 1.0);
+}
+__device__ __forceinline__ double sin_small(double x)
+{
+    const double z = x * x;
+    double p = 1.0 / 355687428096000.0;                // 1/17!
+    p = fma(p, z, -1.0 / 1307674368000.0);             // 1/15!
+    p = fma(p, z, 1.0 / 6227020800.0);                 // 1/13!
+    p = fma(p, z, -1.0 / 39916800.0);                  // 1/11!
+    p = fma(p, z, 1.0 / 362880.0);                     // 1/9!
+    p = fma(p, z, -1.0 / 5040.0);                      // 1/7!
+    p = fma(p, z, 1.0 / 120.0);                        // 1/5!
+    p = fma(p, z, -1.0 / 6.0);
+    return fma(p * z, x, x);
 }
 
 // Standard form table, in E order.  `factor` (optional) receives the orientation sign (+1 when the
@@ -71,24 +125,25 @@ __global__ void coef_table_kernel(int n, const T *__restrict__ theta, const unsi
     if (!form_selected(flag, false)) return;
     const int H = n >> 1;
     const long long N = (long long)(n - 1) * H;
-    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= N) return;
-    const int k = (int)(e / H), p = (int)(e % H);
-    const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-    double s, c;
-    sincos((double)theta[e], &s, &c);
-    if (a > b) s = -s;
-    typename Pair2<T>::type out;
-    out.x = (T)c;
-    out.y = (T)s;
-    table[e] = out;
-    if (factor) factor[e] = (a < b) ? T(1) : T(-1);
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < N;
+         e += (long long)gridDim.x * blockDim.x) {
+        const int k = (int)(e / H), p = (int)(e % H);
+        const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+        double s, c;
+        sincos((double)theta[e], &s, &c);
+        if (a > b) s = -s;
+        typename Pair2<T>::type out;
+        out.x = (T)c;
+        out.y = (T)s;
+        table[e] = out;
+        if (factor) factor[e] = (a < b) ? T(1) : T(-1);
+    }
 }
 
 // Scaled form, step 1.  One thread per (renormalisation period g, row r): walks the row through the
 // period's blocks in sweep order (FWD: k = n-2, n-3, ...; reverse sweep: k = 0, 1, ...), records the
 // row's factor d *before* each block at D[k][position], and leaves the factor after the period's last
-// block in renorm[g][slot] (.x for the top position of the slot, .y for the bottom one).
+// block in renorm[g][arc] (.x for the arc's top position, .y for its bottom position).
 template <bool FWD>
 __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const unsigned *flag,
                                    double *__restrict__ D, float *__restrict__ renorm)
@@ -108,7 +163,7 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
         q = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1); // position of label r in the sequence of block k
         p = (q < H) ? q : n - 1 - q;
         D[(long long)k * n + q] = d;
-        d *= cos((double)theta[(long long)k * H + p]);
+        d *= cos_small((double)theta[(long long)k * H + p]);
     }
     renorm[2 * ((long long)g * H + p) + (q < H ? 0 : 1)] = (float)d;
 }
@@ -130,12 +185,13 @@ __global__ void scaled_table_kernel(int n, const float *__restrict__ theta, cons
     if (e >= N) return;
     const int k = (int)(e / H), p = (int)(e % H);
     const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-    double s, c;
-    sincos((double)theta[e], &s, &c);
+    const double th = (double)theta[e];
+    double s = sin_small(th);
+    const double c = cos_small(th);
     if (a > b) s = -s;
-    const double tn = s / c;
-    const double da = D[(long long)k * n + p], db = D[(long long)k * n + (n - 1 - p)];
-    table[e] = make_float2((float)(tn * db / da), (float)(tn * da / db));
+    const double da = D[(long long)k * n + p], db = D[(long long)k * n + (n - 1 - p)]; // before this block
+    const double inv = s / (c * da * db);                // tan(theta) / (d_top d_bot)
+    table[e] = make_float2((float)(inv * db * db), (float)(inv * da * da));
     if (!FWD && factor) factor[e] = (float)((a < b ? 1.0 : -1.0) * da * db);
 }
 

@@ -181,7 +181,7 @@ int prepare_coefs(int dev, int n, const T *theta, bool forward, bool try_scaled,
             double *D = reinterpret_cast<double *>(ws.scale.ptr);
             float *rn = reinterpret_cast<float *>(ws.renorm.ptr);
             hipLaunchKernelGGL(reset_flag_kernel, dim3(1), dim3(1), 0, stream, flag);
-            hipLaunchKernelGGL(theta_range_kernel, dim3(1024), dim3(256), 0, stream, N, theta, flag);
+            hipLaunchKernelGGL(theta_range_kernel, dim3(512), dim3(512), 0, stream, N, theta, flag);
             const long long scan_threads = (long long)periods * n;
             const unsigned scan_blocks = (unsigned)((scan_threads + threads - 1) / threads);
             if (forward) {
@@ -200,7 +200,7 @@ int prepare_coefs(int dev, int n, const T *theta, bool forward, bool try_scaled,
         }
         out->standard = CarouselCoefs{0, table, nullptr, flag};
     }
-    hipLaunchKernelGGL(coef_table_kernel<T>, dim3(blocks), dim3(threads), 0, stream, n, theta,
+    hipLaunchKernelGGL(coef_table_kernel<T>, dim3(std::min(blocks, 4096u)), dim3(threads), 0, stream, n, theta,
                        static_cast<const unsigned *>(flag), table, factor);
     GIVENS_HIP(hipGetLastError());
     out->table = table;
