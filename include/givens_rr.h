@@ -54,6 +54,12 @@ extern "C" {
 #define GIVENS_FORM_STANDARD 1 /* r_i = c U_i - s U_j, r_j = s U_i + c U_j exactly as in Algorithm 1         */
 #define GIVENS_FORM_SCALED 2   /* same rotations on rows kept divided by their accumulated cosines (2 FMAs)  */
 
+/* How givens_backward sums the per-strip shares of dtheta (givens_set_reduction). */
+#define GIVENS_REDUCTION_AUTO 0      /* the library's default for the kernel family in use                     */
+#define GIVENS_REDUCTION_TWO_STAGE 1 /* one partial sum per (strip, angle), then a fixed-order pass: reproducible */
+#define GIVENS_REDUCTION_ATOMIC 2    /* strips add into one buffer with float atomics (carousel kernels only);  */
+                                     /* order of additions, hence the last bits of dtheta, varies run to run   */
+
 /*
  * rr_schedule -- the round-robin sequence by the circle method (Section 3; the worked n = 6
  * example is Eq. (3), the dimension sequences are the left column of Figure 1).
@@ -128,6 +134,15 @@ int givens_last_kernel(void);
  */
 int givens_set_rotation_form(int which);
 int givens_last_rotation_form(void);
+
+/*
+ * Selects how the reverse sweep reduces over strips (process-wide); returns the previous setting.
+ * TWO_STAGE needs 4*N bytes of workspace per strip (17 GB at n = B = 4096) but gives bit-identical
+ * dtheta from run to run; ATOMIC needs 4*N bytes in all.  The LDS family and the f64 entry points
+ * always use TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
+ */
+int givens_set_reduction(int which);
+int givens_last_reduction(void);
 
 /*
  * Per-kernel timing.  givens_set_timing(1) makes every subsequent call record HIP events on the

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libgivens_rr.so")
 
 KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL = 0, 1, 2
 FORM_AUTO, FORM_STANDARD, FORM_SCALED = 0, 1, 2
+REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_ATOMIC = 0, 1, 2
 
 EXPORTS = [
     "rr_schedule", "givens_forward", "givens_build", "givens_backward",
@@ -23,6 +24,7 @@ EXPORTS = [
     "givens_release", "givens_last_hip_error", "givens_error_string",
     "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
     "givens_set_rotation_form", "givens_last_rotation_form",
+    "givens_set_reduction", "givens_last_reduction",
 ]
 
 _lib = None
@@ -59,6 +61,7 @@ def lib():
     L.givens_error_string.restype = ctypes.c_char_p
     L.givens_set_kernel.argtypes = [i32]
     L.givens_set_rotation_form.argtypes = [i32]
+    L.givens_set_reduction.argtypes = [i32]
     L.givens_set_timing.argtypes = [i32]
     L.givens_last_timing.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for name in EXPORTS:
@@ -175,6 +178,17 @@ def last_rotation_form() -> int:
     if rc < 0:
         raise GivensError(rc, "givens_last_rotation_form")
     return rc
+
+
+def set_reduction(which: int) -> int:
+    rc = lib().givens_set_reduction(which)
+    if rc < 0:
+        raise GivensError(rc, "givens_set_reduction")
+    return rc
+
+
+def last_reduction() -> int:
+    return lib().givens_last_reduction()
 
 
 def set_timing(on: bool) -> int:

@@ -406,7 +406,11 @@ struct CarouselBwd {
     int n, H, lane, wave, tid;
     const float2 *tab_lane;  // table + tid*M
     const float2 *rn_lane;   // renormalisation factors + tid*M (scaled form)
-    float *part_lane;        // this strip's partial sums + tid*M
+    float *part_lane;        // where this lane's sums go (see `accumulate`)
+    int accumulate;          // 0: part_lane = this strip's partial sums + tid*M, plain stores
+                             // 1: part_lane = shared accumulation buffer + tid, atomic adds; the buffer
+                             //    is slot-major within a block, [k][r][lane], so that one atomic
+                             //    instruction of a wavefront covers 64 consecutive floats
     // this lane's LDS addresses for strip z in exchange buffer 0 (strip g and buffer 1 are at
     // compile-time offsets)
     float *out_top, *out_bot, *hold;
@@ -495,10 +499,14 @@ struct CarouselBwd {
                 gt[it][x] *= rn[R].x;
                 gb[ib][x] *= rn[R].y;
             }
-        }
+            // pin every four columns (or at the end): a whole slot in flight at once costs more
+            // registers than this kernel has
+            if ((x & 3) == 3 || x == W - 1) {
 #pragma unroll
-        for (int x = 0; x < W; ++x)
-            asm volatile("" : "+v"(zt[it][x]), "+v"(zb[ib][x]), "+v"(gt[it][x]), "+v"(gb[ib][x]));
+                for (int y = x & ~3; y <= x; ++y)
+                    asm volatile("" : "+v"(zt[it][y]), "+v"(zb[ib][y]), "+v"(gt[it][y]), "+v"(gb[ib][y]), "+v"(acc));
+            }
+        }
         return acc;
     }
     // a run of inner slots (1 .. M-2 take no part in the exchange), starting at slot FIRST
@@ -534,7 +542,11 @@ struct CarouselBwd {
         }
         if constexpr (kInner - kInnerA > 0)
             sweep_inner<U, RN, 1 + kInnerA>(cur, rn, sums, std::make_integer_sequence<int, kInner - kInnerA>{});
-        {
+        if (accumulate) {
+            float *dst = part_lane + (long long)k * H;   // H = M * lanes
+#pragma unroll
+            for (int r = 0; r < M; ++r) unsafeAtomicAdd(dst + r * kLanes, sums[r]);
+        } else {
             float *dst = part_lane + (long long)k * H;
             if constexpr (M % 4 == 0) {
 #pragma unroll
@@ -592,7 +604,8 @@ struct CarouselBwd {
 template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     int n, long long B, long long strip0, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
-    const unsigned *flag, const float *Yin, const float *G, float *dX, float *__restrict__ partial, int vec_ok)
+    const unsigned *flag, const float *Yin, const float *G, float *dX, float *__restrict__ partial, int vec_ok,
+    int accumulate)
 {
     if (!form_selected(flag, FORM == 1)) return;
     using State = CarouselBwd<M, W, WAVES, FORM>;
@@ -605,7 +618,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     st.lane = threadIdx.x & 63;
     st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     st.tab_lane = table + (long long)threadIdx.x * M;
-    st.part_lane = partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) + (long long)threadIdx.x * M;
+    st.accumulate = accumulate;
+    st.part_lane = accumulate ? partial + threadIdx.x
+                              : partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) +
+                                    (long long)threadIdx.x * M;
     {
         constexpr int L = 64 * WAVES;
         auto &z = sh.buf[0].strip[0];
@@ -774,7 +790,7 @@ struct CarouselBwdArgs {
     CarouselCoefs coefs;
     const float *Y, *G;
     float *dX, *partial;
-    int vec_ok;
+    int vec_ok, accumulate;
     hipStream_t stream;
 };
 
@@ -783,7 +799,7 @@ inline void carousel_launch_bwd(const CarouselBwdArgs &a)
 {
     hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.nstrips), dim3(64 * WAVES),
                        0, a.stream, a.n, a.B, a.strip0, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.Y, a.G,
-                       a.dX, a.partial, a.vec_ok);
+                       a.dX, a.partial, a.vec_ok, a.accumulate);
 }
 
 template <int M, int WAVES>
@@ -804,6 +820,16 @@ inline int carousel_dispatch_bwd(int W, const CarouselBwdArgs &a)
 #undef GIVENS_BWD_CASE
 }
 
+// lanes per workgroup and slots per lane of the reverse sweep (the layout of the accumulation buffer)
+inline bool carousel_bwd_layout(int n, int *lanes, int *slots)
+{
+    CarouselShape s;
+    if (!carousel_bwd_shape_for(n, &s)) return false;
+    *lanes = 64 * s.WAVES;
+    *slots = s.M;
+    return true;
+}
+
 // Columns per workgroup of the reverse sweep.
 inline int carousel_bwd_width(int n, long long B)
 {
@@ -812,17 +838,19 @@ inline int carousel_bwd_width(int n, long long B)
     return carousel_width(B, s.WAVES);
 }
 
-// Launches the reverse sweep on strips [strip0, strip0 + nstrips); partial is [nstrips][N].
+// Launches the reverse sweep on strips [strip0, strip0 + nstrips).  accumulate = 0: partial is
+// [nstrips][N], one plain store per (strip, angle); accumulate = 1: partial is one zeroed [N] buffer in
+// the kernel's slot-major order that every strip adds into atomically.
 inline int carousel_backward_strips(int n, long long B, int W, long long strip0, long long nstrips,
                                     const CarouselCoefs &coefs, const float *Y, const float *G, float *dX,
-                                    float *partial, hipStream_t stream)
+                                    float *partial, int accumulate, hipStream_t stream)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const CarouselBwdArgs a{n, B, strip0, nstrips, coefs, Y, G, dX, partial, aligned ? 1 : 0, stream};
+    const CarouselBwdArgs a{n, B, strip0, nstrips, coefs, Y, G, dX, partial, aligned ? 1 : 0, accumulate, stream};
     if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_bwd<2, 1>(W, a);
     if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_bwd<4, 1>(W, a);
     if (s.M == 4 && s.WAVES == 2) return carousel_dispatch_bwd<4, 2>(W, a);

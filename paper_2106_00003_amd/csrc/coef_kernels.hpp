@@ -220,4 +220,27 @@ __global__ void reduce_partials_kernel(int n, long long nstrips, const T *__rest
     dtheta[e] = accumulate ? dtheta[e] + acc : acc;
 }
 
+__global__ void fill_zero_kernel(long long count, float *__restrict__ dst)
+{
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (long long)gridDim.x * blockDim.x)
+        dst[i] = 0.f;
+}
+
+// Last step of the accumulating reduction: the carousel reverse sweep adds every strip's sums into
+// acc, laid out [block k][slot r][lane l] (arc p = l * slots + r); this puts them back in E order and
+// applies the per-angle factor.
+__global__ void finish_accumulated_kernel(int n, int lanes, int slots, const float *__restrict__ acc,
+                                          const float *__restrict__ factor, float *__restrict__ dtheta)
+{
+    const int H = n >> 1;
+    const long long N = (long long)(n - 1) * H;
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= N) return;
+    const long long k = e / H;
+    const int p = (int)(e % H);
+    const int l = p / slots, r = p % slots;
+    dtheta[e] = factor[e] * acc[k * H + (long long)r * lanes + l];
+}
+
 } // namespace givens

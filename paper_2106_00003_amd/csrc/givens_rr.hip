@@ -19,6 +19,7 @@ namespace {
 constexpr int kMaxDevices = 64;
 constexpr size_t kLdsBudgetBytes = 144 * 1024;                 // of the 160 KB per CU on gfx950
 constexpr size_t kPartialCapBytes = size_t(24) << 30;          // cap on one chunk of strip partials
+constexpr bool kAutoReductionIsAtomic = false;                  // what GIVENS_REDUCTION_AUTO means for the carousel family
 
 struct Buffer {
     void *ptr = nullptr;
@@ -31,14 +32,16 @@ struct Workspace {
     Buffer renorm;       // scaled form: renormalisation rows, float2 [periods][n/2]
     Buffer factor;       // per-angle factor of the dtheta reduction
     Buffer flag;         // device word: bit pattern of max |theta|
-    Buffer partial;      // per-strip dtheta partial sums
-    Buffer *all[7] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial};
+    Buffer partial;      // per-strip dtheta partial sums (two-stage reduction)
+    Buffer acc;          // one accumulation buffer of N floats (accumulating reduction)
+    Buffer *all[8] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc};
 };
 
 std::mutex g_mutex;
 Workspace g_ws[kMaxDevices];
 int g_kernel_choice = GIVENS_KERNEL_AUTO;
 int g_form_choice = GIVENS_FORM_AUTO;
+int g_reduction_choice = GIVENS_REDUCTION_AUTO;
 int g_timing_on = 0;
 
 struct TimedSpan {
@@ -48,6 +51,7 @@ struct TimedSpan {
 struct ThreadState {
     int last_hip_error = 0;
     int last_kernel = 0;
+    int last_reduction = 0;
     const unsigned *last_flag = nullptr; // device flag of the last call when both forms were launched
     hipStream_t last_stream = nullptr;
     bool timing_valid = false;
@@ -249,9 +253,43 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
         if (w == 0) return GIVENS_ERR_UNSUPPORTED;
     }
     const long long strips = (B + w - 1) / w;
+    Workspace &ws = g_ws[dev];
+
+    if constexpr (std::is_same<T, float>::value) {
+        // accumulating reduction (carousel family): every strip adds its sums into one zeroed buffer
+        // with float atomics; no per-strip partials, no second pass over them
+        const bool want_acc = g_reduction_choice == GIVENS_REDUCTION_ATOMIC ||
+                              (g_reduction_choice == GIVENS_REDUCTION_AUTO && kAutoReductionIsAtomic);
+        if (family == GIVENS_KERNEL_CAROUSEL && want_acc) {
+            int lanes = 0, slots = 0;
+            if (!carousel_bwd_layout(n, &lanes, &slots)) return GIVENS_ERR_UNSUPPORTED;
+            if (int rc = grow(ws.acc, (size_t)N * sizeof(float))) return rc;
+            float *acc = reinterpret_cast<float *>(ws.acc.ptr);
+            const int threads = 256;
+            {
+                Span span(1, stream);
+                hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(threads), 0, stream, N, acc);
+                if (coefs.both_forms)
+                    if (int rc = carousel_backward_strips(n, B, w, 0, strips, coefs.scaled, Y, G, dX, acc, 1, stream))
+                        return rc;
+                if (int rc = carousel_backward_strips(n, B, w, 0, strips, coefs.standard, Y, G, dX, acc, 1, stream))
+                    return rc;
+                GIVENS_HIP(hipGetLastError());
+            }
+            {
+                Span span(2, stream);
+                hipLaunchKernelGGL(finish_accumulated_kernel, dim3((unsigned)((N + threads - 1) / threads)),
+                                   dim3(threads), 0, stream, n, lanes, slots, acc, coefs.factor, dtheta);
+                GIVENS_HIP(hipGetLastError());
+            }
+            t_state.last_reduction = GIVENS_REDUCTION_ATOMIC;
+            return GIVENS_OK;
+        }
+    }
+    t_state.last_reduction = GIVENS_REDUCTION_TWO_STAGE;
+
     long long chunk = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
     chunk = std::max<long long>(1, std::min(chunk, strips));
-    Workspace &ws = g_ws[dev];
     if (int rc = grow(ws.partial, (size_t)chunk * N * sizeof(T))) return rc;
     T *partial = reinterpret_cast<T *>(ws.partial.ptr);
     for (long long s0 = 0; s0 < strips; s0 += chunk) {
@@ -263,9 +301,9 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
                                    coefs.table, Y, G, dX, partial);
             } else if constexpr (std::is_same<T, float>::value) {
                 if (coefs.both_forms)
-                    if (int rc = carousel_backward_strips(n, B, w, s0, ns, coefs.scaled, Y, G, dX, partial, stream))
+                    if (int rc = carousel_backward_strips(n, B, w, s0, ns, coefs.scaled, Y, G, dX, partial, 0, stream))
                         return rc;
-                if (int rc = carousel_backward_strips(n, B, w, s0, ns, coefs.standard, Y, G, dX, partial, stream))
+                if (int rc = carousel_backward_strips(n, B, w, s0, ns, coefs.standard, Y, G, dX, partial, 0, stream))
                     return rc;
             } else {
                 return GIVENS_ERR_UNSUPPORTED;
@@ -451,6 +489,18 @@ int givens_set_kernel(int which)
 }
 
 int givens_last_kernel(void) { return givens::t_state.last_kernel; }
+
+int givens_set_reduction(int which)
+{
+    if (which != GIVENS_REDUCTION_AUTO && which != GIVENS_REDUCTION_TWO_STAGE && which != GIVENS_REDUCTION_ATOMIC)
+        return GIVENS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(givens::g_mutex);
+    const int prev = givens::g_reduction_choice;
+    givens::g_reduction_choice = which;
+    return prev;
+}
+
+int givens_last_reduction(void) { return givens::t_state.last_reduction; }
 
 int givens_set_rotation_form(int which)
 {

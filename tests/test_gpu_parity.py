@@ -160,6 +160,43 @@ def test_rotation_form_switches_at_the_angle_threshold():
     assert binding.last_rotation_form() == binding.FORM_STANDARD
 
 
+# ---------------------------------------------------------------- the two cross-strip reductions
+@pytest.mark.parametrize("n,B,seed,dist", [(256, 300, 71, "uniform"), (1024, 200, 72, "normal0.1"),
+                                           (2048, 64, 73, "uniform")])
+def test_atomic_reduction_matches_the_oracle_and_the_two_stage_result(n, B, seed, dist):
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    binding.set_kernel(binding.KERNEL_CAROUSEL)
+    th_d, g_d = dev(data["theta"]), dev(data["G"])
+    y_d = binding.givens_forward(th_d, dev(data["X"]))
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], C.forward(data["theta"], data["X"]), data["G"])
+    got = {}
+    try:
+        for mode in (binding.REDUCTION_TWO_STAGE, binding.REDUCTION_ATOMIC):
+            binding.set_reduction(mode)
+            dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+            assert binding.last_reduction() == mode
+            got[mode] = host(dth_d)
+            assert O.rel_fro(got[mode], want_dth) <= TOL_G
+            assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
+        # two runs of the two-stage reduction are bit-identical
+        binding.set_reduction(binding.REDUCTION_TWO_STAGE)
+        _, again = binding.givens_backward(th_d, y_d, g_d)
+        assert np.array_equal(host(again), got[binding.REDUCTION_TWO_STAGE])
+    finally:
+        binding.set_reduction(binding.REDUCTION_AUTO)
+        binding.set_kernel(binding.KERNEL_AUTO)
+
+
+def test_atomic_reduction_falls_back_for_the_lds_family():
+    data = inputs.make_custom(34, 19, seed=74)
+    try:
+        binding.set_reduction(binding.REDUCTION_ATOMIC)
+        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_LDS, TOL_Y, TOL_G)
+        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+    finally:
+        binding.set_reduction(binding.REDUCTION_AUTO)
+
+
 def test_carousel_rejects_shapes_it_does_not_cover():
     data = inputs.make_custom(34, 8, seed=1)
     binding.set_kernel(binding.KERNEL_CAROUSEL)
