@@ -403,11 +403,13 @@ struct CarouselBwd {
 
     float zt[M][W], zb[M][W], gt[M][W], gb[M][W];
     float2 cs[2][M];
+    float prior[2][M]; // sums of this workgroup's earlier strips for the current / next block
     int n, H, lane, wave, tid;
     const float2 *tab_lane;  // table + tid*M
     const float2 *rn_lane;   // renormalisation factors + tid*M (scaled form)
     float *part_lane;        // where this lane's sums go (see `accumulate`)
-    int accumulate;          // 0: part_lane = this strip's partial sums + tid*M, plain stores
+    const float *prior_lane; // what load_prior reads: this workgroup's row, or zeros for its first strip
+    int accumulate;          // 0: part_lane = this workgroup's row of partial sums + tid*M, plain stores
                              // 1: part_lane = shared accumulation buffer + tid, atomic adds; the buffer
                              //    is slot-major within a block, [k][r][lane], so that one atomic
                              //    instruction of a wavefront covers 64 consecutive floats
@@ -430,6 +432,30 @@ struct CarouselBwd {
                 const float4 v = s4[r];
                 dst[2 * r] = make_float2(v.x, v.y);
                 dst[2 * r + 1] = make_float2(v.z, v.w);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < M; ++r) dst[r] = src[r];
+        }
+    }
+
+    // The partial sums already stored for block k by this workgroup's earlier strips.  For its first
+    // strip (and in the accumulating mode) prior_lane points into a row of zeros instead: a branch
+    // here would sit in every block and split the scheduler's region, which costs more than the loads.
+    __device__ __forceinline__ void load_prior(int k, float (&dst)[M])
+    {
+        const float *src = prior_lane + (long long)k * H;
+        if constexpr (M % 4 == 0) {
+#pragma unroll
+            for (int r = 0; r < M / 4; ++r) {
+                const float4 v = reinterpret_cast<const float4 *>(src)[r];
+                dst[4 * r] = v.x; dst[4 * r + 1] = v.y; dst[4 * r + 2] = v.z; dst[4 * r + 3] = v.w;
+            }
+        } else if constexpr (M % 2 == 0) {
+#pragma unroll
+            for (int r = 0; r < M / 2; ++r) {
+                const float2 v = reinterpret_cast<const float2 *>(src)[r];
+                dst[2 * r] = v.x; dst[2 * r + 1] = v.y;
             }
         } else {
 #pragma unroll
@@ -527,6 +553,10 @@ struct CarouselBwd {
         if constexpr (!LAST) load_coefs(k + 1, cs[(U + 1) & 1]);
         float2 rn[M];
         if constexpr (RN) load_row_of(rn_lane, k / kRenormPeriod, rn);
+        // what this workgroup's earlier strips have summed for the NEXT block: fetched a block ahead,
+        // like cos/sin, and before this block's store, so that waiting for it never waits for a store
+        float(&earlier)[M] = prior[U & 1];
+        if constexpr (!LAST) load_prior(k + 1, prior[(U + 1) & 1]);
 
         float sums[M];
         // the inner slots all run after the exchange slots here: splitting them around the exchange as
@@ -548,6 +578,8 @@ struct CarouselBwd {
             for (int r = 0; r < M; ++r) unsafeAtomicAdd(dst + r * kLanes, sums[r]);
         } else {
             float *dst = part_lane + (long long)k * H;
+#pragma unroll
+            for (int r = 0; r < M; ++r) sums[r] += earlier[r];
             if constexpr (M % 4 == 0) {
 #pragma unroll
                 for (int r = 0; r < M / 4; ++r)
@@ -584,6 +616,7 @@ struct CarouselBwd {
     __device__ __forceinline__ void sweep()
     {
         constexpr auto seq = std::make_integer_sequence<int, M>{};
+        load_prior(0, prior[0]);
         int k = 0;
         if constexpr (FORM == 0) {
             for (; k + M <= n - 1; k += M) full_group<false>(k, seq);
@@ -603,9 +636,9 @@ struct CarouselBwd {
 
 template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
-    int n, long long B, long long strip0, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
-    const unsigned *flag, const float *Yin, const float *G, float *dX, float *__restrict__ partial, int vec_ok,
-    int accumulate)
+    int n, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
+    const float2 *__restrict__ renorm, const unsigned *flag, const float *Yin, const float *G, float *dX,
+    float *partial, const float *__restrict__ zeros, int vec_ok, int accumulate)
 {
     if (!form_selected(flag, FORM == 1)) return;
     using State = CarouselBwd<M, W, WAVES, FORM>;
@@ -633,31 +666,39 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
         st.in_bot = (t < L - 1) ? z.bot_out.lane(t + 1) : z.top_out.lane(L - 1); // far end: top[n/2-1] -> bot[n/2-1]
     }
 
-    const long long b0 = (strip0 + blockIdx.x) * W;
-    const int wv = (B - b0) < W ? (int)(B - b0) : W;
-    const bool vec = vec_ok && wv == W;
+    // Persistent workgroup: strips strip0 + blockIdx.x, + gridDim.x, ... of the nstrips of this launch.
+    // Its row of partial sums is written by the first strip and added to by the others, in program
+    // order, so the result does not depend on scheduling.
+    for (long long s = blockIdx.x; s < nstrips; s += gridDim.x) {
+        const bool first_strip = (s == (long long)blockIdx.x);
+        st.prior_lane = (accumulate || first_strip) ? zeros + (long long)threadIdx.x * M : st.part_lane;
+        const long long b0 = (strip0 + s) * W;
+        const int wv = (B - b0) < W ? (int)(B - b0) : W;
+        const bool vec = vec_ok && wv == W;
 
-    // block 1 is processed first: identity position order
-#pragma unroll
-    for (int r = 0; r < M; ++r) {
-        const int p = st.tid * M + r;
-        load_row<W>(st.zt[r], Yin, B, p, b0, wv, vec, 0);
-        load_row<W>(st.zb[r], Yin, B, n - 1 - p, b0, wv, vec, 0);
-        load_row<W>(st.gt[r], G, B, p, b0, wv, vec, 0);
-        load_row<W>(st.gb[r], G, B, n - 1 - p, b0, wv, vec, 0);
-    }
-    st.load_coefs(0, st.cs[0]);
-
-    st.sweep();
-
-    if (dX) {
-        constexpr int UL = State::kLastU;
+        // block 1 is processed first: identity position order
 #pragma unroll
         for (int r = 0; r < M; ++r) {
             const int p = st.tid * M + r;
-            store_row<W>(st.gt[(r - UL + M) % M], dX, B, rr_label(n, n - 2, p), b0, wv, vec);
-            store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), b0, wv, vec);
+            load_row<W>(st.zt[r], Yin, B, p, b0, wv, vec, 0);
+            load_row<W>(st.zb[r], Yin, B, n - 1 - p, b0, wv, vec, 0);
+            load_row<W>(st.gt[r], G, B, p, b0, wv, vec, 0);
+            load_row<W>(st.gb[r], G, B, n - 1 - p, b0, wv, vec, 0);
         }
+        st.load_coefs(0, st.cs[0]);
+
+        st.sweep();
+
+        if (dX) {
+            constexpr int UL = State::kLastU;
+#pragma unroll
+            for (int r = 0; r < M; ++r) {
+                const int p = st.tid * M + r;
+                store_row<W>(st.gt[(r - UL + M) % M], dX, B, rr_label(n, n - 2, p), b0, wv, vec);
+                store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), b0, wv, vec);
+            }
+        }
+        __syncthreads(); // the next strip reuses the exchange buffers
     }
 }
 
@@ -786,10 +827,11 @@ inline int carousel_forward(int n, long long B, const CarouselCoefs &coefs, cons
 
 struct CarouselBwdArgs {
     int n;
-    long long B, strip0, nstrips;
+    long long B, strip0, nstrips, groups;
     CarouselCoefs coefs;
     const float *Y, *G;
     float *dX, *partial;
+    const float *zeros; // N floats that are always zero
     int vec_ok, accumulate;
     hipStream_t stream;
 };
@@ -797,9 +839,9 @@ struct CarouselBwdArgs {
 template <int M, int W, int WAVES, int FORM>
 inline void carousel_launch_bwd(const CarouselBwdArgs &a)
 {
-    hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.nstrips), dim3(64 * WAVES),
-                       0, a.stream, a.n, a.B, a.strip0, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.Y, a.G,
-                       a.dX, a.partial, a.vec_ok, a.accumulate);
+    hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.groups), dim3(64 * WAVES),
+                       0, a.stream, a.n, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.Y,
+                       a.G, a.dX, a.partial, a.zeros, a.vec_ok, a.accumulate);
 }
 
 template <int M, int WAVES>
@@ -838,19 +880,31 @@ inline int carousel_bwd_width(int n, long long B)
     return carousel_width(B, s.WAVES);
 }
 
-// Launches the reverse sweep on strips [strip0, strip0 + nstrips).  accumulate = 0: partial is
-// [nstrips][N], one plain store per (strip, angle); accumulate = 1: partial is one zeroed [N] buffer in
-// the kernel's slot-major order that every strip adds into atomically.
+// Number of persistent workgroups the reverse sweep runs with: what the chip holds at once (the
+// kernel is limited to two wavefronts per SIMD by its registers), or one per strip if that is fewer.
+inline long long carousel_bwd_groups(int n, long long nstrips, int compute_units)
+{
+    CarouselShape s;
+    if (!carousel_bwd_shape_for(n, &s)) return 0;
+    const long long resident = (long long)compute_units * (8 / s.WAVES > 0 ? 8 / s.WAVES : 1);
+    return nstrips < resident ? nstrips : resident;
+}
+
+// Launches the reverse sweep on strips [strip0, strip0 + nstrips) with `groups` persistent workgroups.
+// accumulate = 0: partial is [groups][N]; workgroup g stores the sums of its first strip in row g and
+// adds those of its later strips to them.  accumulate = 1: partial is one zeroed [N] buffer in the
+// kernel's slot-major order that every strip adds into atomically.  zeros: N floats that stay zero.
 inline int carousel_backward_strips(int n, long long B, int W, long long strip0, long long nstrips,
-                                    const CarouselCoefs &coefs, const float *Y, const float *G, float *dX,
-                                    float *partial, int accumulate, hipStream_t stream)
+                                    long long groups, const CarouselCoefs &coefs, const float *Y, const float *G,
+                                    float *dX, float *partial, const float *zeros, int accumulate,
+                                    hipStream_t stream)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const CarouselBwdArgs a{n, B, strip0, nstrips, coefs, Y, G, dX, partial, aligned ? 1 : 0, accumulate, stream};
+    const CarouselBwdArgs a{n, B, strip0, nstrips, groups, coefs, Y, G, dX, partial, zeros, aligned ? 1 : 0, accumulate, stream};
     if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_bwd<2, 1>(W, a);
     if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_bwd<4, 1>(W, a);
     if (s.M == 4 && s.WAVES == 2) return carousel_dispatch_bwd<4, 2>(W, a);

@@ -34,7 +34,8 @@ struct Workspace {
     Buffer flag;         // device word: bit pattern of max |theta|
     Buffer partial;      // per-strip dtheta partial sums (two-stage reduction)
     Buffer acc;          // one accumulation buffer of N floats (accumulating reduction)
-    Buffer *all[8] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc};
+    Buffer zeros;        // N floats that are zeroed when allocated and never written again
+    Buffer *all[9] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc, &zeros};
 };
 
 std::mutex g_mutex;
@@ -254,6 +255,23 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
     }
     const long long strips = (B + w - 1) / w;
     Workspace &ws = g_ws[dev];
+    int cus = 0;
+    GIVENS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const float *zeros = nullptr;
+    if constexpr (std::is_same<T, float>::value) {
+        if (family == GIVENS_KERNEL_CAROUSEL) {
+            const size_t want = (size_t)N * sizeof(float);
+            if (ws.zeros.bytes < want) {
+                if (int rc = grow(ws.zeros, want)) return rc;
+                hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, stream, N,
+                                   reinterpret_cast<float *>(ws.zeros.ptr));
+                GIVENS_HIP(hipGetLastError());
+                // later calls may come on other streams and never write this buffer again
+                GIVENS_HIP(hipStreamSynchronize(stream));
+            }
+            zeros = reinterpret_cast<const float *>(ws.zeros.ptr);
+        }
+    }
 
     if constexpr (std::is_same<T, float>::value) {
         // accumulating reduction (carousel family): every strip adds its sums into one zeroed buffer
@@ -269,10 +287,13 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
             {
                 Span span(1, stream);
                 hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(threads), 0, stream, N, acc);
+                const long long groups = carousel_bwd_groups(n, strips, cus);
                 if (coefs.both_forms)
-                    if (int rc = carousel_backward_strips(n, B, w, 0, strips, coefs.scaled, Y, G, dX, acc, 1, stream))
+                    if (int rc = carousel_backward_strips(n, B, w, 0, strips, groups, coefs.scaled, Y, G, dX, acc, zeros, 1,
+                                                          stream))
                         return rc;
-                if (int rc = carousel_backward_strips(n, B, w, 0, strips, coefs.standard, Y, G, dX, acc, 1, stream))
+                if (int rc = carousel_backward_strips(n, B, w, 0, strips, groups, coefs.standard, Y, G, dX, acc, zeros, 1,
+                                                      stream))
                     return rc;
                 GIVENS_HIP(hipGetLastError());
             }
@@ -288,12 +309,19 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
     }
     t_state.last_reduction = GIVENS_REDUCTION_TWO_STAGE;
 
-    long long chunk = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
-    chunk = std::max<long long>(1, std::min(chunk, strips));
-    if (int rc = grow(ws.partial, (size_t)chunk * N * sizeof(T))) return rc;
+    // Two-stage reduction.  LDS family: one row of partial sums per strip, in chunks of strips that fit
+    // the workspace cap.  Carousel family: one row per persistent workgroup (at most what the chip
+    // holds at once), whatever the number of strips.
+    const bool persistent = family == GIVENS_KERNEL_CAROUSEL;
+    const long long rows_wanted = persistent ? carousel_bwd_groups(n, strips, cus) : strips;
+    long long rows = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
+    rows = std::max<long long>(1, std::min(rows, rows_wanted));
+    if (int rc = grow(ws.partial, (size_t)rows * N * sizeof(T))) return rc;
     T *partial = reinterpret_cast<T *>(ws.partial.ptr);
+    const long long chunk = persistent ? strips : rows;     // strips per launch
     for (long long s0 = 0; s0 < strips; s0 += chunk) {
         const long long ns = std::min(chunk, strips - s0);
+        const long long nrows = persistent ? std::min(rows, ns) : ns;
         {
             Span span(1, stream);
             if (family == GIVENS_KERNEL_LDS) {
@@ -301,9 +329,11 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
                                    coefs.table, Y, G, dX, partial);
             } else if constexpr (std::is_same<T, float>::value) {
                 if (coefs.both_forms)
-                    if (int rc = carousel_backward_strips(n, B, w, s0, ns, coefs.scaled, Y, G, dX, partial, 0, stream))
+                    if (int rc = carousel_backward_strips(n, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX, partial, zeros, 0,
+                                                          stream))
                         return rc;
-                if (int rc = carousel_backward_strips(n, B, w, s0, ns, coefs.standard, Y, G, dX, partial, 0, stream))
+                if (int rc = carousel_backward_strips(n, B, w, s0, ns, nrows, coefs.standard, Y, G, dX, partial, zeros, 0,
+                                                      stream))
                     return rc;
             } else {
                 return GIVENS_ERR_UNSUPPORTED;
@@ -314,7 +344,7 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
             Span span(2, stream);
             const int threads = 256;
             hipLaunchKernelGGL(reduce_partials_kernel<T>, dim3((unsigned)((N + threads - 1) / threads)),
-                               dim3(threads), 0, stream, n, ns, partial, coefs.factor, dtheta, s0 > 0 ? 1 : 0);
+                               dim3(threads), 0, stream, n, nrows, partial, coefs.factor, dtheta, s0 > 0 ? 1 : 0);
             GIVENS_HIP(hipGetLastError());
         }
     }
