@@ -137,9 +137,11 @@ int givens_last_rotation_form(void);
 
 /*
  * Selects how the reverse sweep reduces over strips (process-wide); returns the previous setting.
- * TWO_STAGE needs 4*N bytes of workspace per strip (17 GB at n = B = 4096) but gives bit-identical
- * dtheta from run to run; ATOMIC needs 4*N bytes in all.  The LDS family and the f64 entry points
- * always use TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
+ * TWO_STAGE keeps one row of 4*N bytes of partial sums per resident workgroup of the carousel sweep
+ * (at most 256 rows on this chip: 8.6 GB at n = 4096, whatever B is) or per strip of the LDS family,
+ * capped at 24 GiB per chunk, and gives bit-identical dtheta from run to run; ATOMIC needs 4*N bytes
+ * in all but its summation order is not fixed.  The LDS family and the f64 entry points always use
+ * TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
  */
 int givens_set_reduction(int which);
 int givens_last_reduction(void);

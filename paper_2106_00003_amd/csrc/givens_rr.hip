@@ -233,8 +233,9 @@ int lds_forward(int n, long long B, const typename Pair2<T>::type *table, const 
     return GIVENS_OK;
 }
 
-// Reverse sweep in chunks of strips: each chunk writes one partial sum per (strip, angle) and the
-// second stage folds the chunk into dtheta.  `family` picks the sweep kernel.
+// Reverse sweep and the reduction of its partial sums into dtheta.  LDS family: chunks of strips, one
+// partial sum per (strip, angle), folded into dtheta chunk by chunk.  Carousel family: persistent
+// workgroups with one row of partial sums each, or the accumulating variant.  `family` picks the kernel.
 template <typename T>
 int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coefs, const T *Y, const T *G,
                     T *dX, T *dtheta, hipStream_t stream)
