@@ -50,9 +50,11 @@ extern "C" {
 #define GIVENS_KERNEL_CAROUSEL 2 /* strip held in VGPRs in circle-method position order      */
 
 /* Rotation forms of the float carousel kernels (givens_set_rotation_form). */
-#define GIVENS_FORM_AUTO 0     /* scaled form when every |theta| <= pi/4 (decided on the device), else standard */
+#define GIVENS_FORM_AUTO 0     /* decided on the device from max |theta|: scaled if <= pi/4, lifted if <= 1e6,  */
+                               /* standard otherwise (including NaN)                                          */
 #define GIVENS_FORM_STANDARD 1 /* r_i = c U_i - s U_j, r_j = s U_i + c U_j exactly as in Algorithm 1         */
 #define GIVENS_FORM_SCALED 2   /* same rotations on rows kept divided by their accumulated cosines (2 FMAs)  */
+#define GIVENS_FORM_LIFTED 3   /* same rotations as three shears (3 FMAs), angles reduced modulo pi           */
 
 /* How givens_backward sums the per-strip shares of dtheta (givens_set_reduction). */
 #define GIVENS_REDUCTION_AUTO 0      /* the library's default for the kernel family in use                     */
@@ -123,12 +125,15 @@ int givens_set_kernel(int which);
 int givens_last_kernel(void);
 
 /*
- * The float carousel kernels have two arithmetically equivalent forms of the same Givens update
+ * The float carousel kernels have three arithmetically equivalent forms of the same Givens update
  * (Algorithm 1's loop body).  The scaled form keeps every row divided by the product of the cosines it
  * has met, which turns an update into two FMAs, and multiplies the rows back every 64 blocks; it is
- * used only when every |theta| <= pi/4, which a device-side check of theta decides per call.
- * givens_set_rotation_form(GIVENS_FORM_STANDARD) switches the check and the scaled form off
- * (process-wide); returns the previous setting.  givens_last_rotation_form() reports which form the
+ * used only when every |theta| <= pi/4.  The lifted form writes the rotation as three shears (three
+ * FMAs) after reducing the angle modulo pi, carrying the resulting signs the same way; it is used for
+ * larger finite angles.  A device-side check of theta decides per call.
+ * givens_set_rotation_form(GIVENS_FORM_STANDARD) switches the check and both other forms off,
+ * GIVENS_FORM_LIFTED keeps the check but never picks the scaled form (process-wide; GIVENS_FORM_SCALED
+ * cannot be forced); returns the previous setting.  givens_last_rotation_form() reports which form the
  * last forward/build/backward call on this thread ran (it reads the device flag back and waits for
  * that call's stream).  Other kernel families and the f64 entry points always use the standard form.
  */

@@ -1,17 +1,25 @@
-"""Builds the HIP library in-tree: paper_2106_00003_amd/libgivens_rr.so (gfx950 only)."""
+"""Builds the HIP library in-tree: paper_2106_00003_amd/libgivens_rr.so (gfx950 only).
+
+Every .hip file under csrc/ is one translation unit; they are compiled in parallel into _build/ and
+linked into one shared library.  The carousel kernels are spread over one unit per rotation form
+and sweep direction because their many template instances dominate the compile time.
+"""
 from __future__ import annotations
 
+import concurrent.futures
+import glob
 import os
 import shutil
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgivens_rr.so")
 
 # Packed-FP32 VALU forms are switched off for every translation unit of this library.
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
@@ -24,16 +32,29 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    src = os.path.join(CSRC, "givens_rr.hip")
-    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-o", LIB, src]
+def _run(cmd, verbose):
     if verbose:
-        print(" ".join(cmd))
+        print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    if verbose and res.stderr:
-        print(res.stderr)
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
+    return res
+
+
+def build_library(verbose: bool = False, extra_flags=(), jobs: int | None = None) -> str:
+    hipcc = hipcc_path()
+    sources = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    if not sources:
+        raise RuntimeError(f"no sources under {CSRC}")
+    os.makedirs(OBJ, exist_ok=True)
+    objects = [os.path.join(OBJ, os.path.basename(s)[:-4] + ".o") for s in sources]
+    jobs = jobs or max(1, min(len(sources), os.cpu_count() or 1, 16))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
+        futures = [pool.submit(_run, [hipcc, *HIPCC_FLAGS, *extra_flags, "-c", src, "-o", obj], verbose)
+                   for src, obj in zip(sources, objects)]
+        for f in futures:
+            f.result()
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objects], verbose)
     return LIB
 
 

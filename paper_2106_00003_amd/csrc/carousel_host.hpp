@@ -1,0 +1,177 @@
+// Host side of the register-carousel kernels: shapes, launch arguments and the entry points of the
+// translation units that instantiate the kernels (one per rotation form and sweep direction, so that
+// they compile in parallel).  No device code here.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <type_traits>
+
+#include "../../include/givens_rr.h"
+#include "forms.hpp"
+
+namespace givens {
+
+struct CarouselShape {
+    int M, WAVES;
+};
+
+// What a sweep of one rotation form reads: its table, its renormalisation rows (scaled and lifted
+// forms) and the device flag that says which form is to run (nullptr: this launch always runs).
+struct CarouselCoefs {
+    int form; // kFormStandard, kFormScaled or kFormLifted
+    const float2 *table;
+    const float2 *renorm;
+    const unsigned *flag;
+    float scaled_max; // threshold of the scaled form (negative: never), see form_for_range
+};
+
+// n = 128 * WAVES * M with one of the compiled (M, WAVES) pairs
+inline bool carousel_shape_for(int n, CarouselShape *out)
+{
+    switch (n) {
+    case 256: *out = {2, 1}; return true;
+    case 512: *out = {4, 1}; return true;
+    case 1024: *out = {8, 1}; return true;
+    case 2048: *out = {8, 2}; return true;
+    case 4096: *out = {8, 4}; return true;
+    case 8192: *out = {8, 8}; return true;
+    default: return false;
+    }
+}
+
+template <typename T>
+inline bool carousel_supported(int n, long long B)
+{
+    (void)B;
+    CarouselShape s;
+    return std::is_same<T, float>::value && carousel_shape_for(n, &s);
+}
+
+// shapes of the reverse sweep: two strips per lane, so half the slots per lane of the forward
+inline bool carousel_bwd_shape_for(int n, CarouselShape *out)
+{
+    switch (n) {
+    case 256: *out = {2, 1}; return true;
+    case 512: *out = {4, 1}; return true;
+    case 1024: *out = {4, 2}; return true;
+    case 2048: *out = {4, 4}; return true;
+    case 4096: *out = {4, 8}; return true;
+    default: return false;
+    }
+}
+
+template <typename T>
+inline bool carousel_backward_supported(int n, long long B)
+{
+    (void)B;
+    CarouselShape s;
+    return std::is_same<T, float>::value && carousel_bwd_shape_for(n, &s);
+}
+
+// Columns per lane: the widest of {8,4,2,1} that still gives the chip about two wavefronts per SIMD.
+inline int carousel_width(long long B, int waves)
+{
+    const long long want_waves = 2048; // 256 CUs x 4 SIMDs x 2
+    for (int w = 8; w > 1; w >>= 1)
+        if (((B + w - 1) / w) * waves >= want_waves) return w;
+    return 1;
+}
+
+struct CarouselFwdArgs {
+    int n;
+    long long B;
+    CarouselCoefs coefs;
+    const float *X;
+    float *Y;
+    int identity, vec_ok;
+    hipStream_t stream;
+};
+
+struct CarouselBwdArgs {
+    int n;
+    long long B, strip0, nstrips, groups;
+    CarouselCoefs coefs;
+    const float *Y, *G;
+    float *dX, *partial;
+    const float *zeros; // N floats that are always zero
+    int vec_ok, accumulate;
+    hipStream_t stream;
+};
+
+// Defined in carousel_fwd_<form>.hip / carousel_bwd_<form>.hip: launch the kernel of that form for
+// shape s and W columns per lane; GIVENS_ERR_UNSUPPORTED for a combination that is not compiled.
+int carousel_forward_standard(const CarouselFwdArgs &a, CarouselShape s, int W);
+int carousel_forward_scaled(const CarouselFwdArgs &a, CarouselShape s, int W);
+int carousel_forward_lifted(const CarouselFwdArgs &a, CarouselShape s, int W);
+int carousel_backward_standard(const CarouselBwdArgs &a, CarouselShape s, int W);
+int carousel_backward_scaled(const CarouselBwdArgs &a, CarouselShape s, int W);
+int carousel_backward_lifted(const CarouselBwdArgs &a, CarouselShape s, int W);
+
+inline int carousel_forward(int n, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
+                            int identity, hipStream_t stream)
+{
+    CarouselShape s;
+    if (!carousel_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
+    const int W = carousel_width(B, s.WAVES);
+    const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
+                         (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
+    const CarouselFwdArgs a{n, B, coefs, X, Y, identity, aligned ? 1 : 0, stream};
+    switch (coefs.form) {
+    case kFormScaled: return carousel_forward_scaled(a, s, W);
+    case kFormLifted: return carousel_forward_lifted(a, s, W);
+    default: return carousel_forward_standard(a, s, W);
+    }
+}
+
+// lanes per workgroup and slots per lane of the reverse sweep (the layout of the accumulation buffer)
+inline bool carousel_bwd_layout(int n, int *lanes, int *slots)
+{
+    CarouselShape s;
+    if (!carousel_bwd_shape_for(n, &s)) return false;
+    *lanes = 64 * s.WAVES;
+    *slots = s.M;
+    return true;
+}
+
+// Columns per workgroup of the reverse sweep.
+inline int carousel_bwd_width(int n, long long B)
+{
+    CarouselShape s;
+    if (!carousel_bwd_shape_for(n, &s)) return 0;
+    return carousel_width(B, s.WAVES);
+}
+
+// Number of persistent workgroups the reverse sweep runs with: what the chip holds at once (the
+// kernel is limited to two wavefronts per SIMD by its registers), or one per strip if that is fewer.
+inline long long carousel_bwd_groups(int n, long long nstrips, int compute_units)
+{
+    CarouselShape s;
+    if (!carousel_bwd_shape_for(n, &s)) return 0;
+    const long long resident = (long long)compute_units * (8 / s.WAVES > 0 ? 8 / s.WAVES : 1);
+    return nstrips < resident ? nstrips : resident;
+}
+
+// Launches the reverse sweep on strips [strip0, strip0 + nstrips) with `groups` persistent workgroups.
+// accumulate = 0: partial is [groups][N]; workgroup g stores the sums of its first strip in row g and
+// adds those of its later strips to them.  accumulate = 1: partial is one zeroed [N] buffer in the
+// kernel's slot-major order that every strip adds into atomically.  zeros: N floats that stay zero.
+inline int carousel_backward_strips(int n, long long B, int W, long long strip0, long long nstrips,
+                                    long long groups, const CarouselCoefs &coefs, const float *Y, const float *G,
+                                    float *dX, float *partial, const float *zeros, int accumulate,
+                                    hipStream_t stream)
+{
+    CarouselShape s;
+    if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
+    const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
+                         (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
+    const CarouselBwdArgs a{n, B, strip0, nstrips, groups, coefs, Y, G, dX, partial, zeros, aligned ? 1 : 0, accumulate, stream};
+    switch (coefs.form) {
+    case kFormScaled: return carousel_backward_scaled(a, s, W);
+    case kFormLifted: return carousel_backward_lifted(a, s, W);
+    default: return carousel_backward_standard(a, s, W);
+    }
+}
+
+} // namespace givens

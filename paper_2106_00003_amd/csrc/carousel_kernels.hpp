@@ -30,7 +30,8 @@
 #include <utility>
 
 #include "../../include/givens_rr.h"
-#include "lds_kernels.hpp"
+#include "carousel_host.hpp"
+#include "forms.hpp"
 #include "rr_index.h"
 
 namespace givens {
@@ -104,6 +105,8 @@ __device__ __forceinline__ void lds_load_row(float (&dst)[W], const float *src)
 // FORM 0: standard rotation (2 MUL + 2 FMA per update, table holds cos and sin).
 // FORM 1: scaled rotation (2 FMA per update on values kept divided by their accumulated cosines,
 //         table holds alpha and beta, renormalisation every kRenormPeriod blocks; coef_kernels.hpp).
+// FORM 2: lifted rotation (3 dependent FMA per update: three shears; table holds tan(theta'/2) and
+//         sin(theta') with the carried signs folded in; same renormalisation points, factors +-1).
 template <int M, int W, int WAVES, int FORM>
 struct CarouselFwd {
     static_assert(kRenormPeriod % M == 0, "renormalisation must fall on the last copy of an unrolled group");
@@ -157,9 +160,14 @@ struct CarouselFwd {
             if constexpr (FORM == 0) {
                 top[it][x] = fmaf(c, a, -(s * b)); // r_i = cos U_i - sin U_j
                 bot[ib][x] = fmaf(c, b, s * a);    // r_j = sin U_i + cos U_j
-            } else {
+            } else if constexpr (FORM == 1) {
                 top[it][x] = fmaf(-c, b, a);       // a~ - alpha b~
                 bot[ib][x] = fmaf(s, a, b);        // b~ + beta a~
+            } else {
+                const float a1 = fmaf(-c, b, a);   // a - t b
+                const float b1 = fmaf(s, a1, b);   // b + s a
+                top[it][x] = fmaf(-c, b1, a1);     // a - t b
+                bot[ib][x] = b1;
             }
             if constexpr (RN) {
                 top[it][x] *= rn[R].x;
@@ -195,7 +203,7 @@ struct CarouselFwd {
     template <int U, bool LAST, bool RENORM>
     __device__ __forceinline__ void step(int k)
     {
-        constexpr bool RN = FORM == 1 && (LAST || RENORM);
+        constexpr bool RN = FORM != 0 && (LAST || RENORM);
         float2(&cur)[M] = cs[U & 1];
         if constexpr (!LAST) load_coefs(k - 1, cs[(U + 1) & 1]);
         float2 rn[M];
@@ -319,9 +327,9 @@ __device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long 
 template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
     int n, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
-    const unsigned *flag, const float *X, float *Y, int identity, int vec_ok)
+    const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok)
 {
-    if (!form_selected(flag, FORM == 1)) return;
+    if (!form_selected(flag, FORM, scaled_max)) return;
     using State = CarouselFwd<M, W, WAVES, FORM>;
     __shared__ CarouselExchange<W, WAVES> sh;
     State st;
@@ -513,11 +521,20 @@ struct CarouselBwd {
                 zb[ib][x] = fmaf(c, zv, -(s * za));
                 gt[it][x] = fmaf(c, ga, s * gv);
                 gb[ib][x] = fmaf(c, gv, -(s * ga));
-            } else {
+            } else if constexpr (FORM == 1) {
                 zt[it][x] = fmaf(c, zv, za);       // a~ + alpha b~
                 zb[ib][x] = fmaf(-s, za, zv);      // b~ - beta a~
                 gt[it][x] = fmaf(c, gv, ga);
                 gb[ib][x] = fmaf(-s, ga, gv);
+            } else {
+                const float z1 = fmaf(c, zv, za);  // the three shears of the transposed rotation
+                const float w1 = fmaf(-s, z1, zv);
+                zt[it][x] = fmaf(c, w1, z1);
+                zb[ib][x] = w1;
+                const float g1 = fmaf(c, gv, ga);
+                const float h1 = fmaf(-s, g1, gv);
+                gt[it][x] = fmaf(c, h1, g1);
+                gb[ib][x] = h1;
             }
             if constexpr (RN) {
                 zt[it][x] *= rn[R].x;
@@ -548,7 +565,7 @@ struct CarouselBwd {
     template <int U, bool LAST, bool RENORM>
     __device__ __forceinline__ void step(int k)
     {
-        constexpr bool RN = FORM == 1 && (LAST || RENORM);
+        constexpr bool RN = FORM != 0 && (LAST || RENORM);
         float2(&cur)[M] = cs[U & 1];
         if constexpr (!LAST) load_coefs(k + 1, cs[(U + 1) & 1]);
         float2 rn[M];
@@ -637,10 +654,10 @@ struct CarouselBwd {
 template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     int n, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
-    const float2 *__restrict__ renorm, const unsigned *flag, const float *Yin, const float *G, float *dX,
-    float *partial, const float *__restrict__ zeros, int vec_ok, int accumulate)
+    const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
+    float *dX, float *partial, const float *__restrict__ zeros, int vec_ok, int accumulate)
 {
-    if (!form_selected(flag, FORM == 1)) return;
+    if (!form_selected(flag, FORM, scaled_max)) return;
     using State = CarouselBwd<M, W, WAVES, FORM>;
     __shared__ CarouselExchangeBwd<W, WAVES> sh;
     State st;
@@ -703,213 +720,69 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// host side
+// launches (instantiated per rotation form by carousel_fwd_*.hip / carousel_bwd_*.hip)
 // ---------------------------------------------------------------------------------------------
-struct CarouselShape {
-    int M, WAVES;
-};
-
-// What a sweep of one rotation form reads: its table, its renormalisation rows (scaled form) and the
-// device flag that says which form is to run (nullptr: this launch always runs).
-struct CarouselCoefs {
-    int form; // 0 standard, 1 scaled
-    const float2 *table;
-    const float2 *renorm;
-    const unsigned *flag;
-};
-
-// n = 128 * WAVES * M with one of the compiled (M, WAVES) pairs
-inline bool carousel_shape_for(int n, CarouselShape *out)
-{
-    switch (n) {
-    case 256: *out = {2, 1}; return true;
-    case 512: *out = {4, 1}; return true;
-    case 1024: *out = {8, 1}; return true;
-    case 2048: *out = {8, 2}; return true;
-    case 4096: *out = {8, 4}; return true;
-    case 8192: *out = {8, 8}; return true;
-    default: return false;
-    }
-}
-
-template <typename T>
-inline bool carousel_supported(int n, long long B)
-{
-    (void)B;
-    CarouselShape s;
-    return std::is_same<T, float>::value && carousel_shape_for(n, &s);
-}
-
-// shapes of the reverse sweep: two strips per lane, so half the slots per lane of the forward
-inline bool carousel_bwd_shape_for(int n, CarouselShape *out)
-{
-    switch (n) {
-    case 256: *out = {2, 1}; return true;
-    case 512: *out = {4, 1}; return true;
-    case 1024: *out = {4, 2}; return true;
-    case 2048: *out = {4, 4}; return true;
-    case 4096: *out = {4, 8}; return true;
-    default: return false;
-    }
-}
-
-template <typename T>
-inline bool carousel_backward_supported(int n, long long B)
-{
-    (void)B;
-    CarouselShape s;
-    return std::is_same<T, float>::value && carousel_bwd_shape_for(n, &s);
-}
-
-// Columns per lane: the widest of {8,4,2,1} that still gives the chip about two wavefronts per SIMD.
-inline int carousel_width(long long B, int waves)
-{
-    const long long want_waves = 2048; // 256 CUs x 4 SIMDs x 2
-    for (int w = 8; w > 1; w >>= 1)
-        if (((B + w - 1) / w) * waves >= want_waves) return w;
-    return 1;
-}
-
-struct CarouselFwdArgs {
-    int n;
-    long long B;
-    CarouselCoefs coefs;
-    const float *X;
-    float *Y;
-    int identity, vec_ok;
-    hipStream_t stream;
-};
-
 template <int M, int W, int WAVES, int FORM>
 inline void carousel_launch_fwd(const CarouselFwdArgs &a)
 {
     const long long strips = (a.B + W - 1) / W;
     hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES, FORM>), dim3((unsigned)strips), dim3(64 * WAVES), 0,
-                       a.stream, a.n, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.X, a.Y, a.identity,
-                       a.vec_ok);
+                       a.stream, a.n, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.coefs.scaled_max, a.X, a.Y,
+                       a.identity, a.vec_ok);
 }
 
-template <int M, int WAVES>
-inline int carousel_dispatch_fwd(int W, const CarouselFwdArgs &a)
+template <int M, int WAVES, int FORM>
+inline int carousel_fwd_widths(int W, const CarouselFwdArgs &a)
 {
-#define GIVENS_FWD_CASE(w)                                             \
-    case w:                                                            \
-        if (a.coefs.form == 1) carousel_launch_fwd<M, w, WAVES, 1>(a); \
-        else carousel_launch_fwd<M, w, WAVES, 0>(a);                   \
-        return GIVENS_OK;
     switch (W) {
-        GIVENS_FWD_CASE(8)
-        GIVENS_FWD_CASE(4)
-        GIVENS_FWD_CASE(2)
-        GIVENS_FWD_CASE(1)
+    case 8: carousel_launch_fwd<M, 8, WAVES, FORM>(a); return GIVENS_OK;
+    case 4: carousel_launch_fwd<M, 4, WAVES, FORM>(a); return GIVENS_OK;
+    case 2: carousel_launch_fwd<M, 2, WAVES, FORM>(a); return GIVENS_OK;
+    case 1: carousel_launch_fwd<M, 1, WAVES, FORM>(a); return GIVENS_OK;
     default: return GIVENS_ERR_UNSUPPORTED;
     }
-#undef GIVENS_FWD_CASE
 }
 
-inline int carousel_forward(int n, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
-                            int identity, hipStream_t stream)
+template <int FORM>
+inline int carousel_forward_form(const CarouselFwdArgs &a, CarouselShape s, int W)
 {
-    CarouselShape s;
-    if (!carousel_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
-    const int W = carousel_width(B, s.WAVES);
-    const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
-                         (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
-    const CarouselFwdArgs a{n, B, coefs, X, Y, identity, aligned ? 1 : 0, stream};
-    if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_fwd<2, 1>(W, a);
-    if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_fwd<4, 1>(W, a);
-    if (s.M == 8 && s.WAVES == 1) return carousel_dispatch_fwd<8, 1>(W, a);
-    if (s.M == 8 && s.WAVES == 2) return carousel_dispatch_fwd<8, 2>(W, a);
-    if (s.M == 8 && s.WAVES == 4) return carousel_dispatch_fwd<8, 4>(W, a);
-    if (s.M == 8 && s.WAVES == 8) return carousel_dispatch_fwd<8, 8>(W, a);
+    if (s.M == 2 && s.WAVES == 1) return carousel_fwd_widths<2, 1, FORM>(W, a);
+    if (s.M == 4 && s.WAVES == 1) return carousel_fwd_widths<4, 1, FORM>(W, a);
+    if (s.M == 8 && s.WAVES == 1) return carousel_fwd_widths<8, 1, FORM>(W, a);
+    if (s.M == 8 && s.WAVES == 2) return carousel_fwd_widths<8, 2, FORM>(W, a);
+    if (s.M == 8 && s.WAVES == 4) return carousel_fwd_widths<8, 4, FORM>(W, a);
+    if (s.M == 8 && s.WAVES == 8) return carousel_fwd_widths<8, 8, FORM>(W, a);
     return GIVENS_ERR_UNSUPPORTED;
 }
-
-struct CarouselBwdArgs {
-    int n;
-    long long B, strip0, nstrips, groups;
-    CarouselCoefs coefs;
-    const float *Y, *G;
-    float *dX, *partial;
-    const float *zeros; // N floats that are always zero
-    int vec_ok, accumulate;
-    hipStream_t stream;
-};
 
 template <int M, int W, int WAVES, int FORM>
 inline void carousel_launch_bwd(const CarouselBwdArgs &a)
 {
     hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.groups), dim3(64 * WAVES),
-                       0, a.stream, a.n, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.Y,
-                       a.G, a.dX, a.partial, a.zeros, a.vec_ok, a.accumulate);
+                       0, a.stream, a.n, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
+                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.vec_ok, a.accumulate);
 }
 
-template <int M, int WAVES>
-inline int carousel_dispatch_bwd(int W, const CarouselBwdArgs &a)
+template <int M, int WAVES, int FORM>
+inline int carousel_bwd_widths(int W, const CarouselBwdArgs &a)
 {
-#define GIVENS_BWD_CASE(w)                                             \
-    case w:                                                            \
-        if (a.coefs.form == 1) carousel_launch_bwd<M, w, WAVES, 1>(a); \
-        else carousel_launch_bwd<M, w, WAVES, 0>(a);                   \
-        return GIVENS_OK;
     switch (W) {
-        GIVENS_BWD_CASE(8)
-        GIVENS_BWD_CASE(4)
-        GIVENS_BWD_CASE(2)
-        GIVENS_BWD_CASE(1)
+    case 8: carousel_launch_bwd<M, 8, WAVES, FORM>(a); return GIVENS_OK;
+    case 4: carousel_launch_bwd<M, 4, WAVES, FORM>(a); return GIVENS_OK;
+    case 2: carousel_launch_bwd<M, 2, WAVES, FORM>(a); return GIVENS_OK;
+    case 1: carousel_launch_bwd<M, 1, WAVES, FORM>(a); return GIVENS_OK;
     default: return GIVENS_ERR_UNSUPPORTED;
     }
-#undef GIVENS_BWD_CASE
 }
 
-// lanes per workgroup and slots per lane of the reverse sweep (the layout of the accumulation buffer)
-inline bool carousel_bwd_layout(int n, int *lanes, int *slots)
+template <int FORM>
+inline int carousel_backward_form(const CarouselBwdArgs &a, CarouselShape s, int W)
 {
-    CarouselShape s;
-    if (!carousel_bwd_shape_for(n, &s)) return false;
-    *lanes = 64 * s.WAVES;
-    *slots = s.M;
-    return true;
-}
-
-// Columns per workgroup of the reverse sweep.
-inline int carousel_bwd_width(int n, long long B)
-{
-    CarouselShape s;
-    if (!carousel_bwd_shape_for(n, &s)) return 0;
-    return carousel_width(B, s.WAVES);
-}
-
-// Number of persistent workgroups the reverse sweep runs with: what the chip holds at once (the
-// kernel is limited to two wavefronts per SIMD by its registers), or one per strip if that is fewer.
-inline long long carousel_bwd_groups(int n, long long nstrips, int compute_units)
-{
-    CarouselShape s;
-    if (!carousel_bwd_shape_for(n, &s)) return 0;
-    const long long resident = (long long)compute_units * (8 / s.WAVES > 0 ? 8 / s.WAVES : 1);
-    return nstrips < resident ? nstrips : resident;
-}
-
-// Launches the reverse sweep on strips [strip0, strip0 + nstrips) with `groups` persistent workgroups.
-// accumulate = 0: partial is [groups][N]; workgroup g stores the sums of its first strip in row g and
-// adds those of its later strips to them.  accumulate = 1: partial is one zeroed [N] buffer in the
-// kernel's slot-major order that every strip adds into atomically.  zeros: N floats that stay zero.
-inline int carousel_backward_strips(int n, long long B, int W, long long strip0, long long nstrips,
-                                    long long groups, const CarouselCoefs &coefs, const float *Y, const float *G,
-                                    float *dX, float *partial, const float *zeros, int accumulate,
-                                    hipStream_t stream)
-{
-    CarouselShape s;
-    if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
-    const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
-                         (reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
-                         (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const CarouselBwdArgs a{n, B, strip0, nstrips, groups, coefs, Y, G, dX, partial, zeros, aligned ? 1 : 0, accumulate, stream};
-    if (s.M == 2 && s.WAVES == 1) return carousel_dispatch_bwd<2, 1>(W, a);
-    if (s.M == 4 && s.WAVES == 1) return carousel_dispatch_bwd<4, 1>(W, a);
-    if (s.M == 4 && s.WAVES == 2) return carousel_dispatch_bwd<4, 2>(W, a);
-    if (s.M == 4 && s.WAVES == 4) return carousel_dispatch_bwd<4, 4>(W, a);
-    if (s.M == 4 && s.WAVES == 8) return carousel_dispatch_bwd<4, 8>(W, a);
+    if (s.M == 2 && s.WAVES == 1) return carousel_bwd_widths<2, 1, FORM>(W, a);
+    if (s.M == 4 && s.WAVES == 1) return carousel_bwd_widths<4, 1, FORM>(W, a);
+    if (s.M == 4 && s.WAVES == 2) return carousel_bwd_widths<4, 2, FORM>(W, a);
+    if (s.M == 4 && s.WAVES == 4) return carousel_bwd_widths<4, 4, FORM>(W, a);
+    if (s.M == 4 && s.WAVES == 8) return carousel_bwd_widths<4, 8, FORM>(W, a);
     return GIVENS_ERR_UNSUPPORTED;
 }
 

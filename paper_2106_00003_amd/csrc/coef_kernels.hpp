@@ -19,14 +19,23 @@
 // The result is the same product of Givens rotations (Eq. (2)); only the rounding differs (one
 // rounding per output instead of two).
 //
-// The choice between the two forms is made on the device: theta_range_kernel leaves the bit pattern
-// of max |theta| in a flag word, and every kernel of either form returns at once when the flag says
-// the other form is the one to run.
+// Lifted form (float, any finite angles up to kLiftedMaxAbsTheta).  A rotation is three shears,
+//     a -= t b,   b += s a,   a -= t b,       t = tan(theta/2),  s = sin(theta),
+// i.e. three dependent FMAs instead of 2 MUL + 2 FMA.  To keep |t| <= 1 the angle is first reduced
+// by a multiple of pi, theta = theta' + m*pi with |theta'| <= pi/2, R(theta) = (-1)^m R(theta'), and
+// the signs (-1)^m are carried exactly like the scaled form's cosines: a row's stored value is
+// y_r / d_r with d_r = +-1, the shear coefficients are multiplied by d_a d_b, and the rows are
+// multiplied back by d_r at the same points.  Same scan, same table layout, same sweeps.
+//
+// The choice between the forms is made on the device: theta_range_kernel leaves the bit pattern of
+// max |theta| in a flag word, and every kernel of a form returns at once when the flag says another
+// form is the one to run (form_for_range).
 #pragma once
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 
+#include "forms.hpp"
 #include "rr_index.h"
 
 namespace givens {
@@ -34,17 +43,6 @@ namespace givens {
 template <typename T> struct Pair2;
 template <> struct Pair2<float> { using type = float2; };
 template <> struct Pair2<double> { using type = double2; };
-
-constexpr int kRenormPeriod = 64;                 // blocks between renormalisations of the scaled form
-constexpr float kScaledMaxAbsTheta = 0.78539816f; // scaled form only when every |theta| <= pi/4
-
-// true when the form asked for is the one the flag selects (flag == nullptr: standard form, always)
-__device__ __forceinline__ bool form_selected(const unsigned *flag, bool want_scaled)
-{
-    if (!flag) return !want_scaled;
-    const bool scaled = __uint_as_float(*flag) <= kScaledMaxAbsTheta; // NaN compares false: standard form
-    return scaled == want_scaled;
-}
 
 __global__ void reset_flag_kernel(unsigned *flag) { *flag = 0u; }
 
@@ -116,13 +114,24 @@ __device__ __forceinline__ double sin_small(double x)
     return fma(p * z, x, x);
 }
 
+// Lifted form: theta = theta' + m*pi with |theta'| <= pi/2, so that R(theta) = (-1)^m R(theta') and
+// the three shears of R(theta') have coefficients tan(theta'/2), sin(theta') of magnitude <= 1.
+// Returns theta'; *odd = m is odd.  Used by the scan (signs) and the table (coefficients) alike.
+__device__ __forceinline__ double lift_reduce(double th, bool *odd)
+{
+    const double m = rint(th * 0.31830988618379067154);            // |th| <= 1e6: exact integer
+    *odd = ((long long)m & 1LL) != 0;
+    return fma(-m, 1.2246467991473532e-16, fma(-m, 3.141592653589793116, th)); // pi in two pieces
+}
+
 // Standard form table, in E order.  `factor` (optional) receives the orientation sign (+1 when the
 // top position holds the smaller label) that the dtheta reduction multiplies its sums by.
 template <typename T>
 __global__ void coef_table_kernel(int n, const T *__restrict__ theta, const unsigned *flag,
-                                  typename Pair2<T>::type *__restrict__ table, T *__restrict__ factor)
+                                  float scaled_max, typename Pair2<T>::type *__restrict__ table,
+                                  T *__restrict__ factor)
 {
-    if (!form_selected(flag, false)) return;
+    if (!form_selected(flag, kFormStandard, scaled_max)) return;
     const int H = n >> 1;
     const long long N = (long long)(n - 1) * H;
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < N;
@@ -140,15 +149,18 @@ __global__ void coef_table_kernel(int n, const T *__restrict__ theta, const unsi
     }
 }
 
-// Scaled form, step 1.  One thread per (renormalisation period g, row r): walks the row through the
-// period's blocks in sweep order (FWD: k = n-2, n-3, ...; reverse sweep: k = 0, 1, ...), records the
-// row's factor d *before* each block at D[k][position], and leaves the factor after the period's last
-// block in renorm[g][arc] (.x for the arc's top position, .y for its bottom position).
+// Scaled and lifted forms, step 1.  One thread per (renormalisation period g, row r): walks the row
+// through the period's blocks in sweep order (FWD: k = n-2, n-3, ...; reverse sweep: k = 0, 1, ...),
+// records the row's factor d *before* each block at D[k][position], and leaves the factor after the
+// period's last block in renorm[g][arc] (.x for the arc's top position, .y for its bottom position).
+// A rotation multiplies the factor of both its rows by cos(theta) (scaled form) or by the sign
+// (-1)^m of theta = theta' + m*pi (lifted form).
 template <bool FWD>
 __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const unsigned *flag,
-                                   double *__restrict__ D, float *__restrict__ renorm)
+                                   float scaled_max, double *__restrict__ D, float *__restrict__ renorm)
 {
-    if (!form_selected(flag, true)) return;
+    const int form = selected_form(flag, scaled_max);
+    if (form == kFormStandard) return;
     const int H = n >> 1;
     const int nseg = (n - 1 + kRenormPeriod - 1) / kRenormPeriod;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -163,7 +175,14 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
         q = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1); // position of label r in the sequence of block k
         p = (q < H) ? q : n - 1 - q;
         D[(long long)k * n + q] = d;
-        d *= cos_small((double)theta[(long long)k * H + p]);
+        const double th = (double)theta[(long long)k * H + p];
+        if (form == kFormScaled) {
+            d *= cos_small(th);
+        } else {
+            bool odd;
+            (void)lift_reduce(th, &odd);
+            d = odd ? -d : d;
+        }
     }
     renorm[2 * ((long long)g * H + p) + (q < H ? 0 : 1)] = (float)d;
 }
@@ -173,12 +192,16 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
 // but the factors d differ between the two directions, hence FWD.  For the reverse sweep `factor`
 // receives orientation sign * d_top * d_bot: the sweep sums stored values, and
 // gbar_j z_i - gbar_i z_j = d_i d_j (g~_j z~_i - g~_i z~_j).
+// Lifted form: (T, S) = (tan(theta'/2), sin(theta')) * orientation * d_top * d_bot (the factors are
+// +-1 here): the forward sweep does a -= T b, b += S a, a -= T b on the stored values, the reverse
+// sweep the same with the signs flipped.
 template <bool FWD>
 __global__ void scaled_table_kernel(int n, const float *__restrict__ theta, const unsigned *flag,
-                                    const double *__restrict__ D, float2 *__restrict__ table,
+                                    float scaled_max, const double *__restrict__ D, float2 *__restrict__ table,
                                     float *__restrict__ factor)
 {
-    if (!form_selected(flag, true)) return;
+    const int form = selected_form(flag, scaled_max);
+    if (form == kFormStandard) return;
     const int H = n >> 1;
     const long long N = (long long)(n - 1) * H;
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -186,13 +209,22 @@ __global__ void scaled_table_kernel(int n, const float *__restrict__ theta, cons
     const int k = (int)(e / H), p = (int)(e % H);
     const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
     const double th = (double)theta[e];
-    double s = sin_small(th);
-    const double c = cos_small(th);
-    if (a > b) s = -s;
     const double da = D[(long long)k * n + p], db = D[(long long)k * n + (n - 1 - p)]; // before this block
-    const double inv = s / (c * da * db);                // tan(theta) / (d_top d_bot)
-    table[e] = make_float2((float)(inv * db * db), (float)(inv * da * da));
-    if (!FWD && factor) factor[e] = (float)((a < b ? 1.0 : -1.0) * da * db);
+    const double orient = (a < b) ? 1.0 : -1.0;
+    if (form == kFormScaled) {
+        const double s = orient * sin_small(th);
+        const double c = cos_small(th);
+        const double inv = s / (c * da * db);            // tan(theta) / (d_top d_bot)
+        table[e] = make_float2((float)(inv * db * db), (float)(inv * da * da));
+    } else {
+        bool odd;
+        const double red = lift_reduce(th, &odd);
+        double s, c;
+        sincos(red, &s, &c);
+        const double sg = orient * da * db;
+        table[e] = make_float2((float)(sg * s / (1.0 + c)), (float)(sg * s)); // tan(x/2) = sin x / (1 + cos x)
+    }
+    if (!FWD && factor) factor[e] = (float)(orient * da * db);
 }
 
 // Second stage of the gradient reduction: dtheta[e] (+)= factor[e] * sum over strips s of

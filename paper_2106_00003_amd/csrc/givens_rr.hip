@@ -9,7 +9,8 @@
 #include <vector>
 
 #include "../../include/givens_rr.h"
-#include "carousel_kernels.hpp"
+#include "carousel_host.hpp"
+#include "coef_kernels.hpp"
 #include "lds_kernels.hpp"
 #include "rr_index.h"
 
@@ -53,7 +54,8 @@ struct ThreadState {
     int last_hip_error = 0;
     int last_kernel = 0;
     int last_reduction = 0;
-    const unsigned *last_flag = nullptr; // device flag of the last call when both forms were launched
+    const unsigned *last_flag = nullptr; // device flag of the last call when several forms were launched
+    float last_scaled_max = 0.f;         // that call's threshold for the scaled form
     hipStream_t last_stream = nullptr;
     bool timing_valid = false;
     std::vector<TimedSpan> spans;
@@ -151,17 +153,33 @@ template <typename T>
 struct Coefs {
     const typename Pair2<T>::type *table = nullptr; // standard form
     const T *factor = nullptr;                      // reverse sweep only
-    CarouselCoefs standard{0, nullptr, nullptr, nullptr};
-    CarouselCoefs scaled{1, nullptr, nullptr, nullptr};
-    bool both_forms = false;                        // scaled-form kernels were launched too
+    CarouselCoefs standard{kFormStandard, nullptr, nullptr, nullptr, 0.f};
+    CarouselCoefs scaled{kFormScaled, nullptr, nullptr, nullptr, 0.f};
+    CarouselCoefs lifted{kFormLifted, nullptr, nullptr, nullptr, 0.f};
+    bool all_forms = false;                         // scaled- and lifted-form kernels were launched too
 };
 
-// Launches the coefficient kernels.  `forward` picks the sweep direction of the scaled form's row
-// factors; `try_scaled` adds the range check and the scaled-form tables (float carousel path only).
+// What the process-wide form setting means for a call on the float carousel path: whether the range
+// check and the scaled / lifted tables are wanted, and the threshold of the scaled form.
+struct FormPolicy {
+    bool try_forms;
+    float scaled_max;
+};
+FormPolicy form_policy(bool float_carousel)
+{
+    if (!float_carousel || g_form_choice == GIVENS_FORM_STANDARD) return {false, 0.f};
+    if (g_form_choice == GIVENS_FORM_LIFTED) return {true, -1.f};
+    return {true, kScaledMaxAbsTheta};
+}
+
+// Launches the coefficient kernels.  `forward` picks the sweep direction of the scaled / lifted
+// forms' row factors; `policy.try_forms` adds the range check and those forms' tables.
 template <typename T>
-int prepare_coefs(int dev, int n, const T *theta, bool forward, bool try_scaled, hipStream_t stream,
+int prepare_coefs(int dev, int n, const T *theta, bool forward, FormPolicy policy, hipStream_t stream,
                   Coefs<T> *out)
 {
+    const bool try_scaled = policy.try_forms;
+    const float scaled_max = policy.scaled_max;
     using P2 = typename Pair2<T>::type;
     const long long N = (long long)n * (n - 1) / 2;
     Workspace &ws = g_ws[dev];
@@ -191,26 +209,28 @@ int prepare_coefs(int dev, int n, const T *theta, bool forward, bool try_scaled,
             const unsigned scan_blocks = (unsigned)((scan_threads + threads - 1) / threads);
             if (forward) {
                 hipLaunchKernelGGL(scaled_scan_kernel<true>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
-                                   flag, D, rn);
+                                   flag, scaled_max, D, rn);
                 hipLaunchKernelGGL(scaled_table_kernel<true>, dim3(blocks), dim3(threads), 0, stream, n, theta,
-                                   flag, D, tab_s, factor);
+                                   flag, scaled_max, D, tab_s, factor);
             } else {
                 hipLaunchKernelGGL(scaled_scan_kernel<false>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
-                                   flag, D, rn);
+                                   flag, scaled_max, D, rn);
                 hipLaunchKernelGGL(scaled_table_kernel<false>, dim3(blocks), dim3(threads), 0, stream, n, theta,
-                                   flag, D, tab_s, factor);
+                                   flag, scaled_max, D, tab_s, factor);
             }
-            out->scaled = CarouselCoefs{1, tab_s, reinterpret_cast<const float2 *>(rn), flag};
-            out->both_forms = true;
+            out->scaled = CarouselCoefs{kFormScaled, tab_s, reinterpret_cast<const float2 *>(rn), flag, scaled_max};
+            out->lifted = CarouselCoefs{kFormLifted, tab_s, reinterpret_cast<const float2 *>(rn), flag, scaled_max};
+            out->all_forms = true;
         }
-        out->standard = CarouselCoefs{0, table, nullptr, flag};
+        out->standard = CarouselCoefs{kFormStandard, table, nullptr, flag, scaled_max};
     }
     hipLaunchKernelGGL(coef_table_kernel<T>, dim3(std::min(blocks, 4096u)), dim3(threads), 0, stream, n, theta,
-                       static_cast<const unsigned *>(flag), table, factor);
+                       static_cast<const unsigned *>(flag), scaled_max, table, factor);
     GIVENS_HIP(hipGetLastError());
     out->table = table;
     out->factor = factor;
     t_state.last_flag = flag;
+    t_state.last_scaled_max = scaled_max;
     t_state.last_stream = stream;
     return GIVENS_OK;
 }
@@ -289,10 +309,14 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
                 Span span(1, stream);
                 hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(threads), 0, stream, N, acc);
                 const long long groups = carousel_bwd_groups(n, strips, cus);
-                if (coefs.both_forms)
+                if (coefs.all_forms) {
                     if (int rc = carousel_backward_strips(n, B, w, 0, strips, groups, coefs.scaled, Y, G, dX, acc, zeros, 1,
                                                           stream))
                         return rc;
+                    if (int rc = carousel_backward_strips(n, B, w, 0, strips, groups, coefs.lifted, Y, G, dX, acc, zeros, 1,
+                                                          stream))
+                        return rc;
+                }
                 if (int rc = carousel_backward_strips(n, B, w, 0, strips, groups, coefs.standard, Y, G, dX, acc, zeros, 1,
                                                       stream))
                     return rc;
@@ -329,10 +353,14 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
                 hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, B, w, s0,
                                    coefs.table, Y, G, dX, partial);
             } else if constexpr (std::is_same<T, float>::value) {
-                if (coefs.both_forms)
+                if (coefs.all_forms) {
                     if (int rc = carousel_backward_strips(n, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX, partial, zeros, 0,
                                                           stream))
                         return rc;
+                    if (int rc = carousel_backward_strips(n, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX, partial, zeros, 0,
+                                                          stream))
+                        return rc;
+                }
                 if (int rc = carousel_backward_strips(n, B, w, s0, ns, nrows, coefs.standard, Y, G, dX, partial, zeros, 0,
                                                       stream))
                     return rc;
@@ -375,14 +403,17 @@ int forward_impl(int n, long long B, const T *theta, const T *X, T *Y, int ident
     if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
     const bool use_carousel = can_carousel && choice != GIVENS_KERNEL_LDS;
     Coefs<T> coefs;
-    if (int rc = prepare_coefs<T>(dev, n, theta, true, use_carousel && g_form_choice == GIVENS_FORM_AUTO, stream,
-                                  &coefs))
+    if (int rc = prepare_coefs<T>(dev, n, theta, true, form_policy(use_carousel && std::is_same<T, float>::value),
+                                  stream, &coefs))
         return rc;
     int rc = GIVENS_OK;
     if (use_carousel) {
         if constexpr (std::is_same<T, float>::value) {
             Span span(1, stream);
-            if (coefs.both_forms) rc = carousel_forward(n, B, coefs.scaled, X, Y, identity, stream);
+            if (coefs.all_forms) {
+                rc = carousel_forward(n, B, coefs.scaled, X, Y, identity, stream);
+                if (rc == GIVENS_OK) rc = carousel_forward(n, B, coefs.lifted, X, Y, identity, stream);
+            }
             if (rc == GIVENS_OK) rc = carousel_forward(n, B, coefs.standard, X, Y, identity, stream);
             if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
         } else {
@@ -415,8 +446,8 @@ int backward_impl(int n, long long B, const T *theta, const T *Y, const T *G, T 
     const int family = (can_carousel && choice != GIVENS_KERNEL_LDS) ? GIVENS_KERNEL_CAROUSEL : GIVENS_KERNEL_LDS;
     Coefs<T> coefs;
     if (int rc = prepare_coefs<T>(dev, n, theta, false,
-                                  family == GIVENS_KERNEL_CAROUSEL && g_form_choice == GIVENS_FORM_AUTO, stream,
-                                  &coefs))
+                                  form_policy(family == GIVENS_KERNEL_CAROUSEL && std::is_same<T, float>::value),
+                                  stream, &coefs))
         return rc;
     const int rc = backward_chunks<T>(dev, family, n, B, coefs, Y, G, dX, dtheta, stream);
     t_state.last_kernel = family;
@@ -535,7 +566,8 @@ int givens_last_reduction(void) { return givens::t_state.last_reduction; }
 
 int givens_set_rotation_form(int which)
 {
-    if (which != GIVENS_FORM_AUTO && which != GIVENS_FORM_STANDARD) return GIVENS_ERR_UNSUPPORTED;
+    if (which != GIVENS_FORM_AUTO && which != GIVENS_FORM_STANDARD && which != GIVENS_FORM_LIFTED)
+        return GIVENS_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(givens::g_mutex);
     const int prev = givens::g_form_choice;
     givens::g_form_choice = which;
@@ -554,7 +586,11 @@ int givens_last_rotation_form(void)
     float max_abs;
     static_assert(sizeof(max_abs) == sizeof(bits), "");
     __builtin_memcpy(&max_abs, &bits, sizeof(bits));
-    return (max_abs <= kScaledMaxAbsTheta) ? GIVENS_FORM_SCALED : GIVENS_FORM_STANDARD;
+    switch (form_for_range(max_abs, ts.last_scaled_max)) {
+    case kFormScaled: return GIVENS_FORM_SCALED;
+    case kFormLifted: return GIVENS_FORM_LIFTED;
+    default: return GIVENS_FORM_STANDARD;
+    }
 }
 
 int givens_set_timing(int on)

@@ -50,7 +50,7 @@ def test_full_size_forward_backward(cfg):
     th, X, G = data["theta"], data["X"], data["G"]
     print(f"[fullsize] config {cfg}: n={n} B={B} seed={inputs.BASE_SEED + cfg}", flush=True)
     th_d, x_d, g_d = (torch.from_numpy(a).cuda() for a in (th, X, G))
-    want_form = binding.FORM_SCALED if wl.theta_dist == "normal0.1" else binding.FORM_STANDARD
+    want_form = binding.FORM_SCALED if wl.theta_dist == "normal0.1" else binding.FORM_LIFTED
     y_d = binding.givens_forward(th_d, x_d)
     assert binding.last_kernel() == binding.KERNEL_CAROUSEL
     assert binding.last_rotation_form() == want_form

@@ -154,10 +154,54 @@ def test_rotation_form_switches_at_the_angle_threshold():
     assert binding.last_rotation_form() == binding.FORM_SCALED
     theta[777] = np.float32(-0.80)                                     # one angle beyond pi/4
     check_forward_backward(theta, data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G)
+    assert binding.last_rotation_form() == binding.FORM_LIFTED
+    theta[777] = np.float32(2.0e6)                                     # beyond the lifted form's range
+    check_forward_backward(theta, data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G)
     assert binding.last_rotation_form() == binding.FORM_STANDARD
-    theta[777] = np.float32("nan")                                     # NaN must not select the scaled form
-    binding.givens_forward(dev(theta), dev(data["X"]))
-    assert binding.last_rotation_form() == binding.FORM_STANDARD
+    for bad in ("nan", "inf"):                                         # must select neither special form
+        theta[777] = np.float32(bad)
+        binding.givens_forward(dev(theta), dev(data["X"]))
+        assert binding.last_rotation_form() == binding.FORM_STANDARD
+
+
+# ---------------------------------------------------------------- lifted rotation form (general angles)
+@pytest.mark.parametrize("n,B,seed", [(256, 64, 81), (512, 100, 82), (1024, 67, 83), (2048, 130, 84)])
+def test_lifted_form_is_used_for_general_angles_and_matches_the_oracle(n, B, seed):
+    data = inputs.make_custom(n, B, seed=seed)                         # theta uniform in [-pi, pi)
+    binding.set_rotation_form(binding.FORM_AUTO)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G,
+                           binding.KERNEL_CAROUSEL)
+    assert binding.last_rotation_form() == binding.FORM_LIFTED
+    try:
+        binding.set_rotation_form(binding.FORM_STANDARD)
+        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G)
+        assert binding.last_rotation_form() == binding.FORM_STANDARD
+    finally:
+        binding.set_rotation_form(binding.FORM_AUTO)
+
+
+def test_lifted_form_at_the_edges_of_the_angle_reduction():
+    """Angles on and next to the multiples of pi/2 where the reduction modulo pi changes branch, angles
+    of many turns, and the lifted form forced on near-identity angles."""
+    n, B = 512, 40
+    data = inputs.make_custom(n, B, seed=85)
+    theta = data["theta"].copy()
+    pi = np.float32(np.pi)
+    special = [pi / 2, -pi / 2, np.nextafter(pi / 2, np.float32(4)), np.nextafter(-pi / 2, np.float32(-4)),
+               pi, -pi, np.float32(1.5) * pi, np.float32(-1.5) * pi, np.float32(3) * pi, np.float32(100.25) * pi,
+               np.float32(-999.5) * pi, np.float32(12345.678), np.float32(-9.9e5), np.float32(0), np.float32(1e-30)]
+    rng = np.random.default_rng(85)
+    where = rng.choice(theta.size, size=8 * len(special), replace=False)
+    theta[where] = np.tile(np.array(special, dtype=np.float32), 8)
+    check_forward_backward(theta, data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G)
+    assert binding.last_rotation_form() == binding.FORM_LIFTED
+    small = inputs.make_custom(n, B, seed=86, theta_dist="normal0.1")
+    try:
+        binding.set_rotation_form(binding.FORM_LIFTED)
+        check_forward_backward(small["theta"], small["X"], small["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G)
+        assert binding.last_rotation_form() == binding.FORM_LIFTED
+    finally:
+        binding.set_rotation_form(binding.FORM_AUTO)
 
 
 # ---------------------------------------------------------------- the two cross-strip reductions
