@@ -28,6 +28,11 @@ def lib():
         L.oracle_reverse_sweep.argtypes = [ctypes.c_int, ctypes.c_long, dp, ip, dp, dp, dp, dp, dp,
                                            ctypes.c_int]
         L.oracle_grad_theta_alg3.argtypes = [ctypes.c_int, dp, ip, dp, dp, dp, ctypes.c_int]
+        L.oracle_forward_pairs.argtypes = [ctypes.c_int, ctypes.c_long, ctypes.c_long, dp, ip, dp, dp, ctypes.c_int]
+        L.oracle_grad_operand_pairs.argtypes = [ctypes.c_int, ctypes.c_long, ctypes.c_long, dp, ip, dp, dp,
+                                                ctypes.c_int]
+        L.oracle_reverse_sweep_pairs.argtypes = [ctypes.c_int, ctypes.c_long, ctypes.c_long, dp, ip, dp, dp, dp,
+                                                 dp, dp, ctypes.c_int]
         L.oracle_num_threads.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -107,6 +112,55 @@ def grad_theta_alg3(theta, U, Gamma, pairs=None, threads: int = 0) -> np.ndarray
     _check(lib().oracle_grad_theta_alg3(n, _d(theta), pp, _d(u64), _d(g64), _d(dth), threads),
            "oracle_grad_theta_alg3")
     return dth
+
+
+# ---- any sequence E of pairs, any n >= 2 (restricted parametrisation, odd n)
+def _free(pairs):
+    pairs = np.ascontiguousarray(pairs, dtype=np.int32).reshape(-1, 2)
+    return pairs, pairs.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def forward_pairs(theta, X, pairs, n=None, threads: int = 0) -> np.ndarray:
+    """Algorithm 1 over the listed pairs (E order) from operand X; X=None builds U from I_n."""
+    theta = _f64(theta).reshape(-1)
+    if X is None:
+        B, x64 = n, None
+    else:
+        x64 = _f64(X)
+        n, B = x64.shape
+    keep, pp = _free(pairs)
+    assert keep.shape[0] == theta.size
+    Y = np.empty((n, B), dtype=np.float64)
+    _check(lib().oracle_forward_pairs(n, B, theta.size, _d(theta), pp, _d(x64), _d(Y), threads),
+           "oracle_forward_pairs")
+    return Y
+
+
+def grad_operand_pairs(theta, G, pairs, threads: int = 0) -> np.ndarray:
+    theta = _f64(theta).reshape(-1)
+    g64 = _f64(G)
+    n, B = g64.shape
+    keep, pp = _free(pairs)
+    assert keep.shape[0] == theta.size
+    dX = np.empty((n, B), dtype=np.float64)
+    _check(lib().oracle_grad_operand_pairs(n, B, theta.size, _d(theta), pp, _d(g64), _d(dX), threads),
+           "oracle_grad_operand_pairs")
+    return dX
+
+
+def reverse_sweep_pairs(theta, Y, G, pairs, threads: int = 0, want_dx=True, want_x=True):
+    """Returns (dtheta, dX or None, X_recovered or None) for the listed pairs."""
+    theta = _f64(theta).reshape(-1)
+    y64, g64 = _f64(Y), _f64(G)
+    n, B = y64.shape
+    keep, pp = _free(pairs)
+    assert keep.shape[0] == theta.size
+    dth = np.empty(theta.size, dtype=np.float64)
+    dX = np.empty((n, B), dtype=np.float64) if want_dx else None
+    Xr = np.empty((n, B), dtype=np.float64) if want_x else None
+    _check(lib().oracle_reverse_sweep_pairs(n, B, theta.size, _d(theta), pp, _d(y64), _d(g64), _d(dth), _d(dX),
+                                            _d(Xr), threads), "oracle_reverse_sweep_pairs")
+    return dth, dX, Xr
 
 
 def num_threads() -> int:

@@ -19,6 +19,9 @@
  *   oracle_reverse_sweep     operand-side gradient: for block k = 1..n-1, first
  *                            dtheta_e = sum_b (gbar_j z_i - gbar_i z_j), then z, gbar <- G^{b_k}^T z, gbar
  *                            (Section 4.1: dU/dtheta_e = U^{1:k-1} Q_e U^{k:n-1})
+ *   oracle_*_pairs           the three routines above for any sequence E of pairs and any n >= 2:
+ *                            the free pairs of a restricted parametrisation (Section 5) or of
+ *                            odd n (end of Section 3), listed by oracle/restricted_oracle.py
  *   oracle_grad_theta_alg3   Algorithm 3 with the (parallel) index l taken outermost:
  *                            per l, row l of U^fwd and column l of M are rotated for the
  *                            block, then A[m(e), l] = M[i,l] u[l,j] - M[j,l] u[l,i];
@@ -105,13 +108,13 @@ static void store_group(int n, long B, double *dst, long b0, int w, const double
         for (int x = 0; x < w; ++x) dst[(size_t)r * B + b0 + x] = buf[(size_t)r * CB + x];
 }
 
-/* Algorithm 1.  X == NULL means the operand is I_n (then B must equal n). */
-int oracle_forward(int n, long B, const double *theta, const int32_t *pairs,
-                   const double *X, double *Y, int nthreads)
+/* Algorithm 1 over a given sequence E of `count` pairs.  X == NULL means the operand is I_n (then B
+ * must equal n). */
+static int forward_impl(int n, long B, long count, const double *theta, const int32_t *pairs,
+                        const double *X, double *Y, int nthreads)
 {
-    if (bad_n(n) || B < 1 || !theta || !pairs || !Y) return -1;
+    if (n < 2 || count < 0 || B < 1 || !theta || !pairs || !Y) return -1;
     if (!X && B != n) return -1;
-    long count = (long)n * (n - 1) / 2;
     double *c, *s;
     if (make_cs(count, theta, &c, &s)) return -2;
     set_threads(nthreads);
@@ -153,12 +156,26 @@ int oracle_forward(int n, long B, const double *theta, const int32_t *pairs,
     return fail ? -2 : 0;
 }
 
-/* dL/dX = U^T G: G^{e_1}^T applies first, so the loop runs over E in order. */
-int oracle_grad_operand(int n, long B, const double *theta, const int32_t *pairs,
-                        const double *G, double *dX, int nthreads)
+int oracle_forward(int n, long B, const double *theta, const int32_t *pairs,
+                   const double *X, double *Y, int nthreads)
 {
-    if (bad_n(n) || B < 1 || !theta || !pairs || !G || !dX) return -1;
-    long count = (long)n * (n - 1) / 2;
+    if (bad_n(n)) return -1;
+    return forward_impl(n, B, (long)n * (n - 1) / 2, theta, pairs, X, Y, nthreads);
+}
+
+/* The same for the free pairs of a restricted parametrisation or of odd n (Section 5; end of
+ * Section 3): E is whatever sequence of pairs the caller lists, any n >= 2. */
+int oracle_forward_pairs(int n, long B, long count, const double *theta, const int32_t *pairs,
+                         const double *X, double *Y, int nthreads)
+{
+    return forward_impl(n, B, count, theta, pairs, X, Y, nthreads);
+}
+
+/* dL/dX = U^T G: G^{e_1}^T applies first, so the loop runs over E in order. */
+static int grad_operand_impl(int n, long B, long count, const double *theta, const int32_t *pairs,
+                             const double *G, double *dX, int nthreads)
+{
+    if (n < 2 || count < 0 || B < 1 || !theta || !pairs || !G || !dX) return -1;
     double *c, *s;
     if (make_cs(count, theta, &c, &s)) return -2;
     set_threads(nthreads);
@@ -197,13 +214,25 @@ int oracle_grad_operand(int n, long B, const double *theta, const int32_t *pairs
     return fail ? -2 : 0;
 }
 
-/* Operand-side gradient sweep.  dX and Xrec may be NULL.  dtheta has n(n-1)/2 entries. */
-int oracle_reverse_sweep(int n, long B, const double *theta, const int32_t *pairs,
-                         const double *Y, const double *G, double *dtheta,
-                         double *dX, double *Xrec, int nthreads)
+int oracle_grad_operand(int n, long B, const double *theta, const int32_t *pairs,
+                        const double *G, double *dX, int nthreads)
 {
-    if (bad_n(n) || B < 1 || !theta || !pairs || !Y || !G || !dtheta) return -1;
-    long count = (long)n * (n - 1) / 2;
+    if (bad_n(n)) return -1;
+    return grad_operand_impl(n, B, (long)n * (n - 1) / 2, theta, pairs, G, dX, nthreads);
+}
+
+int oracle_grad_operand_pairs(int n, long B, long count, const double *theta, const int32_t *pairs,
+                              const double *G, double *dX, int nthreads)
+{
+    return grad_operand_impl(n, B, count, theta, pairs, G, dX, nthreads);
+}
+
+/* Operand-side gradient sweep over a sequence E of `count` pairs.  dX and Xrec may be NULL. */
+static int reverse_sweep_impl(int n, long B, long count, const double *theta, const int32_t *pairs,
+                              const double *Y, const double *G, double *dtheta,
+                              double *dX, double *Xrec, int nthreads)
+{
+    if (n < 2 || count < 0 || B < 1 || !theta || !pairs || !Y || !G || !dtheta) return -1;
     double *c, *s;
     if (make_cs(count, theta, &c, &s)) return -2;
     set_threads(nthreads);
@@ -266,6 +295,23 @@ int oracle_reverse_sweep(int n, long B, const double *theta, const int32_t *pair
     }
     free(acc); free(c); free(s);
     return fail ? -2 : 0;
+}
+
+/* dtheta has n(n-1)/2 entries. */
+int oracle_reverse_sweep(int n, long B, const double *theta, const int32_t *pairs,
+                         const double *Y, const double *G, double *dtheta,
+                         double *dX, double *Xrec, int nthreads)
+{
+    if (bad_n(n)) return -1;
+    return reverse_sweep_impl(n, B, (long)n * (n - 1) / 2, theta, pairs, Y, G, dtheta, dX, Xrec, nthreads);
+}
+
+/* dtheta has `count` entries, one per listed pair. */
+int oracle_reverse_sweep_pairs(int n, long B, long count, const double *theta, const int32_t *pairs,
+                               const double *Y, const double *G, double *dtheta,
+                               double *dX, double *Xrec, int nthreads)
+{
+    return reverse_sweep_impl(n, B, count, theta, pairs, Y, G, dtheta, dX, Xrec, nthreads);
 }
 
 /* Algorithm 3.  U and Gamma are n x n row-major.  For a fixed l the algorithm touches
