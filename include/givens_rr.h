@@ -43,6 +43,7 @@ extern "C" {
 #define GIVENS_ERR_HIP (-4)         /* a HIP call failed; see givens_last_hip_error()   */
 #define GIVENS_ERR_UNSUPPORTED (-5) /* shape not supported by the requested kernel      */
 #define GIVENS_ERR_ALIAS (-6)       /* forbidden aliasing between arguments             */
+#define GIVENS_ERR_BAD_M (-7)       /* restricted entry points: m outside 1..n-1        */
 
 /* Kernel families (givens_set_kernel). */
 #define GIVENS_KERNEL_AUTO 0     /* register carousel where the shape allows, else LDS strip */
@@ -105,6 +106,37 @@ int givens_forward_f64(int n, int64_t B, const double *theta, const double *X, d
 int givens_build_f64(int n, const double *theta, double *U, void *stream);
 int givens_backward_f64(int n, int64_t B, const double *theta, const double *Y, const double *G,
                         double *dX, double *dtheta, void *stream);
+
+/*
+ * Restricted parametrisation and odd n.
+ *
+ * Section 5 of the paper ("Restricting the Parametrization"): for an integer 1 <= m <= n-1 no
+ * rotation is performed among the coordinates m..n-1, i.e. of the pairs (i, j), i < j, only those
+ * with i < m are free: N(n, m) = m n - m (m + 1) / 2 angles (n = 8, m = 4: 22).  The blocks are still
+ * the n-1 blocks of the circle method; the pairs that are not free are bypassed.  m = n-1 is the
+ * unrestricted case.  End of Section 3 (and of Section 4.2 for the gradient): odd n is run on the
+ * circle method's sequence for n+1 dimensions, bypassing every pair that contains the added one, so
+ * there are n blocks of at most (n-1)/2 pairs.  Both conditions combine.
+ *
+ * These entry points accept any n >= 2, odd or even.  theta and dtheta have N(n, m) entries: the
+ * free pairs in the order in which the sequence E lists them (rr_schedule_restricted).  The kernels
+ * run a bypassed pair as a rotation by zero, so the cost is that of the unrestricted problem of
+ * n (or n+1) dimensions.  Everything else -- layouts, aliasing, streams, errors -- is as for the
+ * unrestricted entry points; m outside 1..n-1 returns GIVENS_ERR_BAD_M.  The pair map is built on
+ * the host and copied to the device (synchronously) the first time a given (n, m) is used.
+ */
+int64_t givens_num_angles(int n, int m);                         /* N(n, m), or a negative error code  */
+int rr_schedule_restricted(int n, int m, int32_t *pairs);        /* HOST buffer of N(n, m) * 2 int32   */
+int givens_forward_restricted(int n, int m, int64_t B, const float *theta, const float *X, float *Y,
+                              void *stream);
+int givens_build_restricted(int n, int m, const float *theta, float *U, void *stream);
+int givens_backward_restricted(int n, int m, int64_t B, const float *theta, const float *Y, const float *G,
+                               float *dX, float *dtheta, void *stream);
+int givens_forward_restricted_f64(int n, int m, int64_t B, const double *theta, const double *X, double *Y,
+                                  void *stream);
+int givens_build_restricted_f64(int n, int m, const double *theta, double *U, void *stream);
+int givens_backward_restricted_f64(int n, int m, int64_t B, const double *theta, const double *Y,
+                                   const double *G, double *dX, double *dtheta, void *stream);
 
 /* Frees every workspace the library holds (all devices).  Synchronises the devices it touches. */
 int givens_release(void);

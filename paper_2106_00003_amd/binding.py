@@ -25,6 +25,9 @@ EXPORTS = [
     "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
     "givens_set_rotation_form", "givens_last_rotation_form",
     "givens_set_reduction", "givens_last_reduction",
+    "givens_num_angles", "rr_schedule_restricted",
+    "givens_forward_restricted", "givens_build_restricted", "givens_backward_restricted",
+    "givens_forward_restricted_f64", "givens_build_restricted_f64", "givens_backward_restricted_f64",
 ]
 
 _lib = None
@@ -57,6 +60,14 @@ def lib():
         getattr(L, name).argtypes = [i32, vp, vp, vp]
     for name in ("givens_backward", "givens_backward_f64"):
         getattr(L, name).argtypes = [i32, i64, vp, vp, vp, vp, vp, vp]
+    L.givens_num_angles.argtypes = [i32, i32]
+    L.rr_schedule_restricted.argtypes = [i32, i32, vp]
+    for name in ("givens_forward_restricted", "givens_forward_restricted_f64"):
+        getattr(L, name).argtypes = [i32, i32, i64, vp, vp, vp, vp]
+    for name in ("givens_build_restricted", "givens_build_restricted_f64"):
+        getattr(L, name).argtypes = [i32, i32, vp, vp, vp]
+    for name in ("givens_backward_restricted", "givens_backward_restricted_f64"):
+        getattr(L, name).argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
     L.givens_error_string.argtypes = [i32]
     L.givens_error_string.restype = ctypes.c_char_p
     L.givens_set_kernel.argtypes = [i32]
@@ -65,8 +76,9 @@ def lib():
     L.givens_set_timing.argtypes = [i32]
     L.givens_last_timing.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for name in EXPORTS:
-        if name != "givens_error_string":
+        if name not in ("givens_error_string", "givens_num_angles"):
             getattr(L, name).restype = i32
+    L.givens_num_angles.restype = i64
     _lib = L
     return L
 
@@ -152,6 +164,67 @@ def givens_backward(theta, Y, G, dX=None, dtheta=None, want_dx: bool = True, str
     _check(fn(n, B, _dev(theta, "theta", Y.dtype), _dev(Y, "Y"), _dev(G, "G", Y.dtype),
               _dev(dX, "dX", Y.dtype), _dev(dtheta, "dtheta", Y.dtype), _stream_ptr(stream)),
            "givens_backward")
+    return dX, dtheta
+
+
+def num_angles(n: int, m: int | None = None) -> int:
+    """Free angles of the parametrisation restricted to pairs (i, j), i < min(j, m); m=None: unrestricted."""
+    rc = lib().givens_num_angles(n, n - 1 if m is None else m)
+    if rc < 0:
+        raise GivensError(int(rc), "givens_num_angles")
+    return int(rc)
+
+
+def rr_schedule_restricted(n: int, m: int | None = None) -> np.ndarray:
+    """Host call: (N, 2) int32 array of the free pairs (i < j) in E order; any n >= 2."""
+    m = n - 1 if m is None else m
+    count = num_angles(n, m)
+    out = np.empty((count, 2), dtype=np.int32)
+    _check(lib().rr_schedule_restricted(n, m, out.ctypes.data_as(ctypes.c_void_p)), "rr_schedule_restricted")
+    return out
+
+
+def givens_forward_restricted(theta, X, m: int, Y=None, stream=None):
+    """Y = U(theta) X with only the pairs (i, j), i < m, free (any n >= 2)."""
+    import torch
+    n, B = X.shape
+    if theta.numel() != num_angles(n, m):
+        raise ValueError("theta must have m n - m (m + 1) / 2 entries")
+    if Y is None:
+        Y = torch.empty_like(X)
+    fn = getattr(lib(), "givens_forward_restricted" + _suffix(X))
+    _check(fn(n, m, B, _dev(theta, "theta", X.dtype), _dev(X, "X"), _dev(Y, "Y", X.dtype), _stream_ptr(stream)),
+           "givens_forward_restricted")
+    return Y
+
+
+def givens_build_restricted(theta, n: int, m: int, U=None, stream=None):
+    import torch
+    if theta.numel() != num_angles(n, m):
+        raise ValueError("theta must have m n - m (m + 1) / 2 entries")
+    if U is None:
+        U = torch.empty((n, n), dtype=theta.dtype, device=theta.device)
+    fn = getattr(lib(), "givens_build_restricted" + _suffix(theta))
+    _check(fn(n, m, _dev(theta, "theta"), _dev(U, "U", theta.dtype), _stream_ptr(stream)),
+           "givens_build_restricted")
+    return U
+
+
+def givens_backward_restricted(theta, Y, G, m: int, dX=None, dtheta=None, want_dx: bool = True, stream=None):
+    import torch
+    n, B = Y.shape
+    if theta.numel() != num_angles(n, m):
+        raise ValueError("theta must have m n - m (m + 1) / 2 entries")
+    if G.shape != Y.shape:
+        raise ValueError("G must have the shape of Y")
+    if dX is None and want_dx:
+        dX = torch.empty_like(G)
+    if dtheta is None:
+        dtheta = torch.empty_like(theta)
+    fn = getattr(lib(), "givens_backward_restricted" + _suffix(Y))
+    _check(fn(n, m, B, _dev(theta, "theta", Y.dtype), _dev(Y, "Y"), _dev(G, "G", Y.dtype),
+              _dev(dX, "dX", Y.dtype), _dev(dtheta, "dtheta", Y.dtype), _stream_ptr(stream)),
+           "givens_backward_restricted")
     return dX, dtheta
 
 

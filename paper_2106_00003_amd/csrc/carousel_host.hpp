@@ -79,7 +79,7 @@ inline int carousel_width(long long B, int waves)
 }
 
 struct CarouselFwdArgs {
-    int n;
+    int n, rows; // rows: the operand's row count (n, or n - 1 when n pads an odd problem)
     long long B;
     CarouselCoefs coefs;
     const float *X;
@@ -89,7 +89,7 @@ struct CarouselFwdArgs {
 };
 
 struct CarouselBwdArgs {
-    int n;
+    int n, rows;
     long long B, strip0, nstrips, groups;
     CarouselCoefs coefs;
     const float *Y, *G;
@@ -108,7 +108,7 @@ int carousel_backward_standard(const CarouselBwdArgs &a, CarouselShape s, int W)
 int carousel_backward_scaled(const CarouselBwdArgs &a, CarouselShape s, int W);
 int carousel_backward_lifted(const CarouselBwdArgs &a, CarouselShape s, int W);
 
-inline int carousel_forward(int n, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
+inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
                             int identity, hipStream_t stream)
 {
     CarouselShape s;
@@ -116,7 +116,7 @@ inline int carousel_forward(int n, long long B, const CarouselCoefs &coefs, cons
     const int W = carousel_width(B, s.WAVES);
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
-    const CarouselFwdArgs a{n, B, coefs, X, Y, identity, aligned ? 1 : 0, stream};
+    const CarouselFwdArgs a{n, rows, B, coefs, X, Y, identity, aligned ? 1 : 0, stream};
     switch (coefs.form) {
     case kFormScaled: return carousel_forward_scaled(a, s, W);
     case kFormLifted: return carousel_forward_lifted(a, s, W);
@@ -156,7 +156,7 @@ inline long long carousel_bwd_groups(int n, long long nstrips, int compute_units
 // accumulate = 0: partial is [groups][N]; workgroup g stores the sums of its first strip in row g and
 // adds those of its later strips to them.  accumulate = 1: partial is one zeroed [N] buffer in the
 // kernel's slot-major order that every strip adds into atomically.  zeros: N floats that stay zero.
-inline int carousel_backward_strips(int n, long long B, int W, long long strip0, long long nstrips,
+inline int carousel_backward_strips(int n, int rows, long long B, int W, long long strip0, long long nstrips,
                                     long long groups, const CarouselCoefs &coefs, const float *Y, const float *G,
                                     float *dX, float *partial, const float *zeros, int accumulate,
                                     hipStream_t stream)
@@ -166,7 +166,7 @@ inline int carousel_backward_strips(int n, long long B, int W, long long strip0,
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const CarouselBwdArgs a{n, B, strip0, nstrips, groups, coefs, Y, G, dX, partial, zeros, aligned ? 1 : 0, accumulate, stream};
+    const CarouselBwdArgs a{n, rows, B, strip0, nstrips, groups, coefs, Y, G, dX, partial, zeros, aligned ? 1 : 0, accumulate, stream};
     switch (coefs.form) {
     case kFormScaled: return carousel_backward_scaled(a, s, W);
     case kFormLifted: return carousel_backward_lifted(a, s, W);

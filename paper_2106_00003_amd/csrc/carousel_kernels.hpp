@@ -282,10 +282,17 @@ struct CarouselFwd {
     }
 };
 
+// `rows` is the operand's row count (n, or n - 1 for the padded size of an odd problem): a row beyond
+// it is the inactive added dimension, zero on the way in and not stored on the way out.
 template <int W>
-__device__ __forceinline__ void load_row(float (&dst)[W], const float *X, long long B, int row, long long b0,
-                                         int wv, bool vec, int identity)
+__device__ __forceinline__ void load_row(float (&dst)[W], const float *X, long long B, int row, int rows,
+                                         long long b0, int wv, bool vec, int identity)
 {
+    if (row >= rows) {
+#pragma unroll
+        for (int x = 0; x < W; ++x) dst[x] = 0.f;
+        return;
+    }
     if (identity) {
 #pragma unroll
         for (int x = 0; x < W; ++x) dst[x] = (x < wv && (long long)row == b0 + x) ? 1.f : 0.f;
@@ -307,9 +314,10 @@ __device__ __forceinline__ void load_row(float (&dst)[W], const float *X, long l
 }
 
 template <int W>
-__device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long long B, int row, long long b0,
-                                          int wv, bool vec)
+__device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long long B, int row, int rows,
+                                          long long b0, int wv, bool vec)
 {
+    if (row >= rows) return;
     float *dst = Y + (long long)row * B + b0;
     if constexpr (W % 4 == 0) {
         if (vec) {
@@ -326,7 +334,7 @@ __device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long 
 
 template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
-    int n, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
+    int n, int rows, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
     const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok)
 {
     if (!form_selected(flag, FORM, scaled_max)) return;
@@ -359,8 +367,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 #pragma unroll
     for (int r = 0; r < M; ++r) {
         const int p = st.tid * M + r;
-        load_row<W>(st.top[r], X, B, rr_label(n, n - 2, p), b0, wv, vec, identity);
-        load_row<W>(st.bot[r], X, B, rr_label(n, n - 2, n - 1 - p), b0, wv, vec, identity);
+        load_row<W>(st.top[r], X, B, rr_label(n, n - 2, p), rows, b0, wv, vec, identity);
+        load_row<W>(st.bot[r], X, B, rr_label(n, n - 2, n - 1 - p), rows, b0, wv, vec, identity);
     }
     st.load_coefs(n - 2, st.cs[0]);
 
@@ -371,8 +379,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 #pragma unroll
     for (int r = 0; r < M; ++r) {
         const int p = st.tid * M + r;
-        store_row<W>(st.top[(r + UL) % M], Y, B, p, b0, wv, vec);
-        store_row<W>(st.bot[(r - UL + M) % M], Y, B, n - 1 - p, b0, wv, vec);
+        store_row<W>(st.top[(r + UL) % M], Y, B, p, rows, b0, wv, vec);
+        store_row<W>(st.bot[(r - UL + M) % M], Y, B, n - 1 - p, rows, b0, wv, vec);
     }
 }
 
@@ -653,7 +661,7 @@ struct CarouselBwd {
 
 template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
-    int n, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
+    int n, int rows, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
     const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
     float *dX, float *partial, const float *__restrict__ zeros, int vec_ok, int accumulate)
 {
@@ -697,10 +705,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
 #pragma unroll
         for (int r = 0; r < M; ++r) {
             const int p = st.tid * M + r;
-            load_row<W>(st.zt[r], Yin, B, p, b0, wv, vec, 0);
-            load_row<W>(st.zb[r], Yin, B, n - 1 - p, b0, wv, vec, 0);
-            load_row<W>(st.gt[r], G, B, p, b0, wv, vec, 0);
-            load_row<W>(st.gb[r], G, B, n - 1 - p, b0, wv, vec, 0);
+            load_row<W>(st.zt[r], Yin, B, p, rows, b0, wv, vec, 0);
+            load_row<W>(st.zb[r], Yin, B, n - 1 - p, rows, b0, wv, vec, 0);
+            load_row<W>(st.gt[r], G, B, p, rows, b0, wv, vec, 0);
+            load_row<W>(st.gb[r], G, B, n - 1 - p, rows, b0, wv, vec, 0);
         }
         st.load_coefs(0, st.cs[0]);
 
@@ -711,8 +719,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
 #pragma unroll
             for (int r = 0; r < M; ++r) {
                 const int p = st.tid * M + r;
-                store_row<W>(st.gt[(r - UL + M) % M], dX, B, rr_label(n, n - 2, p), b0, wv, vec);
-                store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), b0, wv, vec);
+                store_row<W>(st.gt[(r - UL + M) % M], dX, B, rr_label(n, n - 2, p), rows, b0, wv, vec);
+                store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), rows, b0, wv, vec);
             }
         }
         __syncthreads(); // the next strip reuses the exchange buffers
@@ -727,7 +735,7 @@ inline void carousel_launch_fwd(const CarouselFwdArgs &a)
 {
     const long long strips = (a.B + W - 1) / W;
     hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES, FORM>), dim3((unsigned)strips), dim3(64 * WAVES), 0,
-                       a.stream, a.n, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.coefs.scaled_max, a.X, a.Y,
+                       a.stream, a.n, a.rows, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.coefs.scaled_max, a.X, a.Y,
                        a.identity, a.vec_ok);
 }
 
@@ -759,7 +767,7 @@ template <int M, int W, int WAVES, int FORM>
 inline void carousel_launch_bwd(const CarouselBwdArgs &a)
 {
     hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.groups), dim3(64 * WAVES),
-                       0, a.stream, a.n, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
+                       0, a.stream, a.n, a.rows, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
                        a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.vec_ok, a.accumulate);
 }
 

@@ -124,12 +124,24 @@ __device__ __forceinline__ double lift_reduce(double th, bool *odd)
     return fma(-m, 1.2246467991473532e-16, fma(-m, 3.141592653589793116, th)); // pi in two pieces
 }
 
+// Angle of entry e of the full sequence E.  With a restricted parametrisation or odd n (Section 5 of
+// the paper; end of Section 3) theta lists only the free pairs: `map` (nullptr: every pair is free)
+// gives each entry of E its index in theta, or -1 for a bypassed pair, which is run as a rotation
+// by zero.
+template <typename T>
+__device__ __forceinline__ T theta_at(const T *__restrict__ theta, const int *__restrict__ map, long long e)
+{
+    if (!map) return theta[e];
+    const int c = map[e];
+    return c < 0 ? T(0) : theta[c];
+}
+
 // Standard form table, in E order.  `factor` (optional) receives the orientation sign (+1 when the
 // top position holds the smaller label) that the dtheta reduction multiplies its sums by.
 template <typename T>
-__global__ void coef_table_kernel(int n, const T *__restrict__ theta, const unsigned *flag,
-                                  float scaled_max, typename Pair2<T>::type *__restrict__ table,
-                                  T *__restrict__ factor)
+__global__ void coef_table_kernel(int n, const T *__restrict__ theta, const int *__restrict__ map,
+                                  const unsigned *flag, float scaled_max,
+                                  typename Pair2<T>::type *__restrict__ table, T *__restrict__ factor)
 {
     if (!form_selected(flag, kFormStandard, scaled_max)) return;
     const int H = n >> 1;
@@ -139,7 +151,7 @@ __global__ void coef_table_kernel(int n, const T *__restrict__ theta, const unsi
         const int k = (int)(e / H), p = (int)(e % H);
         const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
         double s, c;
-        sincos((double)theta[e], &s, &c);
+        sincos((double)theta_at(theta, map, e), &s, &c);
         if (a > b) s = -s;
         typename Pair2<T>::type out;
         out.x = (T)c;
@@ -156,8 +168,9 @@ __global__ void coef_table_kernel(int n, const T *__restrict__ theta, const unsi
 // A rotation multiplies the factor of both its rows by cos(theta) (scaled form) or by the sign
 // (-1)^m of theta = theta' + m*pi (lifted form).
 template <bool FWD>
-__global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const unsigned *flag,
-                                   float scaled_max, double *__restrict__ D, float *__restrict__ renorm)
+__global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const int *__restrict__ map,
+                                   const unsigned *flag, float scaled_max, double *__restrict__ D,
+                                   float *__restrict__ renorm)
 {
     const int form = selected_form(flag, scaled_max);
     if (form == kFormStandard) return;
@@ -175,7 +188,7 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
         q = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1); // position of label r in the sequence of block k
         p = (q < H) ? q : n - 1 - q;
         D[(long long)k * n + q] = d;
-        const double th = (double)theta[(long long)k * H + p];
+        const double th = (double)theta_at(theta, map, (long long)k * H + p);
         if (form == kFormScaled) {
             d *= cos_small(th);
         } else {
@@ -196,9 +209,9 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
 // +-1 here): the forward sweep does a -= T b, b += S a, a -= T b on the stored values, the reverse
 // sweep the same with the signs flipped.
 template <bool FWD>
-__global__ void scaled_table_kernel(int n, const float *__restrict__ theta, const unsigned *flag,
-                                    float scaled_max, const double *__restrict__ D, float2 *__restrict__ table,
-                                    float *__restrict__ factor)
+__global__ void scaled_table_kernel(int n, const float *__restrict__ theta, const int *__restrict__ map,
+                                    const unsigned *flag, float scaled_max, const double *__restrict__ D,
+                                    float2 *__restrict__ table, float *__restrict__ factor)
 {
     const int form = selected_form(flag, scaled_max);
     if (form == kFormStandard) return;
@@ -208,7 +221,7 @@ __global__ void scaled_table_kernel(int n, const float *__restrict__ theta, cons
     if (e >= N) return;
     const int k = (int)(e / H), p = (int)(e % H);
     const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-    const double th = (double)theta[e];
+    const double th = (double)theta_at(theta, map, e);
     const double da = D[(long long)k * n + p], db = D[(long long)k * n + (n - 1 - p)]; // before this block
     const double orient = (a < b) ? 1.0 : -1.0;
     if (form == kFormScaled) {
@@ -231,14 +244,18 @@ __global__ void scaled_table_kernel(int n, const float *__restrict__ theta, cons
 // partial[s][e], in strip order (fixed order: reproducible).  The sweeps store
 // sum_b (g_bot z_top - g_top z_bot) of their stored values; `factor` carries the orientation sign
 // (with i < j the paper's term is gbar_j z_i - gbar_i z_j) and, in the scaled form, d_top * d_bot.
+// `map` (see theta_at): dtheta lists the free angles only; sums of bypassed pairs are dropped.
 template <typename T>
 __global__ void reduce_partials_kernel(int n, long long nstrips, const T *__restrict__ partial,
-                                       const T *__restrict__ factor, T *dtheta, int accumulate)
+                                       const T *__restrict__ factor, const int *__restrict__ map, T *dtheta,
+                                       int accumulate)
 {
     const int H = n >> 1;
     const long long N = (long long)(n - 1) * H;
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= N) return;
+    const long long out = map ? (long long)map[e] : e;
+    if (out < 0) return;
     T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
     long long s = 0;
     for (; s + 4 <= nstrips; s += 4) {          // four loads in flight; the order of additions is fixed
@@ -249,7 +266,7 @@ __global__ void reduce_partials_kernel(int n, long long nstrips, const T *__rest
     }
     for (; s < nstrips; ++s) a0 += partial[s * N + e];
     const T acc = ((a0 + a1) + (a2 + a3)) * factor[e];
-    dtheta[e] = accumulate ? dtheta[e] + acc : acc;
+    dtheta[out] = accumulate ? dtheta[out] + acc : acc;
 }
 
 __global__ void fill_zero_kernel(long long count, float *__restrict__ dst)
@@ -263,7 +280,8 @@ __global__ void fill_zero_kernel(long long count, float *__restrict__ dst)
 // acc, laid out [block k][slot r][lane l] (arc p = l * slots + r); this puts them back in E order and
 // applies the per-angle factor.
 __global__ void finish_accumulated_kernel(int n, int lanes, int slots, const float *__restrict__ acc,
-                                          const float *__restrict__ factor, float *__restrict__ dtheta)
+                                          const float *__restrict__ factor, const int *__restrict__ map,
+                                          float *__restrict__ dtheta)
 {
     const int H = n >> 1;
     const long long N = (long long)(n - 1) * H;
@@ -272,7 +290,8 @@ __global__ void finish_accumulated_kernel(int n, int lanes, int slots, const flo
     const long long k = e / H;
     const int p = (int)(e % H);
     const int l = p / slots, r = p % slots;
-    dtheta[e] = factor[e] * acc[k * H + (long long)r * lanes + l];
+    const long long out = map ? (long long)map[e] : e;
+    if (out >= 0) dtheta[out] = factor[e] * acc[k * H + (long long)r * lanes + l];
 }
 
 } // namespace givens

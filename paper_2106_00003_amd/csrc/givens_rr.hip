@@ -36,7 +36,20 @@ struct Workspace {
     Buffer partial;      // per-strip dtheta partial sums (two-stage reduction)
     Buffer acc;          // one accumulation buffer of N floats (accumulating reduction)
     Buffer zeros;        // N floats that are zeroed when allocated and never written again
-    Buffer *all[9] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc, &zeros};
+    Buffer map;          // restricted parametrisation / odd n: index in theta of every entry of E, or -1
+    int map_rows = 0, map_m = 0; // the (row count, m) the map was built for
+    long long map_free = 0;      // its number of free angles
+    Buffer *all[10] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc, &zeros, &map};
+};
+
+// One call's problem: `rows` coordinates of which the first m may rotate with every other one
+// (Section 5 of the paper; m = rows - 1 is the unrestricted case), run by the kernels on n = rows
+// rounded up to even (end of Section 3: an added, inactive dimension).  map == nullptr when every
+// pair of E is free, and then theta is indexed by E directly.
+struct Problem {
+    int n = 0, rows = 0, m = 0;
+    const int *map = nullptr;
+    long long free_angles = 0;
 };
 
 std::mutex g_mutex;
@@ -136,6 +149,60 @@ struct Span {
 
 int check_n(int n) { return (n < 2 || (n & 1)) ? GIVENS_ERR_BAD_N : GIVENS_OK; }
 
+long long count_free_angles(int rows, int m) { return (long long)m * rows - (long long)m * (m + 1) / 2; }
+
+int check_restricted(int rows, int m)
+{
+    if (rows < 2 || rows > (1 << 20)) return GIVENS_ERR_BAD_N;
+    if (m < 1 || m > rows - 1) return GIVENS_ERR_BAD_M;
+    return GIVENS_OK;
+}
+
+// Free pairs in E order: circle-method blocks on n = rows rounded up to even, leaving out the pairs
+// with the added dimension (j >= rows) and the pairs inside m..rows-1 (i >= m).  `visit(e, i, j, free)`
+// is called for every entry e of the full sequence.
+template <typename F>
+void walk_pairs(int rows, int m, F &&visit)
+{
+    const int n = rows + (rows & 1), H = n / 2;
+    long long e = 0;
+    for (int k = 0; k < n - 1; ++k)
+        for (int p = 0; p < H; ++p, ++e) {
+            const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+            const int i = a < b ? a : b, j = a < b ? b : a;
+            visit(e, i, j, j < rows && i < m);
+        }
+}
+
+// Fills in the padded size and, when some pair of E is bypassed, the device map (built on the host
+// once per (rows, m) and kept in the workspace).
+int resolve_problem(int dev, int rows, int m, Problem *out)
+{
+    if (int rc = check_restricted(rows, m)) return rc;
+    out->rows = rows;
+    out->m = m;
+    out->n = rows + (rows & 1);
+    out->free_angles = count_free_angles(rows, m);
+    out->map = nullptr;
+    if (!(rows & 1) && m == rows - 1) return GIVENS_OK;
+    Workspace &ws = g_ws[dev];
+    if (!(ws.map.ptr && ws.map_rows == rows && ws.map_m == m)) {
+        const long long N = (long long)(out->n - 1) * (out->n / 2);
+        std::vector<int> host((size_t)N);
+        long long next = 0;
+        walk_pairs(rows, m, [&](long long e, int, int, bool is_free) { host[(size_t)e] = is_free ? (int)next++ : -1; });
+        if (next != out->free_angles) return GIVENS_ERR_UNSUPPORTED;
+        ws.map_rows = 0;
+        if (int rc = grow(ws.map, (size_t)N * sizeof(int))) return rc;
+        GIVENS_HIP(hipMemcpy(ws.map.ptr, host.data(), (size_t)N * sizeof(int), hipMemcpyHostToDevice));
+        ws.map_rows = rows;
+        ws.map_m = m;
+        ws.map_free = next;
+    }
+    out->map = reinterpret_cast<const int *>(ws.map.ptr);
+    return GIVENS_OK;
+}
+
 // Widest odd strip (<= 15 columns) whose `strips_in_lds` copies fit the LDS budget; narrower
 // when that is needed to give every CU a few workgroups.
 template <typename T>
@@ -175,12 +242,14 @@ FormPolicy form_policy(bool float_carousel)
 // Launches the coefficient kernels.  `forward` picks the sweep direction of the scaled / lifted
 // forms' row factors; `policy.try_forms` adds the range check and those forms' tables.
 template <typename T>
-int prepare_coefs(int dev, int n, const T *theta, bool forward, FormPolicy policy, hipStream_t stream,
+int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, FormPolicy policy, hipStream_t stream,
                   Coefs<T> *out)
 {
     const bool try_scaled = policy.try_forms;
     const float scaled_max = policy.scaled_max;
     using P2 = typename Pair2<T>::type;
+    const int n = pb.n;
+    const int *map = pb.map;
     const long long N = (long long)n * (n - 1) / 2;
     Workspace &ws = g_ws[dev];
     if (int rc = grow(ws.table, (size_t)N * sizeof(P2))) return rc;
@@ -204,19 +273,19 @@ int prepare_coefs(int dev, int n, const T *theta, bool forward, FormPolicy polic
             double *D = reinterpret_cast<double *>(ws.scale.ptr);
             float *rn = reinterpret_cast<float *>(ws.renorm.ptr);
             hipLaunchKernelGGL(reset_flag_kernel, dim3(1), dim3(1), 0, stream, flag);
-            hipLaunchKernelGGL(theta_range_kernel, dim3(512), dim3(512), 0, stream, N, theta, flag);
+            hipLaunchKernelGGL(theta_range_kernel, dim3(512), dim3(512), 0, stream, pb.free_angles, theta, flag);
             const long long scan_threads = (long long)periods * n;
             const unsigned scan_blocks = (unsigned)((scan_threads + threads - 1) / threads);
             if (forward) {
                 hipLaunchKernelGGL(scaled_scan_kernel<true>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
-                                   flag, scaled_max, D, rn);
+                                   map, flag, scaled_max, D, rn);
                 hipLaunchKernelGGL(scaled_table_kernel<true>, dim3(blocks), dim3(threads), 0, stream, n, theta,
-                                   flag, scaled_max, D, tab_s, factor);
+                                   map, flag, scaled_max, D, tab_s, factor);
             } else {
                 hipLaunchKernelGGL(scaled_scan_kernel<false>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
-                                   flag, scaled_max, D, rn);
+                                   map, flag, scaled_max, D, rn);
                 hipLaunchKernelGGL(scaled_table_kernel<false>, dim3(blocks), dim3(threads), 0, stream, n, theta,
-                                   flag, scaled_max, D, tab_s, factor);
+                                   map, flag, scaled_max, D, tab_s, factor);
             }
             out->scaled = CarouselCoefs{kFormScaled, tab_s, reinterpret_cast<const float2 *>(rn), flag, scaled_max};
             out->lifted = CarouselCoefs{kFormLifted, tab_s, reinterpret_cast<const float2 *>(rn), flag, scaled_max};
@@ -225,7 +294,7 @@ int prepare_coefs(int dev, int n, const T *theta, bool forward, FormPolicy polic
         out->standard = CarouselCoefs{kFormStandard, table, nullptr, flag, scaled_max};
     }
     hipLaunchKernelGGL(coef_table_kernel<T>, dim3(std::min(blocks, 4096u)), dim3(threads), 0, stream, n, theta,
-                       static_cast<const unsigned *>(flag), scaled_max, table, factor);
+                       map, static_cast<const unsigned *>(flag), scaled_max, table, factor);
     GIVENS_HIP(hipGetLastError());
     out->table = table;
     out->factor = factor;
@@ -236,7 +305,7 @@ int prepare_coefs(int dev, int n, const T *theta, bool forward, FormPolicy polic
 }
 
 template <typename T>
-int lds_forward(int n, long long B, const typename Pair2<T>::type *table, const T *X, T *Y,
+int lds_forward(int n, int rows, long long B, const typename Pair2<T>::type *table, const T *X, T *Y,
                 int identity, hipStream_t stream)
 {
     const int w = lds_strip_width<T>(n, B, 1);
@@ -247,8 +316,8 @@ int lds_forward(int n, long long B, const typename Pair2<T>::type *table, const 
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     const long long strips = (B + w - 1) / w;
     Span span(1, stream);
-    hipLaunchKernelGGL(kern, dim3((unsigned)strips), dim3(kLdsThreads), smem, stream, n, B, w, table, X, Y,
-                       identity);
+    hipLaunchKernelGGL(kern, dim3((unsigned)strips), dim3(kLdsThreads), smem, stream, n, rows, B, w, table, X,
+                       Y, identity);
     GIVENS_HIP(hipGetLastError());
     return GIVENS_OK;
 }
@@ -257,9 +326,11 @@ int lds_forward(int n, long long B, const typename Pair2<T>::type *table, const 
 // partial sum per (strip, angle), folded into dtheta chunk by chunk.  Carousel family: persistent
 // workgroups with one row of partial sums each, or the accumulating variant.  `family` picks the kernel.
 template <typename T>
-int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coefs, const T *Y, const T *G,
-                    T *dX, T *dtheta, hipStream_t stream)
+int backward_chunks(int dev, int family, const Problem &pb, long long B, const Coefs<T> &coefs, const T *Y,
+                    const T *G, T *dX, T *dtheta, hipStream_t stream)
 {
+    const int n = pb.n, rows = pb.rows;
+    const int *map = pb.map;
     const long long N = (long long)n * (n - 1) / 2;
     int w = 0;
     size_t smem = 0;
@@ -310,14 +381,14 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
                 hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(threads), 0, stream, N, acc);
                 const long long groups = carousel_bwd_groups(n, strips, cus);
                 if (coefs.all_forms) {
-                    if (int rc = carousel_backward_strips(n, B, w, 0, strips, groups, coefs.scaled, Y, G, dX, acc, zeros, 1,
+                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.scaled, Y, G, dX, acc, zeros, 1,
                                                           stream))
                         return rc;
-                    if (int rc = carousel_backward_strips(n, B, w, 0, strips, groups, coefs.lifted, Y, G, dX, acc, zeros, 1,
+                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.lifted, Y, G, dX, acc, zeros, 1,
                                                           stream))
                         return rc;
                 }
-                if (int rc = carousel_backward_strips(n, B, w, 0, strips, groups, coefs.standard, Y, G, dX, acc, zeros, 1,
+                if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.standard, Y, G, dX, acc, zeros, 1,
                                                       stream))
                     return rc;
                 GIVENS_HIP(hipGetLastError());
@@ -325,7 +396,7 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
             {
                 Span span(2, stream);
                 hipLaunchKernelGGL(finish_accumulated_kernel, dim3((unsigned)((N + threads - 1) / threads)),
-                                   dim3(threads), 0, stream, n, lanes, slots, acc, coefs.factor, dtheta);
+                                   dim3(threads), 0, stream, n, lanes, slots, acc, coefs.factor, map, dtheta);
                 GIVENS_HIP(hipGetLastError());
             }
             t_state.last_reduction = GIVENS_REDUCTION_ATOMIC;
@@ -339,29 +410,29 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
     // holds at once), whatever the number of strips.
     const bool persistent = family == GIVENS_KERNEL_CAROUSEL;
     const long long rows_wanted = persistent ? carousel_bwd_groups(n, strips, cus) : strips;
-    long long rows = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
-    rows = std::max<long long>(1, std::min(rows, rows_wanted));
-    if (int rc = grow(ws.partial, (size_t)rows * N * sizeof(T))) return rc;
+    long long prows = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
+    prows = std::max<long long>(1, std::min(prows, rows_wanted));
+    if (int rc = grow(ws.partial, (size_t)prows * N * sizeof(T))) return rc;
     T *partial = reinterpret_cast<T *>(ws.partial.ptr);
-    const long long chunk = persistent ? strips : rows;     // strips per launch
+    const long long chunk = persistent ? strips : prows;     // strips per launch
     for (long long s0 = 0; s0 < strips; s0 += chunk) {
         const long long ns = std::min(chunk, strips - s0);
-        const long long nrows = persistent ? std::min(rows, ns) : ns;
+        const long long nrows = persistent ? std::min(prows, ns) : ns;
         {
             Span span(1, stream);
             if (family == GIVENS_KERNEL_LDS) {
-                hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, B, w, s0,
+                hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, rows, B, w, s0,
                                    coefs.table, Y, G, dX, partial);
             } else if constexpr (std::is_same<T, float>::value) {
                 if (coefs.all_forms) {
-                    if (int rc = carousel_backward_strips(n, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX, partial, zeros, 0,
+                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX, partial, zeros, 0,
                                                           stream))
                         return rc;
-                    if (int rc = carousel_backward_strips(n, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX, partial, zeros, 0,
+                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX, partial, zeros, 0,
                                                           stream))
                         return rc;
                 }
-                if (int rc = carousel_backward_strips(n, B, w, s0, ns, nrows, coefs.standard, Y, G, dX, partial, zeros, 0,
+                if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.standard, Y, G, dX, partial, zeros, 0,
                                                       stream))
                     return rc;
             } else {
@@ -373,7 +444,8 @@ int backward_chunks(int dev, int family, int n, long long B, const Coefs<T> &coe
             Span span(2, stream);
             const int threads = 256;
             hipLaunchKernelGGL(reduce_partials_kernel<T>, dim3((unsigned)((N + threads - 1) / threads)),
-                               dim3(threads), 0, stream, n, nrows, partial, coefs.factor, dtheta, s0 > 0 ? 1 : 0);
+                               dim3(threads), 0, stream, n, nrows, partial, coefs.factor, map, dtheta,
+                               s0 > 0 ? 1 : 0);
             GIVENS_HIP(hipGetLastError());
         }
     }
@@ -387,23 +459,27 @@ int current_device(int *dev)
     return GIVENS_OK;
 }
 
+// rows, m: see Problem.  The unrestricted entry points pass an even rows and m = rows - 1.
 template <typename T>
-int forward_impl(int n, long long B, const T *theta, const T *X, T *Y, int identity, void *stream_v)
+int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y, int identity, void *stream_v)
 {
-    if (int rc = check_n(n)) return rc;
+    if (int rc = check_restricted(rows, m)) return rc;
     if (B < 1) return GIVENS_ERR_BAD_B;
     if (!theta || !Y || (!identity && !X)) return GIVENS_ERR_NULL;
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
     std::lock_guard<std::mutex> lock(g_mutex);
     int dev = 0;
     if (int rc = current_device(&dev)) return rc;
+    Problem pb;
+    if (int rc = resolve_problem(dev, rows, m, &pb)) return rc;
+    const int n = pb.n;
     timing_begin_call();
     const int choice = g_kernel_choice;
     const bool can_carousel = carousel_supported<T>(n, B);
     if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
     const bool use_carousel = can_carousel && choice != GIVENS_KERNEL_LDS;
     Coefs<T> coefs;
-    if (int rc = prepare_coefs<T>(dev, n, theta, true, form_policy(use_carousel && std::is_same<T, float>::value),
+    if (int rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(use_carousel && std::is_same<T, float>::value),
                                   stream, &coefs))
         return rc;
     int rc = GIVENS_OK;
@@ -411,27 +487,27 @@ int forward_impl(int n, long long B, const T *theta, const T *X, T *Y, int ident
         if constexpr (std::is_same<T, float>::value) {
             Span span(1, stream);
             if (coefs.all_forms) {
-                rc = carousel_forward(n, B, coefs.scaled, X, Y, identity, stream);
-                if (rc == GIVENS_OK) rc = carousel_forward(n, B, coefs.lifted, X, Y, identity, stream);
+                rc = carousel_forward(n, rows, B, coefs.scaled, X, Y, identity, stream);
+                if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.lifted, X, Y, identity, stream);
             }
-            if (rc == GIVENS_OK) rc = carousel_forward(n, B, coefs.standard, X, Y, identity, stream);
+            if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.standard, X, Y, identity, stream);
             if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
         } else {
             rc = GIVENS_ERR_UNSUPPORTED;
         }
         t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
     } else {
-        rc = lds_forward<T>(n, B, coefs.table, X, Y, identity, stream);
+        rc = lds_forward<T>(n, rows, B, coefs.table, X, Y, identity, stream);
         t_state.last_kernel = GIVENS_KERNEL_LDS;
     }
     return rc;
 }
 
 template <typename T>
-int backward_impl(int n, long long B, const T *theta, const T *Y, const T *G, T *dX, T *dtheta,
+int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, const T *G, T *dX, T *dtheta,
                   void *stream_v)
 {
-    if (int rc = check_n(n)) return rc;
+    if (int rc = check_restricted(rows, m)) return rc;
     if (B < 1) return GIVENS_ERR_BAD_B;
     if (!theta || !Y || !G || !dtheta) return GIVENS_ERR_NULL;
     if (dX && (const void *)dX == (const void *)Y) return GIVENS_ERR_ALIAS;
@@ -439,17 +515,20 @@ int backward_impl(int n, long long B, const T *theta, const T *Y, const T *G, T 
     std::lock_guard<std::mutex> lock(g_mutex);
     int dev = 0;
     if (int rc = current_device(&dev)) return rc;
+    Problem pb;
+    if (int rc = resolve_problem(dev, rows, m, &pb)) return rc;
+    const int n = pb.n;
     timing_begin_call();
     const int choice = g_kernel_choice;
     const bool can_carousel = carousel_backward_supported<T>(n, B);
     if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
     const int family = (can_carousel && choice != GIVENS_KERNEL_LDS) ? GIVENS_KERNEL_CAROUSEL : GIVENS_KERNEL_LDS;
     Coefs<T> coefs;
-    if (int rc = prepare_coefs<T>(dev, n, theta, false,
+    if (int rc = prepare_coefs<T>(dev, pb, theta, false,
                                   form_policy(family == GIVENS_KERNEL_CAROUSEL && std::is_same<T, float>::value),
                                   stream, &coefs))
         return rc;
-    const int rc = backward_chunks<T>(dev, family, n, B, coefs, Y, G, dX, dtheta, stream);
+    const int rc = backward_chunks<T>(dev, family, pb, B, coefs, Y, G, dX, dtheta, stream);
     t_state.last_kernel = family;
     return rc;
 }
@@ -477,29 +556,83 @@ int rr_schedule(int n, int32_t *pairs)
 
 int givens_forward(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream)
 {
-    return givens::forward_impl<float>(n, B, theta, X, Y, 0, stream);
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream);
 }
 int givens_build(int n, const float *theta, float *U, void *stream)
 {
-    return givens::forward_impl<float>(n, n, theta, nullptr, U, 1, stream);
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::forward_impl<float>(n, n - 1, n, theta, nullptr, U, 1, stream);
 }
 int givens_backward(int n, int64_t B, const float *theta, const float *Y, const float *G, float *dX,
                     float *dtheta, void *stream)
 {
-    return givens::backward_impl<float>(n, B, theta, Y, G, dX, dtheta, stream);
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::backward_impl<float>(n, n - 1, B, theta, Y, G, dX, dtheta, stream);
 }
 int givens_forward_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream)
 {
-    return givens::forward_impl<double>(n, B, theta, X, Y, 0, stream);
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::forward_impl<double>(n, n - 1, B, theta, X, Y, 0, stream);
 }
 int givens_build_f64(int n, const double *theta, double *U, void *stream)
 {
-    return givens::forward_impl<double>(n, n, theta, nullptr, U, 1, stream);
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::forward_impl<double>(n, n - 1, n, theta, nullptr, U, 1, stream);
 }
 int givens_backward_f64(int n, int64_t B, const double *theta, const double *Y, const double *G,
                         double *dX, double *dtheta, void *stream)
 {
-    return givens::backward_impl<double>(n, B, theta, Y, G, dX, dtheta, stream);
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::backward_impl<double>(n, n - 1, B, theta, Y, G, dX, dtheta, stream);
+}
+
+int64_t givens_num_angles(int n, int m)
+{
+    if (int rc = givens::check_restricted(n, m)) return rc;
+    return givens::count_free_angles(n, m);
+}
+
+int rr_schedule_restricted(int n, int m, int32_t *pairs)
+{
+    if (int rc = givens::check_restricted(n, m)) return rc;
+    if (!pairs) return GIVENS_ERR_NULL;
+    long long next = 0;
+    givens::walk_pairs(n, m, [&](long long, int i, int j, bool is_free) {
+        if (!is_free) return;
+        pairs[2 * next] = i;
+        pairs[2 * next + 1] = j;
+        ++next;
+    });
+    return GIVENS_OK;
+}
+
+int givens_forward_restricted(int n, int m, int64_t B, const float *theta, const float *X, float *Y, void *stream)
+{
+    return givens::forward_impl<float>(n, m, B, theta, X, Y, 0, stream);
+}
+int givens_build_restricted(int n, int m, const float *theta, float *U, void *stream)
+{
+    return givens::forward_impl<float>(n, m, n, theta, nullptr, U, 1, stream);
+}
+int givens_backward_restricted(int n, int m, int64_t B, const float *theta, const float *Y, const float *G,
+                               float *dX, float *dtheta, void *stream)
+{
+    return givens::backward_impl<float>(n, m, B, theta, Y, G, dX, dtheta, stream);
+}
+int givens_forward_restricted_f64(int n, int m, int64_t B, const double *theta, const double *X, double *Y,
+                                  void *stream)
+{
+    return givens::forward_impl<double>(n, m, B, theta, X, Y, 0, stream);
+}
+int givens_build_restricted_f64(int n, int m, const double *theta, double *U, void *stream)
+{
+    return givens::forward_impl<double>(n, m, n, theta, nullptr, U, 1, stream);
+}
+int givens_backward_restricted_f64(int n, int m, int64_t B, const double *theta, const double *Y, const double *G,
+                                   double *dX, double *dtheta, void *stream)
+{
+    return givens::backward_impl<double>(n, m, B, theta, Y, G, dX, dtheta, stream);
 }
 
 int givens_release(void)
@@ -519,6 +652,8 @@ int givens_release(void)
             if (b->ptr && !hip_ok(hipFree(b->ptr))) rc = GIVENS_ERR_HIP;
             *b = Buffer{};
         }
+        ws.map_rows = ws.map_m = 0;
+        ws.map_free = 0;
     }
     (void)hipSetDevice(keep);
     return rc;
@@ -536,6 +671,7 @@ const char *givens_error_string(int code)
     case GIVENS_ERR_HIP: return "a HIP call failed (see givens_last_hip_error)";
     case GIVENS_ERR_UNSUPPORTED: return "shape or option not supported by the requested kernel";
     case GIVENS_ERR_ALIAS: return "forbidden aliasing between arguments";
+    case GIVENS_ERR_BAD_M: return "m must satisfy 1 <= m <= n - 1";
     default: return "unknown error code";
     }
 }

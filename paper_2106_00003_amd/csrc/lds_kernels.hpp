@@ -5,6 +5,8 @@
 // per-pair gradient sum of the reverse sweep needs no cross-thread reduction.
 //
 // cos/sin come from the standard-form table of coef_kernels.hpp (orientation folded into the sine).
+// `rows` is the operand's row count: n itself, or n - 1 when n is the padded size of an odd problem
+// (end of Section 3: the added dimension is inactive; its row is zero in LDS and never stored).
 #pragma once
 #include <hip/hip_runtime.h>
 #include "coef_kernels.hpp"
@@ -19,7 +21,7 @@ __host__ __device__ inline int lds_row_stride(int w) { return w | 1; }
 
 template <typename T>
 __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
-    int n, long long B, int w, const typename Pair2<T>::type *__restrict__ table,
+    int n, int rows, long long B, int w, const typename Pair2<T>::type *__restrict__ table,
     const T *X, T *Y, int identity)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -32,7 +34,8 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
     for (long long idx = threadIdx.x; idx < (long long)n * w; idx += blockDim.x) {
         const int r = (int)(idx / w), c = (int)(idx % w);
         T v = T(0);
-        if (c < wv) v = identity ? ((long long)r == b0 + c ? T(1) : T(0)) : X[(long long)r * B + b0 + c];
+        if (c < wv && r < rows)
+            v = identity ? ((long long)r == b0 + c ? T(1) : T(0)) : X[(long long)r * B + b0 + c];
         strip[r * ldw + c] = v;
     }
     __syncthreads();
@@ -54,14 +57,14 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
 
     for (long long idx = threadIdx.x; idx < (long long)n * w; idx += blockDim.x) {
         const int r = (int)(idx / w), c = (int)(idx % w);
-        if (c < wv) Y[(long long)r * B + b0 + c] = strip[r * ldw + c];
+        if (c < wv && r < rows) Y[(long long)r * B + b0 + c] = strip[r * ldw + c];
     }
 }
 
 // Reverse sweep on strips [strip0, strip0 + gridDim.x).  partial is [gridDim.x][N].
 template <typename T>
 __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
-    int n, long long B, int w, long long strip0, const typename Pair2<T>::type *__restrict__ table,
+    int n, int rows, long long B, int w, long long strip0, const typename Pair2<T>::type *__restrict__ table,
     const T *Yin, const T *G, T *dX, T *__restrict__ partial)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -77,7 +80,7 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
     for (long long idx = threadIdx.x; idx < (long long)n * w; idx += blockDim.x) {
         const int r = (int)(idx / w), c = (int)(idx % w);
         T vz = T(0), vg = T(0);
-        if (c < wv) {
+        if (c < wv && r < rows) {
             vz = Yin[(long long)r * B + b0 + c];
             vg = G[(long long)r * B + b0 + c];
         }
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
     if (dX) {
         for (long long idx = threadIdx.x; idx < (long long)n * w; idx += blockDim.x) {
             const int r = (int)(idx / w), c = (int)(idx % w);
-            if (c < wv) dX[(long long)r * B + b0 + c] = gb[r * ldw + c];
+            if (c < wv && r < rows) dX[(long long)r * B + b0 + c] = gb[r * ldw + c];
         }
     }
 }

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "givens_rr.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"^\s*(?:const\s+)?(?:int|char)\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int|int64_t|char)\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
     return sorted(set(names))
 
 
@@ -78,3 +78,35 @@ def test_argument_errors_are_codes_not_crashes():
     assert b"even" in L.givens_error_string(-1)
     with pytest.raises(binding.GivensError):
         binding.rr_schedule(7)
+
+
+# ---------------------------------------------------------------- restricted parametrisation, odd n
+@pytest.mark.parametrize("n,m", [(8, 4), (8, 7), (6, 1), (3, 1), (3, 2), (5, 4), (9, 3), (64, 20), (255, 254), (257, 100)])
+def test_restricted_schedule_is_bit_exact_against_the_oracle(n, m):
+    from oracle import restricted_oracle as R
+    want = R.free_pairs(n, m)
+    got = binding.rr_schedule_restricted(n, m)
+    assert got.dtype == np.int32 and got.shape == want.shape
+    assert np.array_equal(got, want)
+    assert binding.num_angles(n, m) == R.num_free_angles(n, m) == want.shape[0]
+
+
+def test_restricted_schedule_with_m_equal_n_minus_1_is_rr_schedule():
+    for n in (2, 6, 16, 256):
+        assert np.array_equal(binding.rr_schedule_restricted(n, n - 1), binding.rr_schedule(n).reshape(-1, 2))
+
+
+def test_restricted_argument_errors():
+    L = binding.lib()
+    assert L.givens_num_angles(1, 1) == -1
+    assert L.givens_num_angles(8, 0) == -7
+    assert L.givens_num_angles(8, 8) == -7
+    assert L.givens_num_angles(8, 4) == 22                      # the example of Section 5
+    assert L.rr_schedule_restricted(8, 9, None) == -7
+    assert L.rr_schedule_restricted(8, 4, None) == -3
+    assert L.givens_forward_restricted(8, 0, 4, None, None, None, None) == -7
+    assert L.givens_forward_restricted(1, 1, 4, None, None, None, None) == -1
+    assert L.givens_forward_restricted(9, 4, 0, None, None, None, None) == -2
+    assert L.givens_forward_restricted(9, 4, 4, None, None, None, None) == -3
+    assert L.givens_backward_restricted(9, 4, 4, None, None, None, None, None, None) == -3
+    assert b"m must" in L.givens_error_string(-7)
