@@ -66,6 +66,29 @@ def test_gradcheck_on_the_fp64_entry_points():
     assert torch.autograd.gradcheck(lambda t: L.givens_matrix(t, 8), (theta,), eps=1e-6, atol=1e-7, rtol=1e-6)
 
 
+def test_restricted_and_odd_layer_gradients():
+    L = _layer()
+    from oracle import restricted_oracle as R
+    n, m, B = 255, 60, 32
+    rng = np.random.default_rng(94)
+    pairs = R.free_pairs(n, m)
+    th = rng.uniform(-np.pi, np.pi, pairs.shape[0]).astype(np.float32)
+    x, g = rng.standard_normal((n, B)).astype(np.float32), rng.standard_normal((n, B)).astype(np.float32)
+    theta = torch.from_numpy(th).cuda().requires_grad_(True)
+    X = torch.from_numpy(x).cuda().requires_grad_(True)
+    Y = L.givens_apply(theta, X, m)
+    (Y * torch.from_numpy(g).cuda()).sum().backward()
+    want_y = C.forward_pairs(th, x, pairs)
+    want_dth, want_dx, _ = C.reverse_sweep_pairs(th, want_y, g, pairs)
+    assert O.rel_fro(Y.detach().cpu().numpy(), want_y) <= 1e-5
+    assert O.rel_fro(theta.grad.cpu().numpy(), want_dth) <= 1e-4
+    assert O.rel_fro(X.grad.cpu().numpy(), want_dx) <= 1e-4
+    layer = L.OrthogonalLinear(9, m=4, dtype=torch.float64)
+    assert layer.theta.numel() == 4 * 9 - 10
+    assert torch.autograd.gradcheck(lambda t: L.givens_matrix(t, 9, 4), (layer.theta,), eps=1e-6, atol=1e-7,
+                                    rtol=1e-6)
+
+
 def test_gradient_descent_on_the_angles_fits_a_rotation():
     L = _layer()
     torch.manual_seed(5)
