@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=4, choices=[2, 4, 5],
                     help="benchmark workload id (default 4: n=4096, B=4096)")
+    ap.add_argument("--restricted", type=str, default=None, metavar="ROWS,M",
+                    help="time the restricted entry points instead: ROWS coordinates (may be odd), pairs (i, j) "
+                         "with i < M free, the chosen workload's B and angle distribution; not the headline metric")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="after the steps, run one plain device copy of X into Y (n*B*4 bytes read and "
@@ -80,6 +83,15 @@ def main() -> int:
     wl = data["workload"]
     n, B = wl.n, wl.B
     N = wl.num_angles
+    name = wl.name
+    restricted_m = None
+    if args.restricted:
+        n, restricted_m = (int(v) for v in args.restricted.split(","))
+        data = inputs.make_restricted(n, restricted_m, B, seed=inputs.BASE_SEED + 100 + args.workload,
+                                      theta_dist=wl.theta_dist)
+        N = data["theta"].size
+        name = f"restricted_n{n}_m{restricted_m}_B{B}_f32"
+        args.no_cpu_baseline = True
     th_d = torch.from_numpy(data["theta"]).cuda()
     x_d = torch.from_numpy(data["X"]).cuda()
     g_d = torch.from_numpy(data["G"]).cuda()
@@ -88,9 +100,15 @@ def main() -> int:
     dth_d = torch.empty_like(th_d)
 
     def step():
-        binding.givens_forward(th_d, x_d, Y=y_d)
+        if restricted_m is None:
+            binding.givens_forward(th_d, x_d, Y=y_d)
+        else:
+            binding.givens_forward_restricted(th_d, x_d, restricted_m, Y=y_d)
         t_f = binding.last_timing()
-        binding.givens_backward(th_d, y_d, g_d, dX=dx_d, dtheta=dth_d)
+        if restricted_m is None:
+            binding.givens_backward(th_d, y_d, g_d, dX=dx_d, dtheta=dth_d)
+        else:
+            binding.givens_backward_restricted(th_d, y_d, g_d, restricted_m, dX=dx_d, dtheta=dth_d)
         t_b = binding.last_timing()
         return t_f, t_b
 
@@ -116,7 +134,10 @@ def main() -> int:
     # one build (operand = I_n) outside the timed region, for the record
     binding.set_timing(True)
     u_d = torch.empty((n, n), dtype=torch.float32, device="cuda")
-    binding.givens_build(th_d, n, U=u_d)
+    if restricted_m is None:
+        binding.givens_build(th_d, n, U=u_d)
+    else:
+        binding.givens_build_restricted(th_d, n, restricted_m, U=u_d)
     build_ms = binding.last_timing()[1]
     binding.set_timing(False)
     del u_d
@@ -140,7 +161,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": wl.name, "n": n, "B": B, "angles": N, "theta": wl.theta_dist,
+        "config": {"workload": name, "n": n, "B": B, "angles": N, "theta": wl.theta_dist,
                    "step": "givens_forward + givens_backward", "kernel_family": families},
         "fwd_updates_per_s": updates / ((fwd_table + fwd_sweep) * 1e-3),
         "fwd_ms": fwd_table + fwd_sweep,
@@ -150,11 +171,11 @@ def main() -> int:
         "roofline": {"kernel": "carousel_forward_kernel", "bound": "alu", "achieved": fwd_tflops,
                      "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
                      "frac": fwd_tflops / PEAK_FP32_VECTOR_TFLOPS,
-                     "traffic": _traffic_from_profiles(f"carousel_forward_{wl.name}")},
+                     "traffic": _traffic_from_profiles(f"carousel_forward_{name}")},
         "roofline_bwd": {"kernel": "carousel_backward_kernel", "bound": "alu", "achieved": bwd_tflops,
                          "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
                          "frac": bwd_tflops / PEAK_FP32_VECTOR_TFLOPS,
-                         "traffic": _traffic_from_profiles(f"carousel_backward_{wl.name}")},
+                         "traffic": _traffic_from_profiles(f"carousel_backward_{name}")},
     }
 
     if not args.no_cpu_baseline:

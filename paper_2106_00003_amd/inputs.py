@@ -108,3 +108,16 @@ def make_custom(n: int, B: int, *, seed: int, dtype=np.float32,
         "X": s_x.standard_normal((n, B), dtype=dt),
         "G": s_g.standard_normal((n, B), dtype=dt),
     }
+
+
+def make_restricted(n: int, m: int, B: int, *, seed: int, dtype=np.float32,
+                    theta_dist: str = "uniform") -> dict:
+    """Same recipe with one angle per free pair of the parametrisation restricted to pairs (i, j),
+    i < m (m n - m (m + 1) / 2 of them); n may be odd."""
+    s_theta, s_x, s_g = _streams(seed, 3)
+    dt = np.dtype(dtype).type
+    return {
+        "theta": draw_theta(s_theta, m * n - m * (m + 1) // 2, theta_dist, dt),
+        "X": s_x.standard_normal((n, B), dtype=dt),
+        "G": s_g.standard_normal((n, B), dtype=dt),
+    }
