@@ -62,6 +62,8 @@ extern "C" {
 #define GIVENS_REDUCTION_TWO_STAGE 1 /* one partial sum per (strip, angle), then a fixed-order pass: reproducible */
 #define GIVENS_REDUCTION_ATOMIC 2    /* strips add into one buffer with float atomics (carousel kernels only);  */
                                      /* order of additions, hence the last bits of dtheta, varies run to run   */
+#define GIVENS_REDUCTION_GRAM 3      /* C = Y G^T by one SGEMM (rocBLAS, loaded on demand), then the sweep on   */
+                                     /* the n x n operand C; dX by a forward-type sweep (carousel kernels only) */
 
 /*
  * rr_schedule -- the round-robin sequence by the circle method (Section 3; the worked n = 6
@@ -177,8 +179,12 @@ int givens_last_rotation_form(void);
  * TWO_STAGE keeps one row of 4*N bytes of partial sums per resident workgroup of the carousel sweep
  * (at most 256 rows on this chip: 8.6 GB at n = 4096, whatever B is) or per strip of the LDS family,
  * capped at 24 GiB per chunk, and gives bit-identical dtheta from run to run; ATOMIC needs 4*N bytes
- * in all but its summation order is not fixed.  The LDS family and the f64 entry points always use
- * TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
+ * in all but its summation order is not fixed.  GRAM replaces the sweep over B columns by the Gram
+ * matrix C = Y G^T (the sums of the sweep are those of the same sweep on the operand C with upstream
+ * gradient I_n) and computes dX = U^T G by a forward-type sweep; it needs librocblas at run time and
+ * returns GIVENS_ERR_UNSUPPORTED when forced without it.  AUTO means GRAM for the carousel kernels
+ * when B >= 4 n and rocBLAS loads, TWO_STAGE otherwise.  The LDS family and the f64 entry points
+ * always use TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
  */
 int givens_set_reduction(int which);
 int givens_last_reduction(void);

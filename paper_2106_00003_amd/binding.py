@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libgivens_rr.so")
 
 KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL = 0, 1, 2
 FORM_AUTO, FORM_STANDARD, FORM_SCALED, FORM_LIFTED = 0, 1, 2, 3
-REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_ATOMIC = 0, 1, 2
+REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_ATOMIC, REDUCTION_GRAM = 0, 1, 2, 3
 
 EXPORTS = [
     "rr_schedule", "givens_forward", "givens_build", "givens_backward",

@@ -85,6 +85,7 @@ struct CarouselFwdArgs {
     const float *X;
     float *Y;
     int identity, vec_ok;
+    int mirror; // rows relabelled r -> n - r: with mirrored tables the launch applies U^T
     hipStream_t stream;
 };
 
@@ -96,6 +97,7 @@ struct CarouselBwdArgs {
     float *dX, *partial;
     const float *zeros; // N floats that are always zero
     int vec_ok, accumulate;
+    int g_identity; // G is I_n (generated on chip, the pointer is not read)
     hipStream_t stream;
 };
 
@@ -109,14 +111,14 @@ int carousel_backward_scaled(const CarouselBwdArgs &a, CarouselShape s, int W);
 int carousel_backward_lifted(const CarouselBwdArgs &a, CarouselShape s, int W);
 
 inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
-                            int identity, hipStream_t stream)
+                            int identity, int mirror, hipStream_t stream)
 {
     CarouselShape s;
     if (!carousel_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
     const int W = carousel_width(B, s.WAVES);
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
-    const CarouselFwdArgs a{n, rows, B, coefs, X, Y, identity, aligned ? 1 : 0, stream};
+    const CarouselFwdArgs a{n, rows, B, coefs, X, Y, identity, aligned ? 1 : 0, mirror, stream};
     switch (coefs.form) {
     case kFormScaled: return carousel_forward_scaled(a, s, W);
     case kFormLifted: return carousel_forward_lifted(a, s, W);
@@ -158,15 +160,16 @@ inline long long carousel_bwd_groups(int n, long long nstrips, int compute_units
 // kernel's slot-major order that every strip adds into atomically.  zeros: N floats that stay zero.
 inline int carousel_backward_strips(int n, int rows, long long B, int W, long long strip0, long long nstrips,
                                     long long groups, const CarouselCoefs &coefs, const float *Y, const float *G,
-                                    float *dX, float *partial, const float *zeros, int accumulate,
+                                    float *dX, float *partial, const float *zeros, int accumulate, int g_identity,
                                     hipStream_t stream)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
-                         (reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
+                         (g_identity || reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const CarouselBwdArgs a{n, rows, B, strip0, nstrips, groups, coefs, Y, G, dX, partial, zeros, aligned ? 1 : 0, accumulate, stream};
+    const CarouselBwdArgs a{n, rows, B, strip0, nstrips, groups, coefs, Y, G, dX, partial, zeros, aligned ? 1 : 0, accumulate, g_identity,
+                            stream};
     switch (coefs.form) {
     case kFormScaled: return carousel_backward_scaled(a, s, W);
     case kFormLifted: return carousel_backward_lifted(a, s, W);

@@ -332,10 +332,14 @@ __device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long 
         if (x < wv) dst[x] = src[x];
 }
 
+// mirror: rows are relabelled r -> n - r (r >= 1) on the way in and on the way out; with the mirrored
+// coefficient tables (theta_at in coef_kernels.hpp) the launch then computes U(theta)^T X.
+__device__ __forceinline__ int mirrored_row(int n, int r, int mirror) { return (mirror && r) ? n - r : r; }
+
 template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
     int n, int rows, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
-    const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok)
+    const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok, int mirror)
 {
     if (!form_selected(flag, FORM, scaled_max)) return;
     using State = CarouselFwd<M, W, WAVES, FORM>;
@@ -367,8 +371,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 #pragma unroll
     for (int r = 0; r < M; ++r) {
         const int p = st.tid * M + r;
-        load_row<W>(st.top[r], X, B, rr_label(n, n - 2, p), rows, b0, wv, vec, identity);
-        load_row<W>(st.bot[r], X, B, rr_label(n, n - 2, n - 1 - p), rows, b0, wv, vec, identity);
+        load_row<W>(st.top[r], X, B, mirrored_row(n, rr_label(n, n - 2, p), mirror), rows, b0, wv, vec, identity);
+        load_row<W>(st.bot[r], X, B, mirrored_row(n, rr_label(n, n - 2, n - 1 - p), mirror), rows, b0, wv, vec,
+                    identity);
     }
     st.load_coefs(n - 2, st.cs[0]);
 
@@ -379,8 +384,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 #pragma unroll
     for (int r = 0; r < M; ++r) {
         const int p = st.tid * M + r;
-        store_row<W>(st.top[(r + UL) % M], Y, B, p, rows, b0, wv, vec);
-        store_row<W>(st.bot[(r - UL + M) % M], Y, B, n - 1 - p, rows, b0, wv, vec);
+        store_row<W>(st.top[(r + UL) % M], Y, B, mirrored_row(n, p, mirror), rows, b0, wv, vec);
+        store_row<W>(st.bot[(r - UL + M) % M], Y, B, mirrored_row(n, n - 1 - p, mirror), rows, b0, wv, vec);
     }
 }
 
@@ -663,7 +668,7 @@ template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     int n, int rows, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
     const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
-    float *dX, float *partial, const float *__restrict__ zeros, int vec_ok, int accumulate)
+    float *dX, float *partial, const float *__restrict__ zeros, int vec_ok, int accumulate, int g_identity)
 {
     if (!form_selected(flag, FORM, scaled_max)) return;
     using State = CarouselBwd<M, W, WAVES, FORM>;
@@ -707,8 +712,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
             const int p = st.tid * M + r;
             load_row<W>(st.zt[r], Yin, B, p, rows, b0, wv, vec, 0);
             load_row<W>(st.zb[r], Yin, B, n - 1 - p, rows, b0, wv, vec, 0);
-            load_row<W>(st.gt[r], G, B, p, rows, b0, wv, vec, 0);
-            load_row<W>(st.gb[r], G, B, n - 1 - p, rows, b0, wv, vec, 0);
+            load_row<W>(st.gt[r], G, B, p, rows, b0, wv, vec, g_identity);   // g_identity: G = I_n, not read
+            load_row<W>(st.gb[r], G, B, n - 1 - p, rows, b0, wv, vec, g_identity);
         }
         st.load_coefs(0, st.cs[0]);
 
@@ -736,7 +741,7 @@ inline void carousel_launch_fwd(const CarouselFwdArgs &a)
     const long long strips = (a.B + W - 1) / W;
     hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES, FORM>), dim3((unsigned)strips), dim3(64 * WAVES), 0,
                        a.stream, a.n, a.rows, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.coefs.scaled_max, a.X, a.Y,
-                       a.identity, a.vec_ok);
+                       a.identity, a.vec_ok, a.mirror);
 }
 
 template <int M, int WAVES, int FORM>
@@ -768,7 +773,8 @@ inline void carousel_launch_bwd(const CarouselBwdArgs &a)
 {
     hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.groups), dim3(64 * WAVES),
                        0, a.stream, a.n, a.rows, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
-                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.vec_ok, a.accumulate);
+                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.vec_ok, a.accumulate,
+                       a.g_identity);
 }
 
 template <int M, int WAVES, int FORM>

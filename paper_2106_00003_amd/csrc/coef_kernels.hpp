@@ -128,18 +128,36 @@ __device__ __forceinline__ double lift_reduce(double th, bool *odd)
 // the paper; end of Section 3) theta lists only the free pairs: `map` (nullptr: every pair is free)
 // gives each entry of E its index in theta, or -1 for a bypassed pair, which is run as a rotation
 // by zero.
+//
+// `mirror`: the tables are wanted for the mirrored problem, whose forward product equals the
+// transposed product of the original one up to a relabelling of the rows.  Relabel row r >= 1 as
+// n - r and keep row 0: the pairs of block k become the pairs of block n-2-k, arc by arc, and
+//     U(theta)^T = P^T U(theta') P,   theta'[k][p] = -theta[n-2-k][p] for p = 0 (pairs with row 0,
+//     whose order i < j survives the relabelling) and +theta[n-2-k][p] otherwise (order reversed:
+//     the sign change of the transpose and that of the swap cancel),
+// with P the relabelling.  So entry e = (k, p) of the mirrored problem reads the original entry
+// (n-2-k, p) with that sign.
 template <typename T>
-__device__ __forceinline__ T theta_at(const T *__restrict__ theta, const int *__restrict__ map, long long e)
+__device__ __forceinline__ T theta_at(const T *__restrict__ theta, const int *__restrict__ map, int mirror, int n,
+                                      long long e)
 {
-    if (!map) return theta[e];
+    T sign = T(1);
+    if (mirror) {
+        const int H = n >> 1;
+        const long long k = e / H;
+        const int p = (int)(e - k * H);
+        e = (long long)(n - 2 - k) * H + p;
+        if (p == 0) sign = T(-1);
+    }
+    if (!map) return sign * theta[e];
     const int c = map[e];
-    return c < 0 ? T(0) : theta[c];
+    return c < 0 ? T(0) : sign * theta[c];
 }
 
 // Standard form table, in E order.  `factor` (optional) receives the orientation sign (+1 when the
 // top position holds the smaller label) that the dtheta reduction multiplies its sums by.
 template <typename T>
-__global__ void coef_table_kernel(int n, const T *__restrict__ theta, const int *__restrict__ map,
+__global__ void coef_table_kernel(int n, const T *__restrict__ theta, const int *__restrict__ map, int mirror,
                                   const unsigned *flag, float scaled_max,
                                   typename Pair2<T>::type *__restrict__ table, T *__restrict__ factor)
 {
@@ -151,7 +169,7 @@ __global__ void coef_table_kernel(int n, const T *__restrict__ theta, const int 
         const int k = (int)(e / H), p = (int)(e % H);
         const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
         double s, c;
-        sincos((double)theta_at(theta, map, e), &s, &c);
+        sincos((double)theta_at(theta, map, mirror, n, e), &s, &c);
         if (a > b) s = -s;
         typename Pair2<T>::type out;
         out.x = (T)c;
@@ -169,7 +187,7 @@ __global__ void coef_table_kernel(int n, const T *__restrict__ theta, const int 
 // (-1)^m of theta = theta' + m*pi (lifted form).
 template <bool FWD>
 __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const int *__restrict__ map,
-                                   const unsigned *flag, float scaled_max, double *__restrict__ D,
+                                   int mirror, const unsigned *flag, float scaled_max, double *__restrict__ D,
                                    float *__restrict__ renorm)
 {
     const int form = selected_form(flag, scaled_max);
@@ -188,7 +206,7 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
         q = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1); // position of label r in the sequence of block k
         p = (q < H) ? q : n - 1 - q;
         D[(long long)k * n + q] = d;
-        const double th = (double)theta_at(theta, map, (long long)k * H + p);
+        const double th = (double)theta_at(theta, map, mirror, n, (long long)k * H + p);
         if (form == kFormScaled) {
             d *= cos_small(th);
         } else {
@@ -210,7 +228,7 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
 // sweep the same with the signs flipped.
 template <bool FWD>
 __global__ void scaled_table_kernel(int n, const float *__restrict__ theta, const int *__restrict__ map,
-                                    const unsigned *flag, float scaled_max, const double *__restrict__ D,
+                                    int mirror, const unsigned *flag, float scaled_max, const double *__restrict__ D,
                                     float2 *__restrict__ table, float *__restrict__ factor)
 {
     const int form = selected_form(flag, scaled_max);
@@ -221,7 +239,7 @@ __global__ void scaled_table_kernel(int n, const float *__restrict__ theta, cons
     if (e >= N) return;
     const int k = (int)(e / H), p = (int)(e % H);
     const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-    const double th = (double)theta_at(theta, map, e);
+    const double th = (double)theta_at(theta, map, mirror, n, e);
     const double da = D[(long long)k * n + p], db = D[(long long)k * n + (n - 1 - p)]; // before this block
     const double orient = (a < b) ? 1.0 : -1.0;
     if (form == kFormScaled) {

@@ -1,5 +1,6 @@
 // C ABI of the round-robin Givens library (see include/givens_rr.h for the contract).
 // Host side: argument checks, workspace, kernel selection, launches, optional event timing.
+#include <dlfcn.h>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -36,10 +37,11 @@ struct Workspace {
     Buffer partial;      // per-strip dtheta partial sums (two-stage reduction)
     Buffer acc;          // one accumulation buffer of N floats (accumulating reduction)
     Buffer zeros;        // N floats that are zeroed when allocated and never written again
+    Buffer gram;         // Gram-matrix reduction: C = Y G^T, n x n floats
     Buffer map;          // restricted parametrisation / odd n: index in theta of every entry of E, or -1
     int map_rows = 0, map_m = 0; // the (row count, m) the map was built for
     long long map_free = 0;      // its number of free angles
-    Buffer *all[10] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc, &zeros, &map};
+    Buffer *all[11] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc, &zeros, &gram, &map};
 };
 
 // One call's problem: `rows` coordinates of which the first m may rotate with every other one
@@ -243,7 +245,7 @@ FormPolicy form_policy(bool float_carousel)
 // forms' row factors; `policy.try_forms` adds the range check and those forms' tables.
 template <typename T>
 int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, FormPolicy policy, hipStream_t stream,
-                  Coefs<T> *out)
+                  Coefs<T> *out, int mirror = 0)
 {
     const bool try_scaled = policy.try_forms;
     const float scaled_max = policy.scaled_max;
@@ -278,14 +280,14 @@ int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, Form
             const unsigned scan_blocks = (unsigned)((scan_threads + threads - 1) / threads);
             if (forward) {
                 hipLaunchKernelGGL(scaled_scan_kernel<true>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
-                                   map, flag, scaled_max, D, rn);
+                                   map, mirror, flag, scaled_max, D, rn);
                 hipLaunchKernelGGL(scaled_table_kernel<true>, dim3(blocks), dim3(threads), 0, stream, n, theta,
-                                   map, flag, scaled_max, D, tab_s, factor);
+                                   map, mirror, flag, scaled_max, D, tab_s, factor);
             } else {
                 hipLaunchKernelGGL(scaled_scan_kernel<false>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
-                                   map, flag, scaled_max, D, rn);
+                                   map, mirror, flag, scaled_max, D, rn);
                 hipLaunchKernelGGL(scaled_table_kernel<false>, dim3(blocks), dim3(threads), 0, stream, n, theta,
-                                   map, flag, scaled_max, D, tab_s, factor);
+                                   map, mirror, flag, scaled_max, D, tab_s, factor);
             }
             out->scaled = CarouselCoefs{kFormScaled, tab_s, reinterpret_cast<const float2 *>(rn), flag, scaled_max};
             out->lifted = CarouselCoefs{kFormLifted, tab_s, reinterpret_cast<const float2 *>(rn), flag, scaled_max};
@@ -294,7 +296,7 @@ int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, Form
         out->standard = CarouselCoefs{kFormStandard, table, nullptr, flag, scaled_max};
     }
     hipLaunchKernelGGL(coef_table_kernel<T>, dim3(std::min(blocks, 4096u)), dim3(threads), 0, stream, n, theta,
-                       map, static_cast<const unsigned *>(flag), scaled_max, table, factor);
+                       map, mirror, static_cast<const unsigned *>(flag), scaled_max, table, factor);
     GIVENS_HIP(hipGetLastError());
     out->table = table;
     out->factor = factor;
@@ -327,7 +329,7 @@ int lds_forward(int n, int rows, long long B, const typename Pair2<T>::type *tab
 // workgroups with one row of partial sums each, or the accumulating variant.  `family` picks the kernel.
 template <typename T>
 int backward_chunks(int dev, int family, const Problem &pb, long long B, const Coefs<T> &coefs, const T *Y,
-                    const T *G, T *dX, T *dtheta, hipStream_t stream)
+                    const T *G, T *dX, T *dtheta, hipStream_t stream, int g_identity = 0)
 {
     const int n = pb.n, rows = pb.rows;
     const int *map = pb.map;
@@ -381,14 +383,14 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
                 hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(threads), 0, stream, N, acc);
                 const long long groups = carousel_bwd_groups(n, strips, cus);
                 if (coefs.all_forms) {
-                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.scaled, Y, G, dX, acc, zeros, 1,
+                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.scaled, Y, G, dX, acc, zeros, 1, g_identity,
                                                           stream))
                         return rc;
-                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.lifted, Y, G, dX, acc, zeros, 1,
+                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.lifted, Y, G, dX, acc, zeros, 1, g_identity,
                                                           stream))
                         return rc;
                 }
-                if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.standard, Y, G, dX, acc, zeros, 1,
+                if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.standard, Y, G, dX, acc, zeros, 1, g_identity,
                                                       stream))
                     return rc;
                 GIVENS_HIP(hipGetLastError());
@@ -425,14 +427,14 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
                                    coefs.table, Y, G, dX, partial);
             } else if constexpr (std::is_same<T, float>::value) {
                 if (coefs.all_forms) {
-                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX, partial, zeros, 0,
+                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX, partial, zeros, 0, g_identity,
                                                           stream))
                         return rc;
-                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX, partial, zeros, 0,
+                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX, partial, zeros, 0, g_identity,
                                                           stream))
                         return rc;
                 }
-                if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.standard, Y, G, dX, partial, zeros, 0,
+                if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.standard, Y, G, dX, partial, zeros, 0, g_identity,
                                                       stream))
                     return rc;
             } else {
@@ -448,6 +450,106 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
                                s0 > 0 ? 1 : 0);
             GIVENS_HIP(hipGetLastError());
         }
+    }
+    return GIVENS_OK;
+}
+
+// ---- rocBLAS, loaded on first use: only the Gram-matrix reduction needs it (one plain SGEMM), and the
+// library must load and run without it.
+struct RocblasApi {
+    bool tried = false, ok = false;
+    void *lib = nullptr;
+    int (*create_handle)(void **) = nullptr;
+    int (*destroy_handle)(void *) = nullptr;
+    int (*set_stream)(void *, hipStream_t) = nullptr;
+    int (*set_atomics_mode)(void *, int) = nullptr;
+    int (*sgemm)(void *, int, int, int, int, int, const float *, const float *, int, const float *, int,
+                 const float *, float *, int) = nullptr;
+    int (*sgemm_strided_batched)(void *, int, int, int, int, int, const float *, const float *, int, long long,
+                                 const float *, int, long long, const float *, float *, int, long long,
+                                 int) = nullptr;
+    void *handle[kMaxDevices] = {};
+};
+RocblasApi g_blas;
+constexpr int kBlasOpNone = 111, kBlasOpTranspose = 112; // rocblas_operation values of the public API
+
+bool rocblas_available()
+{
+    RocblasApi &b = g_blas;
+    if (b.tried) return b.ok;
+    b.tried = true;
+    for (const char *name : {"librocblas.so.5", "librocblas.so", "/opt/rocm/lib/librocblas.so"}) {
+        b.lib = dlopen(name, RTLD_NOW | RTLD_LOCAL);
+        if (b.lib) break;
+    }
+    if (!b.lib) return false;
+    b.create_handle = reinterpret_cast<decltype(b.create_handle)>(dlsym(b.lib, "rocblas_create_handle"));
+    b.destroy_handle = reinterpret_cast<decltype(b.destroy_handle)>(dlsym(b.lib, "rocblas_destroy_handle"));
+    b.set_stream = reinterpret_cast<decltype(b.set_stream)>(dlsym(b.lib, "rocblas_set_stream"));
+    b.set_atomics_mode = reinterpret_cast<decltype(b.set_atomics_mode)>(dlsym(b.lib, "rocblas_set_atomics_mode"));
+    b.sgemm = reinterpret_cast<decltype(b.sgemm)>(dlsym(b.lib, "rocblas_sgemm"));
+    b.sgemm_strided_batched = reinterpret_cast<decltype(b.sgemm_strided_batched)>(
+        dlsym(b.lib, "rocblas_sgemm_strided_batched"));
+    b.ok = b.create_handle && b.destroy_handle && b.set_stream && b.set_atomics_mode && b.sgemm &&
+           b.sgemm_strided_batched;
+    return b.ok;
+}
+
+// How many slices of the contraction (batch) dimension the Gram matrix is computed in.  The library's
+// SGEMM gives a 256 x 256 tile of C to one workgroup, so a 2048 x 2048 result alone would occupy 64
+// of the 256 CUs; slicing B and summing the slices' results afterwards (fixed order) fills the chip.
+int gram_slices(int rows, long long B)
+{
+    const long long tiles = (long long)((rows + 255) / 256) * ((rows + 255) / 256);
+    long long s = (256 + tiles - 1) / tiles;
+    s = std::min<long long>(s, 16);
+    s = std::min<long long>(s, std::max<long long>(1, B / 1024));
+    return (int)std::max<long long>(1, s);
+}
+
+__global__ void sum_slices_kernel(long long count, int slices, float *__restrict__ c)
+{
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (long long)gridDim.x * blockDim.x) {
+        float acc = c[i];
+        for (int s = 1; s < slices; ++s) acc += c[(long long)s * count + i];
+        c[i] = acc;
+    }
+}
+
+// C (rows x rows, row-major) = Y G^T for row-major rows x B operands: in the library's column-major
+// terms C^T = G_cm^T Y_cm with G_cm, Y_cm the B x rows column-major views of the same memory.
+// C has room for `slices` matrices; the result ends in the first.
+int gram_matrix(int dev, int rows, long long B, int slices, const float *Y, const float *G, float *C,
+                hipStream_t stream)
+{
+    RocblasApi &b = g_blas;
+    if (!rocblas_available() || B > 0x7fffffffLL) return GIVENS_ERR_UNSUPPORTED;
+    if (!b.handle[dev]) {
+        if (b.create_handle(&b.handle[dev]) != 0) { b.handle[dev] = nullptr; return GIVENS_ERR_UNSUPPORTED; }
+        (void)b.set_atomics_mode(b.handle[dev], 0); // no atomics: bit-identical results from run to run
+    }
+    if (b.set_stream(b.handle[dev], stream) != 0) return GIVENS_ERR_UNSUPPORTED;
+    const float one = 1.f, zero = 0.f;
+    const long long count = (long long)rows * rows;
+    const long long kc = B / slices;            // columns per slice; the remainder goes to a last GEMM
+    int st;
+    if (slices > 1)
+        st = b.sgemm_strided_batched(b.handle[dev], kBlasOpTranspose, kBlasOpNone, rows, rows, (int)kc, &one, G,
+                                     (int)B, kc, Y, (int)B, kc, &zero, C, rows, count, slices);
+    else
+        st = b.sgemm(b.handle[dev], kBlasOpTranspose, kBlasOpNone, rows, rows, (int)kc, &one, G, (int)B, Y, (int)B,
+                     &zero, C, rows);
+    if (st != 0) return GIVENS_ERR_UNSUPPORTED;
+    const long long tail = B - kc * slices;
+    if (tail > 0) {
+        st = b.sgemm(b.handle[dev], kBlasOpTranspose, kBlasOpNone, rows, rows, (int)tail, &one, G + kc * slices,
+                     (int)B, Y + kc * slices, (int)B, &one, C, rows);
+        if (st != 0) return GIVENS_ERR_UNSUPPORTED;
+    }
+    if (slices > 1) {
+        hipLaunchKernelGGL(sum_slices_kernel, dim3(1024), dim3(256), 0, stream, count, slices, C);
+        GIVENS_HIP(hipGetLastError());
     }
     return GIVENS_OK;
 }
@@ -487,10 +589,10 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
         if constexpr (std::is_same<T, float>::value) {
             Span span(1, stream);
             if (coefs.all_forms) {
-                rc = carousel_forward(n, rows, B, coefs.scaled, X, Y, identity, stream);
-                if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.lifted, X, Y, identity, stream);
+                rc = carousel_forward(n, rows, B, coefs.scaled, X, Y, identity, 0, stream);
+                if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.lifted, X, Y, identity, 0, stream);
             }
-            if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.standard, X, Y, identity, stream);
+            if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.standard, X, Y, identity, 0, stream);
             if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
         } else {
             rc = GIVENS_ERR_UNSUPPORTED;
@@ -528,9 +630,49 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
                                   form_policy(family == GIVENS_KERNEL_CAROUSEL && std::is_same<T, float>::value),
                                   stream, &coefs))
         return rc;
-    const int rc = backward_chunks<T>(dev, family, pb, B, coefs, Y, G, dX, dtheta, stream);
     t_state.last_kernel = family;
-    return rc;
+    if constexpr (std::is_same<T, float>::value) {
+        // Gram-matrix form for wide batches.  With C = Y G^T (rows x rows) the sums of the reverse sweep
+        // are those of the same sweep run on the operand C with the identity as upstream gradient:
+        // z_k gbar_k^T = A_k C A_k^T for the product A_k of the transposed blocks so far, and the sweep on
+        // (C, I) carries A_k C and A_k.  So dtheta costs one GEMM over B plus a rows-column sweep, and
+        // dX = U^T G one forward-type sweep over B (mirrored tables), instead of a two-strip sweep over B.
+        const bool wide = B >= 4LL * n;
+        const bool want_gram = family == GIVENS_KERNEL_CAROUSEL &&
+                               (g_reduction_choice == GIVENS_REDUCTION_GRAM ||
+                                (g_reduction_choice == GIVENS_REDUCTION_AUTO && wide));
+        if (want_gram && rocblas_available()) {
+            Workspace &ws = g_ws[dev];
+            const int slices = gram_slices(rows, B);
+            if (int rc = grow(ws.gram, (size_t)slices * rows * rows * sizeof(float))) return rc;
+            float *C = reinterpret_cast<float *>(ws.gram.ptr);
+            int rc;
+            {
+                Span span(1, stream);
+                rc = gram_matrix(dev, rows, B, slices, Y, G, C, stream);
+            }
+            if (rc == GIVENS_OK) {
+                rc = backward_chunks<T>(dev, family, pb, rows, coefs, C, nullptr, nullptr, dtheta, stream, 1);
+                if (rc == GIVENS_OK && dX) {
+                    Coefs<T> mirrored;
+                    rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(true), stream, &mirrored, 1);
+                    Span span(1, stream);
+                    if (rc == GIVENS_OK && mirrored.all_forms) {
+                        rc = carousel_forward(n, rows, B, mirrored.scaled, G, dX, 0, 1, stream);
+                        if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, mirrored.lifted, G, dX, 0, 1, stream);
+                    }
+                    if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, mirrored.standard, G, dX, 0, 1, stream);
+                    if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+                }
+                t_state.last_reduction = GIVENS_REDUCTION_GRAM;
+                return rc;
+            }
+            // the GEMM could not be run: fall through to the sweep over all B columns
+        } else if (g_reduction_choice == GIVENS_REDUCTION_GRAM && family == GIVENS_KERNEL_CAROUSEL) {
+            return GIVENS_ERR_UNSUPPORTED; // forced, but rocBLAS could not be loaded
+        }
+    }
+    return backward_chunks<T>(dev, family, pb, B, coefs, Y, G, dX, dtheta, stream);
 }
 
 } // namespace
@@ -654,6 +796,10 @@ int givens_release(void)
         }
         ws.map_rows = ws.map_m = 0;
         ws.map_free = 0;
+        if (g_blas.handle[d]) {
+            (void)g_blas.destroy_handle(g_blas.handle[d]);
+            g_blas.handle[d] = nullptr;
+        }
     }
     (void)hipSetDevice(keep);
     return rc;
@@ -690,7 +836,8 @@ int givens_last_kernel(void) { return givens::t_state.last_kernel; }
 
 int givens_set_reduction(int which)
 {
-    if (which != GIVENS_REDUCTION_AUTO && which != GIVENS_REDUCTION_TWO_STAGE && which != GIVENS_REDUCTION_ATOMIC)
+    if (which != GIVENS_REDUCTION_AUTO && which != GIVENS_REDUCTION_TWO_STAGE && which != GIVENS_REDUCTION_ATOMIC &&
+        which != GIVENS_REDUCTION_GRAM)
         return GIVENS_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(givens::g_mutex);
     const int prev = givens::g_reduction_choice;

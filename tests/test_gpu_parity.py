@@ -231,6 +231,58 @@ def test_atomic_reduction_matches_the_oracle_and_the_two_stage_result(n, B, seed
         binding.set_kernel(binding.KERNEL_AUTO)
 
 
+# ---------------------------------------------------------------- Gram-matrix form for wide batches
+@pytest.mark.parametrize("n,B,seed,dist", [(256, 1100, 75, "uniform"), (512, 2100, 76, "normal0.1"),
+                                           (1024, 4096, 77, "uniform")])
+def test_gram_reduction_for_wide_batches_matches_the_oracle(n, B, seed, dist):
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    binding.set_kernel(binding.KERNEL_CAROUSEL)
+    th_d, g_d = dev(data["theta"]), dev(data["G"])
+    y_d = binding.givens_forward(th_d, dev(data["X"]))
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], C.forward(data["theta"], data["X"]), data["G"])
+    try:
+        binding.set_reduction(binding.REDUCTION_AUTO)                  # B >= 4 n: the Gram form is the default
+        dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+        assert binding.last_reduction() == binding.REDUCTION_GRAM
+        assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
+        assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
+        first = host(dth_d).copy()
+        _, again = binding.givens_backward(th_d, y_d, g_d, want_dx=False)
+        assert np.array_equal(host(again), first)                      # reproducible
+        # dX written over G
+        g_buf = dev(data["G"])
+        binding.givens_backward(th_d, y_d, g_buf, dX=g_buf)
+        assert O.rel_fro(host(g_buf), want_dx) <= TOL_G
+        binding.set_reduction(binding.REDUCTION_TWO_STAGE)
+        _, two = binding.givens_backward(th_d, y_d, g_d, want_dx=False)
+        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+        assert O.rel_fro(first, host(two)) <= 1e-5
+    finally:
+        binding.set_reduction(binding.REDUCTION_AUTO)
+        binding.set_kernel(binding.KERNEL_AUTO)
+
+
+def test_gram_reduction_can_be_forced_on_a_narrow_batch_and_not_on_the_lds_family():
+    data = inputs.make_custom(256, 40, seed=78)
+    th_d, g_d = dev(data["theta"]), dev(data["G"])
+    want_y = C.forward(data["theta"], data["X"])
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
+    try:
+        binding.set_reduction(binding.REDUCTION_GRAM)
+        binding.set_kernel(binding.KERNEL_CAROUSEL)
+        y_d = binding.givens_forward(th_d, dev(data["X"]))
+        dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+        assert binding.last_reduction() == binding.REDUCTION_GRAM
+        assert O.rel_fro(host(dth_d), want_dth) <= TOL_G and O.rel_fro(host(dx_d), want_dx) <= TOL_G
+        binding.set_kernel(binding.KERNEL_LDS)
+        dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+        assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
+    finally:
+        binding.set_reduction(binding.REDUCTION_AUTO)
+        binding.set_kernel(binding.KERNEL_AUTO)
+
+
 def test_atomic_reduction_falls_back_for_the_lds_family():
     data = inputs.make_custom(34, 19, seed=74)
     try:

@@ -120,6 +120,13 @@ def test_standard_form_and_atomic_reduction_with_a_restricted_problem():
         binding.set_reduction(binding.REDUCTION_AUTO)
 
 
+def test_wide_batch_uses_the_gram_form_with_a_restricted_odd_problem():
+    check(255, 100, 1030, 353, kernel=binding.KERNEL_CAROUSEL)
+    assert binding.last_reduction() == binding.REDUCTION_GRAM
+    check(511, 510, 2050, 354, scale=0.1, kernel=binding.KERNEL_CAROUSEL, expect_form=binding.FORM_SCALED)
+    assert binding.last_reduction() == binding.REDUCTION_GRAM
+
+
 def test_unrestricted_m_gives_the_unrestricted_entry_points_result():
     n, B = 256, 24
     theta, X, G = make(n, n - 1, B, 361)
