@@ -183,7 +183,7 @@ int givens_last_rotation_form(void);
  * matrix C = Y G^T (the sums of the sweep are those of the same sweep on the operand C with upstream
  * gradient I_n) and computes dX = U^T G by a forward-type sweep; it needs librocblas at run time and
  * returns GIVENS_ERR_UNSUPPORTED when forced without it.  AUTO means GRAM for the carousel kernels
- * when B >= 4 n and rocBLAS loads, TWO_STAGE otherwise.  The LDS family and the f64 entry points
+ * when B >= 2 n and rocBLAS loads, TWO_STAGE otherwise.  The LDS family and the f64 entry points
  * always use TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
  */
 int givens_set_reduction(int which);

@@ -637,7 +637,7 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
         // z_k gbar_k^T = A_k C A_k^T for the product A_k of the transposed blocks so far, and the sweep on
         // (C, I) carries A_k C and A_k.  So dtheta costs one GEMM over B plus a rows-column sweep, and
         // dX = U^T G one forward-type sweep over B (mirrored tables), instead of a two-strip sweep over B.
-        const bool wide = B >= 4LL * n;
+        const bool wide = B >= 2LL * n;   // measured break-even is near B = 1.6 n
         const bool want_gram = family == GIVENS_KERNEL_CAROUSEL &&
                                (g_reduction_choice == GIVENS_REDUCTION_GRAM ||
                                 (g_reduction_choice == GIVENS_REDUCTION_AUTO && wide));

@@ -241,7 +241,7 @@ def test_gram_reduction_for_wide_batches_matches_the_oracle(n, B, seed, dist):
     y_d = binding.givens_forward(th_d, dev(data["X"]))
     want_dth, want_dx, _ = C.reverse_sweep(data["theta"], C.forward(data["theta"], data["X"]), data["G"])
     try:
-        binding.set_reduction(binding.REDUCTION_AUTO)                  # B >= 4 n: the Gram form is the default
+        binding.set_reduction(binding.REDUCTION_AUTO)                  # B >= 2 n: the Gram form is the default
         dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
         assert binding.last_reduction() == binding.REDUCTION_GRAM
         assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
