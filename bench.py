@@ -196,6 +196,13 @@ def main() -> int:
             "sample": f"fp64 C oracle, forward + reverse sweep on the first {cols} of {B} columns, n={n}",
             "fwd_s": t_f, "bwd_s": t_b,
         }
+        # the paper's own CPU baseline was single-threaded: the same forward on one thread, fewer columns
+        one_cols = min(64, cols)
+        t0 = time.perf_counter()
+        c_oracle.forward(data["theta"], np.ascontiguousarray(xs[:, :one_cols]), pairs=pairs, threads=1)
+        t_1 = time.perf_counter() - t0
+        result["cpu_baseline"]["fwd_1thread_updates_per_s"] = float(N) * one_cols / t_1
+        result["cpu_baseline"]["fwd_1thread_sample"] = f"forward on the first {one_cols} columns, 1 thread"
 
     print(json.dumps(result))
     return 0
