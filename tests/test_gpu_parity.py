@@ -293,6 +293,24 @@ def test_atomic_reduction_falls_back_for_the_lds_family():
         binding.set_reduction(binding.REDUCTION_AUTO)
 
 
+def test_largest_compiled_carousel_size_n8192():
+    """n = 8192 is the largest forward carousel shape; its reverse sweep runs in the LDS family."""
+    n, B = 8192, 24
+    data = inputs.make_custom(n, B, seed=79)
+    binding.set_kernel(binding.KERNEL_AUTO)
+    th_d = dev(data["theta"])
+    y_d = binding.givens_forward(th_d, dev(data["X"]))
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+    want_y = C.forward(data["theta"], data["X"])
+    assert O.rel_fro(host(y_d), want_y) <= TOL_Y
+    dx_d, dth_d = binding.givens_backward(th_d, y_d, dev(data["G"]))
+    assert binding.last_kernel() == binding.KERNEL_LDS
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"], want_x=False)
+    assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
+    assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
+    binding.release()
+
+
 def test_carousel_rejects_shapes_it_does_not_cover():
     data = inputs.make_custom(34, 8, seed=1)
     binding.set_kernel(binding.KERNEL_CAROUSEL)
