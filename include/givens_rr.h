@@ -140,6 +140,32 @@ int givens_build_restricted_f64(int n, int m, const double *theta, double *U, vo
 int givens_backward_restricted_f64(int n, int m, int64_t B, const double *theta, const double *Y,
                                    const double *G, double *dX, double *dtheta, void *stream);
 
+/*
+ * Unitary extension (the paper's appendix "Adaptations to U(n)").  Every pair e = (i, j), i < j, has a
+ * rotation angle theta_e and a phase angle phi_e, and its factor is the identity except for
+ *     G_ii = exp(i phi) cos(theta),  G_ij = -sin(theta),  G_ji = exp(i phi) sin(theta),  G_jj = cos(theta)
+ * (the appendix's forward algorithm: r_i = exp(i phi) cos U_i - sin U_j, r_j = exp(i phi) sin U_i + cos U_j);
+ * U = G^{e_1} ... G^{e_N} over the same round-robin sequence E, n even.
+ *   theta, phi, dtheta, dphi : N reals in E order.
+ *   X, Y, U, G, dX : complex, row-major n x B (n x n for U), each element stored as (re, im): 2 n B reals.
+ * givens_unitary_backward takes the forward output Y and the upstream gradient G = dL/dRe(Y) + i dL/dIm(Y)
+ * of a real loss L (dL = Re sum conj(G) dY) and returns dL/dtheta, dL/dphi and dX = U^dagger G (dX may be
+ * NULL, may be the buffer of G).  Per pair of block k, with z and gbar the carried strips:
+ *     dtheta_e = Re sum_b ( conj(gbar_j) z_i - conj(gbar_i) z_j ),  dphi_e = Re <gbar, P_e z>
+ * (Q_e and P_e of the appendix), then the block is undone with the adjoint factors.
+ * These entry points run in the LDS strip family only.  Aliasing, streams and errors as elsewhere.
+ */
+int givens_unitary_forward(int n, int64_t B, const float *theta, const float *phi, const float *X, float *Y,
+                           void *stream);
+int givens_unitary_build(int n, const float *theta, const float *phi, float *U, void *stream);
+int givens_unitary_backward(int n, int64_t B, const float *theta, const float *phi, const float *Y, const float *G,
+                            float *dX, float *dtheta, float *dphi, void *stream);
+int givens_unitary_forward_f64(int n, int64_t B, const double *theta, const double *phi, const double *X,
+                               double *Y, void *stream);
+int givens_unitary_build_f64(int n, const double *theta, const double *phi, double *U, void *stream);
+int givens_unitary_backward_f64(int n, int64_t B, const double *theta, const double *phi, const double *Y,
+                                const double *G, double *dX, double *dtheta, double *dphi, void *stream);
+
 /* Frees every workspace the library holds (all devices).  Synchronises the devices it touches. */
 int givens_release(void);
 

@@ -203,3 +203,12 @@ def finite_differences(theta, phi, operand, upstream, eps: float = 1e-6, pairs=N
             g[a] = (lp - lm) / (2.0 * eps)
         out.append(g)
     return out[0], out[1]
+
+
+def rel_fro(a, b) -> float:
+    """||a - b||_F / ||b||_F for complex (or real) arrays, in complex128 (b is the reference)."""
+    a = np.asarray(a, dtype=np.complex128)
+    b = np.asarray(b, dtype=np.complex128)
+    den = float(np.linalg.norm(b.ravel()))
+    num = float(np.linalg.norm((a - b).ravel()))
+    return num / den if den > 0 else num

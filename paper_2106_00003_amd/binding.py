@@ -28,6 +28,8 @@ EXPORTS = [
     "givens_num_angles", "rr_schedule_restricted",
     "givens_forward_restricted", "givens_build_restricted", "givens_backward_restricted",
     "givens_forward_restricted_f64", "givens_build_restricted_f64", "givens_backward_restricted_f64",
+    "givens_unitary_forward", "givens_unitary_build", "givens_unitary_backward",
+    "givens_unitary_forward_f64", "givens_unitary_build_f64", "givens_unitary_backward_f64",
 ]
 
 _lib = None
@@ -68,6 +70,12 @@ def lib():
         getattr(L, name).argtypes = [i32, i32, vp, vp, vp]
     for name in ("givens_backward_restricted", "givens_backward_restricted_f64"):
         getattr(L, name).argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp]
+    for name in ("givens_unitary_forward", "givens_unitary_forward_f64"):
+        getattr(L, name).argtypes = [i32, i64, vp, vp, vp, vp, vp]
+    for name in ("givens_unitary_build", "givens_unitary_build_f64"):
+        getattr(L, name).argtypes = [i32, vp, vp, vp, vp]
+    for name in ("givens_unitary_backward", "givens_unitary_backward_f64"):
+        getattr(L, name).argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]
     L.givens_error_string.argtypes = [i32]
     L.givens_error_string.restype = ctypes.c_char_p
     L.givens_set_kernel.argtypes = [i32]
@@ -226,6 +234,70 @@ def givens_backward_restricted(theta, Y, G, m: int, dX=None, dtheta=None, want_d
               _dev(dX, "dX", Y.dtype), _dev(dtheta, "dtheta", Y.dtype), _stream_ptr(stream)),
            "givens_backward_restricted")
     return dX, dtheta
+
+
+def _real_dtype(t):
+    import torch
+    return {torch.complex64: torch.float32, torch.complex128: torch.float64}[t.dtype]
+
+
+def _csuffix(t) -> str:
+    import torch
+    if t.dtype == torch.complex64:
+        return ""
+    if t.dtype == torch.complex128:
+        return "_f64"
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def givens_unitary_forward(theta, phi, X, Y=None, stream=None):
+    """Y = U(theta, phi) X for a complex X of shape (n, B) (complex64 or complex128 device tensor)."""
+    import torch
+    n, B = X.shape
+    if theta.numel() != n * (n - 1) // 2 or phi.numel() != theta.numel():
+        raise ValueError("theta and phi must have n(n-1)/2 entries")
+    if Y is None:
+        Y = torch.empty_like(X)
+    rd = _real_dtype(X)
+    fn = getattr(lib(), "givens_unitary_forward" + _csuffix(X))
+    _check(fn(n, B, _dev(theta, "theta", rd), _dev(phi, "phi", rd), _dev(X, "X"), _dev(Y, "Y", X.dtype),
+              _stream_ptr(stream)), "givens_unitary_forward")
+    return Y
+
+
+def givens_unitary_build(theta, phi, n: int, U=None, stream=None):
+    import torch
+    if theta.numel() != n * (n - 1) // 2 or phi.numel() != theta.numel():
+        raise ValueError("theta and phi must have n(n-1)/2 entries")
+    cd = torch.complex64 if theta.dtype == torch.float32 else torch.complex128
+    if U is None:
+        U = torch.empty((n, n), dtype=cd, device=theta.device)
+    fn = getattr(lib(), "givens_unitary_build" + _csuffix(U))
+    _check(fn(n, _dev(theta, "theta"), _dev(phi, "phi", theta.dtype), _dev(U, "U", cd), _stream_ptr(stream)),
+           "givens_unitary_build")
+    return U
+
+
+def givens_unitary_backward(theta, phi, Y, G, dX=None, dtheta=None, dphi=None, want_dx: bool = True, stream=None):
+    """Returns (dX, dtheta, dphi) from the forward output Y and the upstream gradient G (complex)."""
+    import torch
+    n, B = Y.shape
+    if theta.numel() != n * (n - 1) // 2 or phi.numel() != theta.numel():
+        raise ValueError("theta and phi must have n(n-1)/2 entries")
+    if G.shape != Y.shape:
+        raise ValueError("G must have the shape of Y")
+    rd = _real_dtype(Y)
+    if dX is None and want_dx:
+        dX = torch.empty_like(G)
+    if dtheta is None:
+        dtheta = torch.empty_like(theta)
+    if dphi is None:
+        dphi = torch.empty_like(phi)
+    fn = getattr(lib(), "givens_unitary_backward" + _csuffix(Y))
+    _check(fn(n, B, _dev(theta, "theta", rd), _dev(phi, "phi", rd), _dev(Y, "Y"), _dev(G, "G", Y.dtype),
+              _dev(dX, "dX", Y.dtype), _dev(dtheta, "dtheta", rd), _dev(dphi, "dphi", rd), _stream_ptr(stream)),
+           "givens_unitary_backward")
+    return dX, dtheta, dphi
 
 
 def set_kernel(which: int) -> int:

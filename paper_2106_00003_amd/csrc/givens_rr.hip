@@ -14,6 +14,7 @@
 #include "coef_kernels.hpp"
 #include "lds_kernels.hpp"
 #include "rr_index.h"
+#include "unitary_kernels.hpp"
 
 namespace givens {
 namespace {
@@ -675,6 +676,118 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
     return backward_chunks<T>(dev, family, pb, B, coefs, Y, G, dX, dtheta, stream);
 }
 
+// ---- unitary extension (appendix): complex operands, LDS strip kernels
+template <typename T>
+int unitary_strip_width(int n, long long B, int strips_in_lds)
+{
+    int w = 7;
+    while (w > 1 && (size_t)n * w * 2 * sizeof(T) * strips_in_lds > kLdsBudgetBytes) --w;
+    if ((size_t)n * w * 2 * sizeof(T) * strips_in_lds > kLdsBudgetBytes) return 0;
+    while (w > 1 && (B + w - 1) / w < 1024) --w;
+    return w;
+}
+
+template <typename T>
+int unitary_table(int dev, int n, const T *theta, const T *phi, hipStream_t stream,
+                  const typename Cplx<T>::quad **out)
+{
+    const long long N = (long long)n * (n - 1) / 2;
+    Workspace &ws = g_ws[dev];
+    if (int rc = grow(ws.table, (size_t)N * sizeof(typename Cplx<T>::quad))) return rc;
+    auto *table = reinterpret_cast<typename Cplx<T>::quad *>(ws.table.ptr);
+    Span span(0, stream);
+    const int threads = 256;
+    const unsigned blocks = (unsigned)std::min<long long>((N + threads - 1) / threads, 4096);
+    hipLaunchKernelGGL(unitary_table_kernel<T>, dim3(blocks), dim3(threads), 0, stream, n, theta, phi, table);
+    GIVENS_HIP(hipGetLastError());
+    *out = table;
+    return GIVENS_OK;
+}
+
+template <typename T>
+int unitary_forward_impl(int n, long long B, const T *theta, const T *phi, const T *X, T *Y, int identity,
+                         void *stream_v)
+{
+    using C = typename Cplx<T>::type;
+    if (int rc = check_n(n)) return rc;
+    if (B < 1) return GIVENS_ERR_BAD_B;
+    if (!theta || !phi || !Y || (!identity && !X)) return GIVENS_ERR_NULL;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    if (int rc = current_device(&dev)) return rc;
+    timing_begin_call();
+    const int w = unitary_strip_width<T>(n, B, 1);
+    if (w == 0) return GIVENS_ERR_UNSUPPORTED;
+    const typename Cplx<T>::quad *table = nullptr;
+    if (int rc = unitary_table<T>(dev, n, theta, phi, stream, &table)) return rc;
+    const size_t smem = (size_t)n * w * sizeof(C);
+    auto kern = unitary_forward_kernel<T>;
+    GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    Span span(1, stream);
+    hipLaunchKernelGGL(kern, dim3((unsigned)((B + w - 1) / w)), dim3(kUnitaryThreads), smem, stream, n, B, w, table,
+                       reinterpret_cast<const C *>(X), reinterpret_cast<C *>(Y), identity);
+    GIVENS_HIP(hipGetLastError());
+    t_state.last_kernel = GIVENS_KERNEL_LDS;
+    return GIVENS_OK;
+}
+
+template <typename T>
+int unitary_backward_impl(int n, long long B, const T *theta, const T *phi, const T *Y, const T *G, T *dX,
+                          T *dtheta, T *dphi, void *stream_v)
+{
+    using C = typename Cplx<T>::type;
+    if (int rc = check_n(n)) return rc;
+    if (B < 1) return GIVENS_ERR_BAD_B;
+    if (!theta || !phi || !Y || !G || !dtheta || !dphi) return GIVENS_ERR_NULL;
+    if (dX && (const void *)dX == (const void *)Y) return GIVENS_ERR_ALIAS;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    if (int rc = current_device(&dev)) return rc;
+    timing_begin_call();
+    const int w = unitary_strip_width<T>(n, B, 2);
+    if (w == 0) return GIVENS_ERR_UNSUPPORTED;
+    const typename Cplx<T>::quad *table = nullptr;
+    if (int rc = unitary_table<T>(dev, n, theta, phi, stream, &table)) return rc;
+    const long long N = (long long)n * (n - 1) / 2;
+    const long long strips = (B + w - 1) / w;
+    long long rows = (long long)(kPartialCapBytes / ((size_t)2 * N * sizeof(T)));
+    rows = std::max<long long>(1, std::min(rows, strips));
+    Workspace &ws = g_ws[dev];
+    if (int rc = grow(ws.partial, (size_t)rows * 2 * N * sizeof(T))) return rc;
+    T *partial = reinterpret_cast<T *>(ws.partial.ptr);
+    const size_t smem = (size_t)2 * n * w * sizeof(C);
+    auto kern = unitary_backward_kernel<T>;
+    GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    for (long long s0 = 0; s0 < strips; s0 += rows) {
+        const long long ns = std::min(rows, strips - s0);
+        {
+            Span span(1, stream);
+            hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kUnitaryThreads), smem, stream, n, B, w, s0, table,
+                               reinterpret_cast<const C *>(Y), reinterpret_cast<const C *>(G),
+                               reinterpret_cast<C *>(dX), partial);
+            GIVENS_HIP(hipGetLastError());
+        }
+        {
+            Span span(2, stream);
+            const int threads = 256;
+            const unsigned blocks = (unsigned)((N + threads - 1) / threads);
+            hipLaunchKernelGGL(sum_rows_kernel<T>, dim3(blocks), dim3(threads), 0, stream, N, ns, 2 * N, partial,
+                               dtheta, s0 > 0 ? 1 : 0);
+            hipLaunchKernelGGL(sum_rows_kernel<T>, dim3(blocks), dim3(threads), 0, stream, N, ns, 2 * N, partial + N,
+                               dphi, s0 > 0 ? 1 : 0);
+            GIVENS_HIP(hipGetLastError());
+        }
+    }
+    t_state.last_kernel = GIVENS_KERNEL_LDS;
+    t_state.last_reduction = GIVENS_REDUCTION_TWO_STAGE;
+    t_state.last_flag = nullptr;
+    return GIVENS_OK;
+}
+
 } // namespace
 } // namespace givens
 
@@ -775,6 +888,35 @@ int givens_backward_restricted_f64(int n, int m, int64_t B, const double *theta,
                                    double *dX, double *dtheta, void *stream)
 {
     return givens::backward_impl<double>(n, m, B, theta, Y, G, dX, dtheta, stream);
+}
+
+int givens_unitary_forward(int n, int64_t B, const float *theta, const float *phi, const float *X, float *Y,
+                           void *stream)
+{
+    return givens::unitary_forward_impl<float>(n, B, theta, phi, X, Y, 0, stream);
+}
+int givens_unitary_build(int n, const float *theta, const float *phi, float *U, void *stream)
+{
+    return givens::unitary_forward_impl<float>(n, n, theta, phi, nullptr, U, 1, stream);
+}
+int givens_unitary_backward(int n, int64_t B, const float *theta, const float *phi, const float *Y, const float *G,
+                            float *dX, float *dtheta, float *dphi, void *stream)
+{
+    return givens::unitary_backward_impl<float>(n, B, theta, phi, Y, G, dX, dtheta, dphi, stream);
+}
+int givens_unitary_forward_f64(int n, int64_t B, const double *theta, const double *phi, const double *X,
+                               double *Y, void *stream)
+{
+    return givens::unitary_forward_impl<double>(n, B, theta, phi, X, Y, 0, stream);
+}
+int givens_unitary_build_f64(int n, const double *theta, const double *phi, double *U, void *stream)
+{
+    return givens::unitary_forward_impl<double>(n, n, theta, phi, nullptr, U, 1, stream);
+}
+int givens_unitary_backward_f64(int n, int64_t B, const double *theta, const double *phi, const double *Y,
+                                const double *G, double *dX, double *dtheta, double *dphi, void *stream)
+{
+    return givens::unitary_backward_impl<double>(n, B, theta, phi, Y, G, dX, dtheta, dphi, stream);
 }
 
 int givens_release(void)

@@ -1,0 +1,109 @@
+"""GPU parity of the unitary extension (the paper's appendix) through the C ABI against oracle/unitary_oracle.py."""
+import numpy as np
+import pytest
+
+from oracle import givens_oracle as O
+from oracle import unitary_oracle as V
+from paper_2106_00003_amd import binding
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    binding.lib()
+    yield
+    binding.release()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def make(n, B, seed, real, cplx):
+    rng = np.random.default_rng(seed)
+    count = n * (n - 1) // 2
+    theta = rng.uniform(-np.pi, np.pi, count).astype(real)
+    phi = rng.uniform(-np.pi, np.pi, count).astype(real)
+    x = (rng.standard_normal((n, B)) + 1j * rng.standard_normal((n, B))).astype(cplx)
+    g = (rng.standard_normal((n, B)) + 1j * rng.standard_normal((n, B))).astype(cplx)
+    return theta, phi, x, g
+
+
+def check(n, B, seed, real=np.float32, cplx=np.complex64, tol_y=1e-5, tol_g=1e-4):
+    theta, phi, x, g = make(n, B, seed, real, cplx)
+    print(f"[unitary] n={n} B={B} seed={seed} dtype={np.dtype(cplx).name}", flush=True)
+    th_d, ph_d = dev(theta), dev(phi)
+    y_d = binding.givens_unitary_forward(th_d, ph_d, dev(x))
+    want_y = V.forward_blocks(theta, phi, x)
+    assert V.rel_fro(host(y_d), want_y) <= tol_y
+    dx_d, dth_d, dph_d = binding.givens_unitary_backward(th_d, ph_d, y_d, dev(g))
+    want_dth, want_dph, want_dx, _ = V.reverse_sweep_blocks(theta, phi, want_y, g)
+    assert V.rel_fro(host(dx_d), want_dx) <= tol_g
+    assert V.rel_fro(host(dth_d), want_dth) <= tol_g
+    assert V.rel_fro(host(dph_d), want_dph) <= tol_g
+    u_d = binding.givens_unitary_build(th_d, ph_d, n)
+    want_u = V.forward_blocks(theta, phi, np.eye(n))
+    assert V.rel_fro(host(u_d), want_u) <= tol_y
+    return theta, phi, x, g, host(y_d)
+
+
+def test_float64_against_the_definition_and_finite_differences():
+    n, B = 8, 4
+    theta, phi, x, g, y = check(n, B, 401, np.float64, np.complex128, 1e-12, 1e-12)
+    u = V.dense_product(n, theta, phi)                                   # explicit factors
+    assert V.rel_fro(y, u @ x) <= 1e-12
+    _, dth_d, dph_d = binding.givens_unitary_backward(dev(theta), dev(phi), dev(y), dev(g))
+    fd_th, fd_ph = V.finite_differences(theta, phi, x, g)
+    assert V.rel_fro(host(dth_d), fd_th) <= 1e-7 and V.rel_fro(host(dph_d), fd_ph) <= 1e-7
+
+
+@pytest.mark.parametrize("n,B,seed", [(2, 1, 411), (4, 3, 412), (34, 19, 413), (130, 40, 414), (256, 64, 415)])
+def test_float32_shapes(n, B, seed):
+    check(n, B, seed)
+
+
+def test_n1024_and_in_place():
+    n, B = 1024, 20
+    theta, phi, x, g, y = check(n, B, 421)
+    buf = dev(x)
+    binding.givens_unitary_forward(dev(theta), dev(phi), buf, Y=buf)
+    assert np.array_equal(host(buf), y)
+    g_buf = dev(g)
+    dx_d, _, _ = binding.givens_unitary_backward(dev(theta), dev(phi), dev(y), g_buf, dX=g_buf)
+    want_dx = V.grad_operand(theta, phi, g) if n <= 64 else None
+    u_d = binding.givens_unitary_build(dev(theta), dev(phi), n)
+    u = host(u_d).astype(np.complex128)
+    assert V.rel_fro(u.conj().T @ u, np.eye(n)) <= 1e-5
+    assert V.rel_fro(host(g_buf), u.conj().T @ g.astype(np.complex128)) <= 1e-4
+
+
+def test_zero_phases_reproduce_the_real_entry_points():
+    n, B = 256, 32
+    rng = np.random.default_rng(431)
+    theta = rng.uniform(-np.pi, np.pi, n * (n - 1) // 2).astype(np.float32)
+    x = rng.standard_normal((n, B)).astype(np.float32)
+    y_c = host(binding.givens_unitary_forward(dev(theta), dev(np.zeros_like(theta)), dev(x.astype(np.complex64))))
+    binding.set_kernel(binding.KERNEL_LDS)
+    try:
+        y_r = host(binding.givens_forward(dev(theta), dev(x)))
+    finally:
+        binding.set_kernel(binding.KERNEL_AUTO)
+    assert np.abs(y_c.imag).max() == 0.0
+    assert V.rel_fro(y_c.real, y_r) <= 2e-6
+
+
+def test_argument_errors():
+    L = binding.lib()
+    assert L.givens_unitary_forward(7, 4, None, None, None, None, None) == -1
+    assert L.givens_unitary_forward(8, 0, None, None, None, None, None) == -2
+    assert L.givens_unitary_forward(8, 4, None, None, None, None, None) == -3
+    assert L.givens_unitary_backward(8, 4, None, None, None, None, None, None, None, None) == -3
