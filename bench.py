@@ -47,6 +47,47 @@ def _traffic_from_profiles(kernel_tag: str):
     return float(m.group(1)) if m else None
 
 
+def _bench_unitary(args, binding, torch, np) -> int:
+    """Forward + backward of the unitary extension on synthetic complex64 data (LDS strip kernels)."""
+    n, B = (int(v) for v in args.unitary.split(","))
+    N = n * (n - 1) // 2
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20210699)
+    theta = (torch.rand(N, device="cuda", generator=gen) * 2 - 1) * np.pi
+    phi = (torch.rand(N, device="cuda", generator=gen) * 2 - 1) * np.pi
+    x = torch.randn(n, B, 2, device="cuda", generator=gen)
+    g = torch.randn(n, B, 2, device="cuda", generator=gen)
+    x, g = torch.view_as_complex(x), torch.view_as_complex(g)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    dth, dph = torch.empty_like(theta), torch.empty_like(phi)
+
+    def step():
+        binding.givens_unitary_forward(theta, phi, x, Y=y)
+        t_f = binding.last_timing()
+        binding.givens_unitary_backward(theta, phi, y, g, dX=dx, dtheta=dth, dphi=dph)
+        return t_f, binding.last_timing()
+
+    binding.set_timing(True)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    times = [step() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    binding.set_timing(False)
+    print(json.dumps({
+        "metric": "unitary_row_pair_complex_column_updates_per_s_fwd_bwd", "value": float(N) * B / (ms * 1e-3),
+        "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "dtype": "c64", "data": "synthetic",
+        "config": {"workload": f"unitary_n{n}_B{B}_c64", "n": n, "B": B, "angles": 2 * N},
+        "kernel_ms": {"fwd_table": float(np.mean([t[0][0] for t in times])),
+                      "fwd_sweep": float(np.mean([t[0][1] for t in times])),
+                      "bwd_sweep": float(np.mean([t[1][1] for t in times])),
+                      "bwd_reduce": float(np.mean([t[1][2] for t in times]))}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +98,9 @@ def main() -> int:
     ap.add_argument("--restricted", type=str, default=None, metavar="ROWS,M",
                     help="time the restricted entry points instead: ROWS coordinates (may be odd), pairs (i, j) "
                          "with i < M free, the chosen workload's B and angle distribution; not the headline metric")
+    ap.add_argument("--unitary", type=str, default=None, metavar="N,B",
+                    help="time the unitary (complex) entry points on an N x B complex64 operand instead and print a "
+                         "short JSON line; not the headline metric")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="after the steps, run one plain device copy of X into Y (n*B*4 bytes read and "
@@ -78,6 +122,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     binding.lib()
     binding.set_kernel(binding.KERNEL_AUTO)
+
+    if args.unitary:
+        return _bench_unitary(args, binding, torch, np)
 
     data = inputs.make_inputs(args.workload)
     wl = data["workload"]

@@ -62,6 +62,32 @@ class _GivensMatrix(torch.autograd.Function):
         return dtheta, None, None
 
 
+class _UnitaryApply(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, theta, phi, X):
+        Y = binding.givens_unitary_forward(theta.detach().contiguous(), phi.detach().contiguous(),
+                                           X.detach().contiguous())
+        ctx.save_for_backward(theta, phi, Y)
+        return Y
+
+    @staticmethod
+    @torch.autograd.function.once_differentiable
+    def backward(ctx, G):
+        # PyTorch hands a complex output's gradient over as dL/dRe + i dL/dIm for a real loss L, which is
+        # the convention of givens_unitary_backward, and expects the same for the complex input X.
+        theta, phi, Y = ctx.saved_tensors
+        need_dx = ctx.needs_input_grad[2]
+        dX, dtheta, dphi = binding.givens_unitary_backward(theta.detach().contiguous(), phi.detach().contiguous(),
+                                                           Y, G.contiguous(), want_dx=need_dx)
+        return dtheta, dphi, (dX if need_dx else None)
+
+
+def givens_unitary_apply(theta: torch.Tensor, phi: torch.Tensor, X: torch.Tensor) -> torch.Tensor:
+    """Y = U(theta, phi) X for complex X of shape (n, B) (the paper's appendix on U(n)); differentiable in
+    theta, phi and X."""
+    return _UnitaryApply.apply(theta, phi, X)
+
+
 def givens_apply(theta: torch.Tensor, X: torch.Tensor, m: int | None = None) -> torch.Tensor:
     """Y = U(theta) X for X of shape (n, B) (columns are the batch); differentiable in theta and X.
     m restricts the parametrisation to the pairs (i, j) with i < m (Section 5); n may be odd."""

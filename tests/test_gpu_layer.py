@@ -89,6 +89,27 @@ def test_restricted_and_odd_layer_gradients():
                                     rtol=1e-6)
 
 
+def test_unitary_function_gradcheck_and_oracle():
+    L = _layer()
+    from oracle import unitary_oracle as V
+    n, B = 8, 3
+    rng = np.random.default_rng(95)
+    count = n * (n - 1) // 2
+    theta = torch.from_numpy(rng.uniform(-np.pi, np.pi, count)).cuda().requires_grad_(True)
+    phi = torch.from_numpy(rng.uniform(-np.pi, np.pi, count)).cuda().requires_grad_(True)
+    X = torch.from_numpy(rng.standard_normal((n, B)) + 1j * rng.standard_normal((n, B))).cuda().requires_grad_(True)
+    assert torch.autograd.gradcheck(L.givens_unitary_apply, (theta, phi, X), eps=1e-6, atol=1e-7, rtol=1e-6)
+    g = rng.standard_normal((n, B)) + 1j * rng.standard_normal((n, B))
+    Y = L.givens_unitary_apply(theta, phi, X)
+    loss = (torch.from_numpy(g).cuda().conj() * Y).real.sum()          # L = Re <G, Y>
+    loss.backward()
+    th, ph, x = theta.detach().cpu().numpy(), phi.detach().cpu().numpy(), X.detach().cpu().numpy()
+    want_dth, want_dph, want_dx, _ = V.reverse_sweep(th, ph, V.forward(th, ph, x), g)
+    assert V.rel_fro(theta.grad.cpu().numpy(), want_dth) <= 1e-12
+    assert V.rel_fro(phi.grad.cpu().numpy(), want_dph) <= 1e-12
+    assert V.rel_fro(X.grad.cpu().numpy(), want_dx) <= 1e-12
+
+
 def test_gradient_descent_on_the_angles_fits_a_rotation():
     L = _layer()
     torch.manual_seed(5)
