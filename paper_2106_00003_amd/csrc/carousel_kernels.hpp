@@ -592,16 +592,13 @@ struct CarouselBwd {
         // the inner slots all run after the exchange slots here: splitting them around the exchange as
         // the forward kernel does costs registers this kernel does not have (it spills and gets slower)
         constexpr int kInner = M > 2 ? M - 2 : 0;
-        constexpr int kInnerA = 0;
-        if constexpr (kInnerA > 0) sweep_inner<U, RN, 1>(cur, rn, sums, std::make_integer_sequence<int, kInnerA>{});
         sums[0] = sweep_slot<U, 0, RN>(cur, rn);
         if constexpr (M > 1) sums[M - 1] = sweep_slot<U, M - 1, RN>(cur, rn);
         if constexpr (!LAST) {
             publish<U, 0>(zt, zb);
             publish<U, 1>(gt, gb);
         }
-        if constexpr (kInner - kInnerA > 0)
-            sweep_inner<U, RN, 1 + kInnerA>(cur, rn, sums, std::make_integer_sequence<int, kInner - kInnerA>{});
+        if constexpr (kInner > 0) sweep_inner<U, RN, 1>(cur, rn, sums, std::make_integer_sequence<int, kInner>{});
         if (accumulate) {
             float *dst = part_lane + (long long)k * H;   // H = M * lanes
 #pragma unroll

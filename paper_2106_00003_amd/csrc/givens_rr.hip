@@ -41,7 +41,6 @@ struct Workspace {
     Buffer gram;         // Gram-matrix reduction: C = Y G^T, n x n floats
     Buffer map;          // restricted parametrisation / odd n: index in theta of every entry of E, or -1
     int map_rows = 0, map_m = 0; // the (row count, m) the map was built for
-    long long map_free = 0;      // its number of free angles
     Buffer *all[11] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc, &zeros, &gram, &map};
 };
 
@@ -200,7 +199,6 @@ int resolve_problem(int dev, int rows, int m, Problem *out)
         GIVENS_HIP(hipMemcpy(ws.map.ptr, host.data(), (size_t)N * sizeof(int), hipMemcpyHostToDevice));
         ws.map_rows = rows;
         ws.map_m = m;
-        ws.map_free = next;
     }
     out->map = reinterpret_cast<const int *>(ws.map.ptr);
     return GIVENS_OK;
@@ -937,7 +935,6 @@ int givens_release(void)
             *b = Buffer{};
         }
         ws.map_rows = ws.map_m = 0;
-        ws.map_free = 0;
         if (g_blas.handle[d]) {
             (void)g_blas.destroy_handle(g_blas.handle[d]);
             g_blas.handle[d] = nullptr;

@@ -368,3 +368,31 @@ def test_upstream_equal_to_output_gives_tiny_gradient():
     scale = float(np.linalg.norm(data["X"])) ** 2
     assert float(np.max(np.abs(host(dth_d)))) <= 1e-5 * scale / 256
     assert O.rel_fro(host(dx_d), data["X"]) <= TOL_G
+
+
+def test_calls_on_a_side_stream_and_event_timing():
+    data = inputs.make_custom(512, 96, seed=90)
+    want_y = C.forward(data["theta"], data["X"])
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
+    binding.set_kernel(binding.KERNEL_AUTO)
+    side = torch.cuda.Stream()
+    th_d, x_d, g_d = dev(data["theta"]), dev(data["X"]), dev(data["G"])
+    torch.cuda.synchronize()
+    binding.set_timing(True)
+    try:
+        with torch.cuda.stream(side):
+            y_d = binding.givens_forward(th_d, x_d)                # the binding passes torch's current stream
+            t_fwd = binding.last_timing()
+            dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+            t_bwd = binding.last_timing()
+        side.synchronize()
+    finally:
+        binding.set_timing(False)
+    assert O.rel_fro(y_d.cpu().numpy(), want_y) <= TOL_Y
+    assert O.rel_fro(dx_d.cpu().numpy(), want_dx) <= TOL_G
+    assert O.rel_fro(dth_d.cpu().numpy(), want_dth) <= TOL_G
+    assert t_fwd[0] > 0 and t_fwd[1] > 0 and t_fwd[2] == 0          # coefficient kernels, sweep, no reduction
+    assert t_bwd[0] > 0 and t_bwd[1] > 0 and t_bwd[2] > 0
+    with pytest.raises(binding.GivensError):
+        binding.givens_forward(th_d, x_d)
+        binding.last_timing()                                       # timing was off for that call
