@@ -26,18 +26,19 @@ struct CarouselCoefs {
     float scaled_max; // threshold of the scaled form (negative: never), see form_for_range
 };
 
-// n = 128 * WAVES * M with one of the compiled (M, WAVES) pairs
+// n = 128 * WAVES * M with one of the compiled (M, WAVES) pairs: M slots per lane in {2, 4, 8} (the
+// renormalisation period must be a multiple of M), 1..8 wavefronts per workgroup.  The most slots per
+// lane that fit are preferred: fewer of a lane's slots take part in the exchange.
 inline bool carousel_shape_for(int n, CarouselShape *out)
 {
-    switch (n) {
-    case 256: *out = {2, 1}; return true;
-    case 512: *out = {4, 1}; return true;
-    case 1024: *out = {8, 1}; return true;
-    case 2048: *out = {8, 2}; return true;
-    case 4096: *out = {8, 4}; return true;
-    case 8192: *out = {8, 8}; return true;
-    default: return false;
-    }
+    if (n < 256 || n % 128) return false;
+    const int q = n / 128; // WAVES * M
+    for (int m : {8, 4, 2})
+        if (q % m == 0 && q / m <= 8) {
+            *out = {m, q / m};
+            return true;
+        }
+    return false;
 }
 
 template <typename T>
@@ -48,17 +49,17 @@ inline bool carousel_supported(int n, long long B)
     return std::is_same<T, float>::value && carousel_shape_for(n, &s);
 }
 
-// shapes of the reverse sweep: two strips per lane, so half the slots per lane of the forward
+// shapes of the reverse sweep: two strips per lane, so at most 4 slots per lane
 inline bool carousel_bwd_shape_for(int n, CarouselShape *out)
 {
-    switch (n) {
-    case 256: *out = {2, 1}; return true;
-    case 512: *out = {4, 1}; return true;
-    case 1024: *out = {4, 2}; return true;
-    case 2048: *out = {4, 4}; return true;
-    case 4096: *out = {4, 8}; return true;
-    default: return false;
-    }
+    if (n < 256 || n % 128) return false;
+    const int q = n / 128;
+    for (int m : {4, 2})
+        if (q % m == 0 && q / m <= 8) {
+            *out = {m, q / m};
+            return true;
+        }
+    return false;
 }
 
 template <typename T>

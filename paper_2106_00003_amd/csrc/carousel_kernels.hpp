@@ -756,12 +756,15 @@ inline int carousel_fwd_widths(int W, const CarouselFwdArgs &a)
 template <int FORM>
 inline int carousel_forward_form(const CarouselFwdArgs &a, CarouselShape s, int W)
 {
-    if (s.M == 2 && s.WAVES == 1) return carousel_fwd_widths<2, 1, FORM>(W, a);
-    if (s.M == 4 && s.WAVES == 1) return carousel_fwd_widths<4, 1, FORM>(W, a);
-    if (s.M == 8 && s.WAVES == 1) return carousel_fwd_widths<8, 1, FORM>(W, a);
-    if (s.M == 8 && s.WAVES == 2) return carousel_fwd_widths<8, 2, FORM>(W, a);
-    if (s.M == 8 && s.WAVES == 4) return carousel_fwd_widths<8, 4, FORM>(W, a);
-    if (s.M == 8 && s.WAVES == 8) return carousel_fwd_widths<8, 8, FORM>(W, a);
+    // every (M, WAVES) that carousel_shape_for can return: M = 8 with 1..8 wavefronts (n = 1024 .. 8192),
+    // M = 4 with 1, 3, 5, 7 (n = 512, 1536, 2560, 3584), M = 2 with 1, 3, 5, 7 (n = 256, 768, 1280, 1792)
+#define GIVENS_FWD_SHAPE(m, wv) \
+    if (s.M == m && s.WAVES == wv) return carousel_fwd_widths<m, wv, FORM>(W, a);
+    GIVENS_FWD_SHAPE(8, 1) GIVENS_FWD_SHAPE(8, 2) GIVENS_FWD_SHAPE(8, 3) GIVENS_FWD_SHAPE(8, 4)
+    GIVENS_FWD_SHAPE(8, 5) GIVENS_FWD_SHAPE(8, 6) GIVENS_FWD_SHAPE(8, 7) GIVENS_FWD_SHAPE(8, 8)
+    GIVENS_FWD_SHAPE(4, 1) GIVENS_FWD_SHAPE(4, 3) GIVENS_FWD_SHAPE(4, 5) GIVENS_FWD_SHAPE(4, 7)
+    GIVENS_FWD_SHAPE(2, 1) GIVENS_FWD_SHAPE(2, 3) GIVENS_FWD_SHAPE(2, 5) GIVENS_FWD_SHAPE(2, 7)
+#undef GIVENS_FWD_SHAPE
     return GIVENS_ERR_UNSUPPORTED;
 }
 
@@ -789,11 +792,14 @@ inline int carousel_bwd_widths(int W, const CarouselBwdArgs &a)
 template <int FORM>
 inline int carousel_backward_form(const CarouselBwdArgs &a, CarouselShape s, int W)
 {
-    if (s.M == 2 && s.WAVES == 1) return carousel_bwd_widths<2, 1, FORM>(W, a);
-    if (s.M == 4 && s.WAVES == 1) return carousel_bwd_widths<4, 1, FORM>(W, a);
-    if (s.M == 4 && s.WAVES == 2) return carousel_bwd_widths<4, 2, FORM>(W, a);
-    if (s.M == 4 && s.WAVES == 4) return carousel_bwd_widths<4, 4, FORM>(W, a);
-    if (s.M == 4 && s.WAVES == 8) return carousel_bwd_widths<4, 8, FORM>(W, a);
+    // every (M, WAVES) that carousel_bwd_shape_for can return: M = 4 with 1..8 wavefronts (n = 512 .. 4096),
+    // M = 2 with 1, 3, 5, 7 (n = 256, 768, 1280, 1792)
+#define GIVENS_BWD_SHAPE(m, wv) \
+    if (s.M == m && s.WAVES == wv) return carousel_bwd_widths<m, wv, FORM>(W, a);
+    GIVENS_BWD_SHAPE(4, 1) GIVENS_BWD_SHAPE(4, 2) GIVENS_BWD_SHAPE(4, 3) GIVENS_BWD_SHAPE(4, 4)
+    GIVENS_BWD_SHAPE(4, 5) GIVENS_BWD_SHAPE(4, 6) GIVENS_BWD_SHAPE(4, 7) GIVENS_BWD_SHAPE(4, 8)
+    GIVENS_BWD_SHAPE(2, 1) GIVENS_BWD_SHAPE(2, 3) GIVENS_BWD_SHAPE(2, 5) GIVENS_BWD_SHAPE(2, 7)
+#undef GIVENS_BWD_SHAPE
     return GIVENS_ERR_UNSUPPORTED;
 }
 

@@ -128,6 +128,28 @@ def test_carousel_family_ragged_batches(n, B, seed):
     assert binding.last_kernel() == binding.KERNEL_CAROUSEL      # the reverse sweep too
 
 
+@pytest.mark.parametrize("n,B,seed,dist", [(768, 70, 17, "uniform"), (1280, 45, 18, "normal0.1"),
+                                           (1536, 130, 19, "uniform"), (1792, 33, 20, "uniform"),
+                                           (2560, 64, 22, "normal0.1"), (3072, 40, 23, "uniform"),
+                                           (3584, 24, 24, "uniform")])
+def test_carousel_family_sizes_with_3_5_6_7_wavefronts(n, B, seed, dist):
+    """n = 128 * WAVES * M with a wavefront count that is not a power of two."""
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G,
+                           binding.KERNEL_CAROUSEL)
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+
+
+@pytest.mark.parametrize("n,B,seed", [(5120, 16, 25), (6144, 12, 26), (7168, 9, 27)])
+def test_forward_only_carousel_sizes_above_4096(n, B, seed):
+    data = inputs.make_custom(n, B, seed=seed)
+    binding.set_kernel(binding.KERNEL_AUTO)
+    y_d = binding.givens_forward(dev(data["theta"]), dev(data["X"]))
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+    assert O.rel_fro(host(y_d), C.forward(data["theta"], data["X"])) <= TOL_Y
+    binding.release()
+
+
 # ---------------------------------------------------------------- scaled rotation form (near-identity angles)
 @pytest.mark.parametrize("n,B,seed", [(256, 64, 51), (512, 100, 52), (1024, 67, 53), (2048, 130, 54)])
 def test_scaled_form_is_used_for_small_angles_and_matches_the_oracle(n, B, seed):
