@@ -169,8 +169,8 @@ inline int carousel_backward_strips(int n, int rows, long long B, int W, long lo
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (g_identity || reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const CarouselBwdArgs a{n, rows, B, strip0, nstrips, groups, coefs, Y, G, dX, partial, zeros, aligned ? 1 : 0, accumulate, g_identity,
-                            stream};
+    const CarouselBwdArgs a{n,  rows, B,     strip0, nstrips,         groups,     coefs,      Y,
+                            G,  dX,   partial, zeros, aligned ? 1 : 0, accumulate, g_identity, stream};
     switch (coefs.form) {
     case kFormScaled: return carousel_backward_scaled(a, s, W);
     case kFormLifted: return carousel_backward_lifted(a, s, W);

@@ -323,7 +323,8 @@ __device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long 
         if (vec) {
 #pragma unroll
             for (int x = 0; x < W / 4; ++x)
-                reinterpret_cast<float4 *>(dst)[x] = make_float4(src[4 * x], src[4 * x + 1], src[4 * x + 2], src[4 * x + 3]);
+                reinterpret_cast<float4 *>(dst)[x] =
+                    make_float4(src[4 * x], src[4 * x + 1], src[4 * x + 2], src[4 * x + 3]);
             return;
         }
     }
@@ -689,7 +690,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
         st.out_top = z.top_out.lane(t);
         st.out_bot = z.bot_out.lane(t);
         st.hold = z.top_out.lane(L);                                              // the extra row
-        st.in_top = (t > 0) ? z.top_out.lane(t - 1) : z.top_out.lane(L);         // near end: the held row stays in slot 0
+        // near end: the held row stays in slot 0
+        st.in_top = (t > 0) ? z.top_out.lane(t - 1) : z.top_out.lane(L);
         st.in_bot = (t < L - 1) ? z.bot_out.lane(t + 1) : z.top_out.lane(L - 1); // far end: top[n/2-1] -> bot[n/2-1]
     }
 
@@ -737,8 +739,8 @@ inline void carousel_launch_fwd(const CarouselFwdArgs &a)
 {
     const long long strips = (a.B + W - 1) / W;
     hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES, FORM>), dim3((unsigned)strips), dim3(64 * WAVES), 0,
-                       a.stream, a.n, a.rows, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.coefs.scaled_max, a.X, a.Y,
-                       a.identity, a.vec_ok, a.mirror);
+                       a.stream, a.n, a.rows, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.coefs.scaled_max,
+                       a.X, a.Y, a.identity, a.vec_ok, a.mirror);
 }
 
 template <int M, int WAVES, int FORM>

@@ -22,7 +22,7 @@ namespace {
 constexpr int kMaxDevices = 64;
 constexpr size_t kLdsBudgetBytes = 144 * 1024;                 // of the 160 KB per CU on gfx950
 constexpr size_t kPartialCapBytes = size_t(24) << 30;          // cap on one chunk of strip partials
-constexpr bool kAutoReductionIsAtomic = false;                  // what GIVENS_REDUCTION_AUTO means for the carousel family
+constexpr bool kAutoReductionIsAtomic = false;                 // GIVENS_REDUCTION_AUTO never picks the atomic variant
 
 struct Buffer {
     void *ptr = nullptr;
@@ -382,15 +382,15 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
                 hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(threads), 0, stream, N, acc);
                 const long long groups = carousel_bwd_groups(n, strips, cus);
                 if (coefs.all_forms) {
-                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.scaled, Y, G, dX, acc, zeros, 1, g_identity,
-                                                          stream))
+                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.scaled, Y, G, dX,
+                                                          acc, zeros, 1, g_identity, stream))
                         return rc;
-                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.lifted, Y, G, dX, acc, zeros, 1, g_identity,
-                                                          stream))
+                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.lifted, Y, G, dX,
+                                                          acc, zeros, 1, g_identity, stream))
                         return rc;
                 }
-                if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.standard, Y, G, dX, acc, zeros, 1, g_identity,
-                                                      stream))
+                if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.standard, Y, G, dX,
+                                                      acc, zeros, 1, g_identity, stream))
                     return rc;
                 GIVENS_HIP(hipGetLastError());
             }
@@ -426,15 +426,15 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
                                    coefs.table, Y, G, dX, partial);
             } else if constexpr (std::is_same<T, float>::value) {
                 if (coefs.all_forms) {
-                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX, partial, zeros, 0, g_identity,
-                                                          stream))
+                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX,
+                                                          partial, zeros, 0, g_identity, stream))
                         return rc;
-                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX, partial, zeros, 0, g_identity,
-                                                          stream))
+                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX,
+                                                          partial, zeros, 0, g_identity, stream))
                         return rc;
                 }
-                if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.standard, Y, G, dX, partial, zeros, 0, g_identity,
-                                                      stream))
+                if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.standard, Y, G, dX,
+                                                      partial, zeros, 0, g_identity, stream))
                     return rc;
             } else {
                 return GIVENS_ERR_UNSUPPORTED;
