@@ -46,9 +46,11 @@ extern "C" {
 #define GIVENS_ERR_BAD_M (-7)       /* restricted entry points: m outside 1..n-1        */
 
 /* Kernel families (givens_set_kernel). */
-#define GIVENS_KERNEL_AUTO 0     /* register carousel where the shape allows, else LDS strip */
+#define GIVENS_KERNEL_AUTO 0     /* column kernels for n <= 128, register carousel where the  */
+                                 /* shape allows, else LDS strip                              */
 #define GIVENS_KERNEL_LDS 1      /* strip of the operand held in LDS; any even n that fits   */
 #define GIVENS_KERNEL_CAROUSEL 2 /* strip held in VGPRs in circle-method position order      */
+#define GIVENS_KERNEL_COLUMN 3   /* float, n <= 128: one lane per column, all rows in its VGPRs */
 
 /* Rotation forms of the float carousel kernels (givens_set_rotation_form). */
 #define GIVENS_FORM_AUTO 0     /* decided on the device from max |theta|: scaled if <= pi/4, lifted if <= 1e6,  */
@@ -176,12 +178,15 @@ int givens_last_hip_error(void);
 const char *givens_error_string(int code);
 
 /* Selects the kernel family for subsequent calls (process-wide).  Returns the previous value,
- * or GIVENS_ERR_UNSUPPORTED for an unknown value.  With GIVENS_KERNEL_CAROUSEL a call whose
- * shape the carousel kernels do not cover returns GIVENS_ERR_UNSUPPORTED instead of falling back. */
+ * or GIVENS_ERR_UNSUPPORTED for an unknown value.  With GIVENS_KERNEL_CAROUSEL or GIVENS_KERNEL_COLUMN a
+ * call whose shape those kernels do not cover returns GIVENS_ERR_UNSUPPORTED instead of falling back.
+ * The column family has a forward kernel only: its backward call uses the Gram-matrix reduction (see
+ * givens_set_reduction) with the sweep on the n x n Gram matrix done by the LDS family, and the LDS
+ * family outright when that reduction is not available or not selected. */
 int givens_set_kernel(int which);
 
 /* Which family the last successful forward/build/backward call on this thread used
- * (GIVENS_KERNEL_LDS or GIVENS_KERNEL_CAROUSEL; 0 before any call). */
+ * (GIVENS_KERNEL_LDS, GIVENS_KERNEL_CAROUSEL or GIVENS_KERNEL_COLUMN; 0 before any call). */
 int givens_last_kernel(void);
 
 /*

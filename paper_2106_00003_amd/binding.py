@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgivens_rr.so")
 
-KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL = 0, 1, 2
+KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL, KERNEL_COLUMN = 0, 1, 2, 3
 FORM_AUTO, FORM_STANDARD, FORM_SCALED, FORM_LIFTED = 0, 1, 2, 3
 REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_ATOMIC, REDUCTION_GRAM = 0, 1, 2, 3
 

@@ -102,6 +102,12 @@ struct CarouselBwdArgs {
     hipStream_t stream;
 };
 
+// Column family (column_fwd.hip): forward sweep for even n <= 128, one lane per column, standard-form
+// table.  GIVENS_ERR_UNSUPPORTED for other n.
+constexpr int kColumnFamilyMaxN = 128;
+int column_forward(int n, int rows, long long B, const float2 *table, const float *X, float *Y, int identity,
+                   int mirror, hipStream_t stream);
+
 // Defined in carousel_fwd_<form>.hip / carousel_bwd_<form>.hip: launch the kernel of that form for
 // shape s and W columns per lane; GIVENS_ERR_UNSUPPORTED for a combination that is not compiled.
 int carousel_forward_standard(const CarouselFwdArgs &a, CarouselShape s, int W);

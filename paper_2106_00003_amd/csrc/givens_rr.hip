@@ -423,7 +423,7 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
             Span span(1, stream);
             if (family == GIVENS_KERNEL_LDS) {
                 hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, rows, B, w, s0,
-                                   coefs.table, Y, G, dX, partial);
+                                   coefs.table, Y, G, dX, partial, g_identity);
             } else if constexpr (std::is_same<T, float>::value) {
                 if (coefs.all_forms) {
                     if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX,
@@ -577,8 +577,11 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
     timing_begin_call();
     const int choice = g_kernel_choice;
     const bool can_carousel = carousel_supported<T>(n, B);
+    const bool can_column = std::is_same<T, float>::value && n <= kColumnFamilyMaxN;
     if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
-    const bool use_carousel = can_carousel && choice != GIVENS_KERNEL_LDS;
+    if (choice == GIVENS_KERNEL_COLUMN && !can_column) return GIVENS_ERR_UNSUPPORTED;
+    const bool use_carousel = can_carousel && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_CAROUSEL);
+    const bool use_column = can_column && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_COLUMN);
     Coefs<T> coefs;
     if (int rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(use_carousel && std::is_same<T, float>::value),
                                   stream, &coefs))
@@ -597,6 +600,13 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
             rc = GIVENS_ERR_UNSUPPORTED;
         }
         t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
+    } else if (use_column) {
+        if constexpr (std::is_same<T, float>::value) {
+            Span span(1, stream);
+            rc = column_forward(n, rows, B, coefs.table, X, Y, identity, 0, stream);
+            if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+        }
+        t_state.last_kernel = GIVENS_KERNEL_COLUMN;
     } else {
         rc = lds_forward<T>(n, rows, B, coefs.table, X, Y, identity, stream);
         t_state.last_kernel = GIVENS_KERNEL_LDS;
@@ -622,8 +632,15 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
     timing_begin_call();
     const int choice = g_kernel_choice;
     const bool can_carousel = carousel_backward_supported<T>(n, B);
+    const bool can_column = std::is_same<T, float>::value && n <= kColumnFamilyMaxN;
     if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
-    const int family = (can_carousel && choice != GIVENS_KERNEL_LDS) ? GIVENS_KERNEL_CAROUSEL : GIVENS_KERNEL_LDS;
+    if (choice == GIVENS_KERNEL_COLUMN && !can_column) return GIVENS_ERR_UNSUPPORTED;
+    // the family that sweeps (the n x n operand of the Gram form, or all B columns); the column family has
+    // no reverse sweep of its own and borrows the LDS family's
+    const int family = (can_carousel && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_CAROUSEL))
+                           ? GIVENS_KERNEL_CAROUSEL
+                           : GIVENS_KERNEL_LDS;
+    const bool column = can_column && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_COLUMN);
     Coefs<T> coefs;
     if (int rc = prepare_coefs<T>(dev, pb, theta, false,
                                   form_policy(family == GIVENS_KERNEL_CAROUSEL && std::is_same<T, float>::value),
@@ -637,7 +654,7 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
         // (C, I) carries A_k C and A_k.  So dtheta costs one GEMM over B plus a rows-column sweep, and
         // dX = U^T G one forward-type sweep over B (mirrored tables), instead of a two-strip sweep over B.
         const bool wide = B >= 2LL * n;   // measured break-even is near B = 1.6 n
-        const bool want_gram = family == GIVENS_KERNEL_CAROUSEL &&
+        const bool want_gram = (family == GIVENS_KERNEL_CAROUSEL || column) &&
                                (g_reduction_choice == GIVENS_REDUCTION_GRAM ||
                                 (g_reduction_choice == GIVENS_REDUCTION_AUTO && wide));
         if (want_gram && rocblas_available()) {
@@ -652,7 +669,13 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
             }
             if (rc == GIVENS_OK) {
                 rc = backward_chunks<T>(dev, family, pb, rows, coefs, C, nullptr, nullptr, dtheta, stream, 1);
-                if (rc == GIVENS_OK && dX) {
+                if (rc == GIVENS_OK && dX && column) {
+                    Coefs<T> mirrored;
+                    rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(false), stream, &mirrored, 1);
+                    Span span(1, stream);
+                    if (rc == GIVENS_OK) rc = column_forward(n, rows, B, mirrored.table, G, dX, 0, 1, stream);
+                    if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+                } else if (rc == GIVENS_OK && dX) {
                     Coefs<T> mirrored;
                     rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(true), stream, &mirrored, 1);
                     Span span(1, stream);
@@ -664,10 +687,11 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
                     if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
                 }
                 t_state.last_reduction = GIVENS_REDUCTION_GRAM;
+                if (column) t_state.last_kernel = GIVENS_KERNEL_COLUMN;
                 return rc;
             }
             // the GEMM could not be run: fall through to the sweep over all B columns
-        } else if (g_reduction_choice == GIVENS_REDUCTION_GRAM && family == GIVENS_KERNEL_CAROUSEL) {
+        } else if (g_reduction_choice == GIVENS_REDUCTION_GRAM && (family == GIVENS_KERNEL_CAROUSEL || column)) {
             return GIVENS_ERR_UNSUPPORTED; // forced, but rocBLAS could not be loaded
         }
     }
@@ -963,7 +987,8 @@ const char *givens_error_string(int code)
 
 int givens_set_kernel(int which)
 {
-    if (which != GIVENS_KERNEL_AUTO && which != GIVENS_KERNEL_LDS && which != GIVENS_KERNEL_CAROUSEL)
+    if (which != GIVENS_KERNEL_AUTO && which != GIVENS_KERNEL_LDS && which != GIVENS_KERNEL_CAROUSEL &&
+        which != GIVENS_KERNEL_COLUMN)
         return GIVENS_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(givens::g_mutex);
     const int prev = givens::g_kernel_choice;

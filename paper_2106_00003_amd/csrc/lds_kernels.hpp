@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
 template <typename T>
 __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
     int n, int rows, long long B, int w, long long strip0, const typename Pair2<T>::type *__restrict__ table,
-    const T *Yin, const T *G, T *dX, T *__restrict__ partial)
+    const T *Yin, const T *G, T *dX, T *__restrict__ partial, int g_identity)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int H = n >> 1;
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
         T vz = T(0), vg = T(0);
         if (c < wv && r < rows) {
             vz = Yin[(long long)r * B + b0 + c];
-            vg = G[(long long)r * B + b0 + c];
+            vg = g_identity ? ((long long)r == b0 + c ? T(1) : T(0)) : G[(long long)r * B + b0 + c]; // G = I_n: not read
         }
         z[r * ldw + c] = vz;
         gb[r * ldw + c] = vg;

@@ -128,6 +128,49 @@ def test_carousel_family_ragged_batches(n, B, seed):
     assert binding.last_kernel() == binding.KERNEL_CAROUSEL      # the reverse sweep too
 
 
+# ---------------------------------------------------------------- column family (n <= 128)
+@pytest.mark.parametrize("n,B,seed", [(2, 5, 101), (4, 3, 102), (6, 300, 103), (8, 1, 104), (34, 77, 105),
+                                      (64, 1000, 106), (100, 513, 107), (126, 260, 108), (128, 300, 109)])
+def test_column_family_small_n(n, B, seed):
+    data = inputs.make_custom(n, B, seed=seed)
+    binding.set_kernel(binding.KERNEL_AUTO)
+    th_d = dev(data["theta"])
+    y_d = binding.givens_forward(th_d, dev(data["X"]))
+    assert binding.last_kernel() == binding.KERNEL_COLUMN
+    want_y = C.forward(data["theta"], data["X"])
+    assert O.rel_fro(host(y_d), want_y) <= TOL_Y
+    u_d = binding.givens_build(th_d, n)
+    assert binding.last_kernel() == binding.KERNEL_COLUMN
+    assert O.rel_fro(host(u_d), C.forward(data["theta"], None, n=n)) <= TOL_Y
+    dx_d, dth_d = binding.givens_backward(th_d, y_d, dev(data["G"]))
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
+    if B >= 2 * n:                                            # Gram form: GEMM, sweep on C, mirrored column kernel
+        assert binding.last_kernel() == binding.KERNEL_COLUMN
+        assert binding.last_reduction() == binding.REDUCTION_GRAM
+    else:
+        assert binding.last_kernel() == binding.KERNEL_LDS
+    assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
+    assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
+    # the same through the LDS family, and in place through the column family
+    binding.set_kernel(binding.KERNEL_LDS)
+    y2 = host(binding.givens_forward(th_d, dev(data["X"])))
+    binding.set_kernel(binding.KERNEL_COLUMN)
+    buf = dev(data["X"])
+    binding.givens_forward(th_d, buf, Y=buf)
+    assert np.array_equal(host(buf), host(y_d))
+    assert O.rel_fro(y2, host(y_d)) <= 2e-6
+    binding.set_kernel(binding.KERNEL_AUTO)
+
+
+def test_column_family_rejects_large_n_when_forced():
+    data = inputs.make_custom(130, 8, seed=110)
+    binding.set_kernel(binding.KERNEL_COLUMN)
+    with pytest.raises(binding.GivensError) as err:
+        binding.givens_forward(dev(data["theta"]), dev(data["X"]))
+    assert err.value.code == -5
+    binding.set_kernel(binding.KERNEL_AUTO)
+
+
 @pytest.mark.parametrize("n,B,seed,dist", [(768, 70, 17, "uniform"), (1280, 45, 18, "normal0.1"),
                                            (1536, 130, 19, "uniform"), (1792, 33, 20, "uniform"),
                                            (2560, 64, 22, "normal0.1"), (3072, 40, 23, "uniform"),

@@ -127,6 +127,13 @@ def test_wide_batch_uses_the_gram_form_with_a_restricted_odd_problem():
     assert binding.last_reduction() == binding.REDUCTION_GRAM
 
 
+@pytest.mark.parametrize("n,m,B,seed", [(35, 10, 200, 355), (64, 20, 300, 356), (127, 126, 260, 357), (9, 4, 3, 358)])
+def test_column_family_restricted_and_odd(n, m, B, seed):
+    check(n, m, B, seed, kernel=binding.KERNEL_AUTO)
+    if B >= 2 * (n + n % 2):
+        assert binding.last_reduction() == binding.REDUCTION_GRAM
+
+
 def test_unrestricted_m_gives_the_unrestricted_entry_points_result():
     n, B = 256, 24
     theta, X, G = make(n, n - 1, B, 361)
