@@ -65,7 +65,7 @@ extern "C" {
 #define GIVENS_REDUCTION_ATOMIC 2    /* strips add into one buffer with float atomics (carousel kernels only);  */
                                      /* order of additions, hence the last bits of dtheta, varies run to run   */
 #define GIVENS_REDUCTION_GRAM 3      /* C = Y G^T by one SGEMM (rocBLAS, loaded on demand), then the sweep on   */
-                                     /* the n x n operand C; dX by a forward-type sweep (carousel kernels only) */
+                                     /* the n x n operand C; dX by a forward-type sweep (float entry points)    */
 
 /*
  * rr_schedule -- the round-robin sequence by the circle method (Section 3; the worked n = 6
@@ -213,9 +213,9 @@ int givens_last_rotation_form(void);
  * in all but its summation order is not fixed.  GRAM replaces the sweep over B columns by the Gram
  * matrix C = Y G^T (the sums of the sweep are those of the same sweep on the operand C with upstream
  * gradient I_n) and computes dX = U^T G by a forward-type sweep; it needs librocblas at run time and
- * returns GIVENS_ERR_UNSUPPORTED when forced without it.  AUTO means GRAM for the carousel kernels
- * when B >= 2 n and rocBLAS loads, TWO_STAGE otherwise.  The LDS family and the f64 entry points
- * always use TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
+ * returns GIVENS_ERR_UNSUPPORTED when forced without it.  AUTO means GRAM for every float kernel
+ * family when B >= 2 n and rocBLAS loads, TWO_STAGE otherwise.  ATOMIC exists for the carousel kernels
+ * only (the LDS family then uses TWO_STAGE); the f64 entry points always use TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
  */
 int givens_set_reduction(int which);
 int givens_last_reduction(void);

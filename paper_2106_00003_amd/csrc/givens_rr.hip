@@ -307,7 +307,7 @@ int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, Form
 
 template <typename T>
 int lds_forward(int n, int rows, long long B, const typename Pair2<T>::type *table, const T *X, T *Y,
-                int identity, hipStream_t stream)
+                int identity, hipStream_t stream, int mirror = 0)
 {
     const int w = lds_strip_width<T>(n, B, 1);
     if (w == 0) return GIVENS_ERR_UNSUPPORTED;
@@ -318,7 +318,7 @@ int lds_forward(int n, int rows, long long B, const typename Pair2<T>::type *tab
     const long long strips = (B + w - 1) / w;
     Span span(1, stream);
     hipLaunchKernelGGL(kern, dim3((unsigned)strips), dim3(kLdsThreads), smem, stream, n, rows, B, w, table, X,
-                       Y, identity);
+                       Y, identity, mirror);
     GIVENS_HIP(hipGetLastError());
     return GIVENS_OK;
 }
@@ -654,8 +654,7 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
         // (C, I) carries A_k C and A_k.  So dtheta costs one GEMM over B plus a rows-column sweep, and
         // dX = U^T G one forward-type sweep over B (mirrored tables), instead of a two-strip sweep over B.
         const bool wide = B >= 2LL * n;   // measured break-even is near B = 1.6 n
-        const bool want_gram = (family == GIVENS_KERNEL_CAROUSEL || column) &&
-                               (g_reduction_choice == GIVENS_REDUCTION_GRAM ||
+        const bool want_gram = (g_reduction_choice == GIVENS_REDUCTION_GRAM ||
                                 (g_reduction_choice == GIVENS_REDUCTION_AUTO && wide));
         if (want_gram && rocblas_available()) {
             Workspace &ws = g_ws[dev];
@@ -675,6 +674,10 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
                     Span span(1, stream);
                     if (rc == GIVENS_OK) rc = column_forward(n, rows, B, mirrored.table, G, dX, 0, 1, stream);
                     if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+                } else if (rc == GIVENS_OK && dX && family == GIVENS_KERNEL_LDS) {
+                    Coefs<T> mirrored;
+                    rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(false), stream, &mirrored, 1);
+                    if (rc == GIVENS_OK) rc = lds_forward<T>(n, rows, B, mirrored.table, G, dX, 0, stream, 1);
                 } else if (rc == GIVENS_OK && dX) {
                     Coefs<T> mirrored;
                     rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(true), stream, &mirrored, 1);
@@ -691,7 +694,7 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
                 return rc;
             }
             // the GEMM could not be run: fall through to the sweep over all B columns
-        } else if (g_reduction_choice == GIVENS_REDUCTION_GRAM && (family == GIVENS_KERNEL_CAROUSEL || column)) {
+        } else if (g_reduction_choice == GIVENS_REDUCTION_GRAM) {
             return GIVENS_ERR_UNSUPPORTED; // forced, but rocBLAS could not be loaded
         }
     }

@@ -22,7 +22,7 @@ __host__ __device__ inline int lds_row_stride(int w) { return w | 1; }
 template <typename T>
 __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
     int n, int rows, long long B, int w, const typename Pair2<T>::type *__restrict__ table,
-    const T *X, T *Y, int identity)
+    const T *X, T *Y, int identity, int mirror)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     T *strip = reinterpret_cast<T *>(smem_raw);
@@ -32,11 +32,13 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
     const int wv = (B - b0) < w ? (int)(B - b0) : w;
 
     for (long long idx = threadIdx.x; idx < (long long)n * w; idx += blockDim.x) {
-        const int r = (int)(idx / w), c = (int)(idx % w);
+        // mirror: strip row q holds operand row n - q (q >= 1); with the mirrored table the launch applies U^T
+        const int q = (int)(idx / w), c = (int)(idx % w);
+        const int r = (mirror && q) ? n - q : q;
         T v = T(0);
         if (c < wv && r < rows)
             v = identity ? ((long long)r == b0 + c ? T(1) : T(0)) : X[(long long)r * B + b0 + c];
-        strip[r * ldw + c] = v;
+        strip[q * ldw + c] = v;
     }
     __syncthreads();
 
@@ -56,8 +58,9 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
     }
 
     for (long long idx = threadIdx.x; idx < (long long)n * w; idx += blockDim.x) {
-        const int r = (int)(idx / w), c = (int)(idx % w);
-        if (c < wv && r < rows) Y[(long long)r * B + b0 + c] = strip[r * ldw + c];
+        const int q = (int)(idx / w), c = (int)(idx % w);
+        const int r = (mirror && q) ? n - q : q;
+        if (c < wv && r < rows) Y[(long long)r * B + b0 + c] = strip[q * ldw + c];
     }
 }
 

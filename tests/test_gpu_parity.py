@@ -327,7 +327,7 @@ def test_gram_reduction_for_wide_batches_matches_the_oracle(n, B, seed, dist):
         binding.set_kernel(binding.KERNEL_AUTO)
 
 
-def test_gram_reduction_can_be_forced_on_a_narrow_batch_and_not_on_the_lds_family():
+def test_gram_reduction_can_be_forced_on_a_narrow_batch_in_both_families():
     data = inputs.make_custom(256, 40, seed=78)
     th_d, g_d = dev(data["theta"]), dev(data["G"])
     want_y = C.forward(data["theta"], data["X"])
@@ -341,11 +341,31 @@ def test_gram_reduction_can_be_forced_on_a_narrow_batch_and_not_on_the_lds_famil
         assert O.rel_fro(host(dth_d), want_dth) <= TOL_G and O.rel_fro(host(dx_d), want_dx) <= TOL_G
         binding.set_kernel(binding.KERNEL_LDS)
         dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+        assert binding.last_reduction() == binding.REDUCTION_GRAM and binding.last_kernel() == binding.KERNEL_LDS
+        assert O.rel_fro(host(dth_d), want_dth) <= TOL_G and O.rel_fro(host(dx_d), want_dx) <= TOL_G
+        # the float64 entry points keep the two-stage reduction
+        d64 = inputs.make_custom(34, 19, seed=78, dtype=np.float64)
+        y64 = binding.givens_forward(dev(d64["theta"]), dev(d64["X"]))
+        binding.givens_backward(dev(d64["theta"]), y64, dev(d64["G"]))
         assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
-        assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
     finally:
         binding.set_reduction(binding.REDUCTION_AUTO)
         binding.set_kernel(binding.KERNEL_AUTO)
+
+
+@pytest.mark.parametrize("n,B,seed", [(200, 900, 111), (300, 700, 112), (1000, 2100, 113)])
+def test_lds_family_wide_batches_use_the_gram_form(n, B, seed):
+    data = inputs.make_custom(n, B, seed=seed)
+    binding.set_kernel(binding.KERNEL_AUTO)
+    th_d = dev(data["theta"])
+    y_d = binding.givens_forward(th_d, dev(data["X"]))
+    assert binding.last_kernel() == binding.KERNEL_LDS
+    want_y = C.forward(data["theta"], data["X"])
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
+    dx_d, dth_d = binding.givens_backward(th_d, y_d, dev(data["G"]))
+    assert binding.last_reduction() == binding.REDUCTION_GRAM
+    assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
+    assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
 
 
 def test_atomic_reduction_falls_back_for_the_lds_family():
