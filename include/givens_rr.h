@@ -105,6 +105,16 @@ int givens_build(int n, const float *theta, float *U, void *stream);
 int givens_backward(int n, int64_t B, const float *theta, const float *Y, const float *G,
                     float *dX, float *dtheta, void *stream);
 
+/*
+ * givens_forward_transposed -- Y = U(theta)^T X, i.e. the inverse transform (U is orthogonal): the
+ * transposed rotations applied in E order, which is also what givens_backward computes for dX.  Run as
+ * the forward sweep of the mirrored problem: relabelling row r >= 1 as n - r maps the pairs of block k
+ * onto those of block n-2-k (Section 3's circle method is symmetric under this reflection), so
+ * U(theta)^T = P^T U(theta') P with theta'[k][p] = -/+ theta[n-2-k][p].  Same arguments as givens_forward.
+ */
+int givens_forward_transposed(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream);
+int givens_forward_transposed_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream);
+
 /* float64 variants: same semantics, all arrays double. */
 int givens_forward_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream);
 int givens_build_f64(int n, const double *theta, double *U, void *stream);

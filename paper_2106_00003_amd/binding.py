@@ -21,6 +21,7 @@ REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_ATOMIC, REDUCTION_GRAM = 0, 1, 2,
 EXPORTS = [
     "rr_schedule", "givens_forward", "givens_build", "givens_backward",
     "givens_forward_f64", "givens_build_f64", "givens_backward_f64",
+    "givens_forward_transposed", "givens_forward_transposed_f64",
     "givens_release", "givens_last_hip_error", "givens_error_string",
     "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
     "givens_set_rotation_form", "givens_last_rotation_form",
@@ -56,7 +57,7 @@ def lib():
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     L.rr_schedule.argtypes = [i32, vp]
-    for name in ("givens_forward", "givens_forward_f64"):
+    for name in ("givens_forward", "givens_forward_f64", "givens_forward_transposed", "givens_forward_transposed_f64"):
         getattr(L, name).argtypes = [i32, i64, vp, vp, vp, vp]
     for name in ("givens_build", "givens_build_f64"):
         getattr(L, name).argtypes = [i32, vp, vp, vp]
@@ -141,6 +142,20 @@ def givens_forward(theta, X, Y=None, stream=None):
     fn = getattr(lib(), "givens_forward" + _suffix(X))
     _check(fn(n, B, _dev(theta, "theta", X.dtype), _dev(X, "X"), _dev(Y, "Y", X.dtype), _stream_ptr(stream)),
            "givens_forward")
+    return Y
+
+
+def givens_forward_transposed(theta, X, Y=None, stream=None):
+    """Y = U(theta)^T X (the inverse transform) on the device.  Y=None allocates; Y may be X."""
+    import torch
+    n, B = X.shape
+    if theta.numel() != n * (n - 1) // 2:
+        raise ValueError("theta must have n(n-1)/2 entries")
+    if Y is None:
+        Y = torch.empty_like(X)
+    fn = getattr(lib(), "givens_forward_transposed" + _suffix(X))
+    _check(fn(n, B, _dev(theta, "theta", X.dtype), _dev(X, "X"), _dev(Y, "Y", X.dtype), _stream_ptr(stream)),
+           "givens_forward_transposed")
     return Y
 
 

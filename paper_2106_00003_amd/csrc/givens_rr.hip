@@ -562,7 +562,8 @@ int current_device(int *dev)
 
 // rows, m: see Problem.  The unrestricted entry points pass an even rows and m = rows - 1.
 template <typename T>
-int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y, int identity, void *stream_v)
+int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y, int identity, void *stream_v,
+                 int transpose = 0)
 {
     if (int rc = check_restricted(rows, m)) return rc;
     if (B < 1) return GIVENS_ERR_BAD_B;
@@ -584,17 +585,17 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
     const bool use_column = can_column && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_COLUMN);
     Coefs<T> coefs;
     if (int rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(use_carousel && std::is_same<T, float>::value),
-                                  stream, &coefs))
+                                  stream, &coefs, transpose))
         return rc;
     int rc = GIVENS_OK;
     if (use_carousel) {
         if constexpr (std::is_same<T, float>::value) {
             Span span(1, stream);
             if (coefs.all_forms) {
-                rc = carousel_forward(n, rows, B, coefs.scaled, X, Y, identity, 0, stream);
-                if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.lifted, X, Y, identity, 0, stream);
+                rc = carousel_forward(n, rows, B, coefs.scaled, X, Y, identity, transpose, stream);
+                if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.lifted, X, Y, identity, transpose, stream);
             }
-            if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.standard, X, Y, identity, 0, stream);
+            if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.standard, X, Y, identity, transpose, stream);
             if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
         } else {
             rc = GIVENS_ERR_UNSUPPORTED;
@@ -603,12 +604,12 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
     } else if (use_column) {
         if constexpr (std::is_same<T, float>::value) {
             Span span(1, stream);
-            rc = column_forward(n, rows, B, coefs.table, X, Y, identity, 0, stream);
+            rc = column_forward(n, rows, B, coefs.table, X, Y, identity, transpose, stream);
             if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
         }
         t_state.last_kernel = GIVENS_KERNEL_COLUMN;
     } else {
-        rc = lds_forward<T>(n, rows, B, coefs.table, X, Y, identity, stream);
+        rc = lds_forward<T>(n, rows, B, coefs.table, X, Y, identity, stream, transpose);
         t_state.last_kernel = GIVENS_KERNEL_LDS;
     }
     return rc;
@@ -865,6 +866,17 @@ int givens_backward_f64(int n, int64_t B, const double *theta, const double *Y, 
 {
     if (int rc = givens::check_n(n)) return rc;
     return givens::backward_impl<double>(n, n - 1, B, theta, Y, G, dX, dtheta, stream);
+}
+
+int givens_forward_transposed(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream)
+{
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream, 1);
+}
+int givens_forward_transposed_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream)
+{
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::forward_impl<double>(n, n - 1, B, theta, X, Y, 0, stream, 1);
 }
 
 int64_t givens_num_angles(int n, int m)

@@ -481,3 +481,17 @@ def test_calls_on_a_side_stream_and_event_timing():
     with pytest.raises(binding.GivensError):
         binding.givens_forward(th_d, x_d)
         binding.last_timing()                                       # timing was off for that call
+
+
+@pytest.mark.parametrize("n,B,seed,dtype", [(8, 5, 121, np.float64), (34, 19, 122, np.float64), (64, 300, 123, np.float32),
+                                            (200, 90, 124, np.float32), (256, 130, 125, np.float32),
+                                            (1536, 40, 126, np.float32), (2048, 64, 127, np.float32)])
+def test_transposed_forward_is_the_inverse_transform(n, B, seed, dtype):
+    data = inputs.make_custom(n, B, seed=seed, dtype=dtype)
+    tol = TOL_64 if dtype == np.float64 else TOL_Y
+    binding.set_kernel(binding.KERNEL_AUTO)
+    th_d = dev(data["theta"])
+    z_d = binding.givens_forward_transposed(th_d, dev(data["G"]))
+    assert O.rel_fro(host(z_d), C.grad_operand(data["theta"], data["G"])) <= tol        # U^T G by the oracle
+    back = binding.givens_forward(th_d, z_d)
+    assert O.rel_fro(host(back), data["G"]) <= 3 * tol                                    # U U^T G = G
