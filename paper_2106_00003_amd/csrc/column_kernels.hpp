@@ -56,22 +56,36 @@ struct ColumnFwd {
         (block<Us>(table + (long long)(k - Us) * (N / 2), std::make_integer_sequence<int, N / 2>{}), ...);
         turn<sizeof...(Us)>();
     }
+    static constexpr int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
+    // ring[i] <- ring[(i + S) mod kRing], in place: one temporary per cycle of the permutation
     template <int S>
     __device__ __forceinline__ void turn()
     {
-        float old[kRing];
+        constexpr int g = gcd(kRing, S % kRing);
+        if constexpr (S % kRing != 0) {
 #pragma unroll
-        for (int i = 0; i < kRing; ++i) old[i] = pos[1 + i];
+            for (int c = 0; c < g; ++c) {
+                const float first = pos[1 + c];
+                int i = c;
 #pragma unroll
-        for (int i = 0; i < kRing; ++i) pos[1 + i] = old[(i + S) % kRing];
+                for (int step = 0; step < kRing / g - 1; ++step) {
+                    const int j = (i + S) % kRing;
+                    pos[1 + i] = pos[1 + j];
+                    i = j;
+                }
+                pos[1 + i] = first;
+            }
+        }
     }
 };
 
 // table: standard-form (cos, sin) per angle of the n-dimensional problem in E order (of the mirrored
 // problem when `mirror` is set, see carousel_forward_kernel).  rows: the operand's row count (n, or
 // n - 1 when n pads an odd problem).
+// launch bound: three wavefronts per SIMD for 64 < n <= 112 (the scheduler otherwise spends registers on
+// overlapping more rotations than the issue rate can use)
 template <int N>
-__global__ __launch_bounds__(kColumnThreads) void column_forward_kernel(
+__global__ __launch_bounds__(kColumnThreads, N > 112 ? 2 : (N > 64 ? 3 : 4)) void column_forward_kernel(
     int rows, long long B, const float2 *__restrict__ table, const float *X, float *Y, int identity, int mirror)
 {
     using State = ColumnFwd<N>;
