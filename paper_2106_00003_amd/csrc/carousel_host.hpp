@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <initializer_list>
 #include <type_traits>
 
 #include "../../include/givens_rr.h"
@@ -26,20 +27,23 @@ struct CarouselCoefs {
     float scaled_max; // threshold of the scaled form (negative: never), see form_for_range
 };
 
-// n = 128 * WAVES * M with one of the compiled (M, WAVES) pairs: M slots per lane in {2, 4, 8} (the
-// renormalisation period must be a multiple of M), 1..8 wavefronts per workgroup.  The most slots per
-// lane that fit are preferred: fewer of a lane's slots take part in the exchange.
-inline bool carousel_shape_for(int n, CarouselShape *out)
+// n = 2 * M * L: M slots per lane in {8, 4, 2} (the renormalisation period must be a multiple of M) and
+// L <= 512 lanes, run by a workgroup of WAVES = ceil(L / 64) wavefronts whose spare lanes idle.  So the
+// family takes every n that is a multiple of 4 from kCarouselMinN up to 2048 (M = 2), of 8 up to 4096 and
+// of 16 up to 8192.  The most slots per lane that fit are preferred: fewer of a lane's slots take part in
+// the exchange.  Below kCarouselMinN a workgroup would be mostly idle lanes.
+constexpr int kCarouselMinN = 132;
+inline bool carousel_shape_with(int n, std::initializer_list<int> slots, CarouselShape *out)
 {
-    if (n < 256 || n % 128) return false;
-    const int q = n / 128; // WAVES * M
-    for (int m : {8, 4, 2})
-        if (q % m == 0 && q / m <= 8) {
-            *out = {m, q / m};
+    if (n < kCarouselMinN) return false;
+    for (int m : slots)
+        if (n % (2 * m) == 0 && n / (2 * m) <= 512) {
+            *out = {m, (n / (2 * m) + 63) / 64};
             return true;
         }
     return false;
 }
+inline bool carousel_shape_for(int n, CarouselShape *out) { return carousel_shape_with(n, {8, 4, 2}, out); }
 
 template <typename T>
 inline bool carousel_supported(int n, long long B)
@@ -49,18 +53,9 @@ inline bool carousel_supported(int n, long long B)
     return std::is_same<T, float>::value && carousel_shape_for(n, &s);
 }
 
-// shapes of the reverse sweep: two strips per lane, so at most 4 slots per lane
-inline bool carousel_bwd_shape_for(int n, CarouselShape *out)
-{
-    if (n < 256 || n % 128) return false;
-    const int q = n / 128;
-    for (int m : {4, 2})
-        if (q % m == 0 && q / m <= 8) {
-            *out = {m, q / m};
-            return true;
-        }
-    return false;
-}
+// shapes of the reverse sweep: two strips per lane, so at most 4 slots per lane (multiples of 4 up to
+// 2048, of 8 up to 4096)
+inline bool carousel_bwd_shape_for(int n, CarouselShape *out) { return carousel_shape_with(n, {4, 2}, out); }
 
 template <typename T>
 inline bool carousel_backward_supported(int n, long long B)
@@ -97,6 +92,7 @@ struct CarouselBwdArgs {
     const float *Y, *G;
     float *dX, *partial;
     const float *zeros; // N floats that are always zero
+    float *sink;        // N + 8192 floats that idle lanes write to and nobody reads
     int vec_ok, accumulate;
     int g_identity; // G is I_n (generated on chip, the pointer is not read)
     hipStream_t stream;
@@ -138,7 +134,7 @@ inline bool carousel_bwd_layout(int n, int *lanes, int *slots)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return false;
-    *lanes = 64 * s.WAVES;
+    *lanes = n / (2 * s.M);
     *slots = s.M;
     return true;
 }
@@ -167,16 +163,16 @@ inline long long carousel_bwd_groups(int n, long long nstrips, int compute_units
 // kernel's slot-major order that every strip adds into atomically.  zeros: N floats that stay zero.
 inline int carousel_backward_strips(int n, int rows, long long B, int W, long long strip0, long long nstrips,
                                     long long groups, const CarouselCoefs &coefs, const float *Y, const float *G,
-                                    float *dX, float *partial, const float *zeros, int accumulate, int g_identity,
-                                    hipStream_t stream)
+                                    float *dX, float *partial, const float *zeros, float *sink, int accumulate,
+                                    int g_identity, hipStream_t stream)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (g_identity || reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const CarouselBwdArgs a{n,  rows, B,     strip0, nstrips,         groups,     coefs,      Y,
-                            G,  dX,   partial, zeros, aligned ? 1 : 0, accumulate, g_identity, stream};
+    const CarouselBwdArgs a{n,  rows,    B,     strip0, nstrips,         groups,     coefs,      Y,     G,
+                            dX, partial, zeros, sink,   aligned ? 1 : 0, accumulate, g_identity, stream};
     switch (coefs.form) {
     case kFormScaled: return carousel_backward_scaled(a, s, W);
     case kFormLifted: return carousel_backward_lifted(a, s, W);

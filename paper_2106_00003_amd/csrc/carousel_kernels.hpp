@@ -1,4 +1,6 @@
-// Register-carousel kernels (float): the fast family for n = 128 * WAVES * M.
+// Register-carousel kernels (float): the fast family for n = 2 * M * L with M slots per lane and L lanes,
+// L <= 64 * WAVES (when L is not a multiple of 64 the last wavefront's spare lanes idle: they carry
+// zeros, read lane 0's coefficients and write their sums to a sink).
 //
 // Idea.  The circle method (paper Section 3, Figure 1) keeps a line of n positions; block k
 // pairs position p with position n-1-p, and between blocks the labels move one position along
@@ -110,9 +112,7 @@ __device__ __forceinline__ void lds_load_row(float (&dst)[W], const float *src)
 template <int M, int W, int WAVES, int FORM>
 struct CarouselFwd {
     static_assert(kRenormPeriod % M == 0, "renormalisation must fall on the last copy of an unrolled group");
-    static constexpr int kLanes = 64 * WAVES;
-    static constexpr int kN = 2 * kLanes * M;
-    static constexpr int kLastU = (kN - 2) % M; // register rotation after the n-2 moves
+    static constexpr int kLastU = (2 * M - 2) % M; // register rotation after the n-2 moves (n is a multiple of M)
 
     float top[M][W];
     float bot[M][W];
@@ -288,7 +288,7 @@ template <int W>
 __device__ __forceinline__ void load_row(float (&dst)[W], const float *X, long long B, int row, int rows,
                                          long long b0, int wv, bool vec, int identity)
 {
-    if (row >= rows) {
+    if ((unsigned)row >= (unsigned)rows) { // also catches the meaningless (negative) rows of idle lanes
 #pragma unroll
         for (int x = 0; x < W; ++x) dst[x] = 0.f;
         return;
@@ -317,7 +317,7 @@ template <int W>
 __device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long long B, int row, int rows,
                                           long long b0, int wv, bool vec)
 {
-    if (row >= rows) return;
+    if ((unsigned)row >= (unsigned)rows) return;
     float *dst = Y + (long long)row * B + b0;
     if constexpr (W % 4 == 0) {
         if (vec) {
@@ -346,22 +346,26 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
     using State = CarouselFwd<M, W, WAVES, FORM>;
     __shared__ CarouselExchange<W, WAVES> sh;
     State st;
-    st.rn_lane = renorm + (long long)threadIdx.x * M;
+    const int L = n / (2 * M);                  // lanes that hold slots; the rest of the last wavefront idles
+    const bool idle = (int)threadIdx.x >= L;
+    const int coef_lane = idle ? 0 : (int)threadIdx.x;
+    const int my_rows = idle ? 0 : rows;        // an idle lane loads zeros and stores nothing
+    st.rn_lane = renorm + (long long)coef_lane * M;
     st.n = n;
     st.H = n >> 1;
     st.tid = threadIdx.x;
     st.lane = threadIdx.x & 63;
     st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    st.tab_lane = table + (long long)threadIdx.x * M;
+    st.tab_lane = table + (long long)coef_lane * M;
     {
-        constexpr int L = 64 * WAVES;
+        constexpr int LMAX = 64 * WAVES;
         auto &b = sh.buf[0];
         const int t = threadIdx.x;
         st.out_top = b.top_out.lane(t);
         st.out_bot = b.bot_out.lane(t);
-        st.turn = b.top_out.lane(L);                                              // the extra row
+        st.turn = b.top_out.lane(LMAX);                                           // the extra row
         st.in_top = (t < L - 1) ? b.top_out.lane(t + 1) : b.bot_out.lane(L - 1); // far end: bot[n/2-1] -> top[n/2-1]
-        st.in_bot = (t > 0) ? b.bot_out.lane(t - 1) : b.top_out.lane(L);         // near end: top[1] -> bot[0]
+        st.in_bot = (t > 0) ? b.bot_out.lane(t - 1) : b.top_out.lane(LMAX);      // near end: top[1] -> bot[0]
     }
 
     const long long b0 = (long long)blockIdx.x * W;
@@ -372,8 +376,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 #pragma unroll
     for (int r = 0; r < M; ++r) {
         const int p = st.tid * M + r;
-        load_row<W>(st.top[r], X, B, mirrored_row(n, rr_label(n, n - 2, p), mirror), rows, b0, wv, vec, identity);
-        load_row<W>(st.bot[r], X, B, mirrored_row(n, rr_label(n, n - 2, n - 1 - p), mirror), rows, b0, wv, vec,
+        load_row<W>(st.top[r], X, B, mirrored_row(n, rr_label(n, n - 2, p), mirror), my_rows, b0, wv, vec, identity);
+        load_row<W>(st.bot[r], X, B, mirrored_row(n, rr_label(n, n - 2, n - 1 - p), mirror), my_rows, b0, wv, vec,
                     identity);
     }
     st.load_coefs(n - 2, st.cs[0]);
@@ -385,8 +389,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
 #pragma unroll
     for (int r = 0; r < M; ++r) {
         const int p = st.tid * M + r;
-        store_row<W>(st.top[(r + UL) % M], Y, B, mirrored_row(n, p, mirror), rows, b0, wv, vec);
-        store_row<W>(st.bot[(r - UL + M) % M], Y, B, mirrored_row(n, n - 1 - p, mirror), rows, b0, wv, vec);
+        store_row<W>(st.top[(r + UL) % M], Y, B, mirrored_row(n, p, mirror), my_rows, b0, wv, vec);
+        store_row<W>(st.bot[(r - UL + M) % M], Y, B, mirrored_row(n, n - 1 - p, mirror), my_rows, b0, wv, vec);
     }
 }
 
@@ -419,14 +423,13 @@ struct CarouselExchangeBwd {
 template <int M, int W, int WAVES, int FORM>
 struct CarouselBwd {
     static_assert(kRenormPeriod % M == 0, "renormalisation must fall on the last copy of an unrolled group");
-    static constexpr int kLanes = 64 * WAVES;
-    static constexpr int kN = 2 * kLanes * M;
-    static constexpr int kLastU = (kN - 2) % M;
+    static constexpr int kLastU = (2 * M - 2) % M;
 
     float zt[M][W], zb[M][W], gt[M][W], gb[M][W];
     float2 cs[2][M];
     float prior[2][M]; // sums of this workgroup's earlier strips for the current / next block
     int n, H, lane, wave, tid;
+    int lanes;               // L = n / (2 M): lanes that hold slots
     const float2 *tab_lane;  // table + tid*M
     const float2 *rn_lane;   // renormalisation factors + tid*M (scaled form)
     float *part_lane;        // where this lane's sums go (see `accumulate`)
@@ -603,7 +606,7 @@ struct CarouselBwd {
         if (accumulate) {
             float *dst = part_lane + (long long)k * H;   // H = M * lanes
 #pragma unroll
-            for (int r = 0; r < M; ++r) unsafeAtomicAdd(dst + r * kLanes, sums[r]);
+            for (int r = 0; r < M; ++r) unsafeAtomicAdd(dst + r * lanes, sums[r]);
         } else {
             float *dst = part_lane + (long long)k * H;
 #pragma unroll
@@ -666,32 +669,40 @@ template <int M, int W, int WAVES, int FORM>
 __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     int n, int rows, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
     const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
-    float *dX, float *partial, const float *__restrict__ zeros, int vec_ok, int accumulate, int g_identity)
+    float *dX, float *partial, const float *__restrict__ zeros, float *sink, int vec_ok, int accumulate,
+    int g_identity)
 {
     if (!form_selected(flag, FORM, scaled_max)) return;
     using State = CarouselBwd<M, W, WAVES, FORM>;
     __shared__ CarouselExchangeBwd<W, WAVES> sh;
     State st;
-    st.rn_lane = renorm + (long long)threadIdx.x * M;
+    const int L = n / (2 * M);                  // lanes that hold slots; the rest of the last wavefront idles
+    const bool idle = (int)threadIdx.x >= L;
+    const int coef_lane = idle ? 0 : (int)threadIdx.x;
+    const int my_rows = idle ? 0 : rows;        // an idle lane loads zeros and stores no rows
+    st.lanes = L;
+    st.rn_lane = renorm + (long long)coef_lane * M;
     st.n = n;
     st.H = n >> 1;
     st.tid = threadIdx.x;
     st.lane = threadIdx.x & 63;
     st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    st.tab_lane = table + (long long)threadIdx.x * M;
+    st.tab_lane = table + (long long)coef_lane * M;
     st.accumulate = accumulate;
-    st.part_lane = accumulate ? partial + threadIdx.x
-                              : partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) +
-                                    (long long)threadIdx.x * M;
+    // an idle lane's sums (all zero) go to the sink: N + 8192 floats nobody reads
+    st.part_lane = idle ? sink + (long long)threadIdx.x * M
+                        : (accumulate ? partial + threadIdx.x
+                                      : partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) +
+                                            (long long)threadIdx.x * M);
     {
-        constexpr int L = 64 * WAVES;
+        constexpr int LMAX = 64 * WAVES;
         auto &z = sh.buf[0].strip[0];
         const int t = threadIdx.x;
         st.out_top = z.top_out.lane(t);
         st.out_bot = z.bot_out.lane(t);
-        st.hold = z.top_out.lane(L);                                              // the extra row
+        st.hold = z.top_out.lane(LMAX);                                           // the extra row
         // near end: the held row stays in slot 0
-        st.in_top = (t > 0) ? z.top_out.lane(t - 1) : z.top_out.lane(L);
+        st.in_top = (t > 0) ? z.top_out.lane(t - 1) : z.top_out.lane(LMAX);
         st.in_bot = (t < L - 1) ? z.bot_out.lane(t + 1) : z.top_out.lane(L - 1); // far end: top[n/2-1] -> bot[n/2-1]
     }
 
@@ -700,7 +711,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     // order, so the result does not depend on scheduling.
     for (long long s = blockIdx.x; s < nstrips; s += gridDim.x) {
         const bool first_strip = (s == (long long)blockIdx.x);
-        st.prior_lane = (accumulate || first_strip) ? zeros + (long long)threadIdx.x * M : st.part_lane;
+        st.prior_lane = (accumulate || first_strip) ? zeros + (long long)coef_lane * M : st.part_lane;
         const long long b0 = (strip0 + s) * W;
         const int wv = (B - b0) < W ? (int)(B - b0) : W;
         const bool vec = vec_ok && wv == W;
@@ -709,10 +720,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
 #pragma unroll
         for (int r = 0; r < M; ++r) {
             const int p = st.tid * M + r;
-            load_row<W>(st.zt[r], Yin, B, p, rows, b0, wv, vec, 0);
-            load_row<W>(st.zb[r], Yin, B, n - 1 - p, rows, b0, wv, vec, 0);
-            load_row<W>(st.gt[r], G, B, p, rows, b0, wv, vec, g_identity);   // g_identity: G = I_n, not read
-            load_row<W>(st.gb[r], G, B, n - 1 - p, rows, b0, wv, vec, g_identity);
+            load_row<W>(st.zt[r], Yin, B, p, my_rows, b0, wv, vec, 0);
+            load_row<W>(st.zb[r], Yin, B, n - 1 - p, my_rows, b0, wv, vec, 0);
+            load_row<W>(st.gt[r], G, B, p, my_rows, b0, wv, vec, g_identity);   // g_identity: G = I_n, not read
+            load_row<W>(st.gb[r], G, B, n - 1 - p, my_rows, b0, wv, vec, g_identity);
         }
         st.load_coefs(0, st.cs[0]);
 
@@ -723,8 +734,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
 #pragma unroll
             for (int r = 0; r < M; ++r) {
                 const int p = st.tid * M + r;
-                store_row<W>(st.gt[(r - UL + M) % M], dX, B, rr_label(n, n - 2, p), rows, b0, wv, vec);
-                store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), rows, b0, wv, vec);
+                store_row<W>(st.gt[(r - UL + M) % M], dX, B, rr_label(n, n - 2, p), my_rows, b0, wv, vec);
+                store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), my_rows, b0, wv, vec);
             }
         }
         __syncthreads(); // the next strip reuses the exchange buffers
@@ -758,14 +769,14 @@ inline int carousel_fwd_widths(int W, const CarouselFwdArgs &a)
 template <int FORM>
 inline int carousel_forward_form(const CarouselFwdArgs &a, CarouselShape s, int W)
 {
-    // every (M, WAVES) that carousel_shape_for can return: M = 8 with 1..8 wavefronts (n = 1024 .. 8192),
-    // M = 4 with 1, 3, 5, 7 (n = 512, 1536, 2560, 3584), M = 2 with 1, 3, 5, 7 (n = 256, 768, 1280, 1792)
+    // every (M, WAVES) that carousel_shape_for can return: 1..8 wavefronts for each of M = 8, 4, 2
 #define GIVENS_FWD_SHAPE(m, wv) \
     if (s.M == m && s.WAVES == wv) return carousel_fwd_widths<m, wv, FORM>(W, a);
-    GIVENS_FWD_SHAPE(8, 1) GIVENS_FWD_SHAPE(8, 2) GIVENS_FWD_SHAPE(8, 3) GIVENS_FWD_SHAPE(8, 4)
-    GIVENS_FWD_SHAPE(8, 5) GIVENS_FWD_SHAPE(8, 6) GIVENS_FWD_SHAPE(8, 7) GIVENS_FWD_SHAPE(8, 8)
-    GIVENS_FWD_SHAPE(4, 1) GIVENS_FWD_SHAPE(4, 3) GIVENS_FWD_SHAPE(4, 5) GIVENS_FWD_SHAPE(4, 7)
-    GIVENS_FWD_SHAPE(2, 1) GIVENS_FWD_SHAPE(2, 3) GIVENS_FWD_SHAPE(2, 5) GIVENS_FWD_SHAPE(2, 7)
+#define GIVENS_FWD_SLOTS(m)                                                                             \
+    GIVENS_FWD_SHAPE(m, 1) GIVENS_FWD_SHAPE(m, 2) GIVENS_FWD_SHAPE(m, 3) GIVENS_FWD_SHAPE(m, 4)         \
+    GIVENS_FWD_SHAPE(m, 5) GIVENS_FWD_SHAPE(m, 6) GIVENS_FWD_SHAPE(m, 7) GIVENS_FWD_SHAPE(m, 8)
+    GIVENS_FWD_SLOTS(8) GIVENS_FWD_SLOTS(4) GIVENS_FWD_SLOTS(2)
+#undef GIVENS_FWD_SLOTS
 #undef GIVENS_FWD_SHAPE
     return GIVENS_ERR_UNSUPPORTED;
 }
@@ -775,8 +786,8 @@ inline void carousel_launch_bwd(const CarouselBwdArgs &a)
 {
     hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.groups), dim3(64 * WAVES),
                        0, a.stream, a.n, a.rows, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
-                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.vec_ok, a.accumulate,
-                       a.g_identity);
+                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.sink, a.vec_ok,
+                       a.accumulate, a.g_identity);
 }
 
 template <int M, int WAVES, int FORM>
@@ -794,13 +805,14 @@ inline int carousel_bwd_widths(int W, const CarouselBwdArgs &a)
 template <int FORM>
 inline int carousel_backward_form(const CarouselBwdArgs &a, CarouselShape s, int W)
 {
-    // every (M, WAVES) that carousel_bwd_shape_for can return: M = 4 with 1..8 wavefronts (n = 512 .. 4096),
-    // M = 2 with 1, 3, 5, 7 (n = 256, 768, 1280, 1792)
+    // every (M, WAVES) that carousel_bwd_shape_for can return: 1..8 wavefronts for each of M = 4, 2
 #define GIVENS_BWD_SHAPE(m, wv) \
     if (s.M == m && s.WAVES == wv) return carousel_bwd_widths<m, wv, FORM>(W, a);
-    GIVENS_BWD_SHAPE(4, 1) GIVENS_BWD_SHAPE(4, 2) GIVENS_BWD_SHAPE(4, 3) GIVENS_BWD_SHAPE(4, 4)
-    GIVENS_BWD_SHAPE(4, 5) GIVENS_BWD_SHAPE(4, 6) GIVENS_BWD_SHAPE(4, 7) GIVENS_BWD_SHAPE(4, 8)
-    GIVENS_BWD_SHAPE(2, 1) GIVENS_BWD_SHAPE(2, 3) GIVENS_BWD_SHAPE(2, 5) GIVENS_BWD_SHAPE(2, 7)
+#define GIVENS_BWD_SLOTS(m)                                                                             \
+    GIVENS_BWD_SHAPE(m, 1) GIVENS_BWD_SHAPE(m, 2) GIVENS_BWD_SHAPE(m, 3) GIVENS_BWD_SHAPE(m, 4)         \
+    GIVENS_BWD_SHAPE(m, 5) GIVENS_BWD_SHAPE(m, 6) GIVENS_BWD_SHAPE(m, 7) GIVENS_BWD_SHAPE(m, 8)
+    GIVENS_BWD_SLOTS(4) GIVENS_BWD_SLOTS(2)
+#undef GIVENS_BWD_SLOTS
 #undef GIVENS_BWD_SHAPE
     return GIVENS_ERR_UNSUPPORTED;
 }

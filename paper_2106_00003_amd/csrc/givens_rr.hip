@@ -38,10 +38,12 @@ struct Workspace {
     Buffer partial;      // per-strip dtheta partial sums (two-stage reduction)
     Buffer acc;          // one accumulation buffer of N floats (accumulating reduction)
     Buffer zeros;        // N floats that are zeroed when allocated and never written again
+    Buffer sink;         // N + 8192 floats: where idle lanes of the carousel reverse sweep put their sums
     Buffer gram;         // Gram-matrix reduction: C = Y G^T, n x n floats
     Buffer map;          // restricted parametrisation / odd n: index in theta of every entry of E, or -1
     int map_rows = 0, map_m = 0; // the (row count, m) the map was built for
-    Buffer *all[11] = {&table, &table_scaled, &scale, &renorm, &factor, &flag, &partial, &acc, &zeros, &gram, &map};
+    Buffer *all[12] = {&table, &table_scaled, &scale, &renorm, &factor, &flag,
+                       &partial, &acc, &zeros, &sink, &gram, &map};
 };
 
 // One call's problem: `rows` coordinates of which the first m may rotate with every other one
@@ -351,6 +353,7 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
     int cus = 0;
     GIVENS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     const float *zeros = nullptr;
+    float *sink = nullptr;
     if constexpr (std::is_same<T, float>::value) {
         if (family == GIVENS_KERNEL_CAROUSEL) {
             const size_t want = (size_t)N * sizeof(float);
@@ -363,6 +366,8 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
                 GIVENS_HIP(hipStreamSynchronize(stream));
             }
             zeros = reinterpret_cast<const float *>(ws.zeros.ptr);
+            if (int rc = grow(ws.sink, ((size_t)N + 8192) * sizeof(float))) return rc;
+            sink = reinterpret_cast<float *>(ws.sink.ptr);
         }
     }
 
@@ -383,14 +388,14 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
                 const long long groups = carousel_bwd_groups(n, strips, cus);
                 if (coefs.all_forms) {
                     if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.scaled, Y, G, dX,
-                                                          acc, zeros, 1, g_identity, stream))
+                                                          acc, zeros, sink, 1, g_identity, stream))
                         return rc;
                     if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.lifted, Y, G, dX,
-                                                          acc, zeros, 1, g_identity, stream))
+                                                          acc, zeros, sink, 1, g_identity, stream))
                         return rc;
                 }
                 if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.standard, Y, G, dX,
-                                                      acc, zeros, 1, g_identity, stream))
+                                                      acc, zeros, sink, 1, g_identity, stream))
                     return rc;
                 GIVENS_HIP(hipGetLastError());
             }
@@ -427,14 +432,14 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
             } else if constexpr (std::is_same<T, float>::value) {
                 if (coefs.all_forms) {
                     if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX,
-                                                          partial, zeros, 0, g_identity, stream))
+                                                          partial, zeros, sink, 0, g_identity, stream))
                         return rc;
                     if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX,
-                                                          partial, zeros, 0, g_identity, stream))
+                                                          partial, zeros, sink, 0, g_identity, stream))
                         return rc;
                 }
                 if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.standard, Y, G, dX,
-                                                      partial, zeros, 0, g_identity, stream))
+                                                      partial, zeros, sink, 0, g_identity, stream))
                     return rc;
             } else {
                 return GIVENS_ERR_UNSUPPORTED;

@@ -183,7 +183,30 @@ def test_carousel_family_sizes_with_3_5_6_7_wavefronts(n, B, seed, dist):
     assert binding.last_kernel() == binding.KERNEL_CAROUSEL
 
 
-@pytest.mark.parametrize("n,B,seed", [(5120, 16, 25), (6144, 12, 26), (7168, 9, 27)])
+@pytest.mark.parametrize("n,B,seed,dist,red", [
+    (132, 50, 131, "uniform", "two_stage"), (136, 300, 132, "normal0.1", "gram"), (200, 70, 133, "uniform", "atomic"),
+    (300, 41, 134, "uniform", "two_stage"), (1000, 64, 135, "normal0.1", "two_stage"),
+    (1008, 33, 136, "uniform", "atomic"), (1040, 40, 137, "uniform", "two_stage"),
+    (2044, 24, 138, "uniform", "two_stage"), (2600, 20, 139, "normal0.1", "atomic"), (4088, 12, 140, "uniform", "two_stage")])
+def test_carousel_family_with_partly_filled_last_wavefront(n, B, seed, dist, red):
+    """n = 2 M L with a lane count L that is not a multiple of 64: the spare lanes of the last wavefront idle."""
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    mode = {"two_stage": binding.REDUCTION_TWO_STAGE, "atomic": binding.REDUCTION_ATOMIC,
+            "gram": binding.REDUCTION_GRAM}[red]
+    try:
+        binding.set_reduction(mode)
+        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
+                               binding.KERNEL_CAROUSEL)
+        assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+        assert binding.last_reduction() == mode
+    finally:
+        binding.set_reduction(binding.REDUCTION_AUTO)
+    u_d = binding.givens_build(dev(data["theta"]), n)
+    assert O.rel_fro(host(u_d), C.forward(data["theta"], None, n=n)) <= TOL_Y
+    binding.release()
+
+
+@pytest.mark.parametrize("n,B,seed", [(5120, 16, 25), (6144, 12, 26), (7168, 9, 27), (8176, 8, 28), (4112, 8, 29)])
 def test_forward_only_carousel_sizes_above_4096(n, B, seed):
     data = inputs.make_custom(n, B, seed=seed)
     binding.set_kernel(binding.KERNEL_AUTO)
@@ -353,7 +376,7 @@ def test_gram_reduction_can_be_forced_on_a_narrow_batch_in_both_families():
         binding.set_kernel(binding.KERNEL_AUTO)
 
 
-@pytest.mark.parametrize("n,B,seed", [(200, 900, 111), (300, 700, 112), (1000, 2100, 113)])
+@pytest.mark.parametrize("n,B,seed", [(202, 900, 111), (302, 700, 112), (1002, 2100, 113)])
 def test_lds_family_wide_batches_use_the_gram_form(n, B, seed):
     data = inputs.make_custom(n, B, seed=seed)
     binding.set_kernel(binding.KERNEL_AUTO)

@@ -134,6 +134,11 @@ def test_column_family_restricted_and_odd(n, m, B, seed):
         assert binding.last_reduction() == binding.REDUCTION_GRAM
 
 
+@pytest.mark.parametrize("n,m,B,seed", [(999, 400, 40, 359), (299, 298, 65, 360), (1100, 3, 30, 361)])
+def test_carousel_with_idle_lanes_restricted_and_odd(n, m, B, seed):
+    check(n, m, B, seed, kernel=binding.KERNEL_AUTO, expect_kernel=binding.KERNEL_CAROUSEL)
+
+
 def test_unrestricted_m_gives_the_unrestricted_entry_points_result():
     n, B = 256, 24
     theta, X, G = make(n, n - 1, B, 361)
