@@ -1,13 +1,19 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
 (KERNEL_AUTO): n = 4096, B = 4096 (near-identity angles) and n = 2048, B = 65536.
 
-The oracle cannot sweep these sizes in test time, so it is asked for what it can compute one by
-one, on the same seeded inputs:
-  * sampled columns of Y and dX (columns are independent: the oracle's Algorithm 1 run on the
-    sampled columns alone gives exactly those columns),
-  * sampled components of dtheta from the rank-2 Jacobian form of Section 4.1 (O(n^2 + nB) each),
-and the rest is covered by properties that hold at any size: norm preservation, the adjoint
-identity <G, U X> = <U^T G, X>, and a vanishing gradient when the upstream gradient equals Y.
+Every element of Y and dX and every component of dtheta is compared with the fp64 C oracle
+(Algorithm 1 for Y, the operand-side sweep of Section 4.1 for dX and dtheta) on the same seeded
+inputs.  The oracle runs in chunks of columns -- columns never interact, and dtheta is a plain sum
+over columns -- so host memory stays bounded.  Checks, per quantity:
+  * relative Frobenius error of the whole array within the tolerance,
+  * the same per column (Y, dX) and per block of the round-robin sequence (dtheta), so that one bad
+    strip, lane or renormalisation period cannot hide in a global norm,
+  * the largest single-element error against the root-mean-square size of the oracle's values.
+Kept next to them as independent cross-checks: sampled components of dtheta from the rank-2 Jacobian
+form of Section 4.1, norm preservation, the adjoint identity <G, U X> = <U^T G, X>, and a vanishing
+gradient when the upstream gradient equals Y.  Mid-size cases force the two-stage reduction with more
+strips than resident workgroups, so that the "later strip adds onto its workgroup's row" path is
+compared with the oracle directly.
 """
 import numpy as np
 import pytest
@@ -20,6 +26,12 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 TOL_Y, TOL_G = 1e-5, 1e-4
+# Largest single-element error, in units of the rms of the oracle's values.  fp32 rounding gives each
+# element an error of a few 1e-6 rms (about sqrt(n) roundings of 6e-8, carried isometrically); the
+# largest of 1e8 roughly normal errors is about six times that.  A wrong coefficient, a wrong strip
+# or a missed renormalisation gives errors of order 1.
+MAX_ELEM_Y, MAX_ELEM_G = 1e-4, 1e-3
+CHUNK = 8192
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -29,6 +41,7 @@ def _gpu():
     binding.lib()
     binding.set_kernel(binding.KERNEL_AUTO)
     yield
+    binding.set_reduction(binding.REDUCTION_AUTO)
     binding.release()
     torch.cuda.empty_cache()
 
@@ -42,21 +55,83 @@ def _sample_angles(n, rng, count):
     return sorted(picks)
 
 
+class _ColumnErrors:
+    """Accumulates, chunk by chunk, what the comparison of an n x B array with the oracle needs."""
+
+    def __init__(self):
+        self.diff2 = 0.0
+        self.want2 = 0.0
+        self.count = 0
+        self.worst_col = 0.0
+        self.worst_elem = 0.0
+
+    def add(self, got, want):
+        d = got.astype(np.float64) - want
+        d2, w2 = (d * d).sum(axis=0), (want * want).sum(axis=0)
+        self.diff2 += float(d2.sum())
+        self.want2 += float(w2.sum())
+        self.count += want.size
+        self.worst_col = max(self.worst_col, float(np.sqrt(d2 / w2).max()))
+        self.worst_elem = max(self.worst_elem, float(np.abs(d).max()))
+
+    @property
+    def rel_fro(self):
+        return float(np.sqrt(self.diff2 / self.want2))
+
+    @property
+    def worst_elem_rms(self):
+        return self.worst_elem / float(np.sqrt(self.want2 / self.count))
+
+
+def _oracle_everything(th, X, G, y_d, dx_d, tag):
+    """Oracle Y, dX, dtheta over all columns, chunked; returns (Y errors, dX errors, oracle dtheta)."""
+    n, B = X.shape
+    pairs = C.schedule(n)
+    e_y, e_dx = _ColumnErrors(), _ColumnErrors()
+    want_dth = np.zeros(th.size, dtype=np.float64)
+    for c0 in range(0, B, CHUNK):
+        c1 = min(B, c0 + CHUNK)
+        want_y = C.forward(th, X[:, c0:c1], pairs=pairs)
+        dth, want_dx, _ = C.reverse_sweep(th, want_y, G[:, c0:c1], pairs=pairs, want_x=False)
+        want_dth += dth
+        e_y.add(y_d[:, c0:c1].cpu().numpy(), want_y)
+        e_dx.add(dx_d[:, c0:c1].cpu().numpy(), want_dx)
+        print(f"[fullsize] {tag}: oracle columns {c0}..{c1 - 1} done", flush=True)
+    return e_y, e_dx, want_dth
+
+
+def _check_dtheta(got, want, n, tag):
+    half = n // 2
+    d = got.astype(np.float64) - want
+    err = float(np.linalg.norm(d) / np.linalg.norm(want))
+    per_block = np.sqrt((d.reshape(n - 1, half) ** 2).sum(axis=1) / (want.reshape(n - 1, half) ** 2).sum(axis=1))
+    worst = float(np.abs(d).max() / np.sqrt((want * want).mean()))
+    print(f"[fullsize] {tag}: dtheta err {err:.3e} over all {want.size} angles, worst block {per_block.max():.3e} "
+          f"(block {int(per_block.argmax()) + 1}), worst element {worst:.3e} rms", flush=True)
+    assert err <= TOL_G
+    assert per_block.max() <= TOL_G
+    assert worst <= MAX_ELEM_G
+
+
 @pytest.mark.parametrize("cfg", [4, 5])
-def test_full_size_forward_backward(cfg):
+def test_full_size_forward_backward_every_element(cfg):
     data = inputs.make_inputs(cfg)
     wl = data["workload"]
     n, B = wl.n, wl.B
     th, X, G = data["theta"], data["X"], data["G"]
-    print(f"[fullsize] config {cfg}: n={n} B={B} seed={inputs.BASE_SEED + cfg}", flush=True)
+    tag = f"config {cfg}"
+    print(f"[fullsize] {tag}: n={n} B={B} seed={inputs.BASE_SEED + cfg}", flush=True)
     th_d, x_d, g_d = (torch.from_numpy(a).cuda() for a in (th, X, G))
     want_form = binding.FORM_SCALED if wl.theta_dist == "normal0.1" else binding.FORM_LIFTED
+    binding.set_reduction(binding.REDUCTION_AUTO)
     y_d = binding.givens_forward(th_d, x_d)
     assert binding.last_kernel() == binding.KERNEL_CAROUSEL
     assert binding.last_rotation_form() == want_form
     dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
     assert binding.last_kernel() == binding.KERNEL_CAROUSEL
     assert binding.last_rotation_form() == want_form
+    default_reduction = binding.last_reduction()
+    assert default_reduction == (binding.REDUCTION_GRAM if B >= 2 * n else binding.REDUCTION_TWO_STAGE)
     torch.cuda.synchronize()
 
     # ---- properties at full size (fp64 accumulation on the device)
@@ -68,33 +143,69 @@ def test_full_size_forward_backward(cfg):
     assert abs(lhs - rhs) <= 1e-6 * scale
     assert abs(float(dx_d.double().norm()) - float(g_d.double().norm())) <= 2e-6 * float(g_d.double().norm())
 
-    # ---- sampled columns against the oracle
-    rng = np.random.default_rng(99 + cfg)
-    cols = sorted({0, 1, 7, 8, B - 1, B - 9} | {int(c) for c in rng.integers(0, B, 18)})
-    pairs = C.schedule(n)
-    y_cols = y_d[:, cols].cpu().numpy()
-    dx_cols = dx_d[:, cols].cpu().numpy()
-    want_y = C.forward(th, X[:, cols], pairs=pairs)
-    want_dx = C.grad_operand(th, G[:, cols], pairs=pairs)
-    err_y, err_dx = O.rel_fro(y_cols, want_y), O.rel_fro(dx_cols, want_dx)
-    print(f"[fullsize] config {cfg}: Y err {err_y:.3e} ({len(cols)} columns), dX err {err_dx:.3e}", flush=True)
-    assert err_y <= TOL_Y
-    assert err_dx <= TOL_G
+    # ---- every element against the oracle
+    e_y, e_dx, want_dth = _oracle_everything(th, X, G, y_d, dx_d, tag)
+    print(f"[fullsize] {tag}: Y err {e_y.rel_fro:.3e}, worst column {e_y.worst_col:.3e}, worst element "
+          f"{e_y.worst_elem_rms:.3e} rms; dX err {e_dx.rel_fro:.3e}, worst column {e_dx.worst_col:.3e}, "
+          f"worst element {e_dx.worst_elem_rms:.3e} rms", flush=True)
+    assert e_y.rel_fro <= TOL_Y and e_y.worst_col <= TOL_Y and e_y.worst_elem_rms <= MAX_ELEM_Y
+    assert e_dx.rel_fro <= TOL_G and e_dx.worst_col <= TOL_G and e_dx.worst_elem_rms <= MAX_ELEM_G
+    _check_dtheta(dth_d.cpu().numpy(), want_dth, n, f"{tag}, default reduction ({default_reduction})")
 
-    # ---- sampled gradient components against the rank-2 Jacobian form
+    # ---- the other reduction of the same call (config 5: the two-stage sweep over all B columns)
+    if default_reduction != binding.REDUCTION_TWO_STAGE:
+        binding.set_reduction(binding.REDUCTION_TWO_STAGE)
+        dx2_d, dth2_d = binding.givens_backward(th_d, y_d, g_d)
+        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+        binding.set_reduction(binding.REDUCTION_AUTO)
+        _check_dtheta(dth2_d.cpu().numpy(), want_dth, n, f"{tag}, two-stage reduction")
+        # dX of this path comes from the two-strip sweep, not from the mirrored forward sweep: compare it
+        # with the (checked) dX above
+        dd = float((dx2_d.double() - dx_d.double()).norm() / dx_d.double().norm())
+        print(f"[fullsize] {tag}: dX two-strip sweep vs mirrored forward sweep {dd:.3e}", flush=True)
+        assert dd <= 2e-5
+        del dx2_d, dth2_d
+
+    # ---- sampled gradient components against the rank-2 Jacobian form (independent of the sweep)
+    rng = np.random.default_rng(99 + cfg)
+    pairs = C.schedule(n)
     x64, g64 = X.astype(np.float64), G.astype(np.float64)
     angles = _sample_angles(n, rng, 14)
     want = np.array([O.grad_theta_single(th, x64, g64, e, pairs=pairs) for e in angles])
     got = dth_d.cpu().numpy()[angles].astype(np.float64)
-    err_dth = float(np.linalg.norm(got - want) / np.linalg.norm(want))
-    print(f"[fullsize] config {cfg}: dtheta err {err_dth:.3e} on {len(angles)} sampled angles", flush=True)
-    assert err_dth <= TOL_G
+    err_s = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+    print(f"[fullsize] {tag}: dtheta err {err_s:.3e} on {len(angles)} angles from the rank-2 form", flush=True)
+    assert err_s <= TOL_G
+    assert float(np.linalg.norm(want_dth[angles] - want) / np.linalg.norm(want)) <= 1e-9
     del x64, g64
 
     # ---- upstream gradient equal to the output: gradient of a constant
     _, dth0_d = binding.givens_backward(th_d, y_d, y_d.clone(), want_dx=False)
     typical = float(dth_d.double().abs().mean())
     worst = float(dth0_d.abs().max())
-    print(f"[fullsize] config {cfg}: max |dtheta| with G = Y: {worst:.3e} (typical |dtheta| {typical:.3e})",
+    print(f"[fullsize] {tag}: max |dtheta| with G = Y: {worst:.3e} (typical |dtheta| {typical:.3e})",
           flush=True)
     assert worst <= 1e-3 * typical
+
+
+@pytest.mark.parametrize("n,B,seed,dist", [(512, 2100, 301, "normal0.1"), (1024, 8200, 302, "uniform"),
+                                           (2048, 4104, 303, "normal0.1")])
+def test_two_stage_with_more_strips_than_resident_workgroups(n, B, seed, dist):
+    """The reverse sweep's persistent workgroups take a second strip here; dtheta, dX against the oracle."""
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    th, X, G = data["theta"], data["X"], data["G"]
+    print(f"[fullsize] two-stage n={n} B={B} seed={seed} {dist}", flush=True)
+    th_d, x_d, g_d = (torch.from_numpy(a).cuda() for a in (th, X, G))
+    binding.set_reduction(binding.REDUCTION_TWO_STAGE)
+    try:
+        y_d = binding.givens_forward(th_d, x_d)
+        dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+        assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+    finally:
+        binding.set_reduction(binding.REDUCTION_AUTO)
+    torch.cuda.synchronize()
+    e_y, e_dx, want_dth = _oracle_everything(th, X, G, y_d, dx_d, f"n={n} B={B}")
+    assert e_y.rel_fro <= TOL_Y and e_y.worst_col <= TOL_Y
+    assert e_dx.rel_fro <= TOL_G and e_dx.worst_col <= TOL_G
+    _check_dtheta(dth_d.cpu().numpy(), want_dth, n, f"n={n} B={B}, two-stage")
