@@ -115,6 +115,23 @@ int givens_backward(int n, int64_t B, const float *theta, const float *Y, const 
 int givens_forward_transposed(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream);
 int givens_forward_transposed_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream);
 
+/*
+ * givens_forward_noalloc -- givens_forward for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results, but the coefficient tables (cos/sin or scaled / lifted coefficients, row
+ * factors, renormalisation rows, the range-check flag) are written to a static device array of
+ * GIVENS_NOALLOC_BYTES bytes inside the library instead of the hipMalloc'ed workspace, so the call makes
+ * no hipMalloc, hipFree or other allocating call.  Every GPU the library runs on holds that array until
+ * the process ends.
+ *   n even, 2 <= n <= GIVENS_NOALLOC_MAX_N (larger n: GIVENS_ERR_UNSUPPORTED, nothing launched); any B >= 1.
+ *   All calls on one GPU share the array: calls that overlap on one GPU (two streams, two threads) race.
+ *   Nothing in it needs clearing between calls: every word a call reads it has written first.
+ *   Per-kernel timing (givens_set_timing) is not recorded for this call.
+ */
+#define GIVENS_NOALLOC_MAX_N 1024
+#define GIVENS_NOALLOC_BYTES 16826624 /* both tables, row factors, renormalisation rows, flag at n = 1024 */
+int givens_forward_noalloc(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream);
+
 /* float64 variants: same semantics, all arrays double. */
 int givens_forward_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream);
 int givens_build_f64(int n, const double *theta, double *U, void *stream);

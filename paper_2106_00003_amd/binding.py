@@ -21,7 +21,7 @@ REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_ATOMIC, REDUCTION_GRAM = 0, 1, 2,
 EXPORTS = [
     "rr_schedule", "givens_forward", "givens_build", "givens_backward",
     "givens_forward_f64", "givens_build_f64", "givens_backward_f64",
-    "givens_forward_transposed", "givens_forward_transposed_f64",
+    "givens_forward_transposed", "givens_forward_transposed_f64", "givens_forward_noalloc",
     "givens_release", "givens_last_hip_error", "givens_error_string",
     "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
     "givens_set_rotation_form", "givens_last_rotation_form",
@@ -57,7 +57,8 @@ def lib():
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     L.rr_schedule.argtypes = [i32, vp]
-    for name in ("givens_forward", "givens_forward_f64", "givens_forward_transposed", "givens_forward_transposed_f64"):
+    for name in ("givens_forward", "givens_forward_f64", "givens_forward_transposed", "givens_forward_transposed_f64",
+                 "givens_forward_noalloc"):
         getattr(L, name).argtypes = [i32, i64, vp, vp, vp, vp]
     for name in ("givens_build", "givens_build_f64"):
         getattr(L, name).argtypes = [i32, vp, vp, vp]
@@ -142,6 +143,21 @@ def givens_forward(theta, X, Y=None, stream=None):
     fn = getattr(lib(), "givens_forward" + _suffix(X))
     _check(fn(n, B, _dev(theta, "theta", X.dtype), _dev(X, "X"), _dev(Y, "Y", X.dtype), _stream_ptr(stream)),
            "givens_forward")
+    return Y
+
+
+NOALLOC_MAX_N = 1024
+
+
+def givens_forward_noalloc(theta, X, Y, stream=None):
+    """givens_forward through the entry point that allocates nothing; the caller brings Y (float32 only)."""
+    import torch
+    n, B = X.shape
+    if theta.numel() != n * (n - 1) // 2:
+        raise ValueError("theta must have n(n-1)/2 entries")
+    _check(lib().givens_forward_noalloc(n, B, _dev(theta, "theta", torch.float32), _dev(X, "X", torch.float32),
+                                        _dev(Y, "Y", torch.float32), _stream_ptr(stream)),
+           "givens_forward_noalloc")
     return Y
 
 

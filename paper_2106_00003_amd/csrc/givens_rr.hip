@@ -242,11 +242,92 @@ FormPolicy form_policy(bool float_carousel)
     return {true, kScaledMaxAbsTheta};
 }
 
+// Where the coefficient kernels of one call write: either the per-device workspace (grown on demand) or
+// the static scratch array of the entry point that may not allocate.
+template <typename T>
+struct CoefStorage {
+    typename Pair2<T>::type *table = nullptr; // standard form, N pairs
+    T *factor = nullptr;                      // reverse sweep only, N values
+    unsigned *flag = nullptr;                 // float carousel path only, as are the following
+    float2 *table_scaled = nullptr;           // N pairs
+    double *scale = nullptr;                  // (n-1) * n row factors
+    float *renorm = nullptr;                  // periods * n/2 pairs
+};
+
+inline int renorm_periods(int n) { return (n - 1 + kRenormPeriod - 1) / kRenormPeriod; }
+
+template <typename T>
+int workspace_coef_storage(int dev, int n, bool forward, bool try_forms, CoefStorage<T> *out)
+{
+    using P2 = typename Pair2<T>::type;
+    const long long N = (long long)n * (n - 1) / 2;
+    Workspace &ws = g_ws[dev];
+    if (int rc = grow(ws.table, (size_t)N * sizeof(P2))) return rc;
+    out->table = reinterpret_cast<P2 *>(ws.table.ptr);
+    if (!forward) {
+        if (int rc = grow(ws.factor, (size_t)N * sizeof(T))) return rc;
+        out->factor = reinterpret_cast<T *>(ws.factor.ptr);
+    }
+    if (try_forms) {
+        if (int rc = grow(ws.flag, 256)) return rc;
+        if (int rc = grow(ws.table_scaled, (size_t)N * sizeof(float2))) return rc;
+        if (int rc = grow(ws.scale, (size_t)(n - 1) * n * sizeof(double))) return rc;
+        if (int rc = grow(ws.renorm, (size_t)renorm_periods(n) * (n / 2) * sizeof(float2))) return rc;
+        out->flag = reinterpret_cast<unsigned *>(ws.flag.ptr);
+        out->table_scaled = reinterpret_cast<float2 *>(ws.table_scaled.ptr);
+        out->scale = reinterpret_cast<double *>(ws.scale.ptr);
+        out->renorm = reinterpret_cast<float *>(ws.renorm.ptr);
+    }
+    return GIVENS_OK;
+}
+
+// ---- the entry point that allocates nothing: its coefficient tables live in a static device array.
+constexpr int kNoAllocMaxN = GIVENS_NOALLOC_MAX_N;
+constexpr size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
+constexpr size_t noalloc_bytes(int n)
+{
+    const size_t N = (size_t)n * (n - 1) / 2;
+    return round_up_256(N * sizeof(float2)) * 2                                            // both tables
+           + round_up_256((size_t)(n - 1) * n * sizeof(double))                            // row factors
+           + round_up_256((size_t)((n - 1 + kRenormPeriod - 1) / kRenormPeriod) * (n / 2) * sizeof(float2))
+           + 256;                                                                          // flag word
+}
+constexpr size_t kNoAllocBytes = noalloc_bytes(kNoAllocMaxN);
+static_assert(kNoAllocBytes == GIVENS_NOALLOC_BYTES, "the header states the size of the static array");
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+// Address of `scratch` on each device (every GPU holds its own copy of the array): looked up once per
+// device with that device current.  Host code uses these pointers, never the array's name.
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+int static_coef_storage(int dev, int n, CoefStorage<float> *out)
+{
+    if (n > kNoAllocMaxN) return GIVENS_ERR_UNSUPPORTED;
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        GIVENS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    const size_t N = (size_t)n * (n - 1) / 2;
+    unsigned char *at = g_scratch_ptr[dev];
+    auto take = [&](size_t bytes) {
+        unsigned char *here = at;
+        at += round_up_256(bytes);
+        return here;
+    };
+    out->table = reinterpret_cast<float2 *>(take(N * sizeof(float2)));
+    out->table_scaled = reinterpret_cast<float2 *>(take(N * sizeof(float2)));
+    out->scale = reinterpret_cast<double *>(take((size_t)(n - 1) * n * sizeof(double)));
+    out->renorm = reinterpret_cast<float *>(take((size_t)renorm_periods(n) * (n / 2) * sizeof(float2)));
+    out->flag = reinterpret_cast<unsigned *>(take(256));
+    out->factor = nullptr;
+    return (size_t)(at - g_scratch_ptr[dev]) <= kNoAllocBytes ? GIVENS_OK : GIVENS_ERR_UNSUPPORTED;
+}
+
 // Launches the coefficient kernels.  `forward` picks the sweep direction of the scaled / lifted
 // forms' row factors; `policy.try_forms` adds the range check and those forms' tables.
 template <typename T>
-int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, FormPolicy policy, hipStream_t stream,
-                  Coefs<T> *out, int mirror = 0)
+int prepare_coefs(const CoefStorage<T> &st, const Problem &pb, const T *theta, bool forward, FormPolicy policy,
+                  hipStream_t stream, Coefs<T> *out, int mirror = 0)
 {
     const bool try_scaled = policy.try_forms;
     const float scaled_max = policy.scaled_max;
@@ -254,27 +335,19 @@ int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, Form
     const int n = pb.n;
     const int *map = pb.map;
     const long long N = (long long)n * (n - 1) / 2;
-    Workspace &ws = g_ws[dev];
-    if (int rc = grow(ws.table, (size_t)N * sizeof(P2))) return rc;
-    if (!forward)
-        if (int rc = grow(ws.factor, (size_t)N * sizeof(T))) return rc;
-    P2 *table = reinterpret_cast<P2 *>(ws.table.ptr);
-    T *factor = forward ? nullptr : reinterpret_cast<T *>(ws.factor.ptr);
+    P2 *table = st.table;
+    T *factor = forward ? nullptr : st.factor;
     unsigned *flag = nullptr;
     const int threads = 256;
     const unsigned blocks = (unsigned)((N + threads - 1) / threads);
     Span span(0, stream);
     if constexpr (std::is_same<T, float>::value) {
         if (try_scaled) {
-            const int periods = (n - 1 + kRenormPeriod - 1) / kRenormPeriod;
-            if (int rc = grow(ws.flag, 256)) return rc;
-            if (int rc = grow(ws.table_scaled, (size_t)N * sizeof(float2))) return rc;
-            if (int rc = grow(ws.scale, (size_t)(n - 1) * n * sizeof(double))) return rc;
-            if (int rc = grow(ws.renorm, (size_t)periods * (n / 2) * sizeof(float2))) return rc;
-            flag = reinterpret_cast<unsigned *>(ws.flag.ptr);
-            float2 *tab_s = reinterpret_cast<float2 *>(ws.table_scaled.ptr);
-            double *D = reinterpret_cast<double *>(ws.scale.ptr);
-            float *rn = reinterpret_cast<float *>(ws.renorm.ptr);
+            const int periods = renorm_periods(n);
+            flag = st.flag;
+            float2 *tab_s = st.table_scaled;
+            double *D = st.scale;
+            float *rn = st.renorm;
             hipLaunchKernelGGL(reset_flag_kernel, dim3(1), dim3(1), 0, stream, flag);
             hipLaunchKernelGGL(theta_range_kernel, dim3(512), dim3(512), 0, stream, pb.free_angles, theta, flag);
             const long long scan_threads = (long long)periods * n;
@@ -305,6 +378,18 @@ int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, Form
     t_state.last_scaled_max = scaled_max;
     t_state.last_stream = stream;
     return GIVENS_OK;
+}
+
+// the usual case: storage from the per-device workspace
+template <typename T>
+int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, FormPolicy policy, hipStream_t stream,
+                  Coefs<T> *out, int mirror = 0)
+{
+    CoefStorage<T> st;
+    if (int rc = workspace_coef_storage<T>(dev, pb.n, forward,
+                                           policy.try_forms && std::is_same<T, float>::value, &st))
+        return rc;
+    return prepare_coefs<T>(st, pb, theta, forward, policy, stream, out, mirror);
 }
 
 template <typename T>
@@ -568,11 +653,14 @@ int current_device(int *dev)
 // rows, m: see Problem.  The unrestricted entry points pass an even rows and m = rows - 1.
 template <typename T>
 int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y, int identity, void *stream_v,
-                 int transpose = 0)
+                 int transpose = 0, bool no_alloc = false)
 {
     if (int rc = check_restricted(rows, m)) return rc;
     if (B < 1) return GIVENS_ERR_BAD_B;
     if (!theta || !Y || (!identity && !X)) return GIVENS_ERR_NULL;
+    // the variant that may not allocate: float, every pair free (no index map), n within the static array
+    if (no_alloc && (!std::is_same<T, float>::value || (rows & 1) || m != rows - 1 || rows > kNoAllocMaxN))
+        return GIVENS_ERR_UNSUPPORTED;
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
     std::lock_guard<std::mutex> lock(g_mutex);
     int dev = 0;
@@ -581,6 +669,7 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
     if (int rc = resolve_problem(dev, rows, m, &pb)) return rc;
     const int n = pb.n;
     timing_begin_call();
+    if (no_alloc) t_state.timing_valid = false; // event pairs are created on demand: not here
     const int choice = g_kernel_choice;
     const bool can_carousel = carousel_supported<T>(n, B);
     const bool can_column = std::is_same<T, float>::value && n <= kColumnFamilyMaxN;
@@ -589,9 +678,16 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
     const bool use_carousel = can_carousel && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_CAROUSEL);
     const bool use_column = can_column && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_COLUMN);
     Coefs<T> coefs;
-    if (int rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(use_carousel && std::is_same<T, float>::value),
-                                  stream, &coefs, transpose))
+    const FormPolicy policy = form_policy(use_carousel && std::is_same<T, float>::value);
+    if (no_alloc) {
+        if constexpr (std::is_same<T, float>::value) {
+            CoefStorage<float> st;
+            if (int rc = static_coef_storage(dev, n, &st)) return rc;
+            if (int rc = prepare_coefs<float>(st, pb, theta, true, policy, stream, &coefs, transpose)) return rc;
+        }
+    } else if (int rc = prepare_coefs<T>(dev, pb, theta, true, policy, stream, &coefs, transpose)) {
         return rc;
+    }
     int rc = GIVENS_OK;
     if (use_carousel) {
         if constexpr (std::is_same<T, float>::value) {
@@ -882,6 +978,12 @@ int givens_forward_transposed_f64(int n, int64_t B, const double *theta, const d
 {
     if (int rc = givens::check_n(n)) return rc;
     return givens::forward_impl<double>(n, n - 1, B, theta, X, Y, 0, stream, 1);
+}
+
+int givens_forward_noalloc(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream)
+{
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream, 0, true);
 }
 
 int64_t givens_num_angles(int n, int m)
