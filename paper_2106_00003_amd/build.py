@@ -41,17 +41,21 @@ def _run(cmd, verbose):
     return res
 
 
-def build_library(verbose: bool = False, extra_flags=(), jobs: int | None = None) -> str:
+def build_library(verbose: bool = False, extra_flags=(), jobs: int | None = None, only=()) -> str:
+    """Compiles every translation unit and links the library.  `only` (names without the suffix) restricts
+    the compile step to those units and links them with the other units' existing objects."""
     hipcc = hipcc_path()
     sources = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     if not sources:
         raise RuntimeError(f"no sources under {CSRC}")
     os.makedirs(OBJ, exist_ok=True)
     objects = [os.path.join(OBJ, os.path.basename(s)[:-4] + ".o") for s in sources]
+    todo = [(s, o) for s, o in zip(sources, objects)
+            if not only or os.path.basename(s)[:-4] in only or not os.path.exists(o)]
     jobs = jobs or max(1, min(len(sources), os.cpu_count() or 1, 16))
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
         futures = [pool.submit(_run, [hipcc, *HIPCC_FLAGS, *extra_flags, "-c", src, "-o", obj], verbose)
-                   for src, obj in zip(sources, objects)]
+                   for src, obj in todo]
         for f in futures:
             f.result()
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objects], verbose)
@@ -59,4 +63,5 @@ def build_library(verbose: bool = False, extra_flags=(), jobs: int | None = None
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import sys
+    print(build_library(verbose=True, only=tuple(sys.argv[1:])))
