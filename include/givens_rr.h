@@ -21,9 +21,11 @@
  *   - Unless marked "host", pointers are DEVICE pointers owned by the caller; the library
  *     neither frees nor retains them.  `stream` is a hipStream_t passed as void* (NULL = the
  *     default stream).  Calls are asynchronous on that stream.
- *   - The library owns a per-device workspace (cos/sin table, partial gradients), grown on
- *     demand with hipMalloc and released by givens_release().  Calls that use the same device
- *     share it: they must be ordered on one stream (or otherwise not overlap).
+ *   - The library owns one workspace per (device, stream) it has been called on (coefficient tables,
+ *     partial gradients), grown on demand with hipMalloc and released by givens_release().  Calls on
+ *     different streams use different workspaces and may overlap; calls on one stream are ordered by
+ *     that stream.  At most 8 streams per device keep a workspace: a ninth gives up the one used
+ *     longest ago (after a device-wide synchronisation).
  *   - Return value: 0 on success, a negative GIVENS_ERR_* code otherwise.  Nothing is launched
  *     when an argument check fails.  No exceptions, no aborts.
  */
@@ -44,6 +46,7 @@ extern "C" {
 #define GIVENS_ERR_UNSUPPORTED (-5) /* shape not supported by the requested kernel      */
 #define GIVENS_ERR_ALIAS (-6)       /* forbidden aliasing between arguments             */
 #define GIVENS_ERR_BAD_M (-7)       /* restricted entry points: m outside 1..n-1        */
+#define GIVENS_ERR_STALE (-8)       /* prepared calls: the token's tables are gone      */
 
 /* Kernel families (givens_set_kernel). */
 #define GIVENS_KERNEL_AUTO 0     /* column kernels for n <= 128, register carousel where the  */
@@ -62,10 +65,8 @@ extern "C" {
 /* How givens_backward sums the per-strip shares of dtheta (givens_set_reduction). */
 #define GIVENS_REDUCTION_AUTO 0      /* the library's default for the kernel family in use                     */
 #define GIVENS_REDUCTION_TWO_STAGE 1 /* one partial sum per (strip, angle), then a fixed-order pass: reproducible */
-#define GIVENS_REDUCTION_ATOMIC 2    /* strips add into one buffer with float atomics (carousel kernels only);  */
-                                     /* order of additions, hence the last bits of dtheta, varies run to run   */
-#define GIVENS_REDUCTION_GRAM 3      /* C = Y G^T by one SGEMM (rocBLAS, loaded on demand), then the sweep on   */
-                                     /* the n x n operand C; dX by a forward-type sweep (float entry points)    */
+#define GIVENS_REDUCTION_GRAM 3      /* C = Y G^T by the library's float32 MFMA kernel, then the sweep on the    */
+                                     /* n x n operand C; dX by a forward-type sweep (float entry points)        */
 
 /*
  * rr_schedule -- the round-robin sequence by the circle method (Section 3; the worked n = 6
@@ -125,12 +126,56 @@ int givens_forward_transposed_f64(int n, int64_t B, const double *theta, const d
  * the process ends.
  *   n even, 2 <= n <= GIVENS_NOALLOC_MAX_N (larger n: GIVENS_ERR_UNSUPPORTED, nothing launched); any B >= 1.
  *   All calls on one GPU share the array: calls that overlap on one GPU (two streams, two threads) race.
- *   Nothing in it needs clearing between calls: every word a call reads it has written first.
+ *   Nothing in it needs clearing between calls: every word a call reads it has written first, except the
+ *   range check's ticket counter, which is zero in a fresh array and which the range kernel itself puts back
+ *   to zero before it ends.
  *   Per-kernel timing (givens_set_timing) is not recorded for this call.
  */
 #define GIVENS_NOALLOC_MAX_N 1024
-#define GIVENS_NOALLOC_BYTES 16826624 /* both tables, row factors, renormalisation rows, flag at n = 1024 */
+#define GIVENS_NOALLOC_BYTES 8450048 /* flag area, table, row factors, renormalisation rows at n = 1024 */
 int givens_forward_noalloc(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream);
+
+/*
+ * Per-call choices.  givens_forward_ex / givens_backward_ex are givens_forward_restricted /
+ * givens_backward_restricted (any n >= 2, m = n - 1 for the unrestricted parametrisation) with the kernel
+ * family, rotation form and reduction taken from `options` instead of the process-wide givens_set_* settings
+ * (options == NULL: those settings).  givens_forward_ex with X == NULL builds U (B must equal n).
+ * An unknown value in `options` returns GIVENS_ERR_UNSUPPORTED.
+ */
+typedef struct givens_options {
+    int kernel;        /* GIVENS_KERNEL_*    */
+    int rotation_form; /* GIVENS_FORM_AUTO, _STANDARD or _LIFTED */
+    int reduction;     /* GIVENS_REDUCTION_* */
+} givens_options;
+int givens_forward_ex(int n, int m, int64_t B, const float *theta, const float *X, float *Y, void *stream,
+                      const givens_options *options);
+int givens_backward_ex(int n, int m, int64_t B, const float *theta, const float *Y, const float *G, float *dX,
+                       float *dtheta, void *stream, const givens_options *options);
+
+/*
+ * Prepared coefficients (float).  Everything the sweeps need that depends on theta alone -- the range check
+ * that picks the rotation form and the coefficient tables of Algorithm 2's blocks, for the forward sweep, the
+ * reverse sweep (Section 4.1) or both -- is built once by givens_prepare in the workspace of `stream`, and
+ * the *_prepared calls then run only the sweeps: a layer calls givens_prepare in its forward pass and reuses
+ * the tables in its backward pass (theta cannot change in between), and a model that is only evaluated
+ * prepares once per change of theta.  givens_prepare returns a positive token (or a negative error code).
+ * The tables stay valid until another call on the same stream writes the same coefficient set: a plain
+ * forward / build call replaces the forward set, a plain backward call the reverse set, givens_prepare
+ * both; givens_release drops everything.  A *_prepared call whose token is no longer the workspace's, whose
+ * direction was not prepared or lost, or which asks (through givens_set_kernel) for another kernel family
+ * than the tables were built for returns GIVENS_ERR_STALE and launches nothing: call the plain entry point
+ * instead.  The token must be used on the stream it was prepared on.
+ *   directions : GIVENS_PREPARE_FORWARD, GIVENS_PREPARE_BACKWARD or both (or-ed).
+ *   n, m, B, X, Y, U, G, dX, dtheta : as for the plain calls; n and m are those of givens_prepare.
+ */
+#define GIVENS_PREPARE_FORWARD 1
+#define GIVENS_PREPARE_BACKWARD 2
+int64_t givens_prepare(int n, const float *theta, int directions, void *stream);
+int64_t givens_prepare_restricted(int n, int m, const float *theta, int directions, void *stream);
+int givens_forward_prepared(int64_t token, int64_t B, const float *X, float *Y, void *stream);
+int givens_build_prepared(int64_t token, float *U, void *stream);
+int givens_backward_prepared(int64_t token, int64_t B, const float *Y, const float *G, float *dX, float *dtheta,
+                             void *stream);
 
 /* float64 variants: same semantics, all arrays double. */
 int givens_forward_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream);
@@ -153,8 +198,10 @@ int givens_backward_f64(int n, int64_t B, const double *theta, const double *Y, 
  * free pairs in the order in which the sequence E lists them (rr_schedule_restricted).  The kernels
  * run a bypassed pair as a rotation by zero, so the cost is that of the unrestricted problem of
  * n (or n+1) dimensions.  Everything else -- layouts, aliasing, streams, errors -- is as for the
- * unrestricted entry points; m outside 1..n-1 returns GIVENS_ERR_BAD_M.  The pair map is built on
- * the host and copied to the device (synchronously) the first time a given (n, m) is used.
+ * unrestricted entry points; m outside 1..n-1 returns GIVENS_ERR_BAD_M; n beyond what any kernel
+ * family takes (36864) returns GIVENS_ERR_UNSUPPORTED before anything is allocated.  The map from the
+ * entries of E to the indices in theta is built on the device, by kernels on the caller's stream, the
+ * first time a workspace sees (n, m) and whenever another (n, m) has used it in between.
  */
 int64_t givens_num_angles(int n, int m);                         /* N(n, m), or a negative error code  */
 int rr_schedule_restricted(int n, int m, int32_t *pairs);        /* HOST buffer of N(n, m) * 2 int32   */
@@ -236,13 +283,12 @@ int givens_last_rotation_form(void);
  * Selects how the reverse sweep reduces over strips (process-wide); returns the previous setting.
  * TWO_STAGE keeps one row of 4*N bytes of partial sums per resident workgroup of the carousel sweep
  * (at most 256 rows on this chip: 8.6 GB at n = 4096, whatever B is) or per strip of the LDS family,
- * capped at 24 GiB per chunk, and gives bit-identical dtheta from run to run; ATOMIC needs 4*N bytes
- * in all but its summation order is not fixed.  GRAM replaces the sweep over B columns by the Gram
- * matrix C = Y G^T (the sums of the sweep are those of the same sweep on the operand C with upstream
- * gradient I_n) and computes dX = U^T G by a forward-type sweep; it needs librocblas at run time and
- * returns GIVENS_ERR_UNSUPPORTED when forced without it.  AUTO means GRAM for every float kernel
- * family when B >= 2 n and rocBLAS loads, TWO_STAGE otherwise.  ATOMIC exists for the carousel kernels
- * only (the LDS family then uses TWO_STAGE); the f64 entry points always use TWO_STAGE.  givens_last_reduction() reports what the last backward call on this thread did.
+ * capped at 24 GiB per chunk, and gives bit-identical dtheta from run to run.  GRAM replaces the sweep
+ * over B columns by the Gram matrix C = Y G^T (the sums of the sweep are those of the same sweep on the
+ * operand C with upstream gradient I_n), contracted over B by the library's own float32 MFMA kernel in a
+ * fixed order (reproducible as well), and computes dX = U^T G by a forward-type sweep.  AUTO means GRAM for
+ * every float kernel family when B >= 2 n, TWO_STAGE otherwise; the f64 entry points always use TWO_STAGE.
+ * givens_last_reduction() reports what the last backward call on this thread did.
  */
 int givens_set_reduction(int which);
 int givens_last_reduction(void);

@@ -16,12 +16,17 @@ LIB_PATH = os.path.join(_HERE, "libgivens_rr.so")
 
 KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL, KERNEL_COLUMN = 0, 1, 2, 3
 FORM_AUTO, FORM_STANDARD, FORM_SCALED, FORM_LIFTED = 0, 1, 2, 3
-REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_ATOMIC, REDUCTION_GRAM = 0, 1, 2, 3
+REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_GRAM = 0, 1, 3
+PREPARE_FORWARD, PREPARE_BACKWARD = 1, 2
+ERR_STALE = -8
 
 EXPORTS = [
     "rr_schedule", "givens_forward", "givens_build", "givens_backward",
     "givens_forward_f64", "givens_build_f64", "givens_backward_f64",
     "givens_forward_transposed", "givens_forward_transposed_f64", "givens_forward_noalloc",
+    "givens_forward_ex", "givens_backward_ex",
+    "givens_prepare", "givens_prepare_restricted", "givens_forward_prepared", "givens_build_prepared",
+    "givens_backward_prepared",
     "givens_release", "givens_last_hip_error", "givens_error_string",
     "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
     "givens_set_rotation_form", "givens_last_rotation_form",
@@ -64,6 +69,13 @@ def lib():
         getattr(L, name).argtypes = [i32, vp, vp, vp]
     for name in ("givens_backward", "givens_backward_f64"):
         getattr(L, name).argtypes = [i32, i64, vp, vp, vp, vp, vp, vp]
+    L.givens_forward_ex.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp]
+    L.givens_backward_ex.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp, vp]
+    L.givens_prepare.argtypes = [i32, vp, i32, vp]
+    L.givens_prepare_restricted.argtypes = [i32, i32, vp, i32, vp]
+    L.givens_forward_prepared.argtypes = [i64, i64, vp, vp, vp]
+    L.givens_build_prepared.argtypes = [i64, vp, vp]
+    L.givens_backward_prepared.argtypes = [i64, i64, vp, vp, vp, vp, vp]
     L.givens_num_angles.argtypes = [i32, i32]
     L.rr_schedule_restricted.argtypes = [i32, i32, vp]
     for name in ("givens_forward_restricted", "givens_forward_restricted_f64"):
@@ -86,9 +98,10 @@ def lib():
     L.givens_set_timing.argtypes = [i32]
     L.givens_last_timing.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for name in EXPORTS:
-        if name not in ("givens_error_string", "givens_num_angles"):
+        if name not in ("givens_error_string", "givens_num_angles", "givens_prepare", "givens_prepare_restricted"):
             getattr(L, name).restype = i32
-    L.givens_num_angles.restype = i64
+    for name in ("givens_num_angles", "givens_prepare", "givens_prepare_restricted"):
+        getattr(L, name).restype = i64
     _lib = L
     return L
 
@@ -159,6 +172,98 @@ def givens_forward_noalloc(theta, X, Y, stream=None):
                                         _dev(Y, "Y", torch.float32), _stream_ptr(stream)),
            "givens_forward_noalloc")
     return Y
+
+
+class Options(ctypes.Structure):
+    """givens_options of the C header: per-call kernel family, rotation form and reduction."""
+    _fields_ = [("kernel", ctypes.c_int), ("rotation_form", ctypes.c_int), ("reduction", ctypes.c_int)]
+
+
+def _options(kernel, form, reduction):
+    return ctypes.byref(Options(kernel, form, reduction))
+
+
+def givens_forward_ex(theta, X, m=None, Y=None, n=None, kernel=KERNEL_AUTO, form=FORM_AUTO,
+                      reduction=REDUCTION_AUTO, stream=None):
+    """givens_forward (X given) or givens_build (X=None, n given) with per-call options; float32."""
+    import torch
+    if X is None:
+        B = n
+        if Y is None:
+            Y = torch.empty((n, n), dtype=torch.float32, device=theta.device)
+    else:
+        n, B = X.shape
+        if Y is None:
+            Y = torch.empty_like(X)
+    m = n - 1 if m is None else m
+    _check(lib().givens_forward_ex(n, m, B, _dev(theta, "theta", torch.float32), _dev(X, "X", torch.float32),
+                                   _dev(Y, "Y", torch.float32), _stream_ptr(stream),
+                                   _options(kernel, form, reduction)), "givens_forward_ex")
+    return Y
+
+
+def givens_backward_ex(theta, Y, G, m=None, dX=None, dtheta=None, want_dx=True, kernel=KERNEL_AUTO,
+                       form=FORM_AUTO, reduction=REDUCTION_AUTO, stream=None):
+    """givens_backward with per-call options; float32.  Returns (dX or None, dtheta)."""
+    import torch
+    n, B = Y.shape
+    m = n - 1 if m is None else m
+    if dtheta is None:
+        dtheta = torch.empty_like(theta)
+    if want_dx and dX is None:
+        dX = torch.empty_like(G)
+    _check(lib().givens_backward_ex(n, m, B, _dev(theta, "theta", torch.float32), _dev(Y, "Y", torch.float32),
+                                    _dev(G, "G", torch.float32), _dev(dX if want_dx else None, "dX", torch.float32),
+                                    _dev(dtheta, "dtheta", torch.float32), _stream_ptr(stream),
+                                    _options(kernel, form, reduction)), "givens_backward_ex")
+    return (dX if want_dx else None), dtheta
+
+
+def givens_prepare(theta, n: int, m=None, directions=PREPARE_FORWARD | PREPARE_BACKWARD, stream=None) -> int:
+    """Builds the coefficient tables of theta once in the stream's workspace; returns the token."""
+    import torch
+    th = _dev(theta, "theta", torch.float32)
+    if m is None:
+        tok = lib().givens_prepare(n, th, directions, _stream_ptr(stream))
+    else:
+        tok = lib().givens_prepare_restricted(n, m, th, directions, _stream_ptr(stream))
+    if tok <= 0:
+        raise GivensError(int(tok), "givens_prepare")
+    return int(tok)
+
+
+def givens_forward_prepared(token: int, X, Y=None, stream=None):
+    import torch
+    n, B = X.shape
+    if Y is None:
+        Y = torch.empty_like(X)
+    _check(lib().givens_forward_prepared(token, B, _dev(X, "X", torch.float32), _dev(Y, "Y", torch.float32),
+                                         _stream_ptr(stream)), "givens_forward_prepared")
+    return Y
+
+
+def givens_build_prepared(token: int, n: int, device, U=None, stream=None):
+    import torch
+    if U is None:
+        U = torch.empty((n, n), dtype=torch.float32, device=device)
+    _check(lib().givens_build_prepared(token, _dev(U, "U", torch.float32), _stream_ptr(stream)),
+           "givens_build_prepared")
+    return U
+
+
+def givens_backward_prepared(token: int, Y, G, ntheta: int, dX=None, dtheta=None, want_dx=True, stream=None):
+    """Returns (dX or None, dtheta); ntheta = number of angles (size of dtheta)."""
+    import torch
+    n, B = Y.shape
+    if dtheta is None:
+        dtheta = torch.empty(ntheta, dtype=torch.float32, device=Y.device)
+    if want_dx and dX is None:
+        dX = torch.empty_like(G)
+    _check(lib().givens_backward_prepared(token, B, _dev(Y, "Y", torch.float32), _dev(G, "G", torch.float32),
+                                          _dev(dX if want_dx else None, "dX", torch.float32),
+                                          _dev(dtheta, "dtheta", torch.float32), _stream_ptr(stream)),
+           "givens_backward_prepared")
+    return (dX if want_dx else None), dtheta
 
 
 def givens_forward_transposed(theta, X, Y=None, stream=None):

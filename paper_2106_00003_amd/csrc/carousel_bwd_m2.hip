@@ -1,0 +1,7 @@
+// Reverse-sweep carousel kernels with 2 slots per lane: all workgroup sizes and strip widths, the three
+// rotation forms inside each kernel.
+#include "carousel_kernels.hpp"
+
+namespace givens {
+int carousel_backward_m2(const CarouselBwdArgs &a, int waves, int W) { return carousel_backward_slots<2>(a, waves, W); }
+} // namespace givens

@@ -1,0 +1,7 @@
+// Forward carousel kernels with 4 slots per lane: all workgroup sizes and strip widths, the three rotation
+// forms inside each kernel.
+#include "carousel_kernels.hpp"
+
+namespace givens {
+int carousel_forward_m4(const CarouselFwdArgs &a, int waves, int W) { return carousel_forward_slots<4>(a, waves, W); }
+} // namespace givens

@@ -1,6 +1,6 @@
 // Host side of the register-carousel kernels: shapes, launch arguments and the entry points of the
-// translation units that instantiate the kernels (one per rotation form and sweep direction, so that
-// they compile in parallel).  No device code here.
+// translation units that instantiate the kernels (one per sweep direction and number of slots per lane,
+// so that they compile in parallel).  No device code here.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -17,10 +17,9 @@ struct CarouselShape {
     int M, WAVES;
 };
 
-// What a sweep of one rotation form reads: its table, its renormalisation rows (scaled and lifted
-// forms) and the device flag that says which form is to run (nullptr: this launch always runs).
+// What a sweep reads: the table of the rotation form the device flag selects, the renormalisation rows
+// (scaled and lifted forms) and that flag (nullptr: standard form).
 struct CarouselCoefs {
-    int form; // kFormStandard, kFormScaled or kFormLifted
     const float2 *table;
     const float2 *renorm;
     const unsigned *flag;
@@ -93,7 +92,7 @@ struct CarouselBwdArgs {
     float *dX, *partial;
     const float *zeros; // N floats that are always zero
     float *sink;        // N + 8192 floats that idle lanes write to and nobody reads
-    int vec_ok, accumulate;
+    int vec_ok;
     int g_identity; // G is I_n (generated on chip, the pointer is not read)
     hipStream_t stream;
 };
@@ -104,14 +103,13 @@ constexpr int kColumnFamilyMaxN = 128;
 int column_forward(int n, int rows, long long B, const float2 *table, const float *X, float *Y, int identity,
                    int mirror, hipStream_t stream);
 
-// Defined in carousel_fwd_<form>.hip / carousel_bwd_<form>.hip: launch the kernel of that form for
-// shape s and W columns per lane; GIVENS_ERR_UNSUPPORTED for a combination that is not compiled.
-int carousel_forward_standard(const CarouselFwdArgs &a, CarouselShape s, int W);
-int carousel_forward_scaled(const CarouselFwdArgs &a, CarouselShape s, int W);
-int carousel_forward_lifted(const CarouselFwdArgs &a, CarouselShape s, int W);
-int carousel_backward_standard(const CarouselBwdArgs &a, CarouselShape s, int W);
-int carousel_backward_scaled(const CarouselBwdArgs &a, CarouselShape s, int W);
-int carousel_backward_lifted(const CarouselBwdArgs &a, CarouselShape s, int W);
+// Defined in carousel_fwd_m<M>.hip / carousel_bwd_m<M>.hip: launch the kernel with M slots per lane, `waves`
+// wavefronts per workgroup and W columns per lane; GIVENS_ERR_UNSUPPORTED for a combination that is not compiled.
+int carousel_forward_m8(const CarouselFwdArgs &a, int waves, int W);
+int carousel_forward_m4(const CarouselFwdArgs &a, int waves, int W);
+int carousel_forward_m2(const CarouselFwdArgs &a, int waves, int W);
+int carousel_backward_m4(const CarouselBwdArgs &a, int waves, int W);
+int carousel_backward_m2(const CarouselBwdArgs &a, int waves, int W);
 
 inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
                             int identity, int mirror, hipStream_t stream)
@@ -122,21 +120,12 @@ inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &c
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
     const CarouselFwdArgs a{n, rows, B, coefs, X, Y, identity, aligned ? 1 : 0, mirror, stream};
-    switch (coefs.form) {
-    case kFormScaled: return carousel_forward_scaled(a, s, W);
-    case kFormLifted: return carousel_forward_lifted(a, s, W);
-    default: return carousel_forward_standard(a, s, W);
+    switch (s.M) {
+    case 8: return carousel_forward_m8(a, s.WAVES, W);
+    case 4: return carousel_forward_m4(a, s.WAVES, W);
+    case 2: return carousel_forward_m2(a, s.WAVES, W);
+    default: return GIVENS_ERR_UNSUPPORTED;
     }
-}
-
-// lanes per workgroup and slots per lane of the reverse sweep (the layout of the accumulation buffer)
-inline bool carousel_bwd_layout(int n, int *lanes, int *slots)
-{
-    CarouselShape s;
-    if (!carousel_bwd_shape_for(n, &s)) return false;
-    *lanes = n / (2 * s.M);
-    *slots = s.M;
-    return true;
 }
 
 // Columns per workgroup of the reverse sweep.
@@ -158,25 +147,24 @@ inline long long carousel_bwd_groups(int n, long long nstrips, int compute_units
 }
 
 // Launches the reverse sweep on strips [strip0, strip0 + nstrips) with `groups` persistent workgroups.
-// accumulate = 0: partial is [groups][N]; workgroup g stores the sums of its first strip in row g and
-// adds those of its later strips to them.  accumulate = 1: partial is one zeroed [N] buffer in the
-// kernel's slot-major order that every strip adds into atomically.  zeros: N floats that stay zero.
+// partial is [groups][N]: workgroup g stores the sums of its first strip in row g and adds those of its later
+// strips to them.  zeros: N floats that stay zero.
 inline int carousel_backward_strips(int n, int rows, long long B, int W, long long strip0, long long nstrips,
                                     long long groups, const CarouselCoefs &coefs, const float *Y, const float *G,
-                                    float *dX, float *partial, const float *zeros, float *sink, int accumulate,
-                                    int g_identity, hipStream_t stream)
+                                    float *dX, float *partial, const float *zeros, float *sink, int g_identity,
+                                    hipStream_t stream)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (g_identity || reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
-    const CarouselBwdArgs a{n,  rows,    B,     strip0, nstrips,         groups,     coefs,      Y,     G,
-                            dX, partial, zeros, sink,   aligned ? 1 : 0, accumulate, g_identity, stream};
-    switch (coefs.form) {
-    case kFormScaled: return carousel_backward_scaled(a, s, W);
-    case kFormLifted: return carousel_backward_lifted(a, s, W);
-    default: return carousel_backward_standard(a, s, W);
+    const CarouselBwdArgs a{n,  rows,    B,     strip0, nstrips,         groups,     coefs, Y, G,
+                            dX, partial, zeros, sink,   aligned ? 1 : 0, g_identity, stream};
+    switch (s.M) {
+    case 4: return carousel_backward_m4(a, s.WAVES, W);
+    case 2: return carousel_backward_m2(a, s.WAVES, W);
+    default: return GIVENS_ERR_UNSUPPORTED;
     }
 }
 

@@ -338,13 +338,12 @@ __device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long 
 __device__ __forceinline__ int mirrored_row(int n, int r, int mirror) { return (mirror && r) ? n - r : r; }
 
 template <int M, int W, int WAVES, int FORM>
-__global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
-    int n, int rows, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
-    const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok, int mirror)
+__device__ __forceinline__ void carousel_forward_body(CarouselExchange<W, WAVES> &sh, int n, int rows, long long B,
+                                                      const float2 *__restrict__ table,
+                                                      const float2 *__restrict__ renorm, const float *X, float *Y,
+                                                      int identity, int vec_ok, int mirror)
 {
-    if (!form_selected(flag, FORM, scaled_max)) return;
     using State = CarouselFwd<M, W, WAVES, FORM>;
-    __shared__ CarouselExchange<W, WAVES> sh;
     State st;
     const int L = n / (2 * M);                  // lanes that hold slots; the rest of the last wavefront idles
     const bool idle = (int)threadIdx.x >= L;
@@ -394,6 +393,23 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
     }
 }
 
+// One launch per call: the rotation form is read from the device flag (nullptr: standard) and the
+// matching copy of the sweep runs; `table` holds that form's coefficients (coef_table_kernel).
+template <int M, int W, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
+    int n, int rows, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
+    const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok, int mirror)
+{
+    __shared__ CarouselExchange<W, WAVES> sh;
+    const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
+    if (form == kFormScaled)
+        carousel_forward_body<M, W, WAVES, kFormScaled>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok, mirror);
+    else if (form == kFormLifted)
+        carousel_forward_body<M, W, WAVES, kFormLifted>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok, mirror);
+    else
+        carousel_forward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok, mirror);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Reverse sweep (dtheta and dX from the forward output Y and the upstream gradient G).
 //
@@ -432,12 +448,8 @@ struct CarouselBwd {
     int lanes;               // L = n / (2 M): lanes that hold slots
     const float2 *tab_lane;  // table + tid*M
     const float2 *rn_lane;   // renormalisation factors + tid*M (scaled form)
-    float *part_lane;        // where this lane's sums go (see `accumulate`)
+    float *part_lane;        // this workgroup's row of partial sums + tid*M (idle lanes: the sink)
     const float *prior_lane; // what load_prior reads: this workgroup's row, or zeros for its first strip
-    int accumulate;          // 0: part_lane = this workgroup's row of partial sums + tid*M, plain stores
-                             // 1: part_lane = shared accumulation buffer + tid, atomic adds; the buffer
-                             //    is slot-major within a block, [k][r][lane], so that one atomic
-                             //    instruction of a wavefront covers 64 consecutive floats
     // this lane's LDS addresses for strip z in exchange buffer 0 (strip g and buffer 1 are at
     // compile-time offsets)
     float *out_top, *out_bot, *hold;
@@ -465,8 +477,8 @@ struct CarouselBwd {
     }
 
     // The partial sums already stored for block k by this workgroup's earlier strips.  For its first
-    // strip (and in the accumulating mode) prior_lane points into a row of zeros instead: a branch
-    // here would sit in every block and split the scheduler's region, which costs more than the loads.
+    // strip prior_lane points into a row of zeros instead: a branch here would sit in every block and
+    // split the scheduler's region, which costs more than the loads.
     __device__ __forceinline__ void load_prior(int k, float (&dst)[M])
     {
         const float *src = prior_lane + (long long)k * H;
@@ -603,11 +615,7 @@ struct CarouselBwd {
             publish<U, 1>(gt, gb);
         }
         if constexpr (kInner > 0) sweep_inner<U, RN, 1>(cur, rn, sums, std::make_integer_sequence<int, kInner>{});
-        if (accumulate) {
-            float *dst = part_lane + (long long)k * H;   // H = M * lanes
-#pragma unroll
-            for (int r = 0; r < M; ++r) unsafeAtomicAdd(dst + r * lanes, sums[r]);
-        } else {
+        {
             float *dst = part_lane + (long long)k * H;
 #pragma unroll
             for (int r = 0; r < M; ++r) sums[r] += earlier[r];
@@ -666,15 +674,15 @@ struct CarouselBwd {
 };
 
 template <int M, int W, int WAVES, int FORM>
-__global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
-    int n, int rows, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
-    const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
-    float *dX, float *partial, const float *__restrict__ zeros, float *sink, int vec_ok, int accumulate,
-    int g_identity)
+__device__ __forceinline__ void carousel_backward_body(CarouselExchangeBwd<W, WAVES> &sh, int n, int rows, long long B,
+                                                       long long strip0, long long nstrips,
+                                                       const float2 *__restrict__ table,
+                                                       const float2 *__restrict__ renorm, const float *Yin,
+                                                       const float *G, float *dX, float *partial,
+                                                       const float *__restrict__ zeros, float *sink, int vec_ok,
+                                                       int g_identity)
 {
-    if (!form_selected(flag, FORM, scaled_max)) return;
     using State = CarouselBwd<M, W, WAVES, FORM>;
-    __shared__ CarouselExchangeBwd<W, WAVES> sh;
     State st;
     const int L = n / (2 * M);                  // lanes that hold slots; the rest of the last wavefront idles
     const bool idle = (int)threadIdx.x >= L;
@@ -688,12 +696,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     st.lane = threadIdx.x & 63;
     st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     st.tab_lane = table + (long long)coef_lane * M;
-    st.accumulate = accumulate;
     // an idle lane's sums (all zero) go to the sink: N + 8192 floats nobody reads
     st.part_lane = idle ? sink + (long long)threadIdx.x * M
-                        : (accumulate ? partial + threadIdx.x
-                                      : partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) +
-                                            (long long)threadIdx.x * M);
+                        : partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) +
+                              (long long)threadIdx.x * M;
     {
         constexpr int LMAX = 64 * WAVES;
         auto &z = sh.buf[0].strip[0];
@@ -711,7 +717,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     // order, so the result does not depend on scheduling.
     for (long long s = blockIdx.x; s < nstrips; s += gridDim.x) {
         const bool first_strip = (s == (long long)blockIdx.x);
-        st.prior_lane = (accumulate || first_strip) ? zeros + (long long)coef_lane * M : st.part_lane;
+        st.prior_lane = first_strip ? zeros + (long long)coef_lane * M : st.part_lane;
         const long long b0 = (strip0 + s) * W;
         const int wv = (B - b0) < W ? (int)(B - b0) : W;
         const bool vec = vec_ok && wv == W;
@@ -742,79 +748,100 @@ __global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
     }
 }
 
+template <int M, int W, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
+    int n, int rows, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
+    const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
+    float *dX, float *partial, const float *__restrict__ zeros, float *sink, int vec_ok, int g_identity)
+{
+    __shared__ CarouselExchangeBwd<W, WAVES> sh;
+    const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
+    if (form == kFormScaled)
+        carousel_backward_body<M, W, WAVES, kFormScaled>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G, dX,
+                                                         partial, zeros, sink, vec_ok, g_identity);
+    else if (form == kFormLifted)
+        carousel_backward_body<M, W, WAVES, kFormLifted>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G, dX,
+                                                         partial, zeros, sink, vec_ok, g_identity);
+    else
+        carousel_backward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G, dX,
+                                                           partial, zeros, sink, vec_ok, g_identity);
+}
+
 // ---------------------------------------------------------------------------------------------
-// launches (instantiated per rotation form by carousel_fwd_*.hip / carousel_bwd_*.hip)
+// launches (instantiated per number of slots per lane by carousel_fwd_m*.hip / carousel_bwd_m*.hip)
 // ---------------------------------------------------------------------------------------------
-template <int M, int W, int WAVES, int FORM>
+template <int M, int W, int WAVES>
 inline void carousel_launch_fwd(const CarouselFwdArgs &a)
 {
     const long long strips = (a.B + W - 1) / W;
-    hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES, FORM>), dim3((unsigned)strips), dim3(64 * WAVES), 0,
+    hipLaunchKernelGGL((carousel_forward_kernel<M, W, WAVES>), dim3((unsigned)strips), dim3(64 * WAVES), 0,
                        a.stream, a.n, a.rows, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.coefs.scaled_max,
                        a.X, a.Y, a.identity, a.vec_ok, a.mirror);
 }
 
-template <int M, int WAVES, int FORM>
+template <int M, int WAVES>
 inline int carousel_fwd_widths(int W, const CarouselFwdArgs &a)
 {
     switch (W) {
-    case 8: carousel_launch_fwd<M, 8, WAVES, FORM>(a); return GIVENS_OK;
-    case 4: carousel_launch_fwd<M, 4, WAVES, FORM>(a); return GIVENS_OK;
-    case 2: carousel_launch_fwd<M, 2, WAVES, FORM>(a); return GIVENS_OK;
-    case 1: carousel_launch_fwd<M, 1, WAVES, FORM>(a); return GIVENS_OK;
+    case 8: carousel_launch_fwd<M, 8, WAVES>(a); return GIVENS_OK;
+    case 4: carousel_launch_fwd<M, 4, WAVES>(a); return GIVENS_OK;
+    case 2: carousel_launch_fwd<M, 2, WAVES>(a); return GIVENS_OK;
+    case 1: carousel_launch_fwd<M, 1, WAVES>(a); return GIVENS_OK;
     default: return GIVENS_ERR_UNSUPPORTED;
     }
 }
 
-template <int FORM>
-inline int carousel_forward_form(const CarouselFwdArgs &a, CarouselShape s, int W)
+// every number of wavefronts carousel_shape_for can return for M slots per lane
+template <int M>
+inline int carousel_forward_slots(const CarouselFwdArgs &a, int waves, int W)
 {
-    // every (M, WAVES) that carousel_shape_for can return: 1..8 wavefronts for each of M = 8, 4, 2
-#define GIVENS_FWD_SHAPE(m, wv) \
-    if (s.M == m && s.WAVES == wv) return carousel_fwd_widths<m, wv, FORM>(W, a);
-#define GIVENS_FWD_SLOTS(m)                                                                             \
-    GIVENS_FWD_SHAPE(m, 1) GIVENS_FWD_SHAPE(m, 2) GIVENS_FWD_SHAPE(m, 3) GIVENS_FWD_SHAPE(m, 4)         \
-    GIVENS_FWD_SHAPE(m, 5) GIVENS_FWD_SHAPE(m, 6) GIVENS_FWD_SHAPE(m, 7) GIVENS_FWD_SHAPE(m, 8)
-    GIVENS_FWD_SLOTS(8) GIVENS_FWD_SLOTS(4) GIVENS_FWD_SLOTS(2)
-#undef GIVENS_FWD_SLOTS
-#undef GIVENS_FWD_SHAPE
-    return GIVENS_ERR_UNSUPPORTED;
+    switch (waves) {
+    case 1: return carousel_fwd_widths<M, 1>(W, a);
+    case 2: return carousel_fwd_widths<M, 2>(W, a);
+    case 3: return carousel_fwd_widths<M, 3>(W, a);
+    case 4: return carousel_fwd_widths<M, 4>(W, a);
+    case 5: return carousel_fwd_widths<M, 5>(W, a);
+    case 6: return carousel_fwd_widths<M, 6>(W, a);
+    case 7: return carousel_fwd_widths<M, 7>(W, a);
+    case 8: return carousel_fwd_widths<M, 8>(W, a);
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
 }
 
-template <int M, int W, int WAVES, int FORM>
+template <int M, int W, int WAVES>
 inline void carousel_launch_bwd(const CarouselBwdArgs &a)
 {
-    hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES, FORM>), dim3((unsigned)a.groups), dim3(64 * WAVES),
-                       0, a.stream, a.n, a.rows, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
-                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.sink, a.vec_ok,
-                       a.accumulate, a.g_identity);
+    hipLaunchKernelGGL((carousel_backward_kernel<M, W, WAVES>), dim3((unsigned)a.groups), dim3(64 * WAVES), 0,
+                       a.stream, a.n, a.rows, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
+                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.sink, a.vec_ok, a.g_identity);
 }
 
-template <int M, int WAVES, int FORM>
+template <int M, int WAVES>
 inline int carousel_bwd_widths(int W, const CarouselBwdArgs &a)
 {
     switch (W) {
-    case 8: carousel_launch_bwd<M, 8, WAVES, FORM>(a); return GIVENS_OK;
-    case 4: carousel_launch_bwd<M, 4, WAVES, FORM>(a); return GIVENS_OK;
-    case 2: carousel_launch_bwd<M, 2, WAVES, FORM>(a); return GIVENS_OK;
-    case 1: carousel_launch_bwd<M, 1, WAVES, FORM>(a); return GIVENS_OK;
+    case 8: carousel_launch_bwd<M, 8, WAVES>(a); return GIVENS_OK;
+    case 4: carousel_launch_bwd<M, 4, WAVES>(a); return GIVENS_OK;
+    case 2: carousel_launch_bwd<M, 2, WAVES>(a); return GIVENS_OK;
+    case 1: carousel_launch_bwd<M, 1, WAVES>(a); return GIVENS_OK;
     default: return GIVENS_ERR_UNSUPPORTED;
     }
 }
 
-template <int FORM>
-inline int carousel_backward_form(const CarouselBwdArgs &a, CarouselShape s, int W)
+template <int M>
+inline int carousel_backward_slots(const CarouselBwdArgs &a, int waves, int W)
 {
-    // every (M, WAVES) that carousel_bwd_shape_for can return: 1..8 wavefronts for each of M = 4, 2
-#define GIVENS_BWD_SHAPE(m, wv) \
-    if (s.M == m && s.WAVES == wv) return carousel_bwd_widths<m, wv, FORM>(W, a);
-#define GIVENS_BWD_SLOTS(m)                                                                             \
-    GIVENS_BWD_SHAPE(m, 1) GIVENS_BWD_SHAPE(m, 2) GIVENS_BWD_SHAPE(m, 3) GIVENS_BWD_SHAPE(m, 4)         \
-    GIVENS_BWD_SHAPE(m, 5) GIVENS_BWD_SHAPE(m, 6) GIVENS_BWD_SHAPE(m, 7) GIVENS_BWD_SHAPE(m, 8)
-    GIVENS_BWD_SLOTS(4) GIVENS_BWD_SLOTS(2)
-#undef GIVENS_BWD_SLOTS
-#undef GIVENS_BWD_SHAPE
-    return GIVENS_ERR_UNSUPPORTED;
+    switch (waves) {
+    case 1: return carousel_bwd_widths<M, 1>(W, a);
+    case 2: return carousel_bwd_widths<M, 2>(W, a);
+    case 3: return carousel_bwd_widths<M, 3>(W, a);
+    case 4: return carousel_bwd_widths<M, 4>(W, a);
+    case 5: return carousel_bwd_widths<M, 5>(W, a);
+    case 6: return carousel_bwd_widths<M, 6>(W, a);
+    case 7: return carousel_bwd_widths<M, 7>(W, a);
+    case 8: return carousel_bwd_widths<M, 8>(W, a);
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
 }
 
 } // namespace givens

@@ -44,12 +44,15 @@ template <typename T> struct Pair2;
 template <> struct Pair2<float> { using type = float2; };
 template <> struct Pair2<double> { using type = double2; };
 
-__global__ void reset_flag_kernel(unsigned *flag) { *flag = 0u; }
-
 // flag <- bit pattern of max |theta| (non-negative floats order like unsigned integers; NaN sorts last).
 // theta is read as float4 where alignment allows; N is tiny next to the sweeps but this kernel sits
-// in front of every call, so it should run at memory speed.
-__global__ void theta_range_kernel(long long N, const float *__restrict__ theta, unsigned *flag)
+// in front of every call, so it should run at memory speed.  No atomics on the result and no separate
+// reset: every workgroup leaves its maximum in `slots`, takes a ticket from `counter`, and the workgroup
+// that draws the last ticket combines the slots, writes the flag and puts the counter back to zero (the
+// counter is zero when the buffer is allocated, so it is zero before every launch).
+constexpr int kRangeBlocks = 512;
+__global__ __launch_bounds__(512) void theta_range_kernel(long long N, const float *__restrict__ theta,
+                                                          unsigned *slots, unsigned *counter, unsigned *flag)
 {
     unsigned m = 0u;
     const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -72,16 +75,39 @@ __global__ void theta_range_kernel(long long N, const float *__restrict__ theta,
         const unsigned other = (unsigned)__shfl_xor((int)m, off, 64);
         m = other > m ? other : m;
     }
-    // Atomics on one word serialise (some 10 ns each: thousands of them cost more than reading theta),
-    // so the wavefronts of a workgroup combine through LDS first and send one atomic per workgroup.
     __shared__ unsigned wave_max[16];
+    __shared__ unsigned ticket;
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) wave_max[wave] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
         const int waves = (blockDim.x + 63) >> 6;
         for (int w = 1; w < waves; ++w) m = wave_max[w] > m ? wave_max[w] : m;
-        atomicMax(flag, m);
+        __hip_atomic_store(&slots[blockIdx.x], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();                                  // the slot is visible before the ticket is drawn
+        ticket = atomicAdd(counter, 1u);
+    }
+    __syncthreads();
+    if (ticket != gridDim.x - 1) return;                  // uniform per workgroup
+    __threadfence();
+    // last workgroup: every other workgroup's slot was written before its ticket was drawn
+    unsigned best = 0u;
+    for (unsigned i = threadIdx.x; i < gridDim.x; i += blockDim.x) {
+        const unsigned v = __hip_atomic_load(&slots[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        best = v > best ? v : best;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned other = (unsigned)__shfl_xor((int)best, off, 64);
+        best = other > best ? other : best;
+    }
+    __syncthreads();                                      // wave_max is reused
+    if ((threadIdx.x & 63) == 0) wave_max[wave] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int waves = (blockDim.x + 63) >> 6;
+        for (int w = 1; w < waves; ++w) best = wave_max[w] > best ? wave_max[w] : best;
+        *flag = best;
+        *counter = 0u;
     }
 }
 
@@ -154,40 +180,19 @@ __device__ __forceinline__ T theta_at(const T *__restrict__ theta, const int *__
     return c < 0 ? T(0) : sign * theta[c];
 }
 
-// Standard form table, in E order.  `factor` (optional) receives the orientation sign (+1 when the
-// top position holds the smaller label) that the dtheta reduction multiplies its sums by.
-template <typename T>
-__global__ void coef_table_kernel(int n, const T *__restrict__ theta, const int *__restrict__ map, int mirror,
-                                  const unsigned *flag, float scaled_max,
-                                  typename Pair2<T>::type *__restrict__ table, T *__restrict__ factor)
-{
-    if (!form_selected(flag, kFormStandard, scaled_max)) return;
-    const int H = n >> 1;
-    const long long N = (long long)(n - 1) * H;
-    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < N;
-         e += (long long)gridDim.x * blockDim.x) {
-        const int k = (int)(e / H), p = (int)(e % H);
-        const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-        double s, c;
-        sincos((double)theta_at(theta, map, mirror, n, e), &s, &c);
-        if (a > b) s = -s;
-        typename Pair2<T>::type out;
-        out.x = (T)c;
-        out.y = (T)s;
-        table[e] = out;
-        if (factor) factor[e] = (a < b) ? T(1) : T(-1);
-    }
-}
-
 // Scaled and lifted forms, step 1.  One thread per (renormalisation period g, row r): walks the row
 // through the period's blocks in sweep order (FWD: k = n-2, n-3, ...; reverse sweep: k = 0, 1, ...),
 // records the row's factor d *before* each block at D[k][position], and leaves the factor after the
 // period's last block in renorm[g][arc] (.x for the arc's top position, .y for its bottom position).
 // A rotation multiplies the factor of both its rows by cos(theta) (scaled form) or by the sign
-// (-1)^m of theta = theta' + m*pi (lifted form).
+// (-1)^m of theta = theta' + m*pi (lifted form).  The product is carried in float64; D keeps it rounded
+// to float32 (a relative 6e-8 on a coefficient that is itself rounded to float32 afterwards).  The
+// angles of kScanAhead blocks are fetched before the dependent chain of multiplications starts, so the
+// thread waits for memory once per kScanAhead blocks instead of once per block.
+constexpr int kScanAhead = 16;
 template <bool FWD>
 __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const int *__restrict__ map,
-                                   int mirror, const unsigned *flag, float scaled_max, double *__restrict__ D,
+                                   int mirror, const unsigned *flag, float scaled_max, float *__restrict__ D,
                                    float *__restrict__ renorm)
 {
     const int form = selected_form(flag, scaled_max);
@@ -201,61 +206,171 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
     const int t1 = (t0 + kRenormPeriod < n - 1) ? t0 + kRenormPeriod : n - 1;
     double d = 1.0;
     int q = 0, p = 0;
-    for (int t = t0; t < t1; ++t) {
-        const int k = FWD ? n - 2 - t : t;
-        q = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1); // position of label r in the sequence of block k
-        p = (q < H) ? q : n - 1 - q;
-        D[(long long)k * n + q] = d;
-        const double th = (double)theta_at(theta, map, mirror, n, (long long)k * H + p);
-        if (form == kFormScaled) {
-            d *= cos_small(th);
-        } else {
-            bool odd;
-            (void)lift_reduce(th, &odd);
-            d = odd ? -d : d;
+    for (int tb = t0; tb < t1; tb += kScanAhead) {
+        float th[kScanAhead];
+#pragma unroll
+        for (int u = 0; u < kScanAhead; ++u) {
+            const int t = tb + u < t1 ? tb + u : t1 - 1;
+            const int k = FWD ? n - 2 - t : t;
+            const int qq = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1); // position of label r in the sequence of block k
+            const int pp = (qq < H) ? qq : n - 1 - qq;
+            th[u] = theta_at(theta, map, mirror, n, (long long)k * H + pp);
+        }
+#pragma unroll
+        for (int u = 0; u < kScanAhead; ++u) {
+            const int t = tb + u;
+            if (t < t1) {
+                const int k = FWD ? n - 2 - t : t;
+                q = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1);
+                p = (q < H) ? q : n - 1 - q;
+                D[(long long)k * n + q] = (float)d;
+                if (form == kFormScaled) {
+                    d *= cos_small((double)th[u]);
+                } else {
+                    bool odd;
+                    (void)lift_reduce((double)th[u], &odd);
+                    d = odd ? -d : d;
+                }
+            }
         }
     }
     renorm[2 * ((long long)g * H + p) + (q < H ? 0 : 1)] = (float)d;
 }
 
-// Scaled form, step 2: (alpha, beta) per (block, arc) in E order.  The same magnitudes serve both
-// sweeps; the sweeps apply the signs (forward: a - alpha b, b + beta a; reverse: a + alpha b, b - beta a),
-// but the factors d differ between the two directions, hence FWD.  For the reverse sweep `factor`
-// receives orientation sign * d_top * d_bot: the sweep sums stored values, and
-// gbar_j z_i - gbar_i z_j = d_i d_j (g~_j z~_i - g~_i z~_j).
-// Lifted form: (T, S) = (tan(theta'/2), sin(theta')) * orientation * d_top * d_bot (the factors are
-// +-1 here): the forward sweep does a -= T b, b += S a, a -= T b on the stored values, the reverse
-// sweep the same with the signs flipped.
-template <bool FWD>
-__global__ void scaled_table_kernel(int n, const float *__restrict__ theta, const int *__restrict__ map,
-                                    int mirror, const unsigned *flag, float scaled_max, const double *__restrict__ D,
-                                    float2 *__restrict__ table, float *__restrict__ factor)
+// Step 2, and the only step of the standard form: the table of one sweep direction in E order, in the form
+// the flag selects (flag == nullptr: standard).
+//   standard: (cos, sin) with the orientation folded into the sine; `factor` (reverse sweep only) receives the
+//     orientation sign (+1 when the top position holds the smaller label) that the dtheta reduction
+//     multiplies its sums by.
+//   scaled: (alpha, beta).  The same magnitudes serve both sweeps; the sweeps apply the signs (forward:
+//     a - alpha b, b + beta a; reverse: a + alpha b, b - beta a), but the factors d differ between the two
+//     directions, hence one scan per direction.  factor = orientation sign * d_top * d_bot: the sweep sums
+//     stored values, and gbar_j z_i - gbar_i z_j = d_i d_j (g~_j z~_i - g~_i z~_j).
+//   lifted: (T, S) = (tan(theta'/2), sin(theta')) * orientation * d_top * d_bot (the factors are +-1 here):
+//     the forward sweep does a -= T b, b += S a, a -= T b on the stored values, the reverse sweep the same
+//     with the signs flipped.
+template <typename T>
+__global__ void coef_table_kernel(int n, const T *__restrict__ theta, const int *__restrict__ map, int mirror,
+                                  const unsigned *flag, float scaled_max, const float *__restrict__ D,
+                                  typename Pair2<T>::type *__restrict__ table, T *__restrict__ factor)
 {
     const int form = selected_form(flag, scaled_max);
-    if (form == kFormStandard) return;
     const int H = n >> 1;
     const long long N = (long long)(n - 1) * H;
-    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= N) return;
-    const int k = (int)(e / H), p = (int)(e % H);
-    const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-    const double th = (double)theta_at(theta, map, mirror, n, e);
-    const double da = D[(long long)k * n + p], db = D[(long long)k * n + (n - 1 - p)]; // before this block
-    const double orient = (a < b) ? 1.0 : -1.0;
-    if (form == kFormScaled) {
-        const double s = orient * sin_small(th);
-        const double c = cos_small(th);
-        const double inv = s / (c * da * db);            // tan(theta) / (d_top d_bot)
-        table[e] = make_float2((float)(inv * db * db), (float)(inv * da * da));
-    } else {
-        bool odd;
-        const double red = lift_reduce(th, &odd);
-        double s, c;
-        sincos(red, &s, &c);
-        const double sg = orient * da * db;
-        table[e] = make_float2((float)(sg * s / (1.0 + c)), (float)(sg * s)); // tan(x/2) = sin x / (1 + cos x)
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < N;
+         e += (long long)gridDim.x * blockDim.x) {
+        const int k = (int)(e / H), p = (int)(e % H);
+        const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+        const double th = (double)theta_at(theta, map, mirror, n, e);
+        const double orient = (a < b) ? 1.0 : -1.0;
+        typename Pair2<T>::type out;
+        double fac = orient;
+        if (form == kFormStandard) {
+            double s, c;
+            sincos(th, &s, &c);
+            out.x = (T)c;
+            out.y = (T)(orient * s);
+        } else {
+            const double da = (double)D[(long long)k * n + p], db = (double)D[(long long)k * n + (n - 1 - p)]; // before this block
+            fac = orient * da * db;
+            if (form == kFormScaled) {
+                const double s = orient * sin_small(th);
+                const double c = cos_small(th);
+                const double inv = s / (c * da * db);        // tan(theta) / (d_top d_bot)
+                out.x = (T)(inv * db * db);
+                out.y = (T)(inv * da * da);
+            } else {
+                bool odd;
+                const double red = lift_reduce(th, &odd);
+                double s, c;
+                sincos(red, &s, &c);
+                out.x = (T)(fac * s / (1.0 + c));            // tan(x/2) = sin x / (1 + cos x)
+                out.y = (T)(fac * s);
+            }
+        }
+        table[e] = out;
+        if (factor) factor[e] = (T)fac;
     }
-    if (!FWD && factor) factor[e] = (float)(orient * da * db);
+}
+
+// ---- index map of a restricted parametrisation / odd n (Section 5; end of Section 3), built on the device.
+// map[e] = index in theta of entry e of the full sequence E when its pair (i, j) is free (i < m and
+// j < rows), else -1.  Three small kernels on the caller's stream: free pairs per block, exclusive scan
+// over the blocks, then the positions inside each block.
+__device__ __forceinline__ bool pair_is_free(int n, int rows, int m, int k, int p)
+{
+    const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+    const int i = a < b ? a : b, j = a < b ? b : a;
+    return j < rows && i < m;
+}
+constexpr int kMapThreads = 256;
+__global__ __launch_bounds__(kMapThreads) void map_count_kernel(int n, int rows, int m, int *__restrict__ counts)
+{
+    const int k = blockIdx.x, H = n >> 1;
+    int c = 0;
+    for (int p = threadIdx.x; p < H; p += kMapThreads) c += pair_is_free(n, rows, m, k, p) ? 1 : 0;
+    for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
+    __shared__ int part[kMapThreads / 64];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+        for (int w = 0; w < kMapThreads / 64; ++w) t += part[w];
+        counts[k] = t;
+    }
+}
+// exclusive scan of counts[0 .. blocks) in place, one workgroup (blocks is at most a few ten thousand)
+__global__ __launch_bounds__(kMapThreads) void map_scan_kernel(int blocks, int *__restrict__ counts)
+{
+    __shared__ int buf[kMapThreads];
+    __shared__ int carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < blocks; base += kMapThreads) {
+        const int i = base + threadIdx.x;
+        const int v = i < blocks ? counts[i] : 0;
+        buf[threadIdx.x] = v;
+        __syncthreads();
+        for (int off = 1; off < kMapThreads; off <<= 1) {  // inclusive scan of the chunk
+            const int add = threadIdx.x >= off ? buf[threadIdx.x - off] : 0;
+            __syncthreads();
+            buf[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int incl = buf[threadIdx.x], before = carry;
+        if (i < blocks) counts[i] = before + incl - v;
+        __syncthreads();
+        if (threadIdx.x == kMapThreads - 1) carry = before + incl;
+        __syncthreads();
+    }
+}
+__global__ __launch_bounds__(kMapThreads) void map_fill_kernel(int n, int rows, int m, const int *__restrict__ offsets,
+                                                               int *__restrict__ map)
+{
+    const int k = blockIdx.x, H = n >> 1;
+    __shared__ int wave_count[kMapThreads / 64];
+    __shared__ int carry;
+    if (threadIdx.x == 0) carry = offsets[k];
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int base = 0; base < H; base += kMapThreads) {
+        const int p = base + threadIdx.x;
+        const bool is_free = p < H && pair_is_free(n, rows, m, k, p);
+        const unsigned long long votes = __ballot(is_free);
+        const int before_in_wave = __popcll(votes & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_count[wave] = __popcll(votes);
+        __syncthreads();
+        int before = carry;
+        for (int w = 0; w < wave; ++w) before += wave_count[w];
+        if (p < H) map[(long long)k * H + p] = is_free ? before + before_in_wave : -1;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int t = carry;
+            for (int w = 0; w < kMapThreads / 64; ++w) t += wave_count[w];
+            carry = t;
+        }
+        __syncthreads();
+    }
 }
 
 // Second stage of the gradient reduction: dtheta[e] (+)= factor[e] * sum over strips s of

@@ -1,17 +1,19 @@
 // C ABI of the round-robin Givens library (see include/givens_rr.h for the contract).
-// Host side: argument checks, workspace, kernel selection, launches, optional event timing.
-#include <dlfcn.h>
+// Host side: argument checks, workspaces, kernel selection, launches, optional event timing.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdint>
+#include <memory>
 #include <mutex>
+#include <new>
 #include <type_traits>
 #include <vector>
 
 #include "../../include/givens_rr.h"
 #include "carousel_host.hpp"
 #include "coef_kernels.hpp"
+#include "gram_kernels.hpp"
 #include "lds_kernels.hpp"
 #include "rr_index.h"
 #include "unitary_kernels.hpp"
@@ -20,30 +22,54 @@ namespace givens {
 namespace {
 
 constexpr int kMaxDevices = 64;
+constexpr int kMaxWorkspacesPerDevice = 8;                     // streams with a workspace of their own, per device
 constexpr size_t kLdsBudgetBytes = 144 * 1024;                 // of the 160 KB per CU on gfx950
 constexpr size_t kPartialCapBytes = size_t(24) << 30;          // cap on one chunk of strip partials
-constexpr bool kAutoReductionIsAtomic = false;                 // GIVENS_REDUCTION_AUTO never picks the atomic variant
+constexpr int kMaxRows = 36864;                                // largest n any kernel family takes (one float column in LDS)
+constexpr size_t kFlagBytes = 4096;                            // flag word, ticket counter, per-workgroup slots
 
 struct Buffer {
     void *ptr = nullptr;
     size_t bytes = 0;
 };
+
+// One sweep direction's coefficients.
+struct CoefSet {
+    Buffer table;   // N pairs in the rotation form the flag selects (standard: cos, sin)
+    Buffer renorm;  // scaled / lifted forms: periods * n/2 pairs
+    Buffer factor;  // reverse sweep: per-angle factor of the dtheta reduction
+};
+
+// What a prepared call needs to know about the tables givens_prepare left in a workspace.
+struct Prepared {
+    int64_t token = 0;       // 0: nothing prepared
+    int rows = 0, m = 0;
+    bool fwd = false, rev = false;
+    // whether each set was built with the device-side choice of the rotation form (float carousel kernels
+    // only can read such a set; a set built without it holds the standard form, which every family reads)
+    bool fwd_forms = false, rev_forms = false, mirrored_forms = false;
+    float scaled_max = 0.f;
+};
+
+// Everything the library allocates for the calls made on one stream of one device.  Calls on different
+// streams use different workspaces and may overlap; calls on one stream are ordered by the stream.
 struct Workspace {
-    Buffer table;        // standard-form cos/sin table, E order
-    Buffer table_scaled; // scaled-form (alpha, beta) table, E order
-    Buffer scale;        // scaled form: float64 row factors d, [n-1][n]
-    Buffer renorm;       // scaled form: renormalisation rows, float2 [periods][n/2]
-    Buffer factor;       // per-angle factor of the dtheta reduction
-    Buffer flag;         // device word: bit pattern of max |theta|
-    Buffer partial;      // per-strip dtheta partial sums (two-stage reduction)
-    Buffer acc;          // one accumulation buffer of N floats (accumulating reduction)
-    Buffer zeros;        // N floats that are zeroed when allocated and never written again
-    Buffer sink;         // N + 8192 floats: where idle lanes of the carousel reverse sweep put their sums
-    Buffer gram;         // Gram-matrix reduction: C = Y G^T, n x n floats
-    Buffer map;          // restricted parametrisation / odd n: index in theta of every entry of E, or -1
+    hipStream_t stream = nullptr;
+    uint64_t last_use = 0;
+    Buffer flag;        // [0] bit pattern of max |theta|, [1] ticket counter, [64 ...] per-workgroup maxima
+    Buffer scale;       // scaled / lifted forms: row factors d, float [n-1][n] (scratch of the coefficient kernels)
+    CoefSet fwd, rev;   // forward sweep, reverse sweep
+    CoefSet mirrored;   // forward-type sweep that computes dX = U^T G in the Gram form
+    Buffer partial;     // per-workgroup (carousel) or per-strip (LDS family) dtheta partial sums
+    Buffer zeros;       // N floats that are zeroed when allocated and never written again
+    Buffer sink;        // N + 8192 floats: where idle lanes of the carousel reverse sweep put their sums
+    Buffer gram;        // Gram form: slices of C = Y G^T, rows x rows floats each
+    Buffer map;         // restricted parametrisation / odd n: index in theta of every entry of E, or -1
+    Buffer map_counts;  // free pairs per block (scratch of the map kernels)
     int map_rows = 0, map_m = 0; // the (row count, m) the map was built for
-    Buffer *all[12] = {&table, &table_scaled, &scale, &renorm, &factor, &flag,
-                       &partial, &acc, &zeros, &sink, &gram, &map};
+    Prepared prepared;
+    Buffer *all[16] = {&flag, &scale, &fwd.table, &fwd.renorm, &fwd.factor, &rev.table, &rev.renorm, &rev.factor,
+                       &mirrored.table, &mirrored.renorm, &mirrored.factor, &partial, &zeros, &sink, &gram, &map};
 };
 
 // One call's problem: `rows` coordinates of which the first m may rotate with every other one
@@ -56,8 +82,16 @@ struct Problem {
     long long free_angles = 0;
 };
 
+// Per-call choices.  The plain entry points take the process-wide defaults (givens_set_*); the _ex entry points
+// take them from the caller.
+struct CallOptions {
+    int kernel = GIVENS_KERNEL_AUTO, form = GIVENS_FORM_AUTO, reduction = GIVENS_REDUCTION_AUTO;
+};
+
 std::mutex g_mutex;
-Workspace g_ws[kMaxDevices];
+std::vector<std::unique_ptr<Workspace>> g_ws[kMaxDevices];
+uint64_t g_use_clock = 0;
+int64_t g_next_token = 0;
 int g_kernel_choice = GIVENS_KERNEL_AUTO;
 int g_form_choice = GIVENS_FORM_AUTO;
 int g_reduction_choice = GIVENS_REDUCTION_AUTO;
@@ -71,7 +105,7 @@ struct ThreadState {
     int last_hip_error = 0;
     int last_kernel = 0;
     int last_reduction = 0;
-    const unsigned *last_flag = nullptr; // device flag of the last call when several forms were launched
+    const unsigned *last_flag = nullptr; // device flag of the last call when the form was chosen on the device
     float last_scaled_max = 0.f;         // that call's threshold for the scaled form
     hipStream_t last_stream = nullptr;
     bool timing_valid = false;
@@ -102,6 +136,49 @@ int grow(Buffer &b, size_t want)
     }
     GIVENS_HIP(hipMalloc(&b.ptr, want));
     b.bytes = want;
+    return GIVENS_OK;
+}
+
+int free_workspace(Workspace &ws)
+{
+    int rc = GIVENS_OK;
+    for (Buffer *b : ws.all) {
+        if (b->ptr && !hip_ok(hipFree(b->ptr))) rc = GIVENS_ERR_HIP;
+        *b = Buffer{};
+    }
+    if (ws.map_counts.ptr && !hip_ok(hipFree(ws.map_counts.ptr))) rc = GIVENS_ERR_HIP;
+    ws.map_counts = Buffer{};
+    ws.map_rows = ws.map_m = 0;
+    ws.prepared = Prepared{};
+    return rc;
+}
+
+// The workspace of (device, stream), created on first use.  When a device already has
+// kMaxWorkspacesPerDevice of them, the one used longest ago is given up first (after a device-wide
+// synchronisation: its stream may have work in flight that still reads it).
+int workspace_for(int dev, hipStream_t stream, Workspace **out)
+{
+    auto &list = g_ws[dev];
+    for (auto &w : list)
+        if (w->stream == stream) {
+            w->last_use = ++g_use_clock;
+            *out = w.get();
+            return GIVENS_OK;
+        }
+    if ((int)list.size() >= kMaxWorkspacesPerDevice) {
+        size_t victim = 0;
+        for (size_t i = 1; i < list.size(); ++i)
+            if (list[i]->last_use < list[victim]->last_use) victim = i;
+        GIVENS_HIP(hipDeviceSynchronize());
+        if (int rc = free_workspace(*list[victim])) return rc;
+        list.erase(list.begin() + (long)victim);
+    }
+    std::unique_ptr<Workspace> w(new (std::nothrow) Workspace);
+    if (!w) return GIVENS_ERR_UNSUPPORTED;
+    w->stream = stream;
+    w->last_use = ++g_use_clock;
+    *out = w.get();
+    list.push_back(std::move(w));
     return GIVENS_OK;
 }
 
@@ -157,7 +234,7 @@ long long count_free_angles(int rows, int m) { return (long long)m * rows - (lon
 
 int check_restricted(int rows, int m)
 {
-    if (rows < 2 || rows > (1 << 20)) return GIVENS_ERR_BAD_N;
+    if (rows < 2) return GIVENS_ERR_BAD_N;
     if (m < 1 || m > rows - 1) return GIVENS_ERR_BAD_M;
     return GIVENS_OK;
 }
@@ -178,31 +255,36 @@ void walk_pairs(int rows, int m, F &&visit)
         }
 }
 
-// Fills in the padded size and, when some pair of E is bypassed, the device map (built on the host
-// once per (rows, m) and kept in the workspace).
-int resolve_problem(int dev, int rows, int m, Problem *out)
+// Fills in the padded size and, when some pair of E is bypassed, the device map: built by three small
+// kernels on the caller's stream the first time this workspace sees (rows, m), and again when another
+// (rows, m) has used the buffer in between (the stream orders the rebuild after the previous reader).
+int resolve_problem(Workspace *ws, int rows, int m, hipStream_t stream, Problem *out)
 {
     if (int rc = check_restricted(rows, m)) return rc;
+    if (rows > kMaxRows) return GIVENS_ERR_UNSUPPORTED;      // before anything is allocated
     out->rows = rows;
     out->m = m;
     out->n = rows + (rows & 1);
     out->free_angles = count_free_angles(rows, m);
     out->map = nullptr;
     if (!(rows & 1) && m == rows - 1) return GIVENS_OK;
-    Workspace &ws = g_ws[dev];
-    if (!(ws.map.ptr && ws.map_rows == rows && ws.map_m == m)) {
-        const long long N = (long long)(out->n - 1) * (out->n / 2);
-        std::vector<int> host((size_t)N);
-        long long next = 0;
-        walk_pairs(rows, m, [&](long long e, int, int, bool is_free) { host[(size_t)e] = is_free ? (int)next++ : -1; });
-        if (next != out->free_angles) return GIVENS_ERR_UNSUPPORTED;
-        ws.map_rows = 0;
-        if (int rc = grow(ws.map, (size_t)N * sizeof(int))) return rc;
-        GIVENS_HIP(hipMemcpy(ws.map.ptr, host.data(), (size_t)N * sizeof(int), hipMemcpyHostToDevice));
-        ws.map_rows = rows;
-        ws.map_m = m;
+    if (!ws) return GIVENS_ERR_UNSUPPORTED;
+    if (!(ws->map.ptr && ws->map_rows == rows && ws->map_m == m)) {
+        const int n = out->n;
+        const long long N = (long long)(n - 1) * (n / 2);
+        ws->map_rows = 0;
+        if (int rc = grow(ws->map, (size_t)N * sizeof(int))) return rc;
+        if (int rc = grow(ws->map_counts, (size_t)n * sizeof(int))) return rc;
+        int *map = reinterpret_cast<int *>(ws->map.ptr);
+        int *counts = reinterpret_cast<int *>(ws->map_counts.ptr);
+        hipLaunchKernelGGL(map_count_kernel, dim3(n - 1), dim3(kMapThreads), 0, stream, n, rows, m, counts);
+        hipLaunchKernelGGL(map_scan_kernel, dim3(1), dim3(kMapThreads), 0, stream, n - 1, counts);
+        hipLaunchKernelGGL(map_fill_kernel, dim3(n - 1), dim3(kMapThreads), 0, stream, n, rows, m, counts, map);
+        GIVENS_HIP(hipGetLastError());
+        ws->map_rows = rows;
+        ws->map_m = m;
     }
-    out->map = reinterpret_cast<const int *>(ws.map.ptr);
+    out->map = reinterpret_cast<const int *>(ws->map.ptr);
     return GIVENS_OK;
 }
 
@@ -221,62 +303,65 @@ int lds_strip_width(int n, long long B, int strips_in_lds)
 // Everything the sweeps of one call read that depends on theta only.
 template <typename T>
 struct Coefs {
-    const typename Pair2<T>::type *table = nullptr; // standard form
+    const typename Pair2<T>::type *table = nullptr; // in the form the flag selects
     const T *factor = nullptr;                      // reverse sweep only
-    CarouselCoefs standard{kFormStandard, nullptr, nullptr, nullptr, 0.f};
-    CarouselCoefs scaled{kFormScaled, nullptr, nullptr, nullptr, 0.f};
-    CarouselCoefs lifted{kFormLifted, nullptr, nullptr, nullptr, 0.f};
-    bool all_forms = false;                         // scaled- and lifted-form kernels were launched too
+    const float2 *renorm = nullptr;                 // scaled / lifted forms
+    const unsigned *flag = nullptr;                 // nullptr: standard form, no range check was made
+    float scaled_max = 0.f;
+    CarouselCoefs carousel() const
+    {
+        return CarouselCoefs{reinterpret_cast<const float2 *>(table), renorm, flag, scaled_max};
+    }
 };
 
-// What the process-wide form setting means for a call on the float carousel path: whether the range
-// check and the scaled / lifted tables are wanted, and the threshold of the scaled form.
+// What the rotation-form choice means for a call on the float carousel path: whether the range check and
+// the scaled / lifted tables are wanted, and the threshold of the scaled form.
 struct FormPolicy {
     bool try_forms;
     float scaled_max;
 };
-FormPolicy form_policy(bool float_carousel)
+FormPolicy form_policy(bool float_carousel, int form_choice)
 {
-    if (!float_carousel || g_form_choice == GIVENS_FORM_STANDARD) return {false, 0.f};
-    if (g_form_choice == GIVENS_FORM_LIFTED) return {true, -1.f};
+    if (!float_carousel || form_choice == GIVENS_FORM_STANDARD) return {false, 0.f};
+    if (form_choice == GIVENS_FORM_LIFTED) return {true, -1.f};
     return {true, kScaledMaxAbsTheta};
 }
 
-// Where the coefficient kernels of one call write: either the per-device workspace (grown on demand) or
-// the static scratch array of the entry point that may not allocate.
+// Where the coefficient kernels of one sweep direction write: buffers of the workspace (grown on demand) or
+// pieces of the static scratch array of the entry point that may not allocate.
 template <typename T>
 struct CoefStorage {
-    typename Pair2<T>::type *table = nullptr; // standard form, N pairs
+    typename Pair2<T>::type *table = nullptr; // N pairs
     T *factor = nullptr;                      // reverse sweep only, N values
-    unsigned *flag = nullptr;                 // float carousel path only, as are the following
-    float2 *table_scaled = nullptr;           // N pairs
-    double *scale = nullptr;                  // (n-1) * n row factors
+    unsigned *flag = nullptr;                 // kFlagBytes: flag word, ticket counter, slots (float carousel path)
+    float *scale = nullptr;                   // (n-1) * n row factors
     float *renorm = nullptr;                  // periods * n/2 pairs
 };
 
 inline int renorm_periods(int n) { return (n - 1 + kRenormPeriod - 1) / kRenormPeriod; }
 
 template <typename T>
-int workspace_coef_storage(int dev, int n, bool forward, bool try_forms, CoefStorage<T> *out)
+int workspace_coef_storage(Workspace &ws, CoefSet &set, int n, bool want_factor, bool try_forms, hipStream_t stream,
+                           CoefStorage<T> *out)
 {
     using P2 = typename Pair2<T>::type;
     const long long N = (long long)n * (n - 1) / 2;
-    Workspace &ws = g_ws[dev];
-    if (int rc = grow(ws.table, (size_t)N * sizeof(P2))) return rc;
-    out->table = reinterpret_cast<P2 *>(ws.table.ptr);
-    if (!forward) {
-        if (int rc = grow(ws.factor, (size_t)N * sizeof(T))) return rc;
-        out->factor = reinterpret_cast<T *>(ws.factor.ptr);
+    if (int rc = grow(set.table, (size_t)N * sizeof(P2))) return rc;
+    out->table = reinterpret_cast<P2 *>(set.table.ptr);
+    if (want_factor) {
+        if (int rc = grow(set.factor, (size_t)N * sizeof(T))) return rc;
+        out->factor = reinterpret_cast<T *>(set.factor.ptr);
     }
     if (try_forms) {
-        if (int rc = grow(ws.flag, 256)) return rc;
-        if (int rc = grow(ws.table_scaled, (size_t)N * sizeof(float2))) return rc;
-        if (int rc = grow(ws.scale, (size_t)(n - 1) * n * sizeof(double))) return rc;
-        if (int rc = grow(ws.renorm, (size_t)renorm_periods(n) * (n / 2) * sizeof(float2))) return rc;
+        if (!ws.flag.ptr) {
+            if (int rc = grow(ws.flag, kFlagBytes)) return rc;
+            GIVENS_HIP(hipMemsetAsync(ws.flag.ptr, 0, kFlagBytes, stream));   // the ticket counter starts at zero
+        }
+        if (int rc = grow(ws.scale, (size_t)(n - 1) * n * sizeof(float))) return rc;
+        if (int rc = grow(set.renorm, (size_t)renorm_periods(n) * (n / 2) * sizeof(float2))) return rc;
         out->flag = reinterpret_cast<unsigned *>(ws.flag.ptr);
-        out->table_scaled = reinterpret_cast<float2 *>(ws.table_scaled.ptr);
-        out->scale = reinterpret_cast<double *>(ws.scale.ptr);
-        out->renorm = reinterpret_cast<float *>(ws.renorm.ptr);
+        out->scale = reinterpret_cast<float *>(ws.scale.ptr);
+        out->renorm = reinterpret_cast<float *>(set.renorm.ptr);
     }
     return GIVENS_OK;
 }
@@ -287,10 +372,10 @@ constexpr size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
 constexpr size_t noalloc_bytes(int n)
 {
     const size_t N = (size_t)n * (n - 1) / 2;
-    return round_up_256(N * sizeof(float2)) * 2                                            // both tables
-           + round_up_256((size_t)(n - 1) * n * sizeof(double))                            // row factors
+    return round_up_256(N * sizeof(float2))                                                // the table
+           + round_up_256((size_t)(n - 1) * n * sizeof(float))                             // row factors
            + round_up_256((size_t)((n - 1 + kRenormPeriod - 1) / kRenormPeriod) * (n / 2) * sizeof(float2))
-           + 256;                                                                          // flag word
+           + kFlagBytes;                                                                   // flag, ticket, slots
 }
 constexpr size_t kNoAllocBytes = noalloc_bytes(kNoAllocMaxN);
 static_assert(kNoAllocBytes == GIVENS_NOALLOC_BYTES, "the header states the size of the static array");
@@ -314,82 +399,74 @@ int static_coef_storage(int dev, int n, CoefStorage<float> *out)
         at += round_up_256(bytes);
         return here;
     };
+    // the flag area comes first: its place must not depend on n, because the ticket counter in it has to be
+    // zero at the start of every call and only the range kernel itself puts it back
+    out->flag = reinterpret_cast<unsigned *>(take(kFlagBytes));
     out->table = reinterpret_cast<float2 *>(take(N * sizeof(float2)));
-    out->table_scaled = reinterpret_cast<float2 *>(take(N * sizeof(float2)));
-    out->scale = reinterpret_cast<double *>(take((size_t)(n - 1) * n * sizeof(double)));
+    out->scale = reinterpret_cast<float *>(take((size_t)(n - 1) * n * sizeof(float)));
     out->renorm = reinterpret_cast<float *>(take((size_t)renorm_periods(n) * (n / 2) * sizeof(float2)));
-    out->flag = reinterpret_cast<unsigned *>(take(256));
     out->factor = nullptr;
     return (size_t)(at - g_scratch_ptr[dev]) <= kNoAllocBytes ? GIVENS_OK : GIVENS_ERR_UNSUPPORTED;
 }
 
-// Launches the coefficient kernels.  `forward` picks the sweep direction of the scaled / lifted
-// forms' row factors; `policy.try_forms` adds the range check and those forms' tables.
+// Launches the coefficient kernels of one sweep direction.  `forward` picks the direction of the scaled /
+// lifted forms' row factors; `policy.try_forms` adds those forms (range check unless `range_known`: the
+// flag already holds max |theta| of this theta).
 template <typename T>
-int prepare_coefs(const CoefStorage<T> &st, const Problem &pb, const T *theta, bool forward, FormPolicy policy,
-                  hipStream_t stream, Coefs<T> *out, int mirror = 0)
+int build_coefs(const CoefStorage<T> &st, const Problem &pb, const T *theta, bool forward, FormPolicy policy,
+                hipStream_t stream, Coefs<T> *out, int mirror = 0, bool range_known = false)
 {
-    const bool try_scaled = policy.try_forms;
-    const float scaled_max = policy.scaled_max;
-    using P2 = typename Pair2<T>::type;
     const int n = pb.n;
     const int *map = pb.map;
     const long long N = (long long)n * (n - 1) / 2;
-    P2 *table = st.table;
-    T *factor = forward ? nullptr : st.factor;
     unsigned *flag = nullptr;
     const int threads = 256;
-    const unsigned blocks = (unsigned)((N + threads - 1) / threads);
+    const unsigned blocks = (unsigned)std::min<long long>((N + threads - 1) / threads, 8192);
     Span span(0, stream);
     if constexpr (std::is_same<T, float>::value) {
-        if (try_scaled) {
-            const int periods = renorm_periods(n);
+        if (policy.try_forms) {
             flag = st.flag;
-            float2 *tab_s = st.table_scaled;
-            double *D = st.scale;
-            float *rn = st.renorm;
-            hipLaunchKernelGGL(reset_flag_kernel, dim3(1), dim3(1), 0, stream, flag);
-            hipLaunchKernelGGL(theta_range_kernel, dim3(512), dim3(512), 0, stream, pb.free_angles, theta, flag);
-            const long long scan_threads = (long long)periods * n;
-            const unsigned scan_blocks = (unsigned)((scan_threads + threads - 1) / threads);
-            if (forward) {
-                hipLaunchKernelGGL(scaled_scan_kernel<true>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
-                                   map, mirror, flag, scaled_max, D, rn);
-                hipLaunchKernelGGL(scaled_table_kernel<true>, dim3(blocks), dim3(threads), 0, stream, n, theta,
-                                   map, mirror, flag, scaled_max, D, tab_s, factor);
-            } else {
-                hipLaunchKernelGGL(scaled_scan_kernel<false>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta,
-                                   map, mirror, flag, scaled_max, D, rn);
-                hipLaunchKernelGGL(scaled_table_kernel<false>, dim3(blocks), dim3(threads), 0, stream, n, theta,
-                                   map, mirror, flag, scaled_max, D, tab_s, factor);
+            if (!range_known) {
+                const unsigned range_blocks =
+                    (unsigned)std::min<long long>(kRangeBlocks, (pb.free_angles + 4095) / 4096);
+                hipLaunchKernelGGL(theta_range_kernel, dim3(range_blocks), dim3(512), 0, stream, pb.free_angles, theta,
+                                   flag + 64, flag + 1, flag);
             }
-            out->scaled = CarouselCoefs{kFormScaled, tab_s, reinterpret_cast<const float2 *>(rn), flag, scaled_max};
-            out->lifted = CarouselCoefs{kFormLifted, tab_s, reinterpret_cast<const float2 *>(rn), flag, scaled_max};
-            out->all_forms = true;
+            const long long scan_threads = (long long)renorm_periods(n) * n;
+            const unsigned scan_blocks = (unsigned)((scan_threads + threads - 1) / threads);
+            if (forward)
+                hipLaunchKernelGGL(scaled_scan_kernel<true>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta, map,
+                                   mirror, flag, policy.scaled_max, st.scale, st.renorm);
+            else
+                hipLaunchKernelGGL(scaled_scan_kernel<false>, dim3(scan_blocks), dim3(threads), 0, stream, n, theta, map,
+                                   mirror, flag, policy.scaled_max, st.scale, st.renorm);
+            out->renorm = reinterpret_cast<const float2 *>(st.renorm);
         }
-        out->standard = CarouselCoefs{kFormStandard, table, nullptr, flag, scaled_max};
     }
-    hipLaunchKernelGGL(coef_table_kernel<T>, dim3(std::min(blocks, 4096u)), dim3(threads), 0, stream, n, theta,
-                       map, mirror, static_cast<const unsigned *>(flag), scaled_max, table, factor);
+    hipLaunchKernelGGL(coef_table_kernel<T>, dim3(blocks), dim3(threads), 0, stream, n, theta, map, mirror,
+                       static_cast<const unsigned *>(flag), policy.scaled_max, static_cast<const float *>(st.scale),
+                       st.table, forward ? nullptr : st.factor);
     GIVENS_HIP(hipGetLastError());
-    out->table = table;
-    out->factor = factor;
+    out->table = st.table;
+    out->factor = forward ? nullptr : st.factor;
+    out->flag = flag;
+    out->scaled_max = policy.scaled_max;
     t_state.last_flag = flag;
-    t_state.last_scaled_max = scaled_max;
+    t_state.last_scaled_max = policy.scaled_max;
     t_state.last_stream = stream;
     return GIVENS_OK;
 }
 
-// the usual case: storage from the per-device workspace
+// the usual case: storage from a coefficient set of the workspace
 template <typename T>
-int prepare_coefs(int dev, const Problem &pb, const T *theta, bool forward, FormPolicy policy, hipStream_t stream,
-                  Coefs<T> *out, int mirror = 0)
+int build_coefs(Workspace &ws, CoefSet &set, const Problem &pb, const T *theta, bool forward, FormPolicy policy,
+                hipStream_t stream, Coefs<T> *out, int mirror = 0, bool range_known = false)
 {
     CoefStorage<T> st;
-    if (int rc = workspace_coef_storage<T>(dev, pb.n, forward,
-                                           policy.try_forms && std::is_same<T, float>::value, &st))
+    if (int rc = workspace_coef_storage<T>(ws, set, pb.n, !forward,
+                                           policy.try_forms && std::is_same<T, float>::value, stream, &st))
         return rc;
-    return prepare_coefs<T>(st, pb, theta, forward, policy, stream, out, mirror);
+    return build_coefs<T>(st, pb, theta, forward, policy, stream, out, mirror, range_known);
 }
 
 template <typename T>
@@ -410,12 +487,71 @@ int lds_forward(int n, int rows, long long B, const typename Pair2<T>::type *tab
     return GIVENS_OK;
 }
 
+// Which kernel family a call takes.
+struct Families {
+    bool carousel = false, column = false;  // neither: LDS strip family
+};
+template <typename T>
+int pick_forward_family(int n, long long B, int choice, Families *out)
+{
+    const bool can_carousel = carousel_supported<T>(n, B);
+    const bool can_column = std::is_same<T, float>::value && n <= kColumnFamilyMaxN;
+    if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
+    if (choice == GIVENS_KERNEL_COLUMN && !can_column) return GIVENS_ERR_UNSUPPORTED;
+    out->carousel = can_carousel && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_CAROUSEL);
+    out->column = !out->carousel && can_column && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_COLUMN);
+    return GIVENS_OK;
+}
+template <typename T>
+int pick_backward_family(int n, long long B, int choice, Families *out)
+{
+    const bool can_carousel = carousel_backward_supported<T>(n, B);
+    const bool can_column = std::is_same<T, float>::value && n <= kColumnFamilyMaxN;
+    if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
+    if (choice == GIVENS_KERNEL_COLUMN && !can_column) return GIVENS_ERR_UNSUPPORTED;
+    // the family that sweeps (the n x n operand of the Gram form, or all B columns); the column family has
+    // no reverse sweep of its own and borrows the LDS family's
+    out->carousel = can_carousel && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_CAROUSEL);
+    out->column = can_column && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_COLUMN);
+    return GIVENS_OK;
+}
+
+// The forward-type sweep of one call, coefficients given.
+template <typename T>
+int run_forward_sweep(const Problem &pb, long long B, const Coefs<T> &coefs, Families fam, const T *X, T *Y,
+                      int identity, int transpose, hipStream_t stream)
+{
+    const int n = pb.n, rows = pb.rows;
+    int rc = GIVENS_OK;
+    if (fam.carousel) {
+        if constexpr (std::is_same<T, float>::value) {
+            Span span(1, stream);
+            rc = carousel_forward(n, rows, B, coefs.carousel(), X, Y, identity, transpose, stream);
+            if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+        } else {
+            rc = GIVENS_ERR_UNSUPPORTED;
+        }
+        t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
+    } else if (fam.column) {
+        if constexpr (std::is_same<T, float>::value) {
+            Span span(1, stream);
+            rc = column_forward(n, rows, B, coefs.table, X, Y, identity, transpose, stream);
+            if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
+        }
+        t_state.last_kernel = GIVENS_KERNEL_COLUMN;
+    } else {
+        rc = lds_forward<T>(n, rows, B, coefs.table, X, Y, identity, stream, transpose);
+        t_state.last_kernel = GIVENS_KERNEL_LDS;
+    }
+    return rc;
+}
+
 // Reverse sweep and the reduction of its partial sums into dtheta.  LDS family: chunks of strips, one
 // partial sum per (strip, angle), folded into dtheta chunk by chunk.  Carousel family: persistent
-// workgroups with one row of partial sums each, or the accumulating variant.  `family` picks the kernel.
+// workgroups with one row of partial sums each.
 template <typename T>
-int backward_chunks(int dev, int family, const Problem &pb, long long B, const Coefs<T> &coefs, const T *Y,
-                    const T *G, T *dX, T *dtheta, hipStream_t stream, int g_identity = 0)
+int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, long long B, const Coefs<T> &coefs,
+                    const T *Y, const T *G, T *dX, T *dtheta, hipStream_t stream, int g_identity = 0)
 {
     const int n = pb.n, rows = pb.rows;
     const int *map = pb.map;
@@ -423,7 +559,7 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
     int w = 0;
     size_t smem = 0;
     auto kern = lds_backward_kernel<T>;
-    if (family == GIVENS_KERNEL_LDS) {
+    if (!carousel) {
         w = lds_strip_width<T>(n, B, 2);
         if (w == 0) return GIVENS_ERR_UNSUPPORTED;
         smem = (size_t)2 * n * lds_row_stride(w) * sizeof(T);
@@ -434,64 +570,22 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
         if (w == 0) return GIVENS_ERR_UNSUPPORTED;
     }
     const long long strips = (B + w - 1) / w;
-    Workspace &ws = g_ws[dev];
     int cus = 0;
     GIVENS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     const float *zeros = nullptr;
     float *sink = nullptr;
     if constexpr (std::is_same<T, float>::value) {
-        if (family == GIVENS_KERNEL_CAROUSEL) {
+        if (carousel) {
             const size_t want = (size_t)N * sizeof(float);
             if (ws.zeros.bytes < want) {
                 if (int rc = grow(ws.zeros, want)) return rc;
                 hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, stream, N,
                                    reinterpret_cast<float *>(ws.zeros.ptr));
                 GIVENS_HIP(hipGetLastError());
-                // later calls may come on other streams and never write this buffer again
-                GIVENS_HIP(hipStreamSynchronize(stream));
             }
             zeros = reinterpret_cast<const float *>(ws.zeros.ptr);
             if (int rc = grow(ws.sink, ((size_t)N + 8192) * sizeof(float))) return rc;
             sink = reinterpret_cast<float *>(ws.sink.ptr);
-        }
-    }
-
-    if constexpr (std::is_same<T, float>::value) {
-        // accumulating reduction (carousel family): every strip adds its sums into one zeroed buffer
-        // with float atomics; no per-strip partials, no second pass over them
-        const bool want_acc = g_reduction_choice == GIVENS_REDUCTION_ATOMIC ||
-                              (g_reduction_choice == GIVENS_REDUCTION_AUTO && kAutoReductionIsAtomic);
-        if (family == GIVENS_KERNEL_CAROUSEL && want_acc) {
-            int lanes = 0, slots = 0;
-            if (!carousel_bwd_layout(n, &lanes, &slots)) return GIVENS_ERR_UNSUPPORTED;
-            if (int rc = grow(ws.acc, (size_t)N * sizeof(float))) return rc;
-            float *acc = reinterpret_cast<float *>(ws.acc.ptr);
-            const int threads = 256;
-            {
-                Span span(1, stream);
-                hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(threads), 0, stream, N, acc);
-                const long long groups = carousel_bwd_groups(n, strips, cus);
-                if (coefs.all_forms) {
-                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.scaled, Y, G, dX,
-                                                          acc, zeros, sink, 1, g_identity, stream))
-                        return rc;
-                    if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.lifted, Y, G, dX,
-                                                          acc, zeros, sink, 1, g_identity, stream))
-                        return rc;
-                }
-                if (int rc = carousel_backward_strips(n, rows, B, w, 0, strips, groups, coefs.standard, Y, G, dX,
-                                                      acc, zeros, sink, 1, g_identity, stream))
-                    return rc;
-                GIVENS_HIP(hipGetLastError());
-            }
-            {
-                Span span(2, stream);
-                hipLaunchKernelGGL(finish_accumulated_kernel, dim3((unsigned)((N + threads - 1) / threads)),
-                                   dim3(threads), 0, stream, n, lanes, slots, acc, coefs.factor, map, dtheta);
-                GIVENS_HIP(hipGetLastError());
-            }
-            t_state.last_reduction = GIVENS_REDUCTION_ATOMIC;
-            return GIVENS_OK;
         }
     }
     t_state.last_reduction = GIVENS_REDUCTION_TWO_STAGE;
@@ -499,32 +593,23 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
     // Two-stage reduction.  LDS family: one row of partial sums per strip, in chunks of strips that fit
     // the workspace cap.  Carousel family: one row per persistent workgroup (at most what the chip
     // holds at once), whatever the number of strips.
-    const bool persistent = family == GIVENS_KERNEL_CAROUSEL;
-    const long long rows_wanted = persistent ? carousel_bwd_groups(n, strips, cus) : strips;
+    const long long rows_wanted = carousel ? carousel_bwd_groups(n, strips, cus) : strips;
     long long prows = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
     prows = std::max<long long>(1, std::min(prows, rows_wanted));
     if (int rc = grow(ws.partial, (size_t)prows * N * sizeof(T))) return rc;
     T *partial = reinterpret_cast<T *>(ws.partial.ptr);
-    const long long chunk = persistent ? strips : prows;     // strips per launch
+    const long long chunk = carousel ? strips : prows;     // strips per launch
     for (long long s0 = 0; s0 < strips; s0 += chunk) {
         const long long ns = std::min(chunk, strips - s0);
-        const long long nrows = persistent ? std::min(prows, ns) : ns;
+        const long long nrows = carousel ? std::min(prows, ns) : ns;
         {
             Span span(1, stream);
-            if (family == GIVENS_KERNEL_LDS) {
+            if (!carousel) {
                 hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, rows, B, w, s0,
                                    coefs.table, Y, G, dX, partial, g_identity);
             } else if constexpr (std::is_same<T, float>::value) {
-                if (coefs.all_forms) {
-                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.scaled, Y, G, dX,
-                                                          partial, zeros, sink, 0, g_identity, stream))
-                        return rc;
-                    if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.lifted, Y, G, dX,
-                                                          partial, zeros, sink, 0, g_identity, stream))
-                        return rc;
-                }
-                if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.standard, Y, G, dX,
-                                                      partial, zeros, sink, 0, g_identity, stream))
+                if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.carousel(), Y, G, dX, partial,
+                                                      zeros, sink, g_identity, stream))
                     return rc;
             } else {
                 return GIVENS_ERR_UNSUPPORTED;
@@ -543,106 +628,6 @@ int backward_chunks(int dev, int family, const Problem &pb, long long B, const C
     return GIVENS_OK;
 }
 
-// ---- rocBLAS, loaded on first use: only the Gram-matrix reduction needs it (one plain SGEMM), and the
-// library must load and run without it.
-struct RocblasApi {
-    bool tried = false, ok = false;
-    void *lib = nullptr;
-    int (*create_handle)(void **) = nullptr;
-    int (*destroy_handle)(void *) = nullptr;
-    int (*set_stream)(void *, hipStream_t) = nullptr;
-    int (*set_atomics_mode)(void *, int) = nullptr;
-    int (*sgemm)(void *, int, int, int, int, int, const float *, const float *, int, const float *, int,
-                 const float *, float *, int) = nullptr;
-    int (*sgemm_strided_batched)(void *, int, int, int, int, int, const float *, const float *, int, long long,
-                                 const float *, int, long long, const float *, float *, int, long long,
-                                 int) = nullptr;
-    void *handle[kMaxDevices] = {};
-};
-RocblasApi g_blas;
-constexpr int kBlasOpNone = 111, kBlasOpTranspose = 112; // rocblas_operation values of the public API
-
-bool rocblas_available()
-{
-    RocblasApi &b = g_blas;
-    if (b.tried) return b.ok;
-    b.tried = true;
-    for (const char *name : {"librocblas.so.5", "librocblas.so", "/opt/rocm/lib/librocblas.so"}) {
-        b.lib = dlopen(name, RTLD_NOW | RTLD_LOCAL);
-        if (b.lib) break;
-    }
-    if (!b.lib) return false;
-    b.create_handle = reinterpret_cast<decltype(b.create_handle)>(dlsym(b.lib, "rocblas_create_handle"));
-    b.destroy_handle = reinterpret_cast<decltype(b.destroy_handle)>(dlsym(b.lib, "rocblas_destroy_handle"));
-    b.set_stream = reinterpret_cast<decltype(b.set_stream)>(dlsym(b.lib, "rocblas_set_stream"));
-    b.set_atomics_mode = reinterpret_cast<decltype(b.set_atomics_mode)>(dlsym(b.lib, "rocblas_set_atomics_mode"));
-    b.sgemm = reinterpret_cast<decltype(b.sgemm)>(dlsym(b.lib, "rocblas_sgemm"));
-    b.sgemm_strided_batched = reinterpret_cast<decltype(b.sgemm_strided_batched)>(
-        dlsym(b.lib, "rocblas_sgemm_strided_batched"));
-    b.ok = b.create_handle && b.destroy_handle && b.set_stream && b.set_atomics_mode && b.sgemm &&
-           b.sgemm_strided_batched;
-    return b.ok;
-}
-
-// How many slices of the contraction (batch) dimension the Gram matrix is computed in.  The library's
-// SGEMM gives a 256 x 256 tile of C to one workgroup, so a 2048 x 2048 result alone would occupy 64
-// of the 256 CUs; slicing B and summing the slices' results afterwards (fixed order) fills the chip.
-int gram_slices(int rows, long long B)
-{
-    const long long tiles = (long long)((rows + 255) / 256) * ((rows + 255) / 256);
-    long long s = (256 + tiles - 1) / tiles;
-    s = std::min<long long>(s, 16);
-    s = std::min<long long>(s, std::max<long long>(1, B / 1024));
-    return (int)std::max<long long>(1, s);
-}
-
-__global__ void sum_slices_kernel(long long count, int slices, float *__restrict__ c)
-{
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count;
-         i += (long long)gridDim.x * blockDim.x) {
-        float acc = c[i];
-        for (int s = 1; s < slices; ++s) acc += c[(long long)s * count + i];
-        c[i] = acc;
-    }
-}
-
-// C (rows x rows, row-major) = Y G^T for row-major rows x B operands: in the library's column-major
-// terms C^T = G_cm^T Y_cm with G_cm, Y_cm the B x rows column-major views of the same memory.
-// C has room for `slices` matrices; the result ends in the first.
-int gram_matrix(int dev, int rows, long long B, int slices, const float *Y, const float *G, float *C,
-                hipStream_t stream)
-{
-    RocblasApi &b = g_blas;
-    if (!rocblas_available() || B > 0x7fffffffLL) return GIVENS_ERR_UNSUPPORTED;
-    if (!b.handle[dev]) {
-        if (b.create_handle(&b.handle[dev]) != 0) { b.handle[dev] = nullptr; return GIVENS_ERR_UNSUPPORTED; }
-        (void)b.set_atomics_mode(b.handle[dev], 0); // no atomics: bit-identical results from run to run
-    }
-    if (b.set_stream(b.handle[dev], stream) != 0) return GIVENS_ERR_UNSUPPORTED;
-    const float one = 1.f, zero = 0.f;
-    const long long count = (long long)rows * rows;
-    const long long kc = B / slices;            // columns per slice; the remainder goes to a last GEMM
-    int st;
-    if (slices > 1)
-        st = b.sgemm_strided_batched(b.handle[dev], kBlasOpTranspose, kBlasOpNone, rows, rows, (int)kc, &one, G,
-                                     (int)B, kc, Y, (int)B, kc, &zero, C, rows, count, slices);
-    else
-        st = b.sgemm(b.handle[dev], kBlasOpTranspose, kBlasOpNone, rows, rows, (int)kc, &one, G, (int)B, Y, (int)B,
-                     &zero, C, rows);
-    if (st != 0) return GIVENS_ERR_UNSUPPORTED;
-    const long long tail = B - kc * slices;
-    if (tail > 0) {
-        st = b.sgemm(b.handle[dev], kBlasOpTranspose, kBlasOpNone, rows, rows, (int)tail, &one, G + kc * slices,
-                     (int)B, Y + kc * slices, (int)B, &one, C, rows);
-        if (st != 0) return GIVENS_ERR_UNSUPPORTED;
-    }
-    if (slices > 1) {
-        hipLaunchKernelGGL(sum_slices_kernel, dim3(1024), dim3(256), 0, stream, count, slices, C);
-        GIVENS_HIP(hipGetLastError());
-    }
-    return GIVENS_OK;
-}
-
 int current_device(int *dev)
 {
     GIVENS_HIP(hipGetDevice(dev));
@@ -650,10 +635,33 @@ int current_device(int *dev)
     return GIVENS_OK;
 }
 
+CallOptions default_options() { return CallOptions{g_kernel_choice, g_form_choice, g_reduction_choice}; }
+
+int options_from(const givens_options *o, CallOptions *out)
+{
+    *out = default_options();
+    if (!o) return GIVENS_OK;
+    auto in = [](int v, std::initializer_list<int> ok) { return std::find(ok.begin(), ok.end(), v) != ok.end(); };
+    if (!in(o->kernel, {GIVENS_KERNEL_AUTO, GIVENS_KERNEL_LDS, GIVENS_KERNEL_CAROUSEL, GIVENS_KERNEL_COLUMN}) ||
+        !in(o->rotation_form, {GIVENS_FORM_AUTO, GIVENS_FORM_STANDARD, GIVENS_FORM_LIFTED}) ||
+        !in(o->reduction, {GIVENS_REDUCTION_AUTO, GIVENS_REDUCTION_TWO_STAGE, GIVENS_REDUCTION_GRAM}))
+        return GIVENS_ERR_UNSUPPORTED;
+    *out = CallOptions{o->kernel, o->rotation_form, o->reduction};
+    return GIVENS_OK;
+}
+
+// A call that writes a coefficient set of the workspace ends the validity of what givens_prepare left there.
+void invalidate_prepared(Workspace &ws, bool fwd, bool rev)
+{
+    if (fwd) ws.prepared.fwd = false;
+    if (rev) ws.prepared.rev = false;
+    if (!ws.prepared.fwd && !ws.prepared.rev) ws.prepared.token = 0;
+}
+
 // rows, m: see Problem.  The unrestricted entry points pass an even rows and m = rows - 1.
 template <typename T>
 int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y, int identity, void *stream_v,
-                 int transpose = 0, bool no_alloc = false)
+                 CallOptions opt, int transpose = 0, bool no_alloc = false)
 {
     if (int rc = check_restricted(rows, m)) return rc;
     if (B < 1) return GIVENS_ERR_BAD_B;
@@ -665,60 +673,80 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
     std::lock_guard<std::mutex> lock(g_mutex);
     int dev = 0;
     if (int rc = current_device(&dev)) return rc;
+    Workspace *ws = nullptr;
+    if (!no_alloc)
+        if (int rc = workspace_for(dev, stream, &ws)) return rc;
     Problem pb;
-    if (int rc = resolve_problem(dev, rows, m, &pb)) return rc;
+    if (int rc = resolve_problem(ws, rows, m, stream, &pb)) return rc;
     const int n = pb.n;
     timing_begin_call();
     if (no_alloc) t_state.timing_valid = false; // event pairs are created on demand: not here
-    const int choice = g_kernel_choice;
-    const bool can_carousel = carousel_supported<T>(n, B);
-    const bool can_column = std::is_same<T, float>::value && n <= kColumnFamilyMaxN;
-    if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
-    if (choice == GIVENS_KERNEL_COLUMN && !can_column) return GIVENS_ERR_UNSUPPORTED;
-    const bool use_carousel = can_carousel && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_CAROUSEL);
-    const bool use_column = can_column && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_COLUMN);
+    Families fam;
+    if (int rc = pick_forward_family<T>(n, B, opt.kernel, &fam)) return rc;
     Coefs<T> coefs;
-    const FormPolicy policy = form_policy(use_carousel && std::is_same<T, float>::value);
+    const FormPolicy policy = form_policy(fam.carousel && std::is_same<T, float>::value, opt.form);
     if (no_alloc) {
         if constexpr (std::is_same<T, float>::value) {
             CoefStorage<float> st;
             if (int rc = static_coef_storage(dev, n, &st)) return rc;
-            if (int rc = prepare_coefs<float>(st, pb, theta, true, policy, stream, &coefs, transpose)) return rc;
+            if (int rc = build_coefs<float>(st, pb, theta, true, policy, stream, &coefs, transpose)) return rc;
         }
-    } else if (int rc = prepare_coefs<T>(dev, pb, theta, true, policy, stream, &coefs, transpose)) {
-        return rc;
-    }
-    int rc = GIVENS_OK;
-    if (use_carousel) {
-        if constexpr (std::is_same<T, float>::value) {
-            Span span(1, stream);
-            if (coefs.all_forms) {
-                rc = carousel_forward(n, rows, B, coefs.scaled, X, Y, identity, transpose, stream);
-                if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.lifted, X, Y, identity, transpose, stream);
-            }
-            if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, coefs.standard, X, Y, identity, transpose, stream);
-            if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
-        } else {
-            rc = GIVENS_ERR_UNSUPPORTED;
-        }
-        t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
-    } else if (use_column) {
-        if constexpr (std::is_same<T, float>::value) {
-            Span span(1, stream);
-            rc = column_forward(n, rows, B, coefs.table, X, Y, identity, transpose, stream);
-            if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
-        }
-        t_state.last_kernel = GIVENS_KERNEL_COLUMN;
     } else {
-        rc = lds_forward<T>(n, rows, B, coefs.table, X, Y, identity, stream, transpose);
-        t_state.last_kernel = GIVENS_KERNEL_LDS;
+        invalidate_prepared(*ws, true, false);
+        if (int rc = build_coefs<T>(*ws, ws->fwd, pb, theta, true, policy, stream, &coefs, transpose)) return rc;
     }
-    return rc;
+    return run_forward_sweep<T>(pb, B, coefs, fam, X, Y, identity, transpose, stream);
+}
+
+// The reverse sweep of one call, reverse-direction coefficients given; `mirrored_for_dx` builds (or returns) the
+// forward-type coefficients of the mirrored problem when the Gram form needs them for dX.
+template <typename T, typename MirroredFn>
+int run_backward(Workspace &ws, int dev, const Problem &pb, long long B, const Coefs<T> &coefs, Families fam,
+                 CallOptions opt, const T *Y, const T *G, T *dX, T *dtheta, hipStream_t stream,
+                 MirroredFn &&mirrored_for_dx)
+{
+    const int n = pb.n, rows = pb.rows;
+    t_state.last_kernel = fam.carousel ? GIVENS_KERNEL_CAROUSEL : GIVENS_KERNEL_LDS;
+    if constexpr (std::is_same<T, float>::value) {
+        // Gram-matrix form for wide batches.  With C = Y G^T (rows x rows) the sums of the reverse sweep
+        // are those of the same sweep run on the operand C with the identity as upstream gradient:
+        // z_k gbar_k^T = A_k C A_k^T for the product A_k of the transposed blocks so far, and the sweep on
+        // (C, I) carries A_k C and A_k.  So dtheta costs one contraction over B plus a rows-column sweep, and
+        // dX = U^T G one forward-type sweep over B (mirrored tables), instead of a two-strip sweep over B.
+        const bool wide = B >= 2LL * n;   // measured break-even is near B = 1.6 n
+        const bool want_gram = opt.reduction == GIVENS_REDUCTION_GRAM || (opt.reduction == GIVENS_REDUCTION_AUTO && wide);
+        if (want_gram) {
+            int cus = 0;
+            GIVENS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+            const int slices = gram_slices(rows, B, cus);
+            if (int rc = grow(ws.gram, (size_t)slices * rows * rows * sizeof(float))) return rc;
+            float *C = reinterpret_cast<float *>(ws.gram.ptr);
+            {
+                Span span(1, stream);
+                gram_matrix(rows, B, slices, Y, G, C, stream);
+                GIVENS_HIP(hipGetLastError());
+            }
+            int rc = backward_chunks<T>(ws, dev, fam.carousel, pb, rows, coefs, C, nullptr, nullptr, dtheta, stream, 1);
+            if (rc == GIVENS_OK && dX) {
+                Coefs<T> mirrored;
+                Families dx_fam;
+                dx_fam.column = fam.column;
+                dx_fam.carousel = !fam.column && fam.carousel;
+                rc = mirrored_for_dx(dx_fam, &mirrored);
+                if (rc == GIVENS_OK) rc = run_forward_sweep<T>(pb, B, mirrored, dx_fam, G, dX, 0, 1, stream);
+            }
+            t_state.last_reduction = GIVENS_REDUCTION_GRAM;
+            if (fam.column) t_state.last_kernel = GIVENS_KERNEL_COLUMN;
+            else t_state.last_kernel = fam.carousel ? GIVENS_KERNEL_CAROUSEL : GIVENS_KERNEL_LDS;
+            return rc;
+        }
+    }
+    return backward_chunks<T>(ws, dev, fam.carousel, pb, B, coefs, Y, G, dX, dtheta, stream);
 }
 
 template <typename T>
 int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, const T *G, T *dX, T *dtheta,
-                  void *stream_v)
+                  void *stream_v, CallOptions opt)
 {
     if (int rc = check_restricted(rows, m)) return rc;
     if (B < 1) return GIVENS_ERR_BAD_B;
@@ -728,79 +756,165 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
     std::lock_guard<std::mutex> lock(g_mutex);
     int dev = 0;
     if (int rc = current_device(&dev)) return rc;
+    Workspace *ws = nullptr;
+    if (int rc = workspace_for(dev, stream, &ws)) return rc;
     Problem pb;
-    if (int rc = resolve_problem(dev, rows, m, &pb)) return rc;
+    if (int rc = resolve_problem(ws, rows, m, stream, &pb)) return rc;
     const int n = pb.n;
     timing_begin_call();
-    const int choice = g_kernel_choice;
-    const bool can_carousel = carousel_backward_supported<T>(n, B);
-    const bool can_column = std::is_same<T, float>::value && n <= kColumnFamilyMaxN;
-    if (choice == GIVENS_KERNEL_CAROUSEL && !can_carousel) return GIVENS_ERR_UNSUPPORTED;
-    if (choice == GIVENS_KERNEL_COLUMN && !can_column) return GIVENS_ERR_UNSUPPORTED;
-    // the family that sweeps (the n x n operand of the Gram form, or all B columns); the column family has
-    // no reverse sweep of its own and borrows the LDS family's
-    const int family = (can_carousel && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_CAROUSEL))
-                           ? GIVENS_KERNEL_CAROUSEL
-                           : GIVENS_KERNEL_LDS;
-    const bool column = can_column && (choice == GIVENS_KERNEL_AUTO || choice == GIVENS_KERNEL_COLUMN);
+    Families fam;
+    if (int rc = pick_backward_family<T>(n, B, opt.kernel, &fam)) return rc;
+    invalidate_prepared(*ws, false, true);
     Coefs<T> coefs;
-    if (int rc = prepare_coefs<T>(dev, pb, theta, false,
-                                  form_policy(family == GIVENS_KERNEL_CAROUSEL && std::is_same<T, float>::value),
-                                  stream, &coefs))
+    if (int rc = build_coefs<T>(*ws, ws->rev, pb, theta, false,
+                                form_policy(fam.carousel && std::is_same<T, float>::value, opt.form), stream, &coefs))
         return rc;
-    t_state.last_kernel = family;
-    if constexpr (std::is_same<T, float>::value) {
-        // Gram-matrix form for wide batches.  With C = Y G^T (rows x rows) the sums of the reverse sweep
-        // are those of the same sweep run on the operand C with the identity as upstream gradient:
-        // z_k gbar_k^T = A_k C A_k^T for the product A_k of the transposed blocks so far, and the sweep on
-        // (C, I) carries A_k C and A_k.  So dtheta costs one GEMM over B plus a rows-column sweep, and
-        // dX = U^T G one forward-type sweep over B (mirrored tables), instead of a two-strip sweep over B.
-        const bool wide = B >= 2LL * n;   // measured break-even is near B = 1.6 n
-        const bool want_gram = (g_reduction_choice == GIVENS_REDUCTION_GRAM ||
-                                (g_reduction_choice == GIVENS_REDUCTION_AUTO && wide));
-        if (want_gram && rocblas_available()) {
-            Workspace &ws = g_ws[dev];
-            const int slices = gram_slices(rows, B);
-            if (int rc = grow(ws.gram, (size_t)slices * rows * rows * sizeof(float))) return rc;
-            float *C = reinterpret_cast<float *>(ws.gram.ptr);
-            int rc;
-            {
-                Span span(1, stream);
-                rc = gram_matrix(dev, rows, B, slices, Y, G, C, stream);
-            }
-            if (rc == GIVENS_OK) {
-                rc = backward_chunks<T>(dev, family, pb, rows, coefs, C, nullptr, nullptr, dtheta, stream, 1);
-                if (rc == GIVENS_OK && dX && column) {
-                    Coefs<T> mirrored;
-                    rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(false), stream, &mirrored, 1);
-                    Span span(1, stream);
-                    if (rc == GIVENS_OK) rc = column_forward(n, rows, B, mirrored.table, G, dX, 0, 1, stream);
-                    if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
-                } else if (rc == GIVENS_OK && dX && family == GIVENS_KERNEL_LDS) {
-                    Coefs<T> mirrored;
-                    rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(false), stream, &mirrored, 1);
-                    if (rc == GIVENS_OK) rc = lds_forward<T>(n, rows, B, mirrored.table, G, dX, 0, stream, 1);
-                } else if (rc == GIVENS_OK && dX) {
-                    Coefs<T> mirrored;
-                    rc = prepare_coefs<T>(dev, pb, theta, true, form_policy(true), stream, &mirrored, 1);
-                    Span span(1, stream);
-                    if (rc == GIVENS_OK && mirrored.all_forms) {
-                        rc = carousel_forward(n, rows, B, mirrored.scaled, G, dX, 0, 1, stream);
-                        if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, mirrored.lifted, G, dX, 0, 1, stream);
-                    }
-                    if (rc == GIVENS_OK) rc = carousel_forward(n, rows, B, mirrored.standard, G, dX, 0, 1, stream);
-                    if (rc == GIVENS_OK && !hip_ok(hipGetLastError())) rc = GIVENS_ERR_HIP;
-                }
-                t_state.last_reduction = GIVENS_REDUCTION_GRAM;
-                if (column) t_state.last_kernel = GIVENS_KERNEL_COLUMN;
-                return rc;
-            }
-            // the GEMM could not be run: fall through to the sweep over all B columns
-        } else if (g_reduction_choice == GIVENS_REDUCTION_GRAM) {
-            return GIVENS_ERR_UNSUPPORTED; // forced, but rocBLAS could not be loaded
-        }
+    auto mirrored_for_dx = [&](Families dx_fam, Coefs<T> *out) {
+        return build_coefs<T>(*ws, ws->mirrored, pb, theta, true,
+                              form_policy(dx_fam.carousel && std::is_same<T, float>::value, opt.form), stream, out, 1);
+    };
+    return run_backward<T>(*ws, dev, pb, B, coefs, fam, opt, Y, G, dX, dtheta, stream, mirrored_for_dx);
+}
+
+// ---- prepared coefficients (float): givens_prepare builds the tables of one theta once, in the workspace of
+// the stream, and the *_prepared calls run the sweeps on them.
+int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *stream_v, CallOptions opt)
+{
+    if (int rc = check_restricted(rows, m)) return rc;
+    if (!theta) return GIVENS_ERR_NULL;
+    if (!(directions & (GIVENS_PREPARE_FORWARD | GIVENS_PREPARE_BACKWARD)) ||
+        (directions & ~(GIVENS_PREPARE_FORWARD | GIVENS_PREPARE_BACKWARD)))
+        return GIVENS_ERR_UNSUPPORTED;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    if (int rc = current_device(&dev)) return rc;
+    Workspace *ws = nullptr;
+    if (int rc = workspace_for(dev, stream, &ws)) return rc;
+    Problem pb;
+    if (int rc = resolve_problem(ws, rows, m, stream, &pb)) return rc;
+    const int n = pb.n;
+    timing_begin_call();
+    // the family does not depend on B (B >= 1 is all the shape checks look at)
+    const bool fwd = (directions & GIVENS_PREPARE_FORWARD) != 0, rev = (directions & GIVENS_PREPARE_BACKWARD) != 0;
+    Families ffam, bfam;
+    if (fwd)
+        if (int rc = pick_forward_family<float>(n, 1, opt.kernel, &ffam)) return rc;
+    if (rev)
+        if (int rc = pick_backward_family<float>(n, 1, opt.kernel, &bfam)) return rc;
+    ws->prepared = Prepared{};
+    Coefs<float> c;
+    bool range_known = false, mirrored_forms = false;
+    const FormPolicy fpol = form_policy(ffam.carousel, opt.form), bpol = form_policy(bfam.carousel, opt.form);
+    if (fwd) {
+        if (int rc = build_coefs<float>(*ws, ws->fwd, pb, theta, true, fpol, stream, &c, 0, false)) return rc;
+        range_known = fpol.try_forms;
     }
-    return backward_chunks<T>(dev, family, pb, B, coefs, Y, G, dX, dtheta, stream);
+    if (rev) {
+        if (int rc = build_coefs<float>(*ws, ws->rev, pb, theta, false, bpol, stream, &c, 0, range_known && bpol.try_forms))
+            return rc;
+        // the Gram form's dX sweep (wide batches) reads forward-type tables of the mirrored problem
+        Families dx_fam;
+        dx_fam.column = bfam.column;
+        dx_fam.carousel = !bfam.column && bfam.carousel;
+        const FormPolicy mpol = form_policy(dx_fam.carousel, opt.form);
+        if (int rc = build_coefs<float>(*ws, ws->mirrored, pb, theta, true, mpol, stream, &c, 1,
+                                        (range_known || bpol.try_forms) && mpol.try_forms))
+            return rc;
+        mirrored_forms = mpol.try_forms;
+    }
+    Prepared &p = ws->prepared;
+    p.token = ++g_next_token;
+    p.rows = rows;
+    p.m = m;
+    p.fwd = fwd;
+    p.rev = rev;
+    p.fwd_forms = fwd && fpol.try_forms;
+    p.rev_forms = rev && bpol.try_forms;
+    p.mirrored_forms = rev && mirrored_forms;
+    p.scaled_max = form_policy(true, opt.form).scaled_max;
+    return p.token;
+}
+
+// coefficients of a prepared set, as build_coefs would have returned them
+Coefs<float> prepared_coefs(Workspace &ws, const CoefSet &set, bool reverse, bool forms, float scaled_max)
+{
+    Coefs<float> c;
+    c.table = reinterpret_cast<const float2 *>(set.table.ptr);
+    c.factor = reverse ? reinterpret_cast<const float *>(set.factor.ptr) : nullptr;
+    if (forms) {
+        c.renorm = reinterpret_cast<const float2 *>(set.renorm.ptr);
+        c.flag = reinterpret_cast<const unsigned *>(ws.flag.ptr);
+        c.scaled_max = scaled_max;
+    }
+    t_state.last_flag = c.flag;
+    t_state.last_scaled_max = scaled_max;
+    return c;
+}
+
+int prepared_workspace(int64_t token, hipStream_t stream, int *dev, Workspace **ws)
+{
+    if (token <= 0) return GIVENS_ERR_STALE;
+    if (int rc = current_device(dev)) return rc;
+    for (auto &w : g_ws[*dev])
+        if (w->stream == stream && w->prepared.token == token) {
+            w->last_use = ++g_use_clock;
+            *ws = w.get();
+            return GIVENS_OK;
+        }
+    return GIVENS_ERR_STALE;
+}
+
+int forward_prepared_impl(int64_t token, long long B, const float *X, float *Y, int identity, void *stream_v,
+                          CallOptions opt)
+{
+    if (B < 1 && !identity) return GIVENS_ERR_BAD_B;
+    if (!Y || (!identity && !X)) return GIVENS_ERR_NULL;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    Workspace *ws = nullptr;
+    if (int rc = prepared_workspace(token, stream, &dev, &ws)) return rc;
+    if (!ws->prepared.fwd) return GIVENS_ERR_STALE;
+    Problem pb;
+    if (int rc = resolve_problem(ws, ws->prepared.rows, ws->prepared.m, stream, &pb)) return rc;
+    if (identity) B = pb.rows;
+    timing_begin_call();
+    t_state.last_stream = stream;
+    Families fam;
+    if (int rc = pick_forward_family<float>(pb.n, B, opt.kernel, &fam)) return rc;
+    if (ws->prepared.fwd_forms && !fam.carousel) return GIVENS_ERR_STALE; // another family than the one prepared for
+    const Coefs<float> coefs = prepared_coefs(*ws, ws->fwd, false, ws->prepared.fwd_forms, ws->prepared.scaled_max);
+    return run_forward_sweep<float>(pb, B, coefs, fam, X, Y, identity, 0, stream);
+}
+
+int backward_prepared_impl(int64_t token, long long B, const float *Y, const float *G, float *dX, float *dtheta,
+                           void *stream_v, CallOptions opt)
+{
+    if (B < 1) return GIVENS_ERR_BAD_B;
+    if (!Y || !G || !dtheta) return GIVENS_ERR_NULL;
+    if (dX && (const void *)dX == (const void *)Y) return GIVENS_ERR_ALIAS;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    Workspace *ws = nullptr;
+    if (int rc = prepared_workspace(token, stream, &dev, &ws)) return rc;
+    if (!ws->prepared.rev) return GIVENS_ERR_STALE;
+    Problem pb;
+    if (int rc = resolve_problem(ws, ws->prepared.rows, ws->prepared.m, stream, &pb)) return rc;
+    timing_begin_call();
+    t_state.last_stream = stream;
+    Families fam;
+    if (int rc = pick_backward_family<float>(pb.n, B, opt.kernel, &fam)) return rc;
+    const Prepared prep = ws->prepared;
+    if (prep.rev_forms && !fam.carousel) return GIVENS_ERR_STALE;         // another family than the one prepared for
+    const Coefs<float> coefs = prepared_coefs(*ws, ws->rev, true, prep.rev_forms, prep.scaled_max);
+    auto mirrored_for_dx = [&](Families dx_fam, Coefs<float> *out) {
+        if (prep.mirrored_forms && !dx_fam.carousel) return (int)GIVENS_ERR_STALE;
+        *out = prepared_coefs(*ws, ws->mirrored, false, prep.mirrored_forms, prep.scaled_max);
+        return (int)GIVENS_OK;
+    };
+    return run_backward<float>(*ws, dev, pb, B, coefs, fam, opt, Y, G, dX, dtheta, stream, mirrored_for_dx);
 }
 
 // ---- unitary extension (appendix): complex operands, LDS strip kernels
@@ -815,13 +929,13 @@ int unitary_strip_width(int n, long long B, int strips_in_lds)
 }
 
 template <typename T>
-int unitary_table(int dev, int n, const T *theta, const T *phi, hipStream_t stream,
+int unitary_table(Workspace &ws, int n, const T *theta, const T *phi, hipStream_t stream,
                   const typename Cplx<T>::quad **out)
 {
     const long long N = (long long)n * (n - 1) / 2;
-    Workspace &ws = g_ws[dev];
-    if (int rc = grow(ws.table, (size_t)N * sizeof(typename Cplx<T>::quad))) return rc;
-    auto *table = reinterpret_cast<typename Cplx<T>::quad *>(ws.table.ptr);
+    invalidate_prepared(ws, true, false);
+    if (int rc = grow(ws.fwd.table, (size_t)N * sizeof(typename Cplx<T>::quad))) return rc;
+    auto *table = reinterpret_cast<typename Cplx<T>::quad *>(ws.fwd.table.ptr);
     Span span(0, stream);
     const int threads = 256;
     const unsigned blocks = (unsigned)std::min<long long>((N + threads - 1) / threads, 4096);
@@ -847,7 +961,9 @@ int unitary_forward_impl(int n, long long B, const T *theta, const T *phi, const
     const int w = unitary_strip_width<T>(n, B, 1);
     if (w == 0) return GIVENS_ERR_UNSUPPORTED;
     const typename Cplx<T>::quad *table = nullptr;
-    if (int rc = unitary_table<T>(dev, n, theta, phi, stream, &table)) return rc;
+    Workspace *ws = nullptr;
+    if (int rc = workspace_for(dev, stream, &ws)) return rc;
+    if (int rc = unitary_table<T>(*ws, n, theta, phi, stream, &table)) return rc;
     const size_t smem = (size_t)n * w * sizeof(C);
     auto kern = unitary_forward_kernel<T>;
     GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -877,12 +993,14 @@ int unitary_backward_impl(int n, long long B, const T *theta, const T *phi, cons
     const int w = unitary_strip_width<T>(n, B, 2);
     if (w == 0) return GIVENS_ERR_UNSUPPORTED;
     const typename Cplx<T>::quad *table = nullptr;
-    if (int rc = unitary_table<T>(dev, n, theta, phi, stream, &table)) return rc;
+    Workspace *wsp = nullptr;
+    if (int rc = workspace_for(dev, stream, &wsp)) return rc;
+    Workspace &ws = *wsp;
+    if (int rc = unitary_table<T>(ws, n, theta, phi, stream, &table)) return rc;
     const long long N = (long long)n * (n - 1) / 2;
     const long long strips = (B + w - 1) / w;
     long long rows = (long long)(kPartialCapBytes / ((size_t)2 * N * sizeof(T)));
     rows = std::max<long long>(1, std::min(rows, strips));
-    Workspace &ws = g_ws[dev];
     if (int rc = grow(ws.partial, (size_t)rows * 2 * N * sizeof(T))) return rc;
     T *partial = reinterpret_cast<T *>(ws.partial.ptr);
     const size_t smem = (size_t)2 * n * w * sizeof(C);
@@ -939,51 +1057,90 @@ int rr_schedule(int n, int32_t *pairs)
 int givens_forward(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream);
+    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream, givens::default_options());
 }
 int givens_build(int n, const float *theta, float *U, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::forward_impl<float>(n, n - 1, n, theta, nullptr, U, 1, stream);
+    return givens::forward_impl<float>(n, n - 1, n, theta, nullptr, U, 1, stream, givens::default_options());
 }
 int givens_backward(int n, int64_t B, const float *theta, const float *Y, const float *G, float *dX,
                     float *dtheta, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::backward_impl<float>(n, n - 1, B, theta, Y, G, dX, dtheta, stream);
+    return givens::backward_impl<float>(n, n - 1, B, theta, Y, G, dX, dtheta, stream, givens::default_options());
 }
 int givens_forward_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::forward_impl<double>(n, n - 1, B, theta, X, Y, 0, stream);
+    return givens::forward_impl<double>(n, n - 1, B, theta, X, Y, 0, stream, givens::default_options());
 }
 int givens_build_f64(int n, const double *theta, double *U, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::forward_impl<double>(n, n - 1, n, theta, nullptr, U, 1, stream);
+    return givens::forward_impl<double>(n, n - 1, n, theta, nullptr, U, 1, stream, givens::default_options());
 }
 int givens_backward_f64(int n, int64_t B, const double *theta, const double *Y, const double *G,
                         double *dX, double *dtheta, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::backward_impl<double>(n, n - 1, B, theta, Y, G, dX, dtheta, stream);
+    return givens::backward_impl<double>(n, n - 1, B, theta, Y, G, dX, dtheta, stream, givens::default_options());
 }
 
 int givens_forward_transposed(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream, 1);
+    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream, givens::default_options(), 1);
 }
 int givens_forward_transposed_f64(int n, int64_t B, const double *theta, const double *X, double *Y, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::forward_impl<double>(n, n - 1, B, theta, X, Y, 0, stream, 1);
+    return givens::forward_impl<double>(n, n - 1, B, theta, X, Y, 0, stream, givens::default_options(), 1);
 }
 
 int givens_forward_noalloc(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream)
 {
     if (int rc = givens::check_n(n)) return rc;
-    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream, 0, true);
+    return givens::forward_impl<float>(n, n - 1, B, theta, X, Y, 0, stream, givens::default_options(), 0, true);
+}
+
+int givens_forward_ex(int n, int m, int64_t B, const float *theta, const float *X, float *Y, void *stream,
+                      const givens_options *options)
+{
+    givens::CallOptions opt;
+    if (int rc = givens::options_from(options, &opt)) return rc;
+    if (!X && B != n) return GIVENS_ERR_BAD_B;   // X == NULL: the operand is I_n
+    return givens::forward_impl<float>(n, m, B, theta, X, Y, X ? 0 : 1, stream, opt);
+}
+int givens_backward_ex(int n, int m, int64_t B, const float *theta, const float *Y, const float *G, float *dX,
+                       float *dtheta, void *stream, const givens_options *options)
+{
+    givens::CallOptions opt;
+    if (int rc = givens::options_from(options, &opt)) return rc;
+    return givens::backward_impl<float>(n, m, B, theta, Y, G, dX, dtheta, stream, opt);
+}
+
+int64_t givens_prepare(int n, const float *theta, int directions, void *stream)
+{
+    if (int rc = givens::check_n(n)) return rc;
+    return givens::prepare_impl(n, n - 1, theta, directions, stream, givens::default_options());
+}
+int64_t givens_prepare_restricted(int n, int m, const float *theta, int directions, void *stream)
+{
+    return givens::prepare_impl(n, m, theta, directions, stream, givens::default_options());
+}
+int givens_forward_prepared(int64_t token, int64_t B, const float *X, float *Y, void *stream)
+{
+    return givens::forward_prepared_impl(token, B, X, Y, 0, stream, givens::default_options());
+}
+int givens_build_prepared(int64_t token, float *U, void *stream)
+{
+    return givens::forward_prepared_impl(token, 0, nullptr, U, 1, stream, givens::default_options());
+}
+int givens_backward_prepared(int64_t token, int64_t B, const float *Y, const float *G, float *dX, float *dtheta,
+                             void *stream)
+{
+    return givens::backward_prepared_impl(token, B, Y, G, dX, dtheta, stream, givens::default_options());
 }
 
 int64_t givens_num_angles(int n, int m)
@@ -1008,30 +1165,30 @@ int rr_schedule_restricted(int n, int m, int32_t *pairs)
 
 int givens_forward_restricted(int n, int m, int64_t B, const float *theta, const float *X, float *Y, void *stream)
 {
-    return givens::forward_impl<float>(n, m, B, theta, X, Y, 0, stream);
+    return givens::forward_impl<float>(n, m, B, theta, X, Y, 0, stream, givens::default_options());
 }
 int givens_build_restricted(int n, int m, const float *theta, float *U, void *stream)
 {
-    return givens::forward_impl<float>(n, m, n, theta, nullptr, U, 1, stream);
+    return givens::forward_impl<float>(n, m, n, theta, nullptr, U, 1, stream, givens::default_options());
 }
 int givens_backward_restricted(int n, int m, int64_t B, const float *theta, const float *Y, const float *G,
                                float *dX, float *dtheta, void *stream)
 {
-    return givens::backward_impl<float>(n, m, B, theta, Y, G, dX, dtheta, stream);
+    return givens::backward_impl<float>(n, m, B, theta, Y, G, dX, dtheta, stream, givens::default_options());
 }
 int givens_forward_restricted_f64(int n, int m, int64_t B, const double *theta, const double *X, double *Y,
                                   void *stream)
 {
-    return givens::forward_impl<double>(n, m, B, theta, X, Y, 0, stream);
+    return givens::forward_impl<double>(n, m, B, theta, X, Y, 0, stream, givens::default_options());
 }
 int givens_build_restricted_f64(int n, int m, const double *theta, double *U, void *stream)
 {
-    return givens::forward_impl<double>(n, m, n, theta, nullptr, U, 1, stream);
+    return givens::forward_impl<double>(n, m, n, theta, nullptr, U, 1, stream, givens::default_options());
 }
 int givens_backward_restricted_f64(int n, int m, int64_t B, const double *theta, const double *Y, const double *G,
                                    double *dX, double *dtheta, void *stream)
 {
-    return givens::backward_impl<double>(n, m, B, theta, Y, G, dX, dtheta, stream);
+    return givens::backward_impl<double>(n, m, B, theta, Y, G, dX, dtheta, stream, givens::default_options());
 }
 
 int givens_unitary_forward(int n, int64_t B, const float *theta, const float *phi, const float *X, float *Y,
@@ -1071,20 +1228,12 @@ int givens_release(void)
     if (!hip_ok(hipGetDevice(&keep))) return GIVENS_ERR_HIP;
     int rc = GIVENS_OK;
     for (int d = 0; d < kMaxDevices; ++d) {
-        Workspace &ws = g_ws[d];
-        bool any = false;
-        for (Buffer *b : ws.all) any = any || b->ptr;
-        if (!any) continue;
+        if (g_ws[d].empty()) continue;
         if (!hip_ok(hipSetDevice(d))) { rc = GIVENS_ERR_HIP; continue; }
-        for (Buffer *b : ws.all) {
-            if (b->ptr && !hip_ok(hipFree(b->ptr))) rc = GIVENS_ERR_HIP;
-            *b = Buffer{};
-        }
-        ws.map_rows = ws.map_m = 0;
-        if (g_blas.handle[d]) {
-            (void)g_blas.destroy_handle(g_blas.handle[d]);
-            g_blas.handle[d] = nullptr;
-        }
+        if (!hip_ok(hipDeviceSynchronize())) rc = GIVENS_ERR_HIP;
+        for (auto &w : g_ws[d])
+            if (free_workspace(*w) != GIVENS_OK) rc = GIVENS_ERR_HIP;
+        g_ws[d].clear();
     }
     (void)hipSetDevice(keep);
     return rc;
@@ -1103,6 +1252,7 @@ const char *givens_error_string(int code)
     case GIVENS_ERR_UNSUPPORTED: return "shape or option not supported by the requested kernel";
     case GIVENS_ERR_ALIAS: return "forbidden aliasing between arguments";
     case GIVENS_ERR_BAD_M: return "m must satisfy 1 <= m <= n - 1";
+    case GIVENS_ERR_STALE: return "the prepared coefficients are no longer in the stream's workspace";
     default: return "unknown error code";
     }
 }
@@ -1122,8 +1272,7 @@ int givens_last_kernel(void) { return givens::t_state.last_kernel; }
 
 int givens_set_reduction(int which)
 {
-    if (which != GIVENS_REDUCTION_AUTO && which != GIVENS_REDUCTION_TWO_STAGE && which != GIVENS_REDUCTION_ATOMIC &&
-        which != GIVENS_REDUCTION_GRAM)
+    if (which != GIVENS_REDUCTION_AUTO && which != GIVENS_REDUCTION_TWO_STAGE && which != GIVENS_REDUCTION_GRAM)
         return GIVENS_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(givens::g_mutex);
     const int prev = givens::g_reduction_choice;

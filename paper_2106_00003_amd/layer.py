@@ -4,7 +4,10 @@ Section 2 — "forward" builds or applies U, "backward" turns dL/dY into dL/dthe
 
 Marshalling only.  forward() is one givens_forward / givens_build call; backward() is one
 givens_backward call on the saved *output* (the reverse sweep undoes the rotations, so no
-activations other than Y are kept).  There is no CPU path: tensors must live on the GPU.
+activations other than Y are kept).  For float32 the forward pass prepares the coefficient tables of both
+sweep directions once (givens_prepare) and the backward pass reuses them -- theta cannot change in
+between; if another call on the stream has replaced the tables meanwhile, the backward pass falls back to
+the plain call, which rebuilds them.  There is no CPU path: tensors must live on the GPU.
 """
 from __future__ import annotations
 
@@ -18,13 +21,38 @@ def _plain(n: int, m) -> bool:
     return n % 2 == 0 and (m is None or m == n - 1)
 
 
+def _prepare(th, n, m, want_backward: bool) -> int:
+    """Token of the prepared tables of th (float32), or 0 when the prepared path does not apply."""
+    if th.dtype != torch.float32:
+        return 0
+    directions = binding.PREPARE_FORWARD | (binding.PREPARE_BACKWARD if want_backward else 0)
+    return binding.givens_prepare(th, n, m, directions)
+
+
+def _backward(token, th, Y, g, m, need_dx):
+    """dX, dtheta from the prepared tables when they are still there, else from the plain call."""
+    if token:
+        try:
+            return binding.givens_backward_prepared(token, Y, g, th.numel(), want_dx=need_dx)
+        except binding.GivensError as err:
+            if err.code != binding.ERR_STALE:
+                raise
+    if m is None:
+        return binding.givens_backward(th, Y, g, want_dx=need_dx)
+    return binding.givens_backward_restricted(th, Y, g, m, want_dx=need_dx)
+
+
 class _GivensApply(torch.autograd.Function):
     @staticmethod
     def forward(ctx, theta, X, m):
         th, x = theta.detach().contiguous(), X.detach().contiguous()
         n = x.shape[0]
         ctx.m = None if _plain(n, m) else (n - 1 if m is None else m)
-        Y = binding.givens_forward(th, x) if ctx.m is None else binding.givens_forward_restricted(th, x, ctx.m)
+        ctx.token = _prepare(th, n, ctx.m, any(ctx.needs_input_grad))
+        if ctx.token:
+            Y = binding.givens_forward_prepared(ctx.token, x)
+        else:
+            Y = binding.givens_forward(th, x) if ctx.m is None else binding.givens_forward_restricted(th, x, ctx.m)
         ctx.save_for_backward(theta, Y)
         return Y
 
@@ -34,10 +62,7 @@ class _GivensApply(torch.autograd.Function):
         theta, Y = ctx.saved_tensors
         need_dx = ctx.needs_input_grad[1]
         th, g = theta.detach().contiguous(), G.contiguous()
-        if ctx.m is None:
-            dX, dtheta = binding.givens_backward(th, Y, g, want_dx=need_dx)
-        else:
-            dX, dtheta = binding.givens_backward_restricted(th, Y, g, ctx.m, want_dx=need_dx)
+        dX, dtheta = _backward(ctx.token, th, Y, g, ctx.m, need_dx)
         return (dtheta if ctx.needs_input_grad[0] else None), (dX if need_dx else None), None
 
 
@@ -46,7 +71,11 @@ class _GivensMatrix(torch.autograd.Function):
     def forward(ctx, theta, n, m):
         th = theta.detach().contiguous()
         ctx.m = None if _plain(n, m) else (n - 1 if m is None else m)
-        U = binding.givens_build(th, n) if ctx.m is None else binding.givens_build_restricted(th, n, ctx.m)
+        ctx.token = _prepare(th, n, ctx.m, ctx.needs_input_grad[0])
+        if ctx.token:
+            U = binding.givens_build_prepared(ctx.token, n, th.device)
+        else:
+            U = binding.givens_build(th, n) if ctx.m is None else binding.givens_build_restricted(th, n, ctx.m)
         ctx.save_for_backward(theta, U)
         return U
 
@@ -55,10 +84,7 @@ class _GivensMatrix(torch.autograd.Function):
     def backward(ctx, G):
         theta, U = ctx.saved_tensors
         th, g = theta.detach().contiguous(), G.contiguous()
-        if ctx.m is None:
-            _, dtheta = binding.givens_backward(th, U, g, want_dx=False)
-        else:
-            _, dtheta = binding.givens_backward_restricted(th, U, g, ctx.m, want_dx=False)
+        _, dtheta = _backward(ctx.token, th, U, g, ctx.m, False)
         return dtheta, None, None
 
 
@@ -112,8 +138,26 @@ class OrthogonalLinear(torch.nn.Module):
         count = binding.num_angles(n, m)
         self.theta = torch.nn.Parameter(init_std * torch.randn(count, device=device, dtype=dtype))
 
+        self._eval_tables = None  # (token, version of theta, stream) of tables prepared for evaluation
+
     def forward(self, X: torch.Tensor) -> torch.Tensor:
-        return givens_apply(self.theta, X, self.m)
+        if torch.is_grad_enabled() or self.theta.dtype != torch.float32:
+            return givens_apply(self.theta, X, self.m)
+        # evaluation: the tables of the current theta are prepared once and reused until theta changes
+        key = (self.theta._version, self.theta.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        x = X.contiguous()
+        m = None if _plain(self.n, self.m) else (self.n - 1 if self.m is None else self.m)
+        for _ in range(2):
+            if self._eval_tables is None or self._eval_tables[1] != key:
+                token = binding.givens_prepare(self.theta.detach(), self.n, m, binding.PREPARE_FORWARD)
+                self._eval_tables = (token, key)
+            try:
+                return binding.givens_forward_prepared(self._eval_tables[0], x)
+            except binding.GivensError as err:
+                if err.code != binding.ERR_STALE:
+                    raise
+                self._eval_tables = None
+        raise RuntimeError("prepared tables were replaced twice in a row")
 
     def matrix(self) -> torch.Tensor:
         return givens_matrix(self.theta, self.n, self.m)

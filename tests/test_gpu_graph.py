@@ -22,11 +22,10 @@ def _gpu():
     binding.release()
 
 
-@pytest.mark.parametrize("n,B,dist,reduction", [(1024, 256, "normal0.1", "two_stage"), (512, 200, "uniform", "atomic"),
+@pytest.mark.parametrize("n,B,dist,reduction", [(1024, 256, "normal0.1", "two_stage"), (512, 200, "uniform", "two_stage"),
                                                 (256, 2048, "uniform", "gram"), (64, 4096, "uniform", "gram")])
 def test_forward_and_backward_replay_from_a_graph(n, B, dist, reduction):
-    mode = {"two_stage": binding.REDUCTION_TWO_STAGE, "atomic": binding.REDUCTION_ATOMIC,
-            "gram": binding.REDUCTION_GRAM}[reduction]
+    mode = {"two_stage": binding.REDUCTION_TWO_STAGE, "gram": binding.REDUCTION_GRAM}[reduction]
     binding.set_reduction(mode)
     data = inputs.make_custom(n, B, seed=500 + n, theta_dist=dist)
     theta = torch.from_numpy(data["theta"]).cuda()
@@ -38,7 +37,7 @@ def test_forward_and_backward_replay_from_a_graph(n, B, dist, reduction):
         binding.givens_forward(theta, X, Y=Y)
         binding.givens_backward(theta, Y, G, dX=dX, dtheta=dth)
 
-    run()                                                       # warms the workspace (and rocBLAS)
+    run()                                                       # warms the workspace
     run()
     torch.cuda.synchronize()
     want = [t.clone() for t in (Y, dX, dth)]
@@ -51,7 +50,6 @@ def test_forward_and_backward_replay_from_a_graph(n, B, dist, reduction):
         with torch.cuda.graph(graph, stream=side):
             run()
     torch.cuda.synchronize()
-    exact = reduction != "atomic"
     for replay in range(3):
         for t in (Y, dX, dth):
             t.fill_(float("nan"))
@@ -61,8 +59,4 @@ def test_forward_and_backward_replay_from_a_graph(n, B, dist, reduction):
         torch.cuda.synchronize()
         assert torch.isfinite(filler)
         for got, ref, name in zip((Y, dX, dth), want, ("Y", "dX", "dtheta")):
-            if exact or name != "dtheta":
-                assert torch.equal(got, ref), f"replay {replay}: {name} differs from the eager result"
-            else:
-                err = float((got - ref).norm() / ref.norm())
-                assert err <= 1e-5, f"replay {replay}: {name} off by {err}"
+            assert torch.equal(got, ref), f"replay {replay}: {name} differs from the eager result"

@@ -184,15 +184,14 @@ def test_carousel_family_sizes_with_3_5_6_7_wavefronts(n, B, seed, dist):
 
 
 @pytest.mark.parametrize("n,B,seed,dist,red", [
-    (132, 50, 131, "uniform", "two_stage"), (136, 300, 132, "normal0.1", "gram"), (200, 70, 133, "uniform", "atomic"),
+    (132, 50, 131, "uniform", "two_stage"), (136, 300, 132, "normal0.1", "gram"), (200, 70, 133, "uniform", "two_stage"),
     (300, 41, 134, "uniform", "two_stage"), (1000, 64, 135, "normal0.1", "two_stage"),
-    (1008, 33, 136, "uniform", "atomic"), (1040, 40, 137, "uniform", "two_stage"),
-    (2044, 24, 138, "uniform", "two_stage"), (2600, 20, 139, "normal0.1", "atomic"), (4088, 12, 140, "uniform", "two_stage")])
+    (1008, 33, 136, "uniform", "gram"), (1040, 40, 137, "uniform", "two_stage"),
+    (2044, 24, 138, "uniform", "two_stage"), (2600, 20, 139, "normal0.1", "gram"), (4088, 12, 140, "uniform", "two_stage")])
 def test_carousel_family_with_partly_filled_last_wavefront(n, B, seed, dist, red):
     """n = 2 M L with a lane count L that is not a multiple of 64: the spare lanes of the last wavefront idle."""
     data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
-    mode = {"two_stage": binding.REDUCTION_TWO_STAGE, "atomic": binding.REDUCTION_ATOMIC,
-            "gram": binding.REDUCTION_GRAM}[red]
+    mode = {"two_stage": binding.REDUCTION_TWO_STAGE, "gram": binding.REDUCTION_GRAM}[red]
     try:
         binding.set_reduction(mode)
         check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
@@ -292,28 +291,24 @@ def test_lifted_form_at_the_edges_of_the_angle_reduction():
         binding.set_rotation_form(binding.FORM_AUTO)
 
 
-# ---------------------------------------------------------------- the two cross-strip reductions
+# ---------------------------------------------------------------- the two-stage reduction is reproducible
 @pytest.mark.parametrize("n,B,seed,dist", [(256, 300, 71, "uniform"), (1024, 200, 72, "normal0.1"),
                                            (2048, 64, 73, "uniform")])
-def test_atomic_reduction_matches_the_oracle_and_the_two_stage_result(n, B, seed, dist):
+def test_two_stage_reduction_matches_the_oracle_and_is_bit_reproducible(n, B, seed, dist):
     data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
     binding.set_kernel(binding.KERNEL_CAROUSEL)
     th_d, g_d = dev(data["theta"]), dev(data["G"])
     y_d = binding.givens_forward(th_d, dev(data["X"]))
     want_dth, want_dx, _ = C.reverse_sweep(data["theta"], C.forward(data["theta"], data["X"]), data["G"])
-    got = {}
     try:
-        for mode in (binding.REDUCTION_TWO_STAGE, binding.REDUCTION_ATOMIC):
-            binding.set_reduction(mode)
-            dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
-            assert binding.last_reduction() == mode
-            got[mode] = host(dth_d)
-            assert O.rel_fro(got[mode], want_dth) <= TOL_G
-            assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
-        # two runs of the two-stage reduction are bit-identical
         binding.set_reduction(binding.REDUCTION_TWO_STAGE)
+        dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+        first = host(dth_d)
+        assert O.rel_fro(first, want_dth) <= TOL_G
+        assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
         _, again = binding.givens_backward(th_d, y_d, g_d)
-        assert np.array_equal(host(again), got[binding.REDUCTION_TWO_STAGE])
+        assert np.array_equal(host(again), first)
     finally:
         binding.set_reduction(binding.REDUCTION_AUTO)
         binding.set_kernel(binding.KERNEL_AUTO)
@@ -389,16 +384,6 @@ def test_lds_family_wide_batches_use_the_gram_form(n, B, seed):
     assert binding.last_reduction() == binding.REDUCTION_GRAM
     assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
     assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
-
-
-def test_atomic_reduction_falls_back_for_the_lds_family():
-    data = inputs.make_custom(34, 19, seed=74)
-    try:
-        binding.set_reduction(binding.REDUCTION_ATOMIC)
-        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_LDS, TOL_Y, TOL_G)
-        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
-    finally:
-        binding.set_reduction(binding.REDUCTION_AUTO)
 
 
 def test_largest_compiled_carousel_size_n8192():

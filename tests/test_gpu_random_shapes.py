@@ -40,7 +40,7 @@ def _cases():
             m = n - 1
         dist = ["uniform", "small", "huge"][int(rng.integers(0, 3))]
         form = [binding.FORM_AUTO, binding.FORM_AUTO, binding.FORM_STANDARD, binding.FORM_LIFTED][int(rng.integers(0, 4))]
-        red = [binding.REDUCTION_AUTO, binding.REDUCTION_TWO_STAGE, binding.REDUCTION_ATOMIC,
+        red = [binding.REDUCTION_AUTO, binding.REDUCTION_TWO_STAGE, binding.REDUCTION_TWO_STAGE,
                binding.REDUCTION_GRAM][int(rng.integers(0, 4))]
         out.append((idx, n, B, m, dist, form, red))
     return out

@@ -107,14 +107,14 @@ def test_carousel_family_restricted_and_odd_small_angles_use_the_scaled_form(n, 
           expect_form=binding.FORM_SCALED)
 
 
-def test_standard_form_and_atomic_reduction_with_a_restricted_problem():
+def test_standard_form_and_forced_two_stage_reduction_with_a_restricted_problem():
     try:
         binding.set_rotation_form(binding.FORM_STANDARD)
         check(511, 200, 50, 351, kernel=binding.KERNEL_CAROUSEL, expect_form=binding.FORM_STANDARD)
         binding.set_rotation_form(binding.FORM_AUTO)
-        binding.set_reduction(binding.REDUCTION_ATOMIC)
-        check(255, 77, 300, 352, kernel=binding.KERNEL_CAROUSEL)
-        assert binding.last_reduction() == binding.REDUCTION_ATOMIC
+        binding.set_reduction(binding.REDUCTION_TWO_STAGE)
+        check(255, 77, 1300, 352, kernel=binding.KERNEL_CAROUSEL)
+        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
     finally:
         binding.set_rotation_form(binding.FORM_AUTO)
         binding.set_reduction(binding.REDUCTION_AUTO)
