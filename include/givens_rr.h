@@ -127,12 +127,12 @@ int givens_forward_transposed_f64(int n, int64_t B, const double *theta, const d
  *   n even, 2 <= n <= GIVENS_NOALLOC_MAX_N (larger n: GIVENS_ERR_UNSUPPORTED, nothing launched); any B >= 1.
  *   All calls on one GPU share the array: calls that overlap on one GPU (two streams, two threads) race.
  *   Nothing in it needs clearing between calls: every word a call reads it has written first, except the
- *   range check's ticket counter, which is zero in a fresh array and which the range kernel itself puts back
- *   to zero before it ends.
+ *   flag word of the range check, which must start at zero: two words take turns, the array starts all zero,
+ *   and each call's range kernel zeroes the word the next call will use.
  *   Per-kernel timing (givens_set_timing) is not recorded for this call.
  */
 #define GIVENS_NOALLOC_MAX_N 1024
-#define GIVENS_NOALLOC_BYTES 8450048 /* flag area, table, row factors, renormalisation rows at n = 1024 */
+#define GIVENS_NOALLOC_BYTES 8446208 /* flag words, table, row factors, renormalisation rows at n = 1024 */
 int givens_forward_noalloc(int n, int64_t B, const float *theta, const float *X, float *Y, void *stream);
 
 /*

@@ -46,14 +46,16 @@ template <> struct Pair2<double> { using type = double2; };
 
 // flag <- bit pattern of max |theta| (non-negative floats order like unsigned integers; NaN sorts last).
 // theta is read as float4 where alignment allows; N is tiny next to the sweeps but this kernel sits
-// in front of every call, so it should run at memory speed.  No atomics on the result and no separate
-// reset: every workgroup leaves its maximum in `slots`, takes a ticket from `counter`, and the workgroup
-// that draws the last ticket combines the slots, writes the flag and puts the counter back to zero (the
-// counter is zero when the buffer is allocated, so it is zero before every launch).
+// in front of every call, so it should run at memory speed.  Atomics on one word serialise (some 10 ns
+// each: thousands of them cost more than reading theta), so the wavefronts of a workgroup combine
+// through LDS first and send one atomicMax per workgroup.  `flag` must be zero when the kernel starts: the
+// host alternates between two flag words from call to call, and each launch zeroes the word the next one
+// will use (`next_flag`; nothing reads that word any more: the call that used it is earlier in the stream).
 constexpr int kRangeBlocks = 512;
 __global__ __launch_bounds__(512) void theta_range_kernel(long long N, const float *__restrict__ theta,
-                                                          unsigned *slots, unsigned *counter, unsigned *flag)
+                                                          unsigned *flag, unsigned *next_flag)
 {
+    if (next_flag && blockIdx.x == 0 && threadIdx.x == 0) *next_flag = 0u;
     unsigned m = 0u;
     const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const long long nthreads = (long long)gridDim.x * blockDim.x;
@@ -76,40 +78,17 @@ __global__ __launch_bounds__(512) void theta_range_kernel(long long N, const flo
         m = other > m ? other : m;
     }
     __shared__ unsigned wave_max[16];
-    __shared__ unsigned ticket;
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) wave_max[wave] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
         const int waves = (blockDim.x + 63) >> 6;
         for (int w = 1; w < waves; ++w) m = wave_max[w] > m ? wave_max[w] : m;
-        __hip_atomic_store(&slots[blockIdx.x], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();                                  // the slot is visible before the ticket is drawn
-        ticket = atomicAdd(counter, 1u);
-    }
-    __syncthreads();
-    if (ticket != gridDim.x - 1) return;                  // uniform per workgroup
-    __threadfence();
-    // last workgroup: every other workgroup's slot was written before its ticket was drawn
-    unsigned best = 0u;
-    for (unsigned i = threadIdx.x; i < gridDim.x; i += blockDim.x) {
-        const unsigned v = __hip_atomic_load(&slots[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        best = v > best ? v : best;
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        const unsigned other = (unsigned)__shfl_xor((int)best, off, 64);
-        best = other > best ? other : best;
-    }
-    __syncthreads();                                      // wave_max is reused
-    if ((threadIdx.x & 63) == 0) wave_max[wave] = best;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const int waves = (blockDim.x + 63) >> 6;
-        for (int w = 1; w < waves; ++w) best = wave_max[w] > best ? wave_max[w] : best;
-        *flag = best;
-        *counter = 0u;
+        atomicMax(flag, m);
     }
 }
+// puts one flag word to zero (before the range check of givens_prepare, whose flag word is its own)
+__global__ void reset_flag_kernel(unsigned *flag) { *flag = 0u; }
 
 // sin and cos in float64 for |x| <= pi/4 (the only arguments the scaled form ever sees): plain
 // Taylor polynomials, no range reduction.  Truncation error below 1e-17 relative on that interval.
@@ -206,22 +185,32 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
     const int t1 = (t0 + kRenormPeriod < n - 1) ? t0 + kRenormPeriod : n - 1;
     double d = 1.0;
     int q = 0, p = 0;
+    // position of label r in the sequence of block k: 0 for r = 0, else 1 + (r - 1 + k) mod (n - 1); from one
+    // block of the sweep to the next it moves by one place round the ring of positions 1 .. n-1
+    const int k_first = FWD ? n - 2 - t0 : t0;
+    int q_load = (r == 0) ? 0 : 1 + (r - 1 + k_first) % (n - 1);
+    int q_use = q_load;
+    auto advance = [&](int pos) {
+        if (r == 0) return 0;
+        if (FWD) return pos == 1 ? n - 1 : pos - 1;      // k goes down
+        return pos == n - 1 ? 1 : pos + 1;               // k goes up
+    };
     for (int tb = t0; tb < t1; tb += kScanAhead) {
         float th[kScanAhead];
 #pragma unroll
         for (int u = 0; u < kScanAhead; ++u) {
             const int t = tb + u < t1 ? tb + u : t1 - 1;
             const int k = FWD ? n - 2 - t : t;
-            const int qq = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1); // position of label r in the sequence of block k
-            const int pp = (qq < H) ? qq : n - 1 - qq;
+            const int pp = (q_load < H) ? q_load : n - 1 - q_load;
             th[u] = theta_at(theta, map, mirror, n, (long long)k * H + pp);
+            if (tb + u < t1 - 1) q_load = advance(q_load);
         }
 #pragma unroll
         for (int u = 0; u < kScanAhead; ++u) {
             const int t = tb + u;
             if (t < t1) {
                 const int k = FWD ? n - 2 - t : t;
-                q = (r == 0) ? 0 : 1 + (r - 1 + k) % (n - 1);
+                q = q_use;
                 p = (q < H) ? q : n - 1 - q;
                 D[(long long)k * n + q] = (float)d;
                 if (form == kFormScaled) {
@@ -231,8 +220,10 @@ __global__ void scaled_scan_kernel(int n, const float *__restrict__ theta, const
                     (void)lift_reduce((double)th[u], &odd);
                     d = odd ? -d : d;
                 }
+                q_use = advance(q_use);
             }
         }
+        q_load = q_use;
     }
     renorm[2 * ((long long)g * H + p) + (q < H ? 0 : 1)] = (float)d;
 }

@@ -26,7 +26,7 @@ constexpr int kMaxWorkspacesPerDevice = 8;                     // streams with a
 constexpr size_t kLdsBudgetBytes = 144 * 1024;                 // of the 160 KB per CU on gfx950
 constexpr size_t kPartialCapBytes = size_t(24) << 30;          // cap on one chunk of strip partials
 constexpr int kMaxRows = 36864;                                // largest n any kernel family takes (one float column in LDS)
-constexpr size_t kFlagBytes = 4096;                            // flag word, ticket counter, per-workgroup slots
+constexpr size_t kFlagBytes = 256;                             // the flag words of a workspace
 
 struct Buffer {
     void *ptr = nullptr;
@@ -56,7 +56,9 @@ struct Prepared {
 struct Workspace {
     hipStream_t stream = nullptr;
     uint64_t last_use = 0;
-    Buffer flag;        // [0] bit pattern of max |theta|, [1] ticket counter, [64 ...] per-workgroup maxima
+    Buffer flag;        // three words holding the bit pattern of max |theta|: [0], [1] take turns from call to
+                        // call (each range check zeroes the other for the next call), [2] is givens_prepare's
+    int flag_turn = 0;  // which of [0], [1] the next range check uses
     Buffer scale;       // scaled / lifted forms: row factors d, float [n-1][n] (scratch of the coefficient kernels)
     CoefSet fwd, rev;   // forward sweep, reverse sweep
     CoefSet mirrored;   // forward-type sweep that computes dX = U^T G in the Gram form
@@ -333,7 +335,8 @@ template <typename T>
 struct CoefStorage {
     typename Pair2<T>::type *table = nullptr; // N pairs
     T *factor = nullptr;                      // reverse sweep only, N values
-    unsigned *flag = nullptr;                 // kFlagBytes: flag word, ticket counter, slots (float carousel path)
+    unsigned *flag = nullptr;                 // this call's flag word (float carousel path), zero before the call
+    unsigned *next_flag = nullptr;            // the word the next call will use (zeroed by this call), or nullptr
     float *scale = nullptr;                   // (n-1) * n row factors
     float *renorm = nullptr;                  // periods * n/2 pairs
 };
@@ -342,7 +345,7 @@ inline int renorm_periods(int n) { return (n - 1 + kRenormPeriod - 1) / kRenormP
 
 template <typename T>
 int workspace_coef_storage(Workspace &ws, CoefSet &set, int n, bool want_factor, bool try_forms, hipStream_t stream,
-                           CoefStorage<T> *out)
+                           CoefStorage<T> *out, bool for_prepare)
 {
     using P2 = typename Pair2<T>::type;
     const long long N = (long long)n * (n - 1) / 2;
@@ -355,11 +358,19 @@ int workspace_coef_storage(Workspace &ws, CoefSet &set, int n, bool want_factor,
     if (try_forms) {
         if (!ws.flag.ptr) {
             if (int rc = grow(ws.flag, kFlagBytes)) return rc;
-            GIVENS_HIP(hipMemsetAsync(ws.flag.ptr, 0, kFlagBytes, stream));   // the ticket counter starts at zero
+            GIVENS_HIP(hipMemsetAsync(ws.flag.ptr, 0, kFlagBytes, stream));   // every flag word starts at zero
         }
         if (int rc = grow(ws.scale, (size_t)(n - 1) * n * sizeof(float))) return rc;
         if (int rc = grow(set.renorm, (size_t)renorm_periods(n) * (n / 2) * sizeof(float2))) return rc;
-        out->flag = reinterpret_cast<unsigned *>(ws.flag.ptr);
+        unsigned *words = reinterpret_cast<unsigned *>(ws.flag.ptr);
+        if (for_prepare) {
+            out->flag = words + 2;                              // reset by prepare_impl before the range check
+            out->next_flag = nullptr;
+        } else {
+            out->flag = words + ws.flag_turn;
+            out->next_flag = words + (ws.flag_turn ^ 1);
+            ws.flag_turn ^= 1;
+        }
         out->scale = reinterpret_cast<float *>(ws.scale.ptr);
         out->renorm = reinterpret_cast<float *>(set.renorm.ptr);
     }
@@ -375,7 +386,7 @@ constexpr size_t noalloc_bytes(int n)
     return round_up_256(N * sizeof(float2))                                                // the table
            + round_up_256((size_t)(n - 1) * n * sizeof(float))                             // row factors
            + round_up_256((size_t)((n - 1 + kRenormPeriod - 1) / kRenormPeriod) * (n / 2) * sizeof(float2))
-           + kFlagBytes;                                                                   // flag, ticket, slots
+           + kFlagBytes;                                                                   // flag words
 }
 constexpr size_t kNoAllocBytes = noalloc_bytes(kNoAllocMaxN);
 static_assert(kNoAllocBytes == GIVENS_NOALLOC_BYTES, "the header states the size of the static array");
@@ -383,6 +394,7 @@ static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
 // Address of `scratch` on each device (every GPU holds its own copy of the array): looked up once per
 // device with that device current.  Host code uses these pointers, never the array's name.
 unsigned char *g_scratch_ptr[kMaxDevices] = {};
+int g_scratch_turn[kMaxDevices] = {};   // which of the array's two flag words the next call uses
 
 int static_coef_storage(int dev, int n, CoefStorage<float> *out)
 {
@@ -399,9 +411,12 @@ int static_coef_storage(int dev, int n, CoefStorage<float> *out)
         at += round_up_256(bytes);
         return here;
     };
-    // the flag area comes first: its place must not depend on n, because the ticket counter in it has to be
-    // zero at the start of every call and only the range kernel itself puts it back
-    out->flag = reinterpret_cast<unsigned *>(take(kFlagBytes));
+    // the flag words come first: their place must not depend on n, because the word a call uses has to be zero
+    // when the call starts and it is the call before that puts it to zero (a fresh array is all zero)
+    unsigned *words = reinterpret_cast<unsigned *>(take(kFlagBytes));
+    out->flag = words + g_scratch_turn[dev];
+    out->next_flag = words + (g_scratch_turn[dev] ^ 1);
+    g_scratch_turn[dev] ^= 1;
     out->table = reinterpret_cast<float2 *>(take(N * sizeof(float2)));
     out->scale = reinterpret_cast<float *>(take((size_t)(n - 1) * n * sizeof(float)));
     out->renorm = reinterpret_cast<float *>(take((size_t)renorm_periods(n) * (n / 2) * sizeof(float2)));
@@ -430,7 +445,7 @@ int build_coefs(const CoefStorage<T> &st, const Problem &pb, const T *theta, boo
                 const unsigned range_blocks =
                     (unsigned)std::min<long long>(kRangeBlocks, (pb.free_angles + 4095) / 4096);
                 hipLaunchKernelGGL(theta_range_kernel, dim3(range_blocks), dim3(512), 0, stream, pb.free_angles, theta,
-                                   flag + 64, flag + 1, flag);
+                                   flag, st.next_flag);
             }
             const long long scan_threads = (long long)renorm_periods(n) * n;
             const unsigned scan_blocks = (unsigned)((scan_threads + threads - 1) / threads);
@@ -458,13 +473,15 @@ int build_coefs(const CoefStorage<T> &st, const Problem &pb, const T *theta, boo
 }
 
 // the usual case: storage from a coefficient set of the workspace
+// for_prepare: the tables are givens_prepare's: they read its own flag word, which only givens_prepare writes
+// (range_known: an earlier build of the same givens_prepare call has made the range check already)
 template <typename T>
 int build_coefs(Workspace &ws, CoefSet &set, const Problem &pb, const T *theta, bool forward, FormPolicy policy,
-                hipStream_t stream, Coefs<T> *out, int mirror = 0, bool range_known = false)
+                hipStream_t stream, Coefs<T> *out, int mirror = 0, bool range_known = false, bool for_prepare = false)
 {
     CoefStorage<T> st;
-    if (int rc = workspace_coef_storage<T>(ws, set, pb.n, !forward,
-                                           policy.try_forms && std::is_same<T, float>::value, stream, &st))
+    const bool forms = policy.try_forms && std::is_same<T, float>::value;
+    if (int rc = workspace_coef_storage<T>(ws, set, pb.n, !forward, forms, stream, &st, for_prepare))
         return rc;
     return build_coefs<T>(st, pb, theta, forward, policy, stream, out, mirror, range_known);
 }
@@ -806,21 +823,29 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
     Coefs<float> c;
     bool range_known = false, mirrored_forms = false;
     const FormPolicy fpol = form_policy(ffam.carousel, opt.form), bpol = form_policy(bfam.carousel, opt.form);
-    if (fwd) {
-        if (int rc = build_coefs<float>(*ws, ws->fwd, pb, theta, true, fpol, stream, &c, 0, false)) return rc;
-        range_known = fpol.try_forms;
-    }
+    // one range check for all the sets, into the flag word that belongs to givens_prepare
+    auto build = [&](CoefSet &set, bool forward, FormPolicy pol, int mirror) {
+        if (pol.try_forms && !range_known) {
+            if (!ws->flag.ptr) {
+                if (int rc = grow(ws->flag, kFlagBytes)) return rc;
+                if (!hip_ok(hipMemsetAsync(ws->flag.ptr, 0, kFlagBytes, stream))) return (int)GIVENS_ERR_HIP;
+            }
+            hipLaunchKernelGGL(reset_flag_kernel, dim3(1), dim3(1), 0, stream, reinterpret_cast<unsigned *>(ws->flag.ptr) + 2);
+        }
+        const int rc = build_coefs<float>(*ws, set, pb, theta, forward, pol, stream, &c, mirror, range_known, true);
+        range_known = range_known || pol.try_forms;
+        return rc;
+    };
+    if (fwd)
+        if (int rc = build(ws->fwd, true, fpol, 0)) return rc;
     if (rev) {
-        if (int rc = build_coefs<float>(*ws, ws->rev, pb, theta, false, bpol, stream, &c, 0, range_known && bpol.try_forms))
-            return rc;
+        if (int rc = build(ws->rev, false, bpol, 0)) return rc;
         // the Gram form's dX sweep (wide batches) reads forward-type tables of the mirrored problem
         Families dx_fam;
         dx_fam.column = bfam.column;
         dx_fam.carousel = !bfam.column && bfam.carousel;
         const FormPolicy mpol = form_policy(dx_fam.carousel, opt.form);
-        if (int rc = build_coefs<float>(*ws, ws->mirrored, pb, theta, true, mpol, stream, &c, 1,
-                                        (range_known || bpol.try_forms) && mpol.try_forms))
-            return rc;
+        if (int rc = build(ws->mirrored, true, mpol, 1)) return rc;
         mirrored_forms = mpol.try_forms;
     }
     Prepared &p = ws->prepared;
@@ -844,7 +869,7 @@ Coefs<float> prepared_coefs(Workspace &ws, const CoefSet &set, bool reverse, boo
     c.factor = reverse ? reinterpret_cast<const float *>(set.factor.ptr) : nullptr;
     if (forms) {
         c.renorm = reinterpret_cast<const float2 *>(set.renorm.ptr);
-        c.flag = reinterpret_cast<const unsigned *>(ws.flag.ptr);
+        c.flag = reinterpret_cast<const unsigned *>(ws.flag.ptr) + 2;
         c.scaled_max = scaled_max;
     }
     t_state.last_flag = c.flag;
