@@ -1,20 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the round-robin Givens hot path on one MI355X.
 
-One "step" = one forward (cos/sin table + Algorithm-2 sweep, Y = U(theta) X) and one backward
-(table + reverse sweep + dtheta second-stage reduction, giving dX and dtheta) on the workload
-n = 4096, B = 4096, fp32, theta ~ N(0, 0.1^2), X, G ~ N(0, 1), all resident in HBM before the
-timed region.  `value` is Givens row-pair column updates per second over the whole step:
-N * B / (time of one step), N = n(n-1)/2 (one "update" = one rotation applied to one column in
-the forward pass; the backward pass does two rotations and one two-term product per update).
+One "step" = one forward (coefficient tables + Algorithm-2 sweep, Y = U(theta) X, or U itself for the
+workload whose operand is I_n) and one backward (tables + reverse sweep + dtheta reduction, giving dtheta
+and, unless the operand is I_n, dX), all inputs resident in HBM before the timed region.  `value` is Givens
+row-pair column updates per second over the whole step: N * B / (time of one step), N = n(n-1)/2 (one
+"update" = one rotation applied to one column in the forward pass; the backward pass does two rotations and
+one two-term product per update).
+
+Default workload: n = 4096, B = 4096, fp32, theta ~ N(0, 0.1^2), X, G ~ N(0, 1) (--workload 4).  The other
+workloads of the parity tests can be timed with --workload 1|2|3|5; --theta uniform draws the default
+workload's angles from U[-pi, pi) instead (general angles: the three-FMA rotation form) and --form standard
+switches the device-side choice of the rotation form off; --prepared times givens_prepare +
+givens_forward_prepared + givens_backward_prepared instead of the plain calls.
 
 Prints ONE JSON line.  Besides the contract fields it carries
-  roofline      forward sweep kernel against the vector-FP32 peak (6 flop per update)
-  roofline_bwd  reverse sweep kernel against the same peak (16 flop per update)
-  cpu_baseline  the fp64 C oracle (oracle/givens_oracle.c) timed on the host cores on the first
-                `sample` columns of the same workload
-Kernel durations come from HIP events that the library records on the launch stream around each
-kernel (givens_set_timing), during the timed steps themselves.
+  roofline      forward sweep kernel against the vector-FP32 peak (6 flop per update); `frac_with_tables`
+                counts the coefficient kernels of the forward call into the time
+  roofline_bwd  reverse sweep kernel(s) against the same peak (16 flop per update over the columns they sweep)
+  roofline_gram the Gram-matrix contraction against the dense float32 MFMA peak, when the backward call used it
+  cpu_baseline  the fp64 C oracle (oracle/givens_oracle.c) timed on the host cores on a bounded sample of
+                the same workload's columns
+Kernel durations come from HIP events that the library records on the launch stream around each group of
+kernels (givens_set_timing), during the timed steps themselves.
 """
 from __future__ import annotations
 
@@ -30,9 +38,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_VECTOR_TFLOPS = 157.3      # MI355X published vector FP32 peak (256 CU x 2.4 GHz x 256 flop/clk)
+PEAK_FP64_VECTOR_TFLOPS = 78.6       # same for FP64
+PEAK_FP32_MFMA_TFLOPS = 157.3        # dense float32 MFMA peak
 FWD_FLOP_PER_UPDATE = 6              # 4 mul + 2 add (Algorithm 1's two row updates)
 BWD_FLOP_PER_UPDATE = 16             # two transposed rotations (12) + two-term product and sum (4)
-CPU_SAMPLE_COLUMNS = 4096
+CPU_SAMPLE_UPDATES = 4.0e10          # the oracle's sample: about this many (pair, column) updates forward
 
 
 def _traffic_from_profiles(kernel_tag: str):
@@ -80,7 +90,8 @@ def _bench_unitary(args, binding, torch, np) -> int:
         "metric": "unitary_row_pair_complex_column_updates_per_s_fwd_bwd", "value": float(N) * B / (ms * 1e-3),
         "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "dtype": "c64", "data": "synthetic",
-        "config": {"workload": f"unitary_n{n}_B{B}_c64", "n": n, "B": B, "angles": 2 * N},
+        "config": {"workload": f"unitary_n{n}_B{B}_c64", "n": n, "B": B, "angles": 2 * N,
+                   "kernel_family": binding.last_kernel()},
         "kernel_ms": {"fwd_table": float(np.mean([t[0][0] for t in times])),
                       "fwd_sweep": float(np.mean([t[0][1] for t in times])),
                       "bwd_sweep": float(np.mean([t[1][1] for t in times])),
@@ -91,10 +102,18 @@ def _bench_unitary(args, binding, torch, np) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=4, choices=[2, 4, 5],
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=30,
+                    help="untimed steps first (the shader clock and the caches need some tens of launches to settle)")
+    ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5],
                     help="benchmark workload id (default 4: n=4096, B=4096)")
+    ap.add_argument("--theta", type=str, default=None, choices=["uniform", "normal0.1"],
+                    help="draw the workload's angles from this distribution instead of its own")
+    ap.add_argument("--form", type=str, default="auto", choices=["auto", "standard", "lifted"],
+                    help="rotation form of the float carousel kernels (auto: chosen on the device from max |theta|)")
+    ap.add_argument("--reduction", type=str, default="auto", choices=["auto", "two_stage", "gram"])
+    ap.add_argument("--prepared", action="store_true",
+                    help="step = givens_prepare + givens_forward_prepared + givens_backward_prepared (float32)")
     ap.add_argument("--restricted", type=str, default=None, metavar="ROWS,M",
                     help="time the restricted entry points instead: ROWS coordinates (may be odd), pairs (i, j) "
                          "with i < M free, the chosen workload's B and angle distribution; not the headline metric")
@@ -103,8 +122,8 @@ def main() -> int:
                          "short JSON line; not the headline metric")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
-                    help="after the steps, run one plain device copy of X into Y (n*B*4 bytes read and "
-                         "written) so that a rocprofv3 --pmc run has a kernel of known traffic to scale by")
+                    help="after the steps, run one plain device copy of G into a scratch tensor (n*B*4 bytes read "
+                         "and written) so that a rocprofv3 --pmc run has a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (columns of X shard trivially across GPUs; "
@@ -122,42 +141,68 @@ def main() -> int:
     torch.cuda.set_device(0)
     binding.lib()
     binding.set_kernel(binding.KERNEL_AUTO)
+    binding.set_rotation_form({"auto": binding.FORM_AUTO, "standard": binding.FORM_STANDARD,
+                               "lifted": binding.FORM_LIFTED}[args.form])
+    binding.set_reduction({"auto": binding.REDUCTION_AUTO, "two_stage": binding.REDUCTION_TWO_STAGE,
+                           "gram": binding.REDUCTION_GRAM}[args.reduction])
 
     if args.unitary:
         return _bench_unitary(args, binding, torch, np)
 
-    data = inputs.make_inputs(args.workload)
-    wl = data["workload"]
+    wl = inputs.WORKLOADS[args.workload]
     n, B = wl.n, wl.B
-    N = wl.num_angles
     name = wl.name
+    theta_dist = args.theta or wl.theta_dist
     restricted_m = None
     if args.restricted:
         n, restricted_m = (int(v) for v in args.restricted.split(","))
         data = inputs.make_restricted(n, restricted_m, B, seed=inputs.BASE_SEED + 100 + args.workload,
-                                      theta_dist=wl.theta_dist)
-        N = data["theta"].size
+                                      theta_dist=theta_dist)
         name = f"restricted_n{n}_m{restricted_m}_B{B}_f32"
         args.no_cpu_baseline = True
+    else:
+        data = inputs.make_inputs(args.workload)
+        if theta_dist != wl.theta_dist:
+            rng = np.random.default_rng(inputs.BASE_SEED + 50 + args.workload)
+            data["theta"] = inputs.draw_theta(rng, wl.num_angles, theta_dist, wl.np_dtype)
+            name += "_theta_" + theta_dist
+    if args.form != "auto":
+        name += "_form_" + args.form
+    identity = wl.x_identity and restricted_m is None
+    N = int(data["theta"].size)
     th_d = torch.from_numpy(data["theta"]).cuda()
-    x_d = torch.from_numpy(data["X"]).cuda()
+    x_d = None if identity else torch.from_numpy(data["X"]).cuda()
     g_d = torch.from_numpy(data["G"]).cuda()
-    y_d = torch.empty_like(x_d)
-    dx_d = torch.empty_like(x_d)
+    y_d = torch.empty_like(g_d)
+    dx_d = None if identity else torch.empty_like(g_d)
     dth_d = torch.empty_like(th_d)
+    prepared = args.prepared and wl.dtype == "f32"
 
     def step():
-        if restricted_m is None:
-            binding.givens_forward(th_d, x_d, Y=y_d)
-        else:
+        if prepared:
+            token = binding.givens_prepare(th_d, n, restricted_m, binding.PREPARE_FORWARD | (
+                binding.PREPARE_BACKWARD_WIDE if B >= 2 * n else binding.PREPARE_BACKWARD))
+            t_p = binding.last_timing()
+            if identity:
+                binding.givens_build_prepared(token, n, th_d.device, U=y_d)
+            else:
+                binding.givens_forward_prepared(token, x_d, Y=y_d)
+            t_f = binding.last_timing()
+            binding.givens_backward_prepared(token, y_d, g_d, N, dX=dx_d, dtheta=dth_d, want_dx=not identity)
+            t_b = binding.last_timing()
+            return (t_p[0] + t_f[0], t_f[1], 0.0, 0.0), t_b
+        if restricted_m is not None:
             binding.givens_forward_restricted(th_d, x_d, restricted_m, Y=y_d)
-        t_f = binding.last_timing()
-        if restricted_m is None:
-            binding.givens_backward(th_d, y_d, g_d, dX=dx_d, dtheta=dth_d)
-        else:
+            t_f = binding.last_timing()
             binding.givens_backward_restricted(th_d, y_d, g_d, restricted_m, dX=dx_d, dtheta=dth_d)
-        t_b = binding.last_timing()
-        return t_f, t_b
+            return t_f, binding.last_timing()
+        if identity:
+            binding.givens_build(th_d, n, U=y_d)
+        else:
+            binding.givens_forward(th_d, x_d, Y=y_d)
+        t_f = binding.last_timing()
+        binding.givens_backward(th_d, y_d, g_d, dX=dx_d, dtheta=dth_d, want_dx=not identity)
+        return t_f, binding.last_timing()
 
     binding.set_timing(True)
     for _ in range(args.warmup):
@@ -168,33 +213,36 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     binding.set_timing(False)
-    families = binding.last_kernel()
+    family = binding.last_kernel()
+    form = binding.last_rotation_form() if wl.dtype == "f32" else binding.FORM_STANDARD
+    reduction = binding.last_reduction()
+
+    if args.pmc_copy:
+        scratch = torch.empty_like(g_d)
+        scratch.copy_(g_d)
+        torch.cuda.synchronize()
+        del scratch
 
     ms_per_step = 1e3 * elapsed / args.steps
     updates = float(N) * float(B)
-    fwd_table = float(np.mean([t[0][0] for t in kernel_times]))
-    fwd_sweep = float(np.mean([t[0][1] for t in kernel_times]))
-    bwd_table = float(np.mean([t[1][0] for t in kernel_times]))
-    bwd_sweep = float(np.mean([t[1][1] for t in kernel_times]))
-    bwd_reduce = float(np.mean([t[1][2] for t in kernel_times]))
-
-    # one build (operand = I_n) outside the timed region, for the record
-    binding.set_timing(True)
-    u_d = torch.empty((n, n), dtype=torch.float32, device="cuda")
-    if restricted_m is None:
-        binding.givens_build(th_d, n, U=u_d)
-    else:
-        binding.givens_build_restricted(th_d, n, restricted_m, U=u_d)
-    build_ms = binding.last_timing()[1]
-    binding.set_timing(False)
-    del u_d
-
-    if args.pmc_copy:
-        y_d.copy_(x_d)
-        torch.cuda.synchronize()
+    mean = lambda which, slot: float(np.mean([t[which][slot] for t in kernel_times]))  # noqa: E731
+    fwd_table, fwd_sweep = mean(0, 0), mean(0, 1)
+    bwd_table, bwd_sweep, bwd_reduce, bwd_gram = mean(1, 0), mean(1, 1), mean(1, 2), mean(1, 3)
+    peak = PEAK_FP64_VECTOR_TFLOPS if wl.dtype == "f64" else PEAK_FP32_VECTOR_TFLOPS
+    family_name = {binding.KERNEL_LDS: "lds", binding.KERNEL_CAROUSEL: "carousel", binding.KERNEL_COLUMN: "column"}[family]
+    fwd_kernel = {"lds": "lds_forward_kernel", "carousel": "carousel_forward_kernel",
+                  "column": "column_forward_kernel"}[family_name]
+    bwd_kernel = "lds_backward_kernel" if family_name == "lds" else "carousel_backward_kernel"
 
     fwd_tflops = FWD_FLOP_PER_UPDATE * updates / (fwd_sweep * 1e-3) / 1e12
-    bwd_tflops = BWD_FLOP_PER_UPDATE * updates / (bwd_sweep * 1e-3) / 1e12
+    gram = reduction == binding.REDUCTION_GRAM
+    if gram:
+        # the sweeps of the Gram form: the reverse sweep over the n columns of C = Y G^T (16 flop per update) and,
+        # when dX is wanted, a forward-type sweep over the B columns of G (6 flop per update)
+        bwd_flops = BWD_FLOP_PER_UPDATE * float(N) * n + (0 if identity else FWD_FLOP_PER_UPDATE * updates)
+    else:
+        bwd_flops = BWD_FLOP_PER_UPDATE * updates
+    bwd_tflops = bwd_flops / (bwd_sweep * 1e-3) / 1e12
     result = {
         "metric": "givens_row_pair_column_updates_per_s_fwd_bwd",
         "value": updates / (ms_per_step * 1e-3),
@@ -206,36 +254,51 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": wl.dtype,
         "data": "synthetic",
-        "config": {"workload": name, "n": n, "B": B, "angles": N, "theta": wl.theta_dist,
-                   "step": "givens_forward + givens_backward", "kernel_family": families},
+        "config": {"workload": name, "n": n, "B": B, "angles": N, "theta": theta_dist,
+                   "step": ("givens_prepare + givens_forward_prepared + givens_backward_prepared" if prepared else
+                            ("givens_build" if identity else "givens_forward") + " + givens_backward"),
+                   "kernel_family": family_name,
+                   "rotation_form": {binding.FORM_STANDARD: "standard", binding.FORM_SCALED: "scaled",
+                                     binding.FORM_LIFTED: "lifted"}[form],
+                   "reduction": {binding.REDUCTION_TWO_STAGE: "two_stage", binding.REDUCTION_GRAM: "gram"}[reduction]},
         "fwd_updates_per_s": updates / ((fwd_table + fwd_sweep) * 1e-3),
         "fwd_ms": fwd_table + fwd_sweep,
-        "bwd_ms": bwd_table + bwd_sweep + bwd_reduce,
+        "bwd_ms": bwd_table + bwd_sweep + bwd_reduce + bwd_gram,
         "kernel_ms": {"fwd_table": fwd_table, "fwd_sweep": fwd_sweep, "bwd_table": bwd_table,
-                      "bwd_sweep": bwd_sweep, "bwd_reduce": bwd_reduce, "build_sweep": build_ms},
-        "roofline": {"kernel": "carousel_forward_kernel", "bound": "alu", "achieved": fwd_tflops,
-                     "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                     "frac": fwd_tflops / PEAK_FP32_VECTOR_TFLOPS,
-                     "traffic": _traffic_from_profiles(f"carousel_forward_{name}")},
-        "roofline_bwd": {"kernel": "carousel_backward_kernel", "bound": "alu", "achieved": bwd_tflops,
-                         "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                         "frac": bwd_tflops / PEAK_FP32_VECTOR_TFLOPS,
-                         "traffic": _traffic_from_profiles(f"carousel_backward_{name}")},
+                      "bwd_sweep": bwd_sweep, "bwd_reduce": bwd_reduce, "bwd_gram": bwd_gram},
+        "roofline": {"kernel": fwd_kernel, "bound": "alu", "achieved": fwd_tflops,
+                     "peak": peak, "unit": "TFLOP/s", "frac": fwd_tflops / peak,
+                     "frac_with_tables": FWD_FLOP_PER_UPDATE * updates / ((fwd_table + fwd_sweep) * 1e-3) / 1e12 / peak,
+                     "traffic": _traffic_from_profiles(f"{fwd_kernel.replace('_kernel', '')}_{name}")},
+        "roofline_bwd": {"kernel": bwd_kernel + (" (on C = Y G^T) + " + fwd_kernel + " (dX)" if gram and not identity
+                                                 else (" (on C = Y G^T)" if gram else "")),
+                         "bound": "alu", "achieved": bwd_tflops, "peak": peak, "unit": "TFLOP/s",
+                         "frac": bwd_tflops / peak,
+                         "traffic": _traffic_from_profiles(f"{bwd_kernel.replace('_kernel', '')}_{name}")},
     }
+    if gram and bwd_gram > 0:
+        gram_tflops = 2.0 * n * n * B / (bwd_gram * 1e-3) / 1e12
+        result["roofline_gram"] = {"kernel": "gram_tile_kernel", "bound": "mfma", "achieved": gram_tflops,
+                                   "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": gram_tflops / PEAK_FP32_MFMA_TFLOPS,
+                                   "traffic": _traffic_from_profiles(f"gram_tile_{name}")}
 
     if not args.no_cpu_baseline:
         from oracle import c_oracle
-        cols = min(CPU_SAMPLE_COLUMNS, B)
-        xs = np.ascontiguousarray(data["X"][:, :cols])
-        gs = np.ascontiguousarray(data["G"][:, :cols])
+        cols = int(max(1, min(B, CPU_SAMPLE_UPDATES // N)))
         pairs = c_oracle.schedule(n)
+        gs = np.ascontiguousarray(data["G"][:, :cols])
         t0 = time.perf_counter()
-        ys = c_oracle.forward(data["theta"], xs, pairs=pairs)
-        t_f = time.perf_counter() - t0
+        if identity:
+            ys = c_oracle.forward(data["theta"], None, n=n, pairs=pairs)[:, :cols]
+            t_f = (time.perf_counter() - t0) * cols / n     # the oracle builds all n columns of U
+        else:
+            ys = c_oracle.forward(data["theta"], np.ascontiguousarray(data["X"][:, :cols]), pairs=pairs)
+            t_f = time.perf_counter() - t0
         t0 = time.perf_counter()
-        c_oracle.reverse_sweep(data["theta"], ys, gs, pairs=pairs, want_x=False)
+        c_oracle.reverse_sweep(data["theta"], np.ascontiguousarray(ys), gs, pairs=pairs, want_x=False)
         t_b = time.perf_counter() - t0
         result["cpu_baseline"] = {
             "value": float(N) * cols / (t_f + t_b), "unit": "updates/s", "cores": c_oracle.num_threads(),
@@ -244,12 +307,13 @@ def main() -> int:
             "fwd_s": t_f, "bwd_s": t_b,
         }
         # the paper's own CPU baseline was single-threaded: the same forward on one thread, fewer columns
-        one_cols = min(64, cols)
-        t0 = time.perf_counter()
-        c_oracle.forward(data["theta"], np.ascontiguousarray(xs[:, :one_cols]), pairs=pairs, threads=1)
-        t_1 = time.perf_counter() - t0
-        result["cpu_baseline"]["fwd_1thread_updates_per_s"] = float(N) * one_cols / t_1
-        result["cpu_baseline"]["fwd_1thread_sample"] = f"forward on the first {one_cols} columns, 1 thread"
+        if not identity:
+            one_cols = min(64, cols)
+            t0 = time.perf_counter()
+            c_oracle.forward(data["theta"], np.ascontiguousarray(data["X"][:, :one_cols]), pairs=pairs, threads=1)
+            t_1 = time.perf_counter() - t0
+            result["cpu_baseline"]["fwd_1thread_updates_per_s"] = float(N) * one_cols / t_1
+            result["cpu_baseline"]["fwd_1thread_sample"] = f"forward on the first {one_cols} columns, 1 thread"
 
     print(json.dumps(result))
     return 0

@@ -165,11 +165,15 @@ int givens_backward_ex(int n, int m, int64_t B, const float *theta, const float 
  * direction was not prepared or lost, or which asks (through givens_set_kernel) for another kernel family
  * than the tables were built for returns GIVENS_ERR_STALE and launches nothing: call the plain entry point
  * instead.  The token must be used on the stream it was prepared on.
- *   directions : GIVENS_PREPARE_FORWARD, GIVENS_PREPARE_BACKWARD or both (or-ed).
+ *   directions : GIVENS_PREPARE_FORWARD, GIVENS_PREPARE_BACKWARD or both (or-ed).  GIVENS_PREPARE_BACKWARD_WIDE
+ *     (implies _BACKWARD) also builds the tables of the forward-type sweep that computes dX in the Gram form,
+ *     which the backward call takes for B >= 2 n; without it givens_backward_prepared runs the two-stage sweep
+ *     over all B columns whatever B is (and returns GIVENS_ERR_STALE if the Gram form is forced).
  *   n, m, B, X, Y, U, G, dX, dtheta : as for the plain calls; n and m are those of givens_prepare.
  */
 #define GIVENS_PREPARE_FORWARD 1
 #define GIVENS_PREPARE_BACKWARD 2
+#define GIVENS_PREPARE_BACKWARD_WIDE 4
 int64_t givens_prepare(int n, const float *theta, int directions, void *stream);
 int64_t givens_prepare_restricted(int n, int m, const float *theta, int directions, void *stream);
 int givens_forward_prepared(int64_t token, int64_t B, const float *X, float *Y, void *stream);
@@ -295,13 +299,13 @@ int givens_last_reduction(void);
 
 /*
  * Per-kernel timing.  givens_set_timing(1) makes every subsequent call record HIP events on the
- * caller's stream around each kernel it launches.  givens_last_timing() waits for the events of
+ * caller's stream around each group of kernels it launches.  givens_last_timing() waits for the events of
  * the last call on this thread and writes milliseconds: ms[0] = coefficient kernels (range check, tables),
- * ms[1] = sweep kernel(s), ms[2] = dtheta second-stage reduction (0 for forward/build).
- * Returns GIVENS_ERR_UNSUPPORTED if timing was off for that call.
+ * ms[1] = sweep kernel(s), ms[2] = dtheta second-stage reduction, ms[3] = Gram-matrix contraction and its
+ * slice sum (ms[2], ms[3]: 0 for forward/build).  Returns GIVENS_ERR_UNSUPPORTED if timing was off for that call.
  */
 int givens_set_timing(int on);
-int givens_last_timing(float ms[3]);
+int givens_last_timing(float ms[4]);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgivens_rr.so")
 KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL, KERNEL_COLUMN = 0, 1, 2, 3
 FORM_AUTO, FORM_STANDARD, FORM_SCALED, FORM_LIFTED = 0, 1, 2, 3
 REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_GRAM = 0, 1, 3
-PREPARE_FORWARD, PREPARE_BACKWARD = 1, 2
+PREPARE_FORWARD, PREPARE_BACKWARD, PREPARE_BACKWARD_WIDE = 1, 2, 4
 ERR_STALE = -8
 
 EXPORTS = [
@@ -477,10 +477,10 @@ def set_timing(on: bool) -> int:
 
 
 def last_timing():
-    """(table_ms, sweep_ms, reduce_ms) of the last call on this thread; waits for its events."""
-    buf = (ctypes.c_float * 3)()
+    """(table_ms, sweep_ms, reduce_ms, gram_ms) of the last call on this thread; waits for its events."""
+    buf = (ctypes.c_float * 4)()
     _check(lib().givens_last_timing(buf), "givens_last_timing")
-    return float(buf[0]), float(buf[1]), float(buf[2])
+    return float(buf[0]), float(buf[1]), float(buf[2]), float(buf[3])
 
 
 def release():

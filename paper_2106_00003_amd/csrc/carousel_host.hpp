@@ -64,10 +64,12 @@ inline bool carousel_backward_supported(int n, long long B)
     return std::is_same<T, float>::value && carousel_bwd_shape_for(n, &s);
 }
 
-// Columns per lane: the widest of {8,4,2,1} that still gives the chip about two wavefronts per SIMD.
+// Columns per lane of the forward sweep: the widest of {8,4,2,1} that still gives the chip about one wavefront
+// per SIMD (measured at n = 256 .. 2048, B = 256 .. 2048: at two per SIMD, the earlier rule, n = 2048 ran
+// 1.4 to 1.9 times slower; large batches reach 8 columns either way).
 inline int carousel_width(long long B, int waves)
 {
-    const long long want_waves = 2048; // 256 CUs x 4 SIMDs x 2
+    const long long want_waves = 1024; // 256 CUs x 4 SIMDs
     for (int w = 8; w > 1; w >>= 1)
         if (((B + w - 1) / w) * waves >= want_waves) return w;
     return 1;
@@ -128,12 +130,18 @@ inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &c
     }
 }
 
-// Columns per workgroup of the reverse sweep.
+// Columns per workgroup of the reverse sweep.  Fewer, wider strips mean fewer rows of partial sums to write,
+// add to and reduce, and a workgroup's time per block grows slowly with its width (a lone workgroup is bound
+// by the latency of its exchange, not by arithmetic): the widest of {8, 4, 2} that still gives the chip 512
+// wavefronts, and 2 below that (measured at n = 256 .. 2048, B = 256 .. 2048: 1.1 to 1.8 times faster than
+// the forward sweep's rule).
 inline int carousel_bwd_width(int n, long long B)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return 0;
-    return carousel_width(B, s.WAVES);
+    for (int w = 8; w > 2; w >>= 1)
+        if (((B + w - 1) / w) * s.WAVES >= 512) return w;
+    return B > 1 ? 2 : 1;
 }
 
 // Number of persistent workgroups the reverse sweep runs with: what the chip holds at once (the

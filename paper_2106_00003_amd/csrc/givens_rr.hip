@@ -44,7 +44,7 @@ struct CoefSet {
 struct Prepared {
     int64_t token = 0;       // 0: nothing prepared
     int rows = 0, m = 0;
-    bool fwd = false, rev = false;
+    bool fwd = false, rev = false, mirrored = false;
     // whether each set was built with the device-side choice of the rotation form (float carousel kernels
     // only can read such a set; a set built without it holds the standard form, which every family reads)
     bool fwd_forms = false, rev_forms = false, mirrored_forms = false;
@@ -739,7 +739,7 @@ int run_backward(Workspace &ws, int dev, const Problem &pb, long long B, const C
             if (int rc = grow(ws.gram, (size_t)slices * rows * rows * sizeof(float))) return rc;
             float *C = reinterpret_cast<float *>(ws.gram.ptr);
             {
-                Span span(1, stream);
+                Span span(3, stream);
                 gram_matrix(rows, B, slices, Y, G, C, stream);
                 GIVENS_HIP(hipGetLastError());
             }
@@ -799,9 +799,9 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
 {
     if (int rc = check_restricted(rows, m)) return rc;
     if (!theta) return GIVENS_ERR_NULL;
-    if (!(directions & (GIVENS_PREPARE_FORWARD | GIVENS_PREPARE_BACKWARD)) ||
-        (directions & ~(GIVENS_PREPARE_FORWARD | GIVENS_PREPARE_BACKWARD)))
-        return GIVENS_ERR_UNSUPPORTED;
+    constexpr int kAll = GIVENS_PREPARE_FORWARD | GIVENS_PREPARE_BACKWARD | GIVENS_PREPARE_BACKWARD_WIDE;
+    if (!(directions & kAll) || (directions & ~kAll)) return GIVENS_ERR_UNSUPPORTED;
+    if (directions & GIVENS_PREPARE_BACKWARD_WIDE) directions |= GIVENS_PREPARE_BACKWARD;
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
     std::lock_guard<std::mutex> lock(g_mutex);
     int dev = 0;
@@ -840,6 +840,9 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
         if (int rc = build(ws->fwd, true, fpol, 0)) return rc;
     if (rev) {
         if (int rc = build(ws->rev, false, bpol, 0)) return rc;
+    }
+    const bool wide = (directions & GIVENS_PREPARE_BACKWARD_WIDE) != 0;
+    if (wide) {
         // the Gram form's dX sweep (wide batches) reads forward-type tables of the mirrored problem
         Families dx_fam;
         dx_fam.column = bfam.column;
@@ -854,9 +857,10 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
     p.m = m;
     p.fwd = fwd;
     p.rev = rev;
+    p.mirrored = wide;
     p.fwd_forms = fwd && fpol.try_forms;
     p.rev_forms = rev && bpol.try_forms;
-    p.mirrored_forms = rev && mirrored_forms;
+    p.mirrored_forms = wide && mirrored_forms;
     p.scaled_max = form_policy(true, opt.form).scaled_max;
     return p.token;
 }
@@ -933,6 +937,11 @@ int backward_prepared_impl(int64_t token, long long B, const float *Y, const flo
     if (int rc = pick_backward_family<float>(pb.n, B, opt.kernel, &fam)) return rc;
     const Prepared prep = ws->prepared;
     if (prep.rev_forms && !fam.carousel) return GIVENS_ERR_STALE;         // another family than the one prepared for
+    if (!prep.mirrored) {
+        // no tables for the Gram form's dX sweep: the two-stage sweep over all B columns serves any B
+        if (opt.reduction == GIVENS_REDUCTION_GRAM) return GIVENS_ERR_STALE;
+        opt.reduction = GIVENS_REDUCTION_TWO_STAGE;
+    }
     const Coefs<float> coefs = prepared_coefs(*ws, ws->rev, true, prep.rev_forms, prep.scaled_max);
     auto mirrored_for_dx = [&](Families dx_fam, Coefs<float> *out) {
         if (prep.mirrored_forms && !dx_fam.carousel) return (int)GIVENS_ERR_STALE;
@@ -1344,18 +1353,18 @@ int givens_set_timing(int on)
     return prev;
 }
 
-int givens_last_timing(float ms[3])
+int givens_last_timing(float ms[4])
 {
     using namespace givens;
     if (!ms) return GIVENS_ERR_NULL;
     ThreadState &ts = t_state;
     if (!ts.timing_valid) return GIVENS_ERR_UNSUPPORTED;
-    ms[0] = ms[1] = ms[2] = 0.f;
+    ms[0] = ms[1] = ms[2] = ms[3] = 0.f;
     for (auto &s : ts.spans) {
         if (!hip_ok(hipEventSynchronize(s.stop))) return GIVENS_ERR_HIP;
         float t = 0.f;
         if (!hip_ok(hipEventElapsedTime(&t, s.start, s.stop))) return GIVENS_ERR_HIP;
-        if (s.category >= 0 && s.category < 3) ms[s.category] += t;
+        if (s.category >= 0 && s.category < 4) ms[s.category] += t;
     }
     return GIVENS_OK;
 }

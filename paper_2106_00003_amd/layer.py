@@ -21,11 +21,14 @@ def _plain(n: int, m) -> bool:
     return n % 2 == 0 and (m is None or m == n - 1)
 
 
-def _prepare(th, n, m, want_backward: bool) -> int:
+def _prepare(th, n, m, want_backward: bool, B: int) -> int:
     """Token of the prepared tables of th (float32), or 0 when the prepared path does not apply."""
     if th.dtype != torch.float32:
         return 0
-    directions = binding.PREPARE_FORWARD | (binding.PREPARE_BACKWARD if want_backward else 0)
+    directions = binding.PREPARE_FORWARD
+    if want_backward:
+        # wide batches take the Gram form, whose dX sweep needs tables of its own
+        directions |= binding.PREPARE_BACKWARD_WIDE if B >= 2 * (n + n % 2) else binding.PREPARE_BACKWARD
     return binding.givens_prepare(th, n, m, directions)
 
 
@@ -48,7 +51,7 @@ class _GivensApply(torch.autograd.Function):
         th, x = theta.detach().contiguous(), X.detach().contiguous()
         n = x.shape[0]
         ctx.m = None if _plain(n, m) else (n - 1 if m is None else m)
-        ctx.token = _prepare(th, n, ctx.m, any(ctx.needs_input_grad))
+        ctx.token = _prepare(th, n, ctx.m, any(ctx.needs_input_grad), x.shape[1])
         if ctx.token:
             Y = binding.givens_forward_prepared(ctx.token, x)
         else:
@@ -71,7 +74,7 @@ class _GivensMatrix(torch.autograd.Function):
     def forward(ctx, theta, n, m):
         th = theta.detach().contiguous()
         ctx.m = None if _plain(n, m) else (n - 1 if m is None else m)
-        ctx.token = _prepare(th, n, ctx.m, ctx.needs_input_grad[0])
+        ctx.token = _prepare(th, n, ctx.m, ctx.needs_input_grad[0], n)
         if ctx.token:
             U = binding.givens_build_prepared(ctx.token, n, th.device)
         else:

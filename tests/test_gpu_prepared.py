@@ -47,7 +47,8 @@ def test_prepared_calls_equal_the_plain_calls_and_the_oracle(n, B, seed, dist):
     u_ref = binding.givens_build(th_d, n)
     torch.cuda.synchronize()
 
-    token = binding.givens_prepare(th_d, n)
+    wide = binding.PREPARE_BACKWARD_WIDE if B >= 2 * n else binding.PREPARE_BACKWARD
+    token = binding.givens_prepare(th_d, n, directions=binding.PREPARE_FORWARD | wide)
     y = binding.givens_forward_prepared(token, x_d)
     assert binding.last_kernel() == family and binding.last_rotation_form() == form
     dx, dth = binding.givens_backward_prepared(token, y, g_d, th_d.numel())
@@ -65,6 +66,27 @@ def test_prepared_calls_equal_the_plain_calls_and_the_oracle(n, B, seed, dist):
     assert O.rel_fro(y.cpu().numpy(), want_y) <= TOL_Y
     assert O.rel_fro(dx.cpu().numpy(), want_dx) <= TOL_G
     assert O.rel_fro(dth.cpu().numpy(), want_dth) <= TOL_G
+
+
+def test_prepared_backward_without_the_wide_tables_runs_the_two_stage_sweep():
+    n, B = 256, 1100
+    data = inputs.make_custom(n, B, seed=607)
+    th_d, x_d, g_d = dev(data["theta"]), dev(data["X"]), dev(data["G"])
+    token = binding.givens_prepare(th_d, n)              # forward + backward, no tables for the Gram form's dX sweep
+    y = binding.givens_forward_prepared(token, x_d)
+    dx, dth = binding.givens_backward_prepared(token, y, g_d, th_d.numel())
+    assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+    want_y = C.forward(data["theta"], data["X"])
+    want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
+    assert O.rel_fro(dx.cpu().numpy(), want_dx) <= TOL_G
+    assert O.rel_fro(dth.cpu().numpy(), want_dth) <= TOL_G
+    try:
+        binding.set_reduction(binding.REDUCTION_GRAM)
+        with pytest.raises(binding.GivensError) as info:
+            binding.givens_backward_prepared(token, y, g_d, th_d.numel())
+        assert info.value.code == binding.ERR_STALE
+    finally:
+        binding.set_reduction(binding.REDUCTION_AUTO)
 
 
 def test_prepared_restricted_and_odd():
