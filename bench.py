@@ -112,14 +112,21 @@ def main() -> int:
     ap.add_argument("--form", type=str, default="auto", choices=["auto", "standard", "lifted"],
                     help="rotation form of the float carousel kernels (auto: chosen on the device from max |theta|)")
     ap.add_argument("--reduction", type=str, default="auto", choices=["auto", "two_stage", "gram"])
-    ap.add_argument("--prepared", action="store_true",
-                    help="step = givens_prepare + givens_forward_prepared + givens_backward_prepared (float32)")
+    ap.add_argument("--prepared", nargs="?", const="step", default=None, choices=["step", "frozen"],
+                    help="float32 only. step: a step is givens_prepare + givens_forward_prepared + "
+                         "givens_backward_prepared (angles change every step, as in training). frozen: the token is "
+                         "prepared once before the warmup and a step is the two prepared calls (angles fixed)")
     ap.add_argument("--restricted", type=str, default=None, metavar="ROWS,M",
                     help="time the restricted entry points instead: ROWS coordinates (may be odd), pairs (i, j) "
                          "with i < M free, the chosen workload's B and angle distribution; not the headline metric")
     ap.add_argument("--unitary", type=str, default=None, metavar="N,B",
                     help="time the unitary (complex) entry points on an N x B complex64 operand instead and print a "
                          "short JSON line; not the headline metric")
+    ap.add_argument("--enqueue-only", action="store_true",
+                    help="time the steps with the library's per-kernel event timing switched off, so that the host "
+                         "only enqueues (no wait between calls); the per-kernel figures then come from a second, "
+                         "untimed pass of at most 20 steps.  For the small workloads, where the host's wait after "
+                         "every call is a visible part of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="after the steps, run one plain device copy of G into a scratch tensor (n*B*4 bytes read "
@@ -176,35 +183,44 @@ def main() -> int:
     y_d = torch.empty_like(g_d)
     dx_d = None if identity else torch.empty_like(g_d)
     dth_d = torch.empty_like(th_d)
-    prepared = args.prepared and wl.dtype == "f32"
+    prepared = args.prepared if wl.dtype == "f32" else None
+    directions = binding.PREPARE_FORWARD | (binding.PREPARE_BACKWARD_WIDE if B >= 2 * n else binding.PREPARE_BACKWARD)
+    frozen_token = binding.givens_prepare(th_d, n, restricted_m, directions) if prepared == "frozen" else None
+
+    timing_on = [True]
+    zeros = (0.0, 0.0, 0.0, 0.0)
+    last_timing = lambda: binding.last_timing() if timing_on[0] else zeros  # noqa: E731
 
     def step():
         if prepared:
-            token = binding.givens_prepare(th_d, n, restricted_m, binding.PREPARE_FORWARD | (
-                binding.PREPARE_BACKWARD_WIDE if B >= 2 * n else binding.PREPARE_BACKWARD))
-            t_p = binding.last_timing()
+            if frozen_token is None:
+                token = binding.givens_prepare(th_d, n, restricted_m, directions)
+                t_p = last_timing()
+            else:
+                token, t_p = frozen_token, (0.0, 0.0, 0.0, 0.0)
             if identity:
                 binding.givens_build_prepared(token, n, th_d.device, U=y_d)
             else:
                 binding.givens_forward_prepared(token, x_d, Y=y_d)
-            t_f = binding.last_timing()
+            t_f = last_timing()
             binding.givens_backward_prepared(token, y_d, g_d, N, dX=dx_d, dtheta=dth_d, want_dx=not identity)
-            t_b = binding.last_timing()
+            t_b = last_timing()
             return (t_p[0] + t_f[0], t_f[1], 0.0, 0.0), t_b
         if restricted_m is not None:
             binding.givens_forward_restricted(th_d, x_d, restricted_m, Y=y_d)
-            t_f = binding.last_timing()
+            t_f = last_timing()
             binding.givens_backward_restricted(th_d, y_d, g_d, restricted_m, dX=dx_d, dtheta=dth_d)
-            return t_f, binding.last_timing()
+            return t_f, last_timing()
         if identity:
             binding.givens_build(th_d, n, U=y_d)
         else:
             binding.givens_forward(th_d, x_d, Y=y_d)
-        t_f = binding.last_timing()
+        t_f = last_timing()
         binding.givens_backward(th_d, y_d, g_d, dX=dx_d, dtheta=dth_d, want_dx=not identity)
-        return t_f, binding.last_timing()
+        return t_f, last_timing()
 
-    binding.set_timing(True)
+    timing_on[0] = not args.enqueue_only
+    binding.set_timing(timing_on[0])
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -212,6 +228,11 @@ def main() -> int:
     kernel_times = [step() for _ in range(args.steps)]
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    if args.enqueue_only:
+        timing_on[0] = True
+        binding.set_timing(True)
+        kernel_times = [step() for _ in range(min(args.steps, 20))]
+        torch.cuda.synchronize()
     binding.set_timing(False)
     family = binding.last_kernel()
     form = binding.last_rotation_form() if wl.dtype == "f32" else binding.FORM_STANDARD
@@ -257,8 +278,12 @@ def main() -> int:
         "dtype": wl.dtype,
         "data": "synthetic",
         "config": {"workload": name, "n": n, "B": B, "angles": N, "theta": theta_dist,
-                   "step": ("givens_prepare + givens_forward_prepared + givens_backward_prepared" if prepared else
-                            ("givens_build" if identity else "givens_forward") + " + givens_backward"),
+                   "step": ("givens_prepare + givens_forward_prepared + givens_backward_prepared" if prepared == "step"
+                            else "givens_forward_prepared + givens_backward_prepared (token prepared once)"
+                            if prepared == "frozen"
+                            else ("givens_build" if identity else "givens_forward") + " + givens_backward"),
+                   "host": ("enqueues only; kernel_ms from a second pass" if args.enqueue_only
+                            else "waits for each call's timing events"),
                    "kernel_family": family_name,
                    "rotation_form": {binding.FORM_STANDARD: "standard", binding.FORM_SCALED: "scaled",
                                      binding.FORM_LIFTED: "lifted"}[form],
