@@ -15,7 +15,10 @@
 // takes row l % 32 of the panel and the four columns 4 * (l / 32) + 8 j .. + 3 for j = 0, 1, so that the s-th
 // of the 8 MFMAs of a step (K = 2 each) contracts columns {8 j + s', 8 j + 4 + s'} (j = s / 4, s' = s % 4) --
 // a permutation of the step's 16 columns that is the same for both operands.  Rows of a panel are padded by
-// four floats in LDS (no bank conflicts measured).  41 KB of LDS and under 168 registers: three workgroups per
+// four floats in LDS: the operand reads are then free of bank conflicts; the 16-byte stores of the staging step
+// still collide a little (a third of the LDS cycles carry a conflict), hidden behind the MFMA pipe, which is busy
+// 93 % of the time.  An unpadded layout with the pieces of a row exchanged by two bits of the row number removes
+// those conflicts and measures 5 % slower (4.48 against 4.25 ms), so the padding stays.  41 KB of LDS and under 168 registers: three workgroups per
 // compute unit, so that one workgroup's staging and barrier hide behind the others' MFMAs (measured: steps of
 // 32 columns with two workgroups per compute unit 4.77 ms, this 4.5 ms at rows = 2048, B = 65536).
 // The contraction range is cut into `slices` (split-K): slice s writes its own rows x rows matrix and
