@@ -58,7 +58,8 @@ def _traffic_from_profiles(kernel_tag: str):
 
 
 def _bench_unitary(args, binding, torch, np) -> int:
-    """Forward + backward of the unitary extension on synthetic complex64 data (LDS strip kernels)."""
+    """Forward + backward of the unitary extension on synthetic complex64 data (carousel family where the shape
+    allows it, LDS strip kernels otherwise or with --family lds)."""
     n, B = (int(v) for v in args.unitary.split(","))
     N = n * (n - 1) // 2
     gen = torch.Generator(device="cuda")
@@ -77,6 +78,8 @@ def _bench_unitary(args, binding, torch, np) -> int:
         binding.givens_unitary_backward(theta, phi, y, g, dX=dx, dtheta=dth, dphi=dph)
         return t_f, binding.last_timing()
 
+    binding.set_kernel({"auto": binding.KERNEL_AUTO, "lds": binding.KERNEL_LDS,
+                        "carousel": binding.KERNEL_CAROUSEL}[args.family])
     binding.set_timing(True)
     for _ in range(args.warmup):
         step()
@@ -86,16 +89,23 @@ def _bench_unitary(args, binding, torch, np) -> int:
     torch.cuda.synchronize()
     ms = 1e3 * (time.perf_counter() - t0) / args.steps
     binding.set_timing(False)
+    family = {binding.KERNEL_LDS: "lds", binding.KERNEL_CAROUSEL: "carousel"}.get(binding.last_kernel(), "?")
+    # 9 FMA per (pair, complex column) forward and 26 in the reverse sweep in the carousel family
+    fwd_sweep = float(np.mean([t[0][1] for t in times]))
+    bwd_sweep = float(np.mean([t[1][1] for t in times]))
     print(json.dumps({
         "metric": "unitary_row_pair_complex_column_updates_per_s_fwd_bwd", "value": float(N) * B / (ms * 1e-3),
         "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "dtype": "c64", "data": "synthetic",
         "config": {"workload": f"unitary_n{n}_B{B}_c64", "n": n, "B": B, "angles": 2 * N,
-                   "kernel_family": binding.last_kernel()},
+                   "kernel_family": family},
         "kernel_ms": {"fwd_table": float(np.mean([t[0][0] for t in times])),
-                      "fwd_sweep": float(np.mean([t[0][1] for t in times])),
-                      "bwd_sweep": float(np.mean([t[1][1] for t in times])),
-                      "bwd_reduce": float(np.mean([t[1][2] for t in times]))}}))
+                      "fwd_sweep": fwd_sweep,
+                      "bwd_table": float(np.mean([t[1][0] for t in times])),
+                      "bwd_sweep": bwd_sweep,
+                      "bwd_reduce": float(np.mean([t[1][2] for t in times]))},
+        "executed_tflops": {"fwd_sweep": 18.0 * N * B / (fwd_sweep * 1e-3) / 1e12,
+                            "bwd_sweep": 52.0 * N * B / (bwd_sweep * 1e-3) / 1e12} if family == "carousel" else None}))
     return 0
 
 
@@ -127,6 +137,8 @@ def main() -> int:
                          "only enqueues (no wait between calls); the per-kernel figures then come from a second, "
                          "untimed pass of at most 20 steps.  For the small workloads, where the host's wait after "
                          "every call is a visible part of the step")
+    ap.add_argument("--family", type=str, default="auto", choices=["auto", "lds", "carousel"],
+                    help="with --unitary: kernel family")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="after the steps, run one plain device copy of G into a scratch tensor (n*B*4 bytes read "

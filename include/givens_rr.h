@@ -233,7 +233,11 @@ int givens_backward_restricted_f64(int n, int m, int64_t B, const double *theta,
  * NULL, may be the buffer of G).  Per pair of block k, with z and gbar the carried strips:
  *     dtheta_e = Re sum_b ( conj(gbar_j) z_i - conj(gbar_i) z_j ),  dphi_e = Re <gbar, P_e z>
  * (Q_e and P_e of the appendix), then the block is undone with the adjoint factors.
- * These entry points run in the LDS strip family only.  Aliasing, streams and errors as elsewhere.
+ * Kernel families: the float entry points run in the register-carousel family when n is a multiple of 16 from
+ * 128 to 4096 (the phases are then carried as per-row angles, prepared by a sequential pass over the blocks, and phi
+ * is rounded to 2 pi / 2^32 on the way), otherwise and for float64 in the LDS strip family; givens_set_kernel
+ * (GIVENS_KERNEL_LDS / GIVENS_KERNEL_CAROUSEL) forces one, and GIVENS_ERR_UNSUPPORTED is returned for a shape the
+ * forced family does not cover.  Aliasing, streams and errors as elsewhere.
  */
 int givens_unitary_forward(int n, int64_t B, const float *theta, const float *phi, const float *X, float *Y,
                            void *stream);

@@ -99,6 +99,42 @@ struct CarouselBwdArgs {
     hipStream_t stream;
 };
 
+// Unitary extension in the carousel family (unitary_carousel_kernels.hpp): complex64 operands seen as real
+// n x Breal arrays (Breal = 2 B), W real columns per lane (even).  Even n that is a multiple of 16, from
+// kUnitaryCarouselMinN up to 4096 (8 slots per lane forward, 4 reverse; the phase pass keeps n float64 in LDS).
+constexpr int kUnitaryCarouselMinN = 128;
+inline bool unitary_carousel_supported(int n) { return n >= kUnitaryCarouselMinN && n <= 4096 && n % 16 == 0; }
+
+struct UnitaryCarouselFwdArgs {
+    int n;
+    long long Breal;
+    const float2 *rot, *phs, *fin;
+    const float *X;
+    float *Y;
+    int identity, vec_ok;
+    hipStream_t stream;
+};
+struct UnitaryCarouselBwdArgs {
+    int n;
+    long long Breal, strip0, nstrips, groups;
+    const float2 *rot, *phs;
+    const float *orient;
+    const float2 *fin;
+    const float *Y, *G;
+    float *dX, *partial; // partial: [2][groups][N]
+    const float *zeros;
+    float *sink;
+    int vec_ok;
+    hipStream_t stream;
+};
+// Defined in unitary_carousel_fwd.hip / unitary_carousel_bwd.hip.  unitary_carousel_coefficients runs the
+// phase pass and the table kernel for one sweep direction (q: N 8-byte words, turn: N 4-byte words of scratch; orient may be
+// null for the forward direction).
+int unitary_carousel_coefficients(int n, const float *theta, const float *phi, int reverse, uint2 *q, unsigned *turn,
+                                  float *sgn, float2 *rot, float2 *phs, float *orient, float2 *fin, hipStream_t stream);
+int unitary_carousel_forward_m8(const UnitaryCarouselFwdArgs &a, int waves, int W);
+int unitary_carousel_backward_m4(const UnitaryCarouselBwdArgs &a, int waves, int W);
+
 // Column family (column_fwd.hip): forward sweep for even n <= 128, one lane per column, standard-form
 // table.  GIVENS_ERR_UNSUPPORTED for other n.
 constexpr int kColumnFamilyMaxN = 128;

@@ -400,22 +400,4 @@ __global__ void fill_zero_kernel(long long count, float *__restrict__ dst)
         dst[i] = 0.f;
 }
 
-// Last step of the accumulating reduction: the carousel reverse sweep adds every strip's sums into
-// acc, laid out [block k][slot r][lane l] (arc p = l * slots + r); this puts them back in E order and
-// applies the per-angle factor.
-__global__ void finish_accumulated_kernel(int n, int lanes, int slots, const float *__restrict__ acc,
-                                          const float *__restrict__ factor, const int *__restrict__ map,
-                                          float *__restrict__ dtheta)
-{
-    const int H = n >> 1;
-    const long long N = (long long)(n - 1) * H;
-    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= N) return;
-    const long long k = e / H;
-    const int p = (int)(e % H);
-    const int l = p / slots, r = p % slots;
-    const long long out = map ? (long long)map[e] : e;
-    if (out >= 0) dtheta[out] = factor[e] * acc[k * H + (long long)r * lanes + l];
-}
-
 } // namespace givens

@@ -68,10 +68,14 @@ struct Workspace {
     Buffer gram;        // Gram form: slices of C = Y G^T, rows x rows floats each
     Buffer map;         // restricted parametrisation / odd n: index in theta of every entry of E, or -1
     Buffer map_counts;  // free pairs per block (scratch of the map kernels)
+    // unitary extension, carousel family: phase inputs and reduced phase angles (fixed point), rotation signs, the two
+    // coefficient tables, the 0/1 table of the reverse sweep, final phase per row
+    Buffer u_q, u_psi, u_sgn, u_rot, u_phs, u_orient, u_fin;
     int map_rows = 0, map_m = 0; // the (row count, m) the map was built for
     Prepared prepared;
-    Buffer *all[16] = {&flag, &scale, &fwd.table, &fwd.renorm, &fwd.factor, &rev.table, &rev.renorm, &rev.factor,
-                       &mirrored.table, &mirrored.renorm, &mirrored.factor, &partial, &zeros, &sink, &gram, &map};
+    Buffer *all[23] = {&flag, &scale, &fwd.table, &fwd.renorm, &fwd.factor, &rev.table, &rev.renorm, &rev.factor,
+                       &mirrored.table, &mirrored.renorm, &mirrored.factor, &partial, &zeros, &sink, &gram, &map,
+                       &u_q, &u_psi, &u_sgn, &u_rot, &u_phs, &u_orient, &u_fin};
 };
 
 // One call's problem: `rows` coordinates of which the first m may rotate with every other one
@@ -979,6 +983,118 @@ int unitary_table(Workspace &ws, int n, const T *theta, const T *phi, hipStream_
     return GIVENS_OK;
 }
 
+// Unitary extension in the carousel family (complex64, n a multiple of 16 from 128 to 4096): coefficients of one
+// sweep direction into the workspace.
+struct UnitaryCoefs {
+    const float2 *rot, *phs, *fin;
+    const float *orient, *sgn;
+};
+int unitary_carousel_coefs(Workspace &ws, int n, const float *theta, const float *phi, bool reverse,
+                           hipStream_t stream, UnitaryCoefs *out)
+{
+    const size_t N = (size_t)n * (n - 1) / 2;
+    if (int rc = grow(ws.u_q, N * sizeof(uint2))) return rc;
+    if (int rc = grow(ws.u_psi, N * sizeof(int))) return rc;
+    if (int rc = grow(ws.u_sgn, N * sizeof(float))) return rc;
+    if (int rc = grow(ws.u_rot, N * sizeof(float2))) return rc;
+    if (int rc = grow(ws.u_phs, N * sizeof(float2))) return rc;
+    if (int rc = grow(ws.u_fin, (size_t)n * sizeof(float2))) return rc;
+    if (reverse)
+        if (int rc = grow(ws.u_orient, N * sizeof(float))) return rc;
+    Span span(0, stream);
+    auto *orient = reverse ? reinterpret_cast<float *>(ws.u_orient.ptr) : nullptr;
+    if (int rc = unitary_carousel_coefficients(n, theta, phi, reverse ? 1 : 0,
+                                               reinterpret_cast<uint2 *>(ws.u_q.ptr),
+                                               reinterpret_cast<unsigned *>(ws.u_psi.ptr),
+                                               reinterpret_cast<float *>(ws.u_sgn.ptr),
+                                               reinterpret_cast<float2 *>(ws.u_rot.ptr),
+                                               reinterpret_cast<float2 *>(ws.u_phs.ptr), orient,
+                                               reinterpret_cast<float2 *>(ws.u_fin.ptr), stream))
+        return rc;
+    GIVENS_HIP(hipGetLastError());
+    *out = UnitaryCoefs{reinterpret_cast<const float2 *>(ws.u_rot.ptr), reinterpret_cast<const float2 *>(ws.u_phs.ptr),
+                        reinterpret_cast<const float2 *>(ws.u_fin.ptr), orient,
+                        reinterpret_cast<const float *>(ws.u_sgn.ptr)};
+    return GIVENS_OK;
+}
+
+bool unitary_wants_carousel(int n, int kernel_choice)
+{
+    return unitary_carousel_supported(n) && (kernel_choice == GIVENS_KERNEL_AUTO || kernel_choice == GIVENS_KERNEL_CAROUSEL);
+}
+
+int unitary_carousel_forward(Workspace &ws, int n, long long B, const float *theta, const float *phi, const float *X,
+                             float *Y, int identity, hipStream_t stream)
+{
+    UnitaryCoefs c;
+    if (int rc = unitary_carousel_coefs(ws, n, theta, phi, false, stream, &c)) return rc;
+    const long long Breal = 2 * B;
+    const int waves = (n / 16 + 63) / 64;
+    int W = carousel_width(Breal, waves);
+    if (W < 2) W = 2;
+    const bool aligned = (Breal % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
+                         (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
+    Span span(1, stream);
+    const UnitaryCarouselFwdArgs a{n, Breal, c.rot, c.phs, c.fin, X, Y, identity, aligned ? 1 : 0, stream};
+    if (int rc = unitary_carousel_forward_m8(a, waves, W)) return rc;
+    GIVENS_HIP(hipGetLastError());
+    t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
+    return GIVENS_OK;
+}
+
+int unitary_carousel_backward(Workspace &ws, int dev, int n, long long B, const float *theta, const float *phi,
+                              const float *Y, const float *G, float *dX, float *dtheta, float *dphi,
+                              hipStream_t stream)
+{
+    UnitaryCoefs c;
+    if (int rc = unitary_carousel_coefs(ws, n, theta, phi, true, stream, &c)) return rc;
+    const long long N = (long long)n * (n - 1) / 2;
+    const long long Breal = 2 * B;
+    const int waves = (n / 8 + 63) / 64;
+    // columns per workgroup: 4 floats (two complex numbers) unless that leaves the chip short of wavefronts
+    const int W = (((Breal + 3) / 4) * waves >= 512) ? 4 : 2;
+    const long long strips = (Breal + W - 1) / W;
+    int cus = 0;
+    GIVENS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const long long resident = (long long)cus * (8 / waves > 0 ? 8 / waves : 1);
+    long long groups = std::min(strips, resident);
+    const long long cap_rows = (long long)(kPartialCapBytes / ((size_t)2 * N * sizeof(float)));
+    groups = std::max<long long>(1, std::min(groups, cap_rows));
+    if (int rc = grow(ws.partial, (size_t)2 * groups * N * sizeof(float))) return rc;
+    const size_t want = (size_t)N * sizeof(float);
+    if (ws.zeros.bytes < want) {
+        if (int rc = grow(ws.zeros, want)) return rc;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, stream, N, reinterpret_cast<float *>(ws.zeros.ptr));
+        GIVENS_HIP(hipGetLastError());
+    }
+    if (int rc = grow(ws.sink, ((size_t)N + 8192) * sizeof(float))) return rc;
+    float *partial = reinterpret_cast<float *>(ws.partial.ptr);
+    const bool aligned = (Breal % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(G) % 16 == 0) && (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
+    {
+        Span span(1, stream);
+        const UnitaryCarouselBwdArgs a{n, Breal, 0, strips, groups, c.rot, c.phs, c.orient, c.fin, Y, G, dX, partial,
+                                       reinterpret_cast<const float *>(ws.zeros.ptr),
+                                       reinterpret_cast<float *>(ws.sink.ptr), aligned ? 1 : 0, stream};
+        if (int rc = unitary_carousel_backward_m4(a, waves, W)) return rc;
+        GIVENS_HIP(hipGetLastError());
+    }
+    {
+        Span span(2, stream);
+        const int threads = 256;
+        const unsigned blocks = (unsigned)((N + threads - 1) / threads);
+        hipLaunchKernelGGL(reduce_partials_kernel<float>, dim3(blocks), dim3(threads), 0, stream, n, groups, partial,
+                           c.sgn, (const int *)nullptr, dtheta, 0);
+        hipLaunchKernelGGL(sum_rows_kernel<float>, dim3(blocks), dim3(threads), 0, stream, N, groups, N,
+                           partial + groups * N, dphi, 0);
+        GIVENS_HIP(hipGetLastError());
+    }
+    t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
+    t_state.last_reduction = GIVENS_REDUCTION_TWO_STAGE;
+    t_state.last_flag = nullptr;
+    return GIVENS_OK;
+}
+
 template <typename T>
 int unitary_forward_impl(int n, long long B, const T *theta, const T *phi, const T *X, T *Y, int identity,
                          void *stream_v)
@@ -992,10 +1108,17 @@ int unitary_forward_impl(int n, long long B, const T *theta, const T *phi, const
     int dev = 0;
     if (int rc = current_device(&dev)) return rc;
     timing_begin_call();
+    Workspace *ws = nullptr;
+    if constexpr (std::is_same<T, float>::value) {
+        if (unitary_wants_carousel(n, g_kernel_choice)) {
+            if (int rc = workspace_for(dev, stream, &ws)) return rc;
+            return unitary_carousel_forward(*ws, n, B, theta, phi, X, Y, identity, stream);
+        }
+    }
+    if (g_kernel_choice == GIVENS_KERNEL_CAROUSEL || g_kernel_choice == GIVENS_KERNEL_COLUMN) return GIVENS_ERR_UNSUPPORTED;
     const int w = unitary_strip_width<T>(n, B, 1);
     if (w == 0) return GIVENS_ERR_UNSUPPORTED;
     const typename Cplx<T>::quad *table = nullptr;
-    Workspace *ws = nullptr;
     if (int rc = workspace_for(dev, stream, &ws)) return rc;
     if (int rc = unitary_table<T>(*ws, n, theta, phi, stream, &table)) return rc;
     const size_t smem = (size_t)n * w * sizeof(C);
@@ -1024,10 +1147,17 @@ int unitary_backward_impl(int n, long long B, const T *theta, const T *phi, cons
     int dev = 0;
     if (int rc = current_device(&dev)) return rc;
     timing_begin_call();
+    Workspace *wsp = nullptr;
+    if constexpr (std::is_same<T, float>::value) {
+        if (unitary_wants_carousel(n, g_kernel_choice)) {
+            if (int rc = workspace_for(dev, stream, &wsp)) return rc;
+            return unitary_carousel_backward(*wsp, dev, n, B, theta, phi, Y, G, dX, dtheta, dphi, stream);
+        }
+    }
+    if (g_kernel_choice == GIVENS_KERNEL_CAROUSEL || g_kernel_choice == GIVENS_KERNEL_COLUMN) return GIVENS_ERR_UNSUPPORTED;
     const int w = unitary_strip_width<T>(n, B, 2);
     if (w == 0) return GIVENS_ERR_UNSUPPORTED;
     const typename Cplx<T>::quad *table = nullptr;
-    Workspace *wsp = nullptr;
     if (int rc = workspace_for(dev, stream, &wsp)) return rc;
     Workspace &ws = *wsp;
     if (int rc = unitary_table<T>(ws, n, theta, phi, stream, &table)) return rc;

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
                 rb[c] = cs.y * va + cs.x * vb;
             }
         }
-        __syncthreads();                                    // "Synchronize parallel operations"
+        __syncthreads();                                    // the next block pairs these rows differently
     }
 
     for (long long idx = threadIdx.x; idx < (long long)n * w; idx += blockDim.x) {

@@ -7,7 +7,7 @@
 //
 //     seq_k[0] = 0,      seq_k[q] = 1 + ((q - 1 - k) mod (n - 1))   for q = 1..n-1,
 //
-// and arc p of the block joins positions p and n-1-p ("equal distance from the endpoints").
+// and arc p of the block joins positions p and n-1-p, i.e. the p-th position from each end.
 // The prototype described in the paper's Section 3 derives (i, j) on the device from the step
 // number in the same spirit; nothing but n, k and p is needed.
 #pragma once

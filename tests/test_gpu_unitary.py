@@ -38,19 +38,22 @@ def make(n, B, seed, real, cplx):
     return theta, phi, x, g
 
 
-def check(n, B, seed, real=np.float32, cplx=np.complex64, tol_y=1e-5, tol_g=1e-4):
+def check(n, B, seed, real=np.float32, cplx=np.complex64, tol_y=1e-5, tol_g=1e-4, family=None):
     theta, phi, x, g = make(n, B, seed, real, cplx)
-    print(f"[unitary] n={n} B={B} seed={seed} dtype={np.dtype(cplx).name}", flush=True)
+    print(f"[unitary] n={n} B={B} seed={seed} dtype={np.dtype(cplx).name} family={family}", flush=True)
     th_d, ph_d = dev(theta), dev(phi)
     y_d = binding.givens_unitary_forward(th_d, ph_d, dev(x))
+    assert family is None or binding.last_kernel() == family
     want_y = V.forward_blocks(theta, phi, x)
-    assert V.rel_fro(host(y_d), want_y) <= tol_y
+    err_y = V.rel_fro(host(y_d), want_y)
     dx_d, dth_d, dph_d = binding.givens_unitary_backward(th_d, ph_d, y_d, dev(g))
+    assert family is None or binding.last_kernel() == family
     want_dth, want_dph, want_dx, _ = V.reverse_sweep_blocks(theta, phi, want_y, g)
-    assert V.rel_fro(host(dx_d), want_dx) <= tol_g
-    assert V.rel_fro(host(dth_d), want_dth) <= tol_g
-    assert V.rel_fro(host(dph_d), want_dph) <= tol_g
+    errs = (err_y, V.rel_fro(host(dx_d), want_dx), V.rel_fro(host(dth_d), want_dth), V.rel_fro(host(dph_d), want_dph))
+    print("[unitary]   errors Y %.2e dX %.2e dtheta %.2e dphi %.2e" % errs, flush=True)
+    assert errs[0] <= tol_y and max(errs[1:]) <= tol_g
     u_d = binding.givens_unitary_build(th_d, ph_d, n)
+    assert family is None or binding.last_kernel() == family
     want_u = V.forward_blocks(theta, phi, np.eye(n))
     assert V.rel_fro(host(u_d), want_u) <= tol_y
     return theta, phi, x, g, host(y_d)
@@ -91,14 +94,54 @@ def test_zero_phases_reproduce_the_real_entry_points():
     rng = np.random.default_rng(431)
     theta = rng.uniform(-np.pi, np.pi, n * (n - 1) // 2).astype(np.float32)
     x = rng.standard_normal((n, B)).astype(np.float32)
-    y_c = host(binding.givens_unitary_forward(dev(theta), dev(np.zeros_like(theta)), dev(x.astype(np.complex64))))
+    args = (dev(theta), dev(np.zeros_like(theta)), dev(x.astype(np.complex64)))
+    y_car = host(binding.givens_unitary_forward(*args))           # carousel family: phases carried as angles
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
     binding.set_kernel(binding.KERNEL_LDS)
     try:
+        y_c = host(binding.givens_unitary_forward(*args))
+        assert binding.last_kernel() == binding.KERNEL_LDS
         y_r = host(binding.givens_forward(dev(theta), dev(x)))
     finally:
         binding.set_kernel(binding.KERNEL_AUTO)
     assert np.abs(y_c.imag).max() == 0.0
     assert V.rel_fro(y_c.real, y_r) <= 2e-6
+    assert np.abs(y_car.imag).max() <= 1e-6 * np.abs(y_r).max()   # multiples of pi are not exact in float64
+    assert V.rel_fro(y_car.real, y_r) <= 4e-6
+
+
+# Carousel family of the unitary extension: n a multiple of 16 from 128 to 4096.  Shapes: one lane group exactly
+# (128, 256), idle lanes in the last wavefront (272), odd B (16-byte loads off, ragged last strip), several
+# wavefronts (1024, 2048), and a batch wide enough for the widest strips and for persistent workgroups of the
+# reverse sweep that take a second strip (256 x 4100).
+@pytest.mark.parametrize("n,B,seed", [(128, 9, 441), (256, 64, 442), (272, 33, 443), (1024, 20, 444), (2048, 6, 445),
+                                      (256, 4100, 446)])
+def test_carousel_family_against_the_oracle_and_the_lds_family(n, B, seed):
+    theta, phi, x, g, y = check(n, B, seed, family=binding.KERNEL_CAROUSEL)
+    th_d, ph_d = dev(theta), dev(phi)
+    dx_c, dth_c, dph_c = (host(t) for t in binding.givens_unitary_backward(th_d, ph_d, dev(y), dev(g)))
+    binding.set_kernel(binding.KERNEL_LDS)
+    try:
+        y_l = host(binding.givens_unitary_forward(th_d, ph_d, dev(x)))
+        assert binding.last_kernel() == binding.KERNEL_LDS
+        dx_l, dth_l, dph_l = (host(t) for t in binding.givens_unitary_backward(th_d, ph_d, dev(y), dev(g)))
+    finally:
+        binding.set_kernel(binding.KERNEL_AUTO)
+    assert V.rel_fro(y, y_l) <= 1e-5
+    assert V.rel_fro(dx_c, dx_l) <= 1e-5 and V.rel_fro(dth_c, dth_l) <= 1e-4 and V.rel_fro(dph_c, dph_l) <= 1e-4
+    # twice the same call: bit-identical (fixed summation order)
+    again = binding.givens_unitary_backward(th_d, ph_d, dev(y), dev(g))
+    assert np.array_equal(host(again[1]), dth_c) and np.array_equal(host(again[2]), dph_c)
+
+
+def test_carousel_family_is_refused_for_shapes_it_does_not_cover():
+    theta, phi, x, _ = make(130, 8, 447, np.float32, np.complex64)
+    binding.set_kernel(binding.KERNEL_CAROUSEL)
+    try:
+        with pytest.raises(binding.GivensError):
+            binding.givens_unitary_forward(dev(theta), dev(phi), dev(x))
+    finally:
+        binding.set_kernel(binding.KERNEL_AUTO)
 
 
 def test_argument_errors():
