@@ -134,6 +134,7 @@ int unitary_carousel_coefficients(int n, const float *theta, const float *phi, i
                                   float *sgn, float2 *rot, float2 *phs, float *orient, float2 *fin, hipStream_t stream);
 int unitary_carousel_forward_m8(const UnitaryCarouselFwdArgs &a, int waves, int W);
 int unitary_carousel_backward_m4(const UnitaryCarouselBwdArgs &a, int waves, int W);
+int unitary_carousel_backward_m2(const UnitaryCarouselBwdArgs &a, int waves, int W);
 
 // Column family (column_fwd.hip): forward sweep for even n <= 128, one lane per column, standard-form
 // table.  GIVENS_ERR_UNSUPPORTED for other n.

@@ -601,7 +601,13 @@ inline void unitary_carousel_launch_bwd(const UnitaryCarouselBwdArgs &a)
 template <int M, int WAVES>
 inline int unitary_carousel_bwd_widths(int W, const UnitaryCarouselBwdArgs &a)
 {
-    // 8 floats per lane and strip would need more registers than a lane has (it compiles with 340 bytes of scratch)
+    // with 4 slots per lane, 8 floats per slot and strip would need more registers than a lane has (it compiles
+    // with 340 bytes of scratch); with 2 slots they fit
+    if constexpr (M == 2)
+        if (W == 8) {
+            unitary_carousel_launch_bwd<M, 8, WAVES>(a);
+            return GIVENS_OK;
+        }
     switch (W) {
     case 4: unitary_carousel_launch_bwd<M, 4, WAVES>(a); return GIVENS_OK;
     case 2: unitary_carousel_launch_bwd<M, 2, WAVES>(a); return GIVENS_OK;

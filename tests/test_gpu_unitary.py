@@ -112,10 +112,11 @@ def test_zero_phases_reproduce_the_real_entry_points():
 
 # Carousel family of the unitary extension: n a multiple of 16 from 128 to 4096.  Shapes: one lane group exactly
 # (128, 256), idle lanes in the last wavefront (272), odd B (16-byte loads off, ragged last strip), several
-# wavefronts (1024, 2048), and a batch wide enough for the widest strips and for persistent workgroups of the
-# reverse sweep that take a second strip (256 x 4100).
+# wavefronts (1024, 2048), a batch wide enough for the widest strips and for persistent workgroups of the
+# reverse sweep that take a second strip (256 x 4100), and batches that put the reverse sweep into its shape with
+# two slots per lane and several wavefronts (1024 x 520, 2048 x 264; 256 x 4100 runs it with one wavefront).
 @pytest.mark.parametrize("n,B,seed", [(128, 9, 441), (256, 64, 442), (272, 33, 443), (1024, 20, 444), (2048, 6, 445),
-                                      (256, 4100, 446)])
+                                      (256, 4100, 446), (1024, 520, 447), (2048, 264, 448)])
 def test_carousel_family_against_the_oracle_and_the_lds_family(n, B, seed):
     theta, phi, x, g, y = check(n, B, seed, family=binding.KERNEL_CAROUSEL)
     th_d, ph_d = dev(theta), dev(phi)
@@ -135,7 +136,7 @@ def test_carousel_family_against_the_oracle_and_the_lds_family(n, B, seed):
 
 
 def test_carousel_family_is_refused_for_shapes_it_does_not_cover():
-    theta, phi, x, _ = make(130, 8, 447, np.float32, np.complex64)
+    theta, phi, x, _ = make(130, 8, 449, np.float32, np.complex64)
     binding.set_kernel(binding.KERNEL_CAROUSEL)
     try:
         with pytest.raises(binding.GivensError):
