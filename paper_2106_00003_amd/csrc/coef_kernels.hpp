@@ -368,7 +368,7 @@ __global__ __launch_bounds__(kMapThreads) void map_fill_kernel(int n, int rows, 
 // partial[s][e], in strip order (fixed order: reproducible).  The sweeps store
 // sum_b (g_bot z_top - g_top z_bot) of their stored values; `factor` carries the orientation sign
 // (with i < j the paper's term is gbar_j z_i - gbar_i z_j) and, in the scaled form, d_top * d_bot.
-// `map` (see theta_at): dtheta lists the free angles only; sums of bypassed pairs are dropped.
+// (factor == nullptr: 1).  `map` (see theta_at): dtheta lists the free angles only; sums of bypassed pairs are dropped.
 template <typename T>
 __global__ void reduce_partials_kernel(int n, long long nstrips, const T *__restrict__ partial,
                                        const T *__restrict__ factor, const int *__restrict__ map, T *dtheta,
@@ -389,7 +389,7 @@ __global__ void reduce_partials_kernel(int n, long long nstrips, const T *__rest
         a3 += partial[(s + 3) * N + e];
     }
     for (; s < nstrips; ++s) a0 += partial[s * N + e];
-    const T acc = ((a0 + a1) + (a2 + a3)) * factor[e];
+    const T acc = ((a0 + a1) + (a2 + a3)) * (factor ? factor[e] : T(1));
     dtheta[out] = accumulate ? dtheta[out] + acc : acc;
 }
 

@@ -1091,8 +1091,8 @@ int unitary_carousel_backward(Workspace &ws, int dev, int n, long long B, const 
         const unsigned blocks = (unsigned)((N + threads - 1) / threads);
         hipLaunchKernelGGL(reduce_partials_kernel<float>, dim3(blocks), dim3(threads), 0, stream, n, groups, partial,
                            c.sgn, (const int *)nullptr, dtheta, 0);
-        hipLaunchKernelGGL(sum_rows_kernel<float>, dim3(blocks), dim3(threads), 0, stream, N, groups, N,
-                           partial + groups * N, dphi, 0);
+        hipLaunchKernelGGL(reduce_partials_kernel<float>, dim3(blocks), dim3(threads), 0, stream, n, groups,
+                           partial + groups * N, (const float *)nullptr, (const int *)nullptr, dphi, 0);
         GIVENS_HIP(hipGetLastError());
     }
     t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
