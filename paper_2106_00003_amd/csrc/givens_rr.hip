@@ -183,8 +183,12 @@ int workspace_for(int dev, hipStream_t stream, Workspace **out)
     if (!w) return GIVENS_ERR_UNSUPPORTED;
     w->stream = stream;
     w->last_use = ++g_use_clock;
-    *out = w.get();
-    list.push_back(std::move(w));
+    try {
+        list.push_back(std::move(w));   // no exception may cross the C boundary
+    } catch (...) {
+        return GIVENS_ERR_UNSUPPORTED;
+    }
+    *out = list.back().get();
     return GIVENS_OK;
 }
 
@@ -204,9 +208,12 @@ hipEvent_t take_event()
 void timing_begin_call()
 {
     ThreadState &ts = t_state;
-    for (auto &s : ts.spans) {
-        ts.pool.push_back(s.start);
-        ts.pool.push_back(s.stop);
+    try {
+        for (auto &s : ts.spans) {
+            ts.pool.push_back(s.start);
+            ts.pool.push_back(s.stop);
+        }
+    } catch (...) {   // out of host memory: the events stay with their spans' records and are not reused
     }
     ts.spans.clear();
     ts.timing_valid = g_timing_on != 0;
@@ -230,7 +237,10 @@ struct Span {
     {
         if (!on) return;
         (void)hipEventRecord(rec.stop, stream);
-        t_state.spans.push_back(rec);
+        try {
+            t_state.spans.push_back(rec);
+        } catch (...) {   // out of host memory: this span is not reported
+        }
     }
 };
 
