@@ -7,7 +7,8 @@ namespace givens {
 template <bool REVERSE>
 static void launch_phase_scan(int n, const uint2 *q, unsigned *turn, float2 *fin, hipStream_t stream)
 {
-    // one thread per pair up to 1024 threads, then two pairs per thread (more pairs per thread measured slower)
+    // one thread per pair up to 1024 threads, then two pairs per thread (more pairs per thread measured slower: the pass is bound by the
+    // latency of its LDS round trip per pair, not by the barrier)
     const int H = n / 2;
     if (H <= kPhaseScanThreads)
         hipLaunchKernelGGL((unitary_phase_scan_kernel<REVERSE, 1>), dim3(1), dim3((H + 63) / 64 * 64), 0, stream, n, q,

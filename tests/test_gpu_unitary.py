@@ -54,8 +54,13 @@ def check(n, B, seed, real=np.float32, cplx=np.complex64, tol_y=1e-5, tol_g=1e-4
     assert errs[0] <= tol_y and max(errs[1:]) <= tol_g
     u_d = binding.givens_unitary_build(th_d, ph_d, n)
     assert family is None or binding.last_kernel() == family
-    want_u = V.forward_blocks(theta, phi, np.eye(n))
-    assert V.rel_fro(host(u_d), want_u) <= tol_y
+    # the oracle builds all n columns of U up to n = 1024 and a sample of them beyond (columns do not interact)
+    cols = np.arange(n) if n <= 1024 else np.unique(np.concatenate([[0, 1, n // 2, n - 1],
+                                                                   np.random.default_rng(seed).integers(0, n, 12)]))
+    want_u = V.forward_blocks(theta, phi, np.eye(n)[:, cols])
+    err_u = V.rel_fro(host(u_d)[:, cols], want_u)
+    print("[unitary]   U %.2e on %d columns" % (err_u, cols.size), flush=True)
+    assert err_u <= tol_y
     return theta, phi, x, g, host(y_d)
 
 
@@ -114,9 +119,10 @@ def test_zero_phases_reproduce_the_real_entry_points():
 # (128, 256), idle lanes in the last wavefront (272), odd B (16-byte loads off, ragged last strip), several
 # wavefronts (1024, 2048), a batch wide enough for the widest strips and for persistent workgroups of the
 # reverse sweep that take a second strip (256 x 4100), and batches that put the reverse sweep into its shape with
-# two slots per lane and several wavefronts (1024 x 520, 2048 x 264; 256 x 4100 runs it with one wavefront).
+# two slots per lane and several wavefronts (1024 x 520, 2048 x 264; 256 x 4100 runs it with one wavefront); the
+# largest n, where the phase pass takes two pairs per thread (4096 x 16).
 @pytest.mark.parametrize("n,B,seed", [(128, 9, 441), (256, 64, 442), (272, 33, 443), (1024, 20, 444), (2048, 6, 445),
-                                      (256, 4100, 446), (1024, 520, 447), (2048, 264, 448)])
+                                      (256, 4100, 446), (1024, 520, 447), (2048, 264, 448), (4096, 16, 450)])
 def test_carousel_family_against_the_oracle_and_the_lds_family(n, B, seed):
     theta, phi, x, g, y = check(n, B, seed, family=binding.KERNEL_CAROUSEL)
     th_d, ph_d = dev(theta), dev(phi)
@@ -133,6 +139,38 @@ def test_carousel_family_against_the_oracle_and_the_lds_family(n, B, seed):
     # twice the same call: bit-identical (fixed summation order)
     again = binding.givens_unitary_backward(th_d, ph_d, dev(y), dev(g))
     assert np.array_equal(host(again[1]), dth_c) and np.array_equal(host(again[2]), dph_c)
+
+
+def test_carousel_family_at_a_benchmark_size():
+    """n = B = 2048, the shape bench.py --unitary is quoted on: sampled columns of Y and dX against the oracle
+    (columns do not interact), all of dtheta and dphi against the LDS family, which the small cases pin."""
+    n, B = 2048, 2048
+    theta, phi, x, g = make(n, B, 451, np.float32, np.complex64)
+    print(f"[unitary] n={n} B={B} seed=451 full batch", flush=True)
+    th_d, ph_d = dev(theta), dev(phi)
+    y_d = binding.givens_unitary_forward(th_d, ph_d, dev(x))
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+    dx_d, dth_d, dph_d = binding.givens_unitary_backward(th_d, ph_d, y_d, dev(g))
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+    cols = np.unique(np.concatenate([[0, 1, 7, 8, B - 1, B - 2], np.random.default_rng(452).integers(0, B, 26)]))
+    want_y = V.forward_blocks(theta, phi, x[:, cols])
+    y = host(y_d)
+    err_y = V.rel_fro(y[:, cols], want_y)
+    want_dx = V.reverse_sweep_blocks(theta, phi, want_y, g[:, cols])[2]
+    err_dx = V.rel_fro(host(dx_d)[:, cols], want_dx)
+    binding.set_kernel(binding.KERNEL_LDS)
+    try:
+        y_l = binding.givens_unitary_forward(th_d, ph_d, dev(x))
+        _, dth_l, dph_l = binding.givens_unitary_backward(th_d, ph_d, y_d, dev(g))
+        assert binding.last_kernel() == binding.KERNEL_LDS
+    finally:
+        binding.set_kernel(binding.KERNEL_AUTO)
+    errs = (err_y, err_dx, V.rel_fro(y, host(y_l)), V.rel_fro(host(dth_d), host(dth_l)), V.rel_fro(host(dph_d), host(dph_l)))
+    print("[unitary]   Y %.2e dX %.2e (sampled columns, oracle); Y %.2e dtheta %.2e dphi %.2e (LDS family)" % errs,
+          flush=True)
+    assert errs[0] <= 1e-5 and errs[1] <= 1e-4 and errs[2] <= 1e-5 and errs[3] <= 1e-4 and errs[4] <= 1e-4
+    ny, nx = float(np.linalg.norm(y.astype(np.complex128))), float(np.linalg.norm(x.astype(np.complex128)))
+    assert abs(ny - nx) <= 2e-6 * nx
 
 
 def test_carousel_family_is_refused_for_shapes_it_does_not_cover():
