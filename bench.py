@@ -137,6 +137,10 @@ def main() -> int:
                          "only enqueues (no wait between calls); the per-kernel figures then come from a second, "
                          "untimed pass of at most 20 steps.  For the small workloads, where the host's wait after "
                          "every call is a visible part of the step")
+    ap.add_argument("--build", type=int, default=None, metavar="N",
+                    help="the paper's own experiment at size N: build U(theta) from N(N-1)/2 uniform random angles "
+                         "(givens_build) and take the gradient of a loss on U (dtheta-only givens_backward with a "
+                         "random N x N upstream gradient); workload 3 is this at N = 1024; not the headline metric")
     ap.add_argument("--family", type=str, default="auto", choices=["auto", "lds", "carousel"],
                     help="with --unitary: kernel family")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -169,8 +173,10 @@ def main() -> int:
         return _bench_unitary(args, binding, torch, np)
 
     wl = inputs.WORKLOADS[args.workload]
+    if args.build:
+        wl = inputs.Workload(3, args.build, args.build, "f32", "uniform", True)
     n, B = wl.n, wl.B
-    name = wl.name
+    name = wl.name if not args.build else f"build_n{n}_f32"
     theta_dist = args.theta or wl.theta_dist
     restricted_m = None
     if args.restricted:
@@ -179,6 +185,9 @@ def main() -> int:
                                       theta_dist=theta_dist)
         name = f"restricted_n{n}_m{restricted_m}_B{B}_f32"
         args.no_cpu_baseline = True
+    elif args.build:
+        data = inputs.make_custom(n, n, seed=inputs.BASE_SEED + 200 + (n % 997), theta_dist=theta_dist)
+        args.no_cpu_baseline = args.no_cpu_baseline or n > 2048
     else:
         data = inputs.make_inputs(args.workload)
         if theta_dist != wl.theta_dist:

@@ -52,9 +52,14 @@ inline bool carousel_supported(int n, long long B)
     return std::is_same<T, float>::value && carousel_shape_for(n, &s);
 }
 
-// shapes of the reverse sweep: two strips per lane, so at most 4 slots per lane (multiples of 4 up to
-// 2048, of 8 up to 4096)
-inline bool carousel_bwd_shape_for(int n, CarouselShape *out) { return carousel_shape_with(n, {4, 2}, out); }
+// shapes of the reverse sweep: two strips per lane, so 4 slots per lane where that covers n (multiples of 8 up
+// to 4096), 2 for the other multiples of 4 up to 2048, and 8 slots per lane with narrower strips for the
+// multiples of 16 beyond 4096, up to 8192
+inline bool carousel_bwd_shape_for(int n, CarouselShape *out)
+{
+    if (carousel_shape_with(n, {4, 2}, out)) return true;
+    return n > 4096 && carousel_shape_with(n, {8}, out);
+}
 
 template <typename T>
 inline bool carousel_backward_supported(int n, long long B)
@@ -149,6 +154,7 @@ int carousel_forward_m4(const CarouselFwdArgs &a, int waves, int W);
 int carousel_forward_m2(const CarouselFwdArgs &a, int waves, int W);
 int carousel_backward_m4(const CarouselBwdArgs &a, int waves, int W);
 int carousel_backward_m2(const CarouselBwdArgs &a, int waves, int W);
+int carousel_backward_m8(const CarouselBwdArgs &a, int waves, int W);
 
 inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
                             int identity, int mirror, hipStream_t stream)
@@ -176,7 +182,8 @@ inline int carousel_bwd_width(int n, long long B)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return 0;
-    for (int w = 8; w > 2; w >>= 1)
+    const int widest = s.M == 8 ? 4 : 8;       // 8 slots per lane: strips of at most 4 columns (registers)
+    for (int w = widest; w > 2; w >>= 1)
         if (((B + w - 1) / w) * s.WAVES >= 512) return w;
     return B > 1 ? 2 : 1;
 }
@@ -207,6 +214,7 @@ inline int carousel_backward_strips(int n, int rows, long long B, int W, long lo
     const CarouselBwdArgs a{n,  rows,    B,     strip0, nstrips,         groups,     coefs, Y, G,
                             dX, partial, zeros, sink,   aligned ? 1 : 0, g_identity, stream};
     switch (s.M) {
+    case 8: return carousel_backward_m8(a, s.WAVES, W);
     case 4: return carousel_backward_m4(a, s.WAVES, W);
     case 2: return carousel_backward_m2(a, s.WAVES, W);
     default: return GIVENS_ERR_UNSUPPORTED;

@@ -205,13 +205,19 @@ def test_carousel_family_with_partly_filled_last_wavefront(n, B, seed, dist, red
     binding.release()
 
 
-@pytest.mark.parametrize("n,B,seed", [(5120, 16, 25), (6144, 12, 26), (7168, 9, 27), (8176, 8, 28), (4112, 8, 29)])
-def test_forward_only_carousel_sizes_above_4096(n, B, seed):
-    data = inputs.make_custom(n, B, seed=seed)
-    binding.set_kernel(binding.KERNEL_AUTO)
-    y_d = binding.givens_forward(dev(data["theta"]), dev(data["X"]))
-    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
-    assert O.rel_fro(host(y_d), C.forward(data["theta"], data["X"])) <= TOL_Y
+@pytest.mark.parametrize("n,B,seed,dist", [(5120, 16, 25, "uniform"), (6144, 12, 26, "uniform"),
+                                           (7168, 9, 27, "normal0.1"), (8176, 8, 28, "uniform"),
+                                           (4112, 8, 29, "uniform"), (8192, 8, 30, "normal0.1"),
+                                           (4112, 1040, 31, "normal0.1")])
+def test_carousel_sizes_above_4096(n, B, seed, dist):
+    """Multiples of 16 beyond 4096: 8 slots per lane in both sweeps (5 to 8 wavefronts, the last one partly
+    filled at 4112 and 8176); 4112 x 1040 gives the reverse sweep's persistent workgroups a second strip."""
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    print(f"[parity] n={n} B={B} seed={seed} {dist}", flush=True)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
+                           binding.KERNEL_CAROUSEL)
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL      # the reverse sweep too
+    assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
     binding.release()
 
 
