@@ -637,7 +637,7 @@ int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, lo
             Span span(1, stream);
             if (!carousel) {
                 hipLaunchKernelGGL(kern, dim3((unsigned)ns), dim3(kLdsThreads), smem, stream, n, rows, B, w, s0,
-                                   coefs.table, Y, G, dX, partial, g_identity);
+                                   coefs.table, Y, G, dX, partial, g_identity, map);
             } else if constexpr (std::is_same<T, float>::value) {
                 if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.carousel(), Y, G, dX, partial,
                                                       zeros, sink, g_identity, stream))

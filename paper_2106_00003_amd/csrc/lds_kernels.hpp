@@ -15,6 +15,7 @@
 namespace givens {
 
 constexpr int kLdsThreads = 256;
+constexpr int kLdsAhead = 10;    // arcs per thread whose coefficients are fetched a block ahead (n <= 5120: all)
 
 // row stride of the strip in LDS: odd, so that consecutive rows fall in different banks
 __host__ __device__ inline int lds_row_stride(int w) { return w | 1; }
@@ -42,18 +43,43 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
     }
     __syncthreads();
 
-    for (int k = n - 2; k >= 0; --k) {                      // reversed(B)
-        for (int p = threadIdx.x; p < H; p += blockDim.x) { // the block's arcs: disjoint rows
-            const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-            const auto cs = table[(long long)k * H + p];
-            T *ra = strip + a * ldw;
-            T *rb = strip + b * ldw;
-            for (int c = 0; c < w; ++c) {
-                const T va = ra[c], vb = rb[c];
-                ra[c] = cs.x * va - cs.y * vb;
-                rb[c] = cs.y * va + cs.x * vb;
-            }
+    // One arc: rotate its two rows over the strip's columns.  Section 5 / odd n: a pair that is not a free
+    // parameter is bypassed, and its table entry is the identity.  Skipping every identity entry is exact (a free
+    // angle of exactly 0 rotates nothing) and lets wavefronts whose 64 arcs are all bypassed move on.
+    auto rotate = [&](int k, int p, typename Pair2<T>::type cs) {
+        if (cs.x == T(1) && cs.y == T(0)) return;
+        const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+        T *ra = strip + a * ldw;
+        T *rb = strip + b * ldw;
+        for (int c = 0; c < w; ++c) {
+            const T va = ra[c], vb = rb[c];
+            ra[c] = cs.x * va - cs.y * vb;
+            rb[c] = cs.y * va + cs.x * vb;
         }
+    };
+    // A thread's first kLdsAhead arcs of a block get their cos/sin a block ahead, in registers: a block is short
+    // (a few microseconds) and ends in a barrier, so a load issued inside it is waited for in full.
+    typename Pair2<T>::type ahead[kLdsAhead];
+    auto fetch = [&](int k) {
+#pragma unroll
+        for (int i = 0; i < kLdsAhead; ++i) {
+            const int p = threadIdx.x + i * kLdsThreads;
+            if (k >= 0 && p < H) ahead[i] = table[(long long)k * H + p];
+        }
+    };
+    fetch(n - 2);
+    for (int k = n - 2; k >= 0; --k) {                      // the blocks in reverse order (Algorithm 2)
+        typename Pair2<T>::type cur[kLdsAhead];
+#pragma unroll
+        for (int i = 0; i < kLdsAhead; ++i) cur[i] = ahead[i];
+        fetch(k - 1);
+#pragma unroll
+        for (int i = 0; i < kLdsAhead; ++i) {
+            const int p = threadIdx.x + i * kLdsThreads;
+            if (p < H) rotate(k, p, cur[i]);
+        }
+        for (int p = threadIdx.x + kLdsAhead * kLdsThreads; p < H; p += kLdsThreads)
+            rotate(k, p, table[(long long)k * H + p]);
         __syncthreads();                                    // the next block pairs these rows differently
     }
 
@@ -64,11 +90,12 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
     }
 }
 
-// Reverse sweep on strips [strip0, strip0 + gridDim.x).  partial is [gridDim.x][N].
+// Reverse sweep on strips [strip0, strip0 + gridDim.x).  partial is [gridDim.x][N].  map: nullptr, or the index
+// in theta of every entry of E (-1: bypassed pair).
 template <typename T>
 __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
     int n, int rows, long long B, int w, long long strip0, const typename Pair2<T>::type *__restrict__ table,
-    const T *Yin, const T *G, T *dX, T *__restrict__ partial, int g_identity)
+    const T *Yin, const T *G, T *dX, T *__restrict__ partial, int g_identity, const int *__restrict__ map)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int H = n >> 1;
@@ -92,23 +119,56 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
     }
     __syncthreads();
 
-    for (int k = 0; k <= n - 2; ++k) {                      // blocks b_1, b_2, ... in order
-        for (int p = threadIdx.x; p < H; p += blockDim.x) {
-            const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-            const auto cs = table[(long long)k * H + p];
-            T *za = z + a * ldw, *zb = z + b * ldw;
-            T *ga = gb + a * ldw, *gbb = gb + b * ldw;
-            T sum = T(0);
-            for (int c = 0; c < w; ++c) {
-                const T va = za[c], vb = zb[c], ua = ga[c], ub = gbb[c];
-                sum += ub * va - ua * vb;                   // gbar_bot z_top - gbar_top z_bot
-                za[c] = cs.x * va + cs.y * vb;              // transposed rotation
-                zb[c] = cs.x * vb - cs.y * va;
-                ga[c] = cs.x * ua + cs.y * ub;
-                gbb[c] = cs.x * ub - cs.y * ua;
+    // One arc: its share of dL/dtheta, then the transposed rotation of both strips' rows.  A bypassed pair
+    // (bypass: Section 5, odd n) has no gradient component and rotates nothing; its entry of the partial sums
+    // stays unwritten and the second stage drops it.  (A free angle of exactly 0 still needs its sum, so the
+    // coefficient alone does not decide here.)
+    auto undo = [&](int k, int p, typename Pair2<T>::type cs, bool bypass) {
+        if (bypass) return;
+        const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+        T *za = z + a * ldw, *zb = z + b * ldw;
+        T *ga = gb + a * ldw, *gbb = gb + b * ldw;
+        T sum = T(0);
+        for (int c = 0; c < w; ++c) {
+            const T va = za[c], vb = zb[c], ua = ga[c], ub = gbb[c];
+            sum += ub * va - ua * vb;                   // gbar_bot z_top - gbar_top z_bot
+            za[c] = cs.x * va + cs.y * vb;              // transposed rotation
+            zb[c] = cs.x * vb - cs.y * va;
+            ga[c] = cs.x * ua + cs.y * ub;
+            gbb[c] = cs.x * ub - cs.y * ua;
+        }
+        // the orientation sign is applied by the second-stage reduction (factor array)
+        mine[(long long)k * H + p] = sum;
+    };
+    // coefficients (and bypass marks) of a thread's first kLdsAhead arcs a block ahead, as in the forward kernel
+    // (the marks are kept as loaded and compared when used: a comparison here would wait for the load)
+    typename Pair2<T>::type ahead[kLdsAhead];
+    int mark_ahead[kLdsAhead];
+    auto fetch = [&](int k) {
+#pragma unroll
+        for (int i = 0; i < kLdsAhead; ++i) {
+            const int p = threadIdx.x + i * kLdsThreads;
+            if (k <= n - 2 && p < H) {
+                ahead[i] = table[(long long)k * H + p];
+                mark_ahead[i] = map ? map[(long long)k * H + p] : 0;
             }
-            // the orientation sign is applied by the second-stage reduction (factor array)
-            mine[(long long)k * H + p] = sum;
+        }
+    };
+    fetch(0);
+    for (int k = 0; k <= n - 2; ++k) {                      // blocks b_1, b_2, ... in order
+        typename Pair2<T>::type cur[kLdsAhead];
+        int mark[kLdsAhead];
+#pragma unroll
+        for (int i = 0; i < kLdsAhead; ++i) { cur[i] = ahead[i]; mark[i] = mark_ahead[i]; }
+        fetch(k + 1);
+#pragma unroll
+        for (int i = 0; i < kLdsAhead; ++i) {
+            const int p = threadIdx.x + i * kLdsThreads;
+            if (p < H) undo(k, p, cur[i], mark[i] < 0);
+        }
+        for (int p = threadIdx.x + kLdsAhead * kLdsThreads; p < H; p += kLdsThreads) {
+            const bool bypass = map && map[(long long)k * H + p] < 0;
+            if (!bypass) undo(k, p, table[(long long)k * H + p], false);
         }
         __syncthreads();
     }

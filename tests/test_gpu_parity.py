@@ -393,7 +393,7 @@ def test_lds_family_wide_batches_use_the_gram_form(n, B, seed):
 
 
 def test_largest_compiled_carousel_size_n8192():
-    """n = 8192 is the largest forward carousel shape; its reverse sweep runs in the LDS family."""
+    """n = 8192 is the largest carousel shape of both sweeps; the LDS family still takes it when asked."""
     n, B = 8192, 24
     data = inputs.make_custom(n, B, seed=79)
     binding.set_kernel(binding.KERNEL_AUTO)
@@ -403,10 +403,18 @@ def test_largest_compiled_carousel_size_n8192():
     want_y = C.forward(data["theta"], data["X"])
     assert O.rel_fro(host(y_d), want_y) <= TOL_Y
     dx_d, dth_d = binding.givens_backward(th_d, y_d, dev(data["G"]))
-    assert binding.last_kernel() == binding.KERNEL_LDS
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
     want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"], want_x=False)
     assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
     assert O.rel_fro(host(dth_d), want_dth) <= TOL_G
+    binding.set_kernel(binding.KERNEL_LDS)
+    try:
+        dx_l, dth_l = binding.givens_backward(th_d, y_d, dev(data["G"]))
+        assert binding.last_kernel() == binding.KERNEL_LDS
+    finally:
+        binding.set_kernel(binding.KERNEL_AUTO)
+    assert O.rel_fro(host(dx_l), want_dx) <= TOL_G
+    assert O.rel_fro(host(dth_l), want_dth) <= TOL_G
     binding.release()
 
 
