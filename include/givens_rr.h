@@ -56,11 +56,14 @@ extern "C" {
 #define GIVENS_KERNEL_COLUMN 3   /* float, n <= 128: one lane per column, all rows in its VGPRs */
 
 /* Rotation forms of the float carousel kernels (givens_set_rotation_form). */
-#define GIVENS_FORM_AUTO 0     /* decided on the device from max |theta|: scaled if <= pi/4, lifted if <= 1e6,  */
-                               /* standard otherwise (including NaN)                                          */
+#define GIVENS_FORM_AUTO 0     /* GIVENS_FORM_RANGE where the sweeps are long enough to pay for its extra       */
+                               /* coefficient work (n (n-1)/2 * B >= 1e9 updates; always in givens_prepare),    */
+                               /* GIVENS_FORM_STANDARD below that                                               */
 #define GIVENS_FORM_STANDARD 1 /* r_i = c U_i - s U_j, r_j = s U_i + c U_j exactly as in Algorithm 1         */
 #define GIVENS_FORM_SCALED 2   /* same rotations on rows kept divided by their accumulated cosines (2 FMAs)  */
 #define GIVENS_FORM_LIFTED 3   /* same rotations as three shears (3 FMAs), angles reduced modulo pi           */
+#define GIVENS_FORM_RANGE 4    /* decided on the device from max |theta|: scaled if <= pi/4, lifted if <= 1e6,  */
+                               /* standard otherwise (including NaN)                                          */
 
 /* How givens_backward sums the per-strip shares of dtheta (givens_set_reduction). */
 #define GIVENS_REDUCTION_AUTO 0      /* the library's default for the kernel family in use                     */

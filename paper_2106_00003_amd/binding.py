@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgivens_rr.so")
 
 KERNEL_AUTO, KERNEL_LDS, KERNEL_CAROUSEL, KERNEL_COLUMN = 0, 1, 2, 3
-FORM_AUTO, FORM_STANDARD, FORM_SCALED, FORM_LIFTED = 0, 1, 2, 3
+FORM_AUTO, FORM_STANDARD, FORM_SCALED, FORM_LIFTED, FORM_RANGE = 0, 1, 2, 3, 4
 REDUCTION_AUTO, REDUCTION_TWO_STAGE, REDUCTION_GRAM = 0, 1, 3
 PREPARE_FORWARD, PREPARE_BACKWARD, PREPARE_BACKWARD_WIDE = 1, 2, 4
 ERR_STALE = -8

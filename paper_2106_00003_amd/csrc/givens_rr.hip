@@ -336,12 +336,19 @@ struct FormPolicy {
     bool try_forms;
     float scaled_max;
 };
-FormPolicy form_policy(bool float_carousel, int form_choice)
+// `updates`: pair-column updates of the sweep the coefficients are for.  The scaled and lifted forms cost a range
+// check and a row-factor scan per direction (0.07 - 0.1 ms) and save arithmetic only where the sweep is bound by
+// it: measured, they pay from about n = B = 2048 (4.3e9 updates; 2.97 against 3.08 ms per step) and lose below
+// (n = B = 1024, 5.4e8: 0.98 against 0.92 ms; n = B = 256: 0.20 against 0.14 ms).
+constexpr double kFormsMinUpdates = 1.0e9;
+FormPolicy form_policy(bool float_carousel, int form_choice, double updates)
 {
     if (!float_carousel || form_choice == GIVENS_FORM_STANDARD) return {false, 0.f};
     if (form_choice == GIVENS_FORM_LIFTED) return {true, -1.f};
+    if (form_choice == GIVENS_FORM_AUTO && updates < kFormsMinUpdates) return {false, 0.f};
     return {true, kScaledMaxAbsTheta};
 }
+inline double sweep_updates(int n, long long B) { return 0.5 * (double)n * (double)(n - 1) * (double)B; }
 
 // Where the coefficient kernels of one sweep direction write: buffers of the workspace (grown on demand) or
 // pieces of the static scratch array of the entry point that may not allocate.
@@ -674,7 +681,7 @@ int options_from(const givens_options *o, CallOptions *out)
     if (!o) return GIVENS_OK;
     auto in = [](int v, std::initializer_list<int> ok) { return std::find(ok.begin(), ok.end(), v) != ok.end(); };
     if (!in(o->kernel, {GIVENS_KERNEL_AUTO, GIVENS_KERNEL_LDS, GIVENS_KERNEL_CAROUSEL, GIVENS_KERNEL_COLUMN}) ||
-        !in(o->rotation_form, {GIVENS_FORM_AUTO, GIVENS_FORM_STANDARD, GIVENS_FORM_LIFTED}) ||
+        !in(o->rotation_form, {GIVENS_FORM_AUTO, GIVENS_FORM_STANDARD, GIVENS_FORM_LIFTED, GIVENS_FORM_RANGE}) ||
         !in(o->reduction, {GIVENS_REDUCTION_AUTO, GIVENS_REDUCTION_TWO_STAGE, GIVENS_REDUCTION_GRAM}))
         return GIVENS_ERR_UNSUPPORTED;
     *out = CallOptions{o->kernel, o->rotation_form, o->reduction};
@@ -715,7 +722,7 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
     Families fam;
     if (int rc = pick_forward_family<T>(n, B, opt.kernel, &fam)) return rc;
     Coefs<T> coefs;
-    const FormPolicy policy = form_policy(fam.carousel && std::is_same<T, float>::value, opt.form);
+    const FormPolicy policy = form_policy(fam.carousel && std::is_same<T, float>::value, opt.form, sweep_updates(n, B));
     if (no_alloc) {
         if constexpr (std::is_same<T, float>::value) {
             CoefStorage<float> st;
@@ -798,11 +805,13 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
     invalidate_prepared(*ws, false, true);
     Coefs<T> coefs;
     if (int rc = build_coefs<T>(*ws, ws->rev, pb, theta, false,
-                                form_policy(fam.carousel && std::is_same<T, float>::value, opt.form), stream, &coefs))
+                                form_policy(fam.carousel && std::is_same<T, float>::value, opt.form, sweep_updates(n, B)),
+                                stream, &coefs))
         return rc;
     auto mirrored_for_dx = [&](Families dx_fam, Coefs<T> *out) {
         return build_coefs<T>(*ws, ws->mirrored, pb, theta, true,
-                              form_policy(dx_fam.carousel && std::is_same<T, float>::value, opt.form), stream, out, 1);
+                              form_policy(dx_fam.carousel && std::is_same<T, float>::value, opt.form, sweep_updates(n, B)),
+                              stream, out, 1);
     };
     return run_backward<T>(*ws, dev, pb, B, coefs, fam, opt, Y, G, dX, dtheta, stream, mirrored_for_dx);
 }
@@ -836,7 +845,9 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
     ws->prepared = Prepared{};
     Coefs<float> c;
     bool range_known = false, mirrored_forms = false;
-    const FormPolicy fpol = form_policy(ffam.carousel, opt.form), bpol = form_policy(bfam.carousel, opt.form);
+    // the batch is not known here: AUTO means GIVENS_FORM_RANGE
+    constexpr double kAnyBatch = 1.0e300;
+    const FormPolicy fpol = form_policy(ffam.carousel, opt.form, kAnyBatch), bpol = form_policy(bfam.carousel, opt.form, kAnyBatch);
     // one range check for all the sets, into the flag word that belongs to givens_prepare
     auto build = [&](CoefSet &set, bool forward, FormPolicy pol, int mirror) {
         if (pol.try_forms && !range_known) {
@@ -861,7 +872,7 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
         Families dx_fam;
         dx_fam.column = bfam.column;
         dx_fam.carousel = !bfam.column && bfam.carousel;
-        const FormPolicy mpol = form_policy(dx_fam.carousel, opt.form);
+        const FormPolicy mpol = form_policy(dx_fam.carousel, opt.form, kAnyBatch);
         if (int rc = build(ws->mirrored, true, mpol, 1)) return rc;
         mirrored_forms = mpol.try_forms;
     }
@@ -875,7 +886,7 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
     p.fwd_forms = fwd && fpol.try_forms;
     p.rev_forms = rev && bpol.try_forms;
     p.mirrored_forms = wide && mirrored_forms;
-    p.scaled_max = form_policy(true, opt.form).scaled_max;
+    p.scaled_max = form_policy(true, opt.form, kAnyBatch).scaled_max;
     return p.token;
 }
 
@@ -1464,7 +1475,8 @@ int givens_last_reduction(void) { return givens::t_state.last_reduction; }
 
 int givens_set_rotation_form(int which)
 {
-    if (which != GIVENS_FORM_AUTO && which != GIVENS_FORM_STANDARD && which != GIVENS_FORM_LIFTED)
+    if (which != GIVENS_FORM_AUTO && which != GIVENS_FORM_STANDARD && which != GIVENS_FORM_LIFTED &&
+        which != GIVENS_FORM_RANGE)
         return GIVENS_ERR_UNSUPPORTED;
     std::lock_guard<std::mutex> lock(givens::g_mutex);
     const int prev = givens::g_form_choice;

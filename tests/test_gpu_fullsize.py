@@ -121,6 +121,7 @@ def test_full_size_forward_backward_every_element(cfg):
     th, X, G = data["theta"], data["X"], data["G"]
     tag = f"config {cfg}"
     print(f"[fullsize] {tag}: n={n} B={B} seed={inputs.BASE_SEED + cfg}", flush=True)
+    binding.set_rotation_form(binding.FORM_AUTO)      # the library's default, as bench.py runs it
     th_d, x_d, g_d = (torch.from_numpy(a).cuda() for a in (th, X, G))
     want_form = binding.FORM_SCALED if wl.theta_dist == "normal0.1" else binding.FORM_LIFTED
     binding.set_reduction(binding.REDUCTION_AUTO)

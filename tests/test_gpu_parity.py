@@ -226,7 +226,7 @@ def test_carousel_sizes_above_4096(n, B, seed, dist):
 def test_scaled_form_is_used_for_small_angles_and_matches_the_oracle(n, B, seed):
     data = inputs.make_custom(n, B, seed=seed, theta_dist="normal0.1")
     assert float(np.abs(data["theta"]).max()) < 0.78
-    binding.set_rotation_form(binding.FORM_AUTO)
+    binding.set_rotation_form(binding.FORM_RANGE)
     check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G,
                            binding.KERNEL_CAROUSEL)
     assert binding.last_rotation_form() == binding.FORM_SCALED
@@ -235,7 +235,24 @@ def test_scaled_form_is_used_for_small_angles_and_matches_the_oracle(n, B, seed)
         check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G)
         assert binding.last_rotation_form() == binding.FORM_STANDARD
     finally:
-        binding.set_rotation_form(binding.FORM_AUTO)
+        binding.set_rotation_form(binding.FORM_RANGE)
+
+
+def test_default_form_follows_the_size_of_the_sweep():
+    """GIVENS_FORM_AUTO: the standard form below 1e9 updates (the scaled and lifted forms' extra coefficient work
+    does not pay there), the form the angles allow from there on; both against the oracle."""
+    small = inputs.make_custom(256, 64, seed=55, theta_dist="normal0.1")
+    large = inputs.make_custom(2048, 520, seed=56, theta_dist="normal0.1")       # 2.1e6 angles x 520 columns
+    binding.set_rotation_form(binding.FORM_AUTO)
+    try:
+        check_forward_backward(small["theta"], small["X"], small["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
+                               binding.KERNEL_CAROUSEL)
+        assert binding.last_rotation_form() == binding.FORM_STANDARD
+        check_forward_backward(large["theta"], large["X"], large["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
+                               binding.KERNEL_CAROUSEL)
+        assert binding.last_rotation_form() == binding.FORM_SCALED
+    finally:
+        binding.set_rotation_form(binding.FORM_RANGE)
 
 
 def test_rotation_form_switches_at_the_angle_threshold():
@@ -261,7 +278,7 @@ def test_rotation_form_switches_at_the_angle_threshold():
 @pytest.mark.parametrize("n,B,seed", [(256, 64, 81), (512, 100, 82), (1024, 67, 83), (2048, 130, 84)])
 def test_lifted_form_is_used_for_general_angles_and_matches_the_oracle(n, B, seed):
     data = inputs.make_custom(n, B, seed=seed)                         # theta uniform in [-pi, pi)
-    binding.set_rotation_form(binding.FORM_AUTO)
+    binding.set_rotation_form(binding.FORM_RANGE)
     check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G,
                            binding.KERNEL_CAROUSEL)
     assert binding.last_rotation_form() == binding.FORM_LIFTED
@@ -270,7 +287,7 @@ def test_lifted_form_is_used_for_general_angles_and_matches_the_oracle(n, B, see
         check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G)
         assert binding.last_rotation_form() == binding.FORM_STANDARD
     finally:
-        binding.set_rotation_form(binding.FORM_AUTO)
+        binding.set_rotation_form(binding.FORM_RANGE)
 
 
 def test_lifted_form_at_the_edges_of_the_angle_reduction():
@@ -294,7 +311,7 @@ def test_lifted_form_at_the_edges_of_the_angle_reduction():
         check_forward_backward(small["theta"], small["X"], small["G"], binding.KERNEL_CAROUSEL, TOL_Y, TOL_G)
         assert binding.last_rotation_form() == binding.FORM_LIFTED
     finally:
-        binding.set_rotation_form(binding.FORM_AUTO)
+        binding.set_rotation_form(binding.FORM_RANGE)
 
 
 # ---------------------------------------------------------------- the two-stage reduction is reproducible

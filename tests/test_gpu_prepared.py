@@ -184,11 +184,11 @@ def test_per_call_options():
     want_y = C.forward(th, X)
     want_dth, want_dx, _ = C.reverse_sweep(th, want_y, G)
     for kernel, expect in ((binding.KERNEL_LDS, binding.KERNEL_LDS), (binding.KERNEL_CAROUSEL, binding.KERNEL_CAROUSEL)):
-        for form in (binding.FORM_AUTO, binding.FORM_STANDARD):
+        for form in (binding.FORM_RANGE, binding.FORM_STANDARD):
             y = binding.givens_forward_ex(th_d, x_d, kernel=kernel, form=form)
             assert binding.last_kernel() == expect
             if expect == binding.KERNEL_CAROUSEL:
-                assert binding.last_rotation_form() == (binding.FORM_LIFTED if form == binding.FORM_AUTO else binding.FORM_STANDARD)
+                assert binding.last_rotation_form() == (binding.FORM_LIFTED if form == binding.FORM_RANGE else binding.FORM_STANDARD)
             assert O.rel_fro(y.cpu().numpy(), want_y) <= TOL_Y
             for red in (binding.REDUCTION_TWO_STAGE, binding.REDUCTION_GRAM):
                 dx, dth = binding.givens_backward_ex(th_d, y, g_d, kernel=kernel, form=form, reduction=red)

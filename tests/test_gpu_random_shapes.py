@@ -19,7 +19,7 @@ def _gpu():
     binding.lib()
     yield
     binding.set_kernel(binding.KERNEL_AUTO)
-    binding.set_rotation_form(binding.FORM_AUTO)
+    binding.set_rotation_form(binding.FORM_RANGE)
     binding.set_reduction(binding.REDUCTION_AUTO)
     binding.release()
 
@@ -39,7 +39,7 @@ def _cases():
         if n % 2 and not restricted:
             m = n - 1
         dist = ["uniform", "small", "huge"][int(rng.integers(0, 3))]
-        form = [binding.FORM_AUTO, binding.FORM_AUTO, binding.FORM_STANDARD, binding.FORM_LIFTED][int(rng.integers(0, 4))]
+        form = [binding.FORM_RANGE, binding.FORM_RANGE, binding.FORM_STANDARD, binding.FORM_LIFTED][int(rng.integers(0, 4))]
         red = [binding.REDUCTION_AUTO, binding.REDUCTION_TWO_STAGE, binding.REDUCTION_TWO_STAGE,
                binding.REDUCTION_GRAM][int(rng.integers(0, 4))]
         out.append((idx, n, B, m, dist, form, red))

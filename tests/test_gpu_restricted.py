@@ -20,10 +20,10 @@ def _gpu():
         pytest.skip("no GPU")
     binding.lib()
     binding.set_kernel(binding.KERNEL_AUTO)
-    binding.set_rotation_form(binding.FORM_AUTO)
+    binding.set_rotation_form(binding.FORM_RANGE)
     yield
     binding.set_kernel(binding.KERNEL_AUTO)
-    binding.set_rotation_form(binding.FORM_AUTO)
+    binding.set_rotation_form(binding.FORM_RANGE)
     binding.release()
 
 
@@ -111,12 +111,12 @@ def test_standard_form_and_forced_two_stage_reduction_with_a_restricted_problem(
     try:
         binding.set_rotation_form(binding.FORM_STANDARD)
         check(511, 200, 50, 351, kernel=binding.KERNEL_CAROUSEL, expect_form=binding.FORM_STANDARD)
-        binding.set_rotation_form(binding.FORM_AUTO)
+        binding.set_rotation_form(binding.FORM_RANGE)
         binding.set_reduction(binding.REDUCTION_TWO_STAGE)
         check(255, 77, 1300, 352, kernel=binding.KERNEL_CAROUSEL)
         assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
     finally:
-        binding.set_rotation_form(binding.FORM_AUTO)
+        binding.set_rotation_form(binding.FORM_RANGE)
         binding.set_reduction(binding.REDUCTION_AUTO)
 
 
