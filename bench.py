@@ -206,7 +206,7 @@ def main() -> int:
     dth_d = torch.empty_like(th_d)
     prepared = args.prepared if wl.dtype == "f32" else None
     directions = binding.PREPARE_FORWARD | (binding.PREPARE_BACKWARD_WIDE if B >= 2 * n else binding.PREPARE_BACKWARD)
-    frozen_token = binding.givens_prepare(th_d, n, restricted_m, directions) if prepared == "frozen" else None
+    frozen_token = binding.givens_prepare(th_d, n, restricted_m, directions, batch=B) if prepared == "frozen" else None
 
     timing_on = [True]
     zeros = (0.0, 0.0, 0.0, 0.0)
@@ -215,7 +215,7 @@ def main() -> int:
     def step():
         if prepared:
             if frozen_token is None:
-                token = binding.givens_prepare(th_d, n, restricted_m, directions)
+                token = binding.givens_prepare(th_d, n, restricted_m, directions, batch=B)
                 t_p = last_timing()
             else:
                 token, t_p = frozen_token, (0.0, 0.0, 0.0, 0.0)

@@ -179,6 +179,10 @@ int givens_backward_ex(int n, int m, int64_t B, const float *theta, const float 
 #define GIVENS_PREPARE_BACKWARD_WIDE 4
 int64_t givens_prepare(int n, const float *theta, int directions, void *stream);
 int64_t givens_prepare_restricted(int n, int m, const float *theta, int directions, void *stream);
+/* The same with per-call options (NULL: the process-wide defaults) and the batch the tables will be used with
+ * (batch_hint >= 1; 0: not known), which GIVENS_FORM_AUTO needs for its size rule; m = n - 1: unrestricted. */
+int64_t givens_prepare_ex(int n, int m, const float *theta, int directions, int64_t batch_hint, void *stream,
+                          const givens_options *options);
 int givens_forward_prepared(int64_t token, int64_t B, const float *X, float *Y, void *stream);
 int givens_build_prepared(int64_t token, float *U, void *stream);
 int givens_backward_prepared(int64_t token, int64_t B, const float *Y, const float *G, float *dX, float *dtheta,

@@ -25,7 +25,7 @@ EXPORTS = [
     "givens_forward_f64", "givens_build_f64", "givens_backward_f64",
     "givens_forward_transposed", "givens_forward_transposed_f64", "givens_forward_noalloc",
     "givens_forward_ex", "givens_backward_ex",
-    "givens_prepare", "givens_prepare_restricted", "givens_forward_prepared", "givens_build_prepared",
+    "givens_prepare", "givens_prepare_restricted", "givens_prepare_ex", "givens_forward_prepared", "givens_build_prepared",
     "givens_backward_prepared",
     "givens_release", "givens_last_hip_error", "givens_error_string",
     "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
@@ -73,6 +73,7 @@ def lib():
     L.givens_backward_ex.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp, vp, vp]
     L.givens_prepare.argtypes = [i32, vp, i32, vp]
     L.givens_prepare_restricted.argtypes = [i32, i32, vp, i32, vp]
+    L.givens_prepare_ex.argtypes = [i32, i32, vp, i32, i64, vp, vp]
     L.givens_forward_prepared.argtypes = [i64, i64, vp, vp, vp]
     L.givens_build_prepared.argtypes = [i64, vp, vp]
     L.givens_backward_prepared.argtypes = [i64, i64, vp, vp, vp, vp, vp]
@@ -98,9 +99,10 @@ def lib():
     L.givens_set_timing.argtypes = [i32]
     L.givens_last_timing.argtypes = [ctypes.POINTER(ctypes.c_float)]
     for name in EXPORTS:
-        if name not in ("givens_error_string", "givens_num_angles", "givens_prepare", "givens_prepare_restricted"):
+        if name not in ("givens_error_string", "givens_num_angles", "givens_prepare", "givens_prepare_restricted",
+                        "givens_prepare_ex"):
             getattr(L, name).restype = i32
-    for name in ("givens_num_angles", "givens_prepare", "givens_prepare_restricted"):
+    for name in ("givens_num_angles", "givens_prepare", "givens_prepare_restricted", "givens_prepare_ex"):
         getattr(L, name).restype = i64
     _lib = L
     return L
@@ -219,11 +221,16 @@ def givens_backward_ex(theta, Y, G, m=None, dX=None, dtheta=None, want_dx=True, 
     return (dX if want_dx else None), dtheta
 
 
-def givens_prepare(theta, n: int, m=None, directions=PREPARE_FORWARD | PREPARE_BACKWARD, stream=None) -> int:
-    """Builds the coefficient tables of theta once in the stream's workspace; returns the token."""
+def givens_prepare(theta, n: int, m=None, directions=PREPARE_FORWARD | PREPARE_BACKWARD, stream=None,
+                   batch=None) -> int:
+    """Builds the coefficient tables of theta once in the stream's workspace; returns the token.
+    batch: the number of columns the tables will be used with, if known (the default rotation form depends on it)."""
     import torch
     th = _dev(theta, "theta", torch.float32)
-    if m is None:
+    if batch is not None:
+        tok = lib().givens_prepare_ex(n, (n - 1) if m is None else m, th, directions, int(batch), _stream_ptr(stream),
+                                      None)
+    elif m is None:
         tok = lib().givens_prepare(n, th, directions, _stream_ptr(stream))
     else:
         tok = lib().givens_prepare_restricted(n, m, th, directions, _stream_ptr(stream))

@@ -818,7 +818,8 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
 
 // ---- prepared coefficients (float): givens_prepare builds the tables of one theta once, in the workspace of
 // the stream, and the *_prepared calls run the sweeps on them.
-int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *stream_v, CallOptions opt)
+int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *stream_v, CallOptions opt,
+                     long long batch_hint = 0)
 {
     if (int rc = check_restricted(rows, m)) return rc;
     if (!theta) return GIVENS_ERR_NULL;
@@ -845,8 +846,8 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
     ws->prepared = Prepared{};
     Coefs<float> c;
     bool range_known = false, mirrored_forms = false;
-    // the batch is not known here: AUTO means GIVENS_FORM_RANGE
-    constexpr double kAnyBatch = 1.0e300;
+    // without a hint the batch is not known here and AUTO means GIVENS_FORM_RANGE
+    const double kAnyBatch = batch_hint > 0 ? sweep_updates(n, batch_hint) : 1.0e300;
     const FormPolicy fpol = form_policy(ffam.carousel, opt.form, kAnyBatch), bpol = form_policy(bfam.carousel, opt.form, kAnyBatch);
     // one range check for all the sets, into the flag word that belongs to givens_prepare
     auto build = [&](CoefSet &set, bool forward, FormPolicy pol, int mirror) {
@@ -1319,6 +1320,14 @@ int64_t givens_prepare(int n, const float *theta, int directions, void *stream)
 int64_t givens_prepare_restricted(int n, int m, const float *theta, int directions, void *stream)
 {
     return givens::prepare_impl(n, m, theta, directions, stream, givens::default_options());
+}
+int64_t givens_prepare_ex(int n, int m, const float *theta, int directions, int64_t batch_hint, void *stream,
+                          const givens_options *options)
+{
+    givens::CallOptions opt;
+    if (int rc = givens::options_from(options, &opt)) return rc;
+    if (batch_hint < 0) return GIVENS_ERR_BAD_B;
+    return givens::prepare_impl(n, m, theta, directions, stream, opt, batch_hint);
 }
 int givens_forward_prepared(int64_t token, int64_t B, const float *X, float *Y, void *stream)
 {

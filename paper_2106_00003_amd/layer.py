@@ -29,7 +29,7 @@ def _prepare(th, n, m, want_backward: bool, B: int) -> int:
     if want_backward:
         # wide batches take the Gram form, whose dX sweep needs tables of its own
         directions |= binding.PREPARE_BACKWARD_WIDE if B >= 2 * (n + n % 2) else binding.PREPARE_BACKWARD
-    return binding.givens_prepare(th, n, m, directions)
+    return binding.givens_prepare(th, n, m, directions, batch=B)
 
 
 def _backward(token, th, Y, g, m, need_dx):

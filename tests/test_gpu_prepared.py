@@ -262,3 +262,32 @@ def test_sizes_no_kernel_family_takes_are_rejected_before_allocation():
     rc = binding.lib().givens_forward_restricted(40001, 3, 1, th.data_ptr(), x.data_ptr(), x.data_ptr(), None)
     assert rc == -5
     assert abs(torch.cuda.mem_get_info()[0] - before) < (64 << 20)
+
+
+def test_batch_hint_lets_prepare_follow_the_default_form_rule():
+    """givens_prepare_ex with the batch: GIVENS_FORM_AUTO prepares the standard form for a short sweep and the form
+    the angles allow for a long one; without the hint it always prepares the latter.  Results against the oracle."""
+    from oracle import c_oracle as C
+    from oracle import givens_oracle as O
+    binding.set_rotation_form(binding.FORM_AUTO)
+    try:
+        for n, B, want in ((256, 64, binding.FORM_STANDARD), (2048, 520, binding.FORM_SCALED)):
+            data = inputs.make_custom(n, B, seed=900 + n, theta_dist="normal0.1")
+            th_d = torch.from_numpy(data["theta"]).cuda()
+            x_d, g_d = torch.from_numpy(data["X"]).cuda(), torch.from_numpy(data["G"]).cuda()
+            tok = binding.givens_prepare(th_d, n, None, binding.PREPARE_FORWARD | binding.PREPARE_BACKWARD, batch=B)
+            y_d = binding.givens_forward_prepared(tok, x_d)
+            assert binding.last_rotation_form() == want
+            dx_d, dth_d = binding.givens_backward_prepared(tok, y_d, g_d, data["theta"].size)
+            assert binding.last_rotation_form() == want
+            want_y = C.forward(data["theta"], data["X"])
+            want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
+            assert O.rel_fro(y_d.cpu().numpy(), want_y) <= 1e-5
+            assert O.rel_fro(dx_d.cpu().numpy(), want_dx) <= 1e-4
+            assert O.rel_fro(dth_d.cpu().numpy(), want_dth) <= 1e-4
+        data = inputs.make_custom(256, 64, seed=1156, theta_dist="normal0.1")
+        tok = binding.givens_prepare(torch.from_numpy(data["theta"]).cuda(), 256, None, binding.PREPARE_FORWARD)
+        binding.givens_forward_prepared(tok, torch.from_numpy(data["X"]).cuda())
+        assert binding.last_rotation_form() == binding.FORM_SCALED
+    finally:
+        binding.set_rotation_form(binding.FORM_RANGE)
