@@ -141,6 +141,32 @@ def test_carousel_family_against_the_oracle_and_the_lds_family(n, B, seed):
     assert np.array_equal(host(again[1]), dth_c) and np.array_equal(host(again[2]), dph_c)
 
 
+def test_carousel_family_at_the_edges_of_the_angle_reductions():
+    """theta and phi on and next to the multiples of pi/2 where the reductions modulo pi change branch, angles of many
+    turns, zeros; the carried phases and the three-shear forms must reproduce the oracle there too."""
+    n, B = 256, 24
+    theta, phi, x, g = make(n, B, 453, np.float32, np.complex64)
+    pi = np.float32(np.pi)
+    special = np.array([pi / 2, -pi / 2, np.nextafter(pi / 2, np.float32(4)), np.nextafter(-pi / 2, np.float32(-4)),
+                        pi, -pi, np.float32(1.5) * pi, np.float32(-1.5) * pi, np.float32(3) * pi,
+                        np.float32(100.25) * pi, np.float32(-999.5) * pi, np.float32(12345.678), np.float32(-9.9e5),
+                        np.float32(0), np.float32(1e-30), np.float32(0.25) * pi, np.float32(-0.75) * pi], dtype=np.float32)
+    rng = np.random.default_rng(454)
+    for arr in (theta, phi):
+        where = rng.choice(arr.size, size=16 * special.size, replace=False)
+        arr[where] = np.tile(special, 16)
+    th_d, ph_d = dev(theta), dev(phi)
+    y_d = binding.givens_unitary_forward(th_d, ph_d, dev(x))
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+    want_y = V.forward_blocks(theta, phi, x)
+    dx_d, dth_d, dph_d = binding.givens_unitary_backward(th_d, ph_d, y_d, dev(g))
+    want_dth, want_dph, want_dx, _ = V.reverse_sweep_blocks(theta, phi, want_y, g)
+    errs = (V.rel_fro(host(y_d), want_y), V.rel_fro(host(dx_d), want_dx), V.rel_fro(host(dth_d), want_dth),
+            V.rel_fro(host(dph_d), want_dph))
+    print("[unitary]   special angles: Y %.2e dX %.2e dtheta %.2e dphi %.2e" % errs, flush=True)
+    assert errs[0] <= 1e-5 and max(errs[1:]) <= 1e-4
+
+
 def test_carousel_family_at_a_benchmark_size():
     """n = B = 2048, the shape bench.py --unitary is quoted on: sampled columns of Y and dX against the oracle
     (columns do not interact), all of dtheta and dphi against the LDS family, which the small cases pin."""
