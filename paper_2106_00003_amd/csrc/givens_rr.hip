@@ -507,6 +507,12 @@ int build_coefs(Workspace &ws, CoefSet &set, const Problem &pb, const T *theta, 
     return build_coefs<T>(st, pb, theta, forward, policy, stream, out, mirror, range_known);
 }
 
+// From n = 2048 on (four or more arcs per thread and block) the LDS-family kernels run the instance that fetches
+// its coefficients a block ahead.  Measured, complex64 B = 2048: n = 2048 reverse sweep 15.5 -> 9.7 ms with it,
+// n = 1024 (B = 4096) 5.97 -> 6.33 ms: below that a block is short enough, and the resident workgroups many
+// enough, that the loads are hidden anyway and the prefetch only costs registers.
+inline bool lds_wants_ahead(int n) { return n >= 2048; }
+
 template <typename T>
 int lds_forward(int n, int rows, long long B, const typename Pair2<T>::type *table, const T *X, T *Y,
                 int identity, hipStream_t stream, int mirror = 0)
@@ -514,7 +520,7 @@ int lds_forward(int n, int rows, long long B, const typename Pair2<T>::type *tab
     const int w = lds_strip_width<T>(n, B, 1);
     if (w == 0) return GIVENS_ERR_UNSUPPORTED;
     const size_t smem = (size_t)n * lds_row_stride(w) * sizeof(T);
-    auto kern = lds_forward_kernel<T>;
+    auto kern = lds_wants_ahead(n) ? lds_forward_kernel<T, kLdsAhead> : lds_forward_kernel<T, 0>;
     GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     const long long strips = (B + w - 1) / w;
@@ -596,11 +602,12 @@ int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, lo
     const long long N = (long long)n * (n - 1) / 2;
     int w = 0;
     size_t smem = 0;
-    auto kern = lds_backward_kernel<T>;
+    auto kern = lds_backward_kernel<T, 0>;
     if (!carousel) {
         w = lds_strip_width<T>(n, B, 2);
         if (w == 0) return GIVENS_ERR_UNSUPPORTED;
         smem = (size_t)2 * n * lds_row_stride(w) * sizeof(T);
+        if (lds_wants_ahead(n)) kern = lds_backward_kernel<T, kLdsAhead>;
         GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     } else {
@@ -1150,7 +1157,7 @@ int unitary_forward_impl(int n, long long B, const T *theta, const T *phi, const
     if (int rc = workspace_for(dev, stream, &ws)) return rc;
     if (int rc = unitary_table<T>(*ws, n, theta, phi, stream, &table)) return rc;
     const size_t smem = (size_t)n * w * sizeof(C);
-    auto kern = unitary_forward_kernel<T>;
+    auto kern = lds_wants_ahead(n) ? unitary_forward_kernel<T, kUnitaryAhead> : unitary_forward_kernel<T, 0>;
     GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     Span span(1, stream);
@@ -1196,7 +1203,7 @@ int unitary_backward_impl(int n, long long B, const T *theta, const T *phi, cons
     if (int rc = grow(ws.partial, (size_t)rows * 2 * N * sizeof(T))) return rc;
     T *partial = reinterpret_cast<T *>(ws.partial.ptr);
     const size_t smem = (size_t)2 * n * w * sizeof(C);
-    auto kern = unitary_backward_kernel<T>;
+    auto kern = lds_wants_ahead(n) ? unitary_backward_kernel<T, kUnitaryAhead> : unitary_backward_kernel<T, 0>;
     GIVENS_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     for (long long s0 = 0; s0 < strips; s0 += rows) {

@@ -15,12 +15,15 @@
 namespace givens {
 
 constexpr int kLdsThreads = 256;
-constexpr int kLdsAhead = 10;    // arcs per thread whose coefficients are fetched a block ahead (n <= 5120: all)
+// AHEAD (template argument of the sweep kernels): arcs per thread whose coefficients are fetched a block ahead, in
+// registers.  It pays for large n (many arcs per thread, long tables); for small n the resident workgroups hide
+// the loads and the prefetch only costs registers, so the launch picks 0 there.
+constexpr int kLdsAhead = 10;   // n <= 5120: all of a thread's arcs
 
 // row stride of the strip in LDS: odd, so that consecutive rows fall in different banks
 __host__ __device__ inline int lds_row_stride(int w) { return w | 1; }
 
-template <typename T>
+template <typename T, int AHEAD>
 __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
     int n, int rows, long long B, int w, const typename Pair2<T>::type *__restrict__ table,
     const T *X, T *Y, int identity, int mirror)
@@ -57,28 +60,28 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
             rb[c] = cs.y * va + cs.x * vb;
         }
     };
-    // A thread's first kLdsAhead arcs of a block get their cos/sin a block ahead, in registers: a block is short
+    // A thread's first AHEAD arcs of a block get their cos/sin a block ahead, in registers: a block is short
     // (a few microseconds) and ends in a barrier, so a load issued inside it is waited for in full.
-    typename Pair2<T>::type ahead[kLdsAhead];
+    typename Pair2<T>::type ahead[AHEAD > 0 ? AHEAD : 1];
     auto fetch = [&](int k) {
 #pragma unroll
-        for (int i = 0; i < kLdsAhead; ++i) {
+        for (int i = 0; i < AHEAD; ++i) {
             const int p = threadIdx.x + i * kLdsThreads;
             if (k >= 0 && p < H) ahead[i] = table[(long long)k * H + p];
         }
     };
     fetch(n - 2);
     for (int k = n - 2; k >= 0; --k) {                      // the blocks in reverse order (Algorithm 2)
-        typename Pair2<T>::type cur[kLdsAhead];
+        typename Pair2<T>::type cur[AHEAD > 0 ? AHEAD : 1];
 #pragma unroll
-        for (int i = 0; i < kLdsAhead; ++i) cur[i] = ahead[i];
+        for (int i = 0; i < AHEAD; ++i) cur[i] = ahead[i];
         fetch(k - 1);
 #pragma unroll
-        for (int i = 0; i < kLdsAhead; ++i) {
+        for (int i = 0; i < AHEAD; ++i) {
             const int p = threadIdx.x + i * kLdsThreads;
             if (p < H) rotate(k, p, cur[i]);
         }
-        for (int p = threadIdx.x + kLdsAhead * kLdsThreads; p < H; p += kLdsThreads)
+        for (int p = threadIdx.x + AHEAD * kLdsThreads; p < H; p += kLdsThreads)
             rotate(k, p, table[(long long)k * H + p]);
         __syncthreads();                                    // the next block pairs these rows differently
     }
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(kLdsThreads) void lds_forward_kernel(
 
 // Reverse sweep on strips [strip0, strip0 + gridDim.x).  partial is [gridDim.x][N].  map: nullptr, or the index
 // in theta of every entry of E (-1: bypassed pair).
-template <typename T>
+template <typename T, int AHEAD>
 __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
     int n, int rows, long long B, int w, long long strip0, const typename Pair2<T>::type *__restrict__ table,
     const T *Yin, const T *G, T *dX, T *__restrict__ partial, int g_identity, const int *__restrict__ map)
@@ -140,13 +143,13 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
         // the orientation sign is applied by the second-stage reduction (factor array)
         mine[(long long)k * H + p] = sum;
     };
-    // coefficients (and bypass marks) of a thread's first kLdsAhead arcs a block ahead, as in the forward kernel
+    // coefficients (and bypass marks) of a thread's first AHEAD arcs a block ahead, as in the forward kernel
     // (the marks are kept as loaded and compared when used: a comparison here would wait for the load)
-    typename Pair2<T>::type ahead[kLdsAhead];
-    int mark_ahead[kLdsAhead];
+    typename Pair2<T>::type ahead[AHEAD > 0 ? AHEAD : 1];
+    int mark_ahead[AHEAD > 0 ? AHEAD : 1];
     auto fetch = [&](int k) {
 #pragma unroll
-        for (int i = 0; i < kLdsAhead; ++i) {
+        for (int i = 0; i < AHEAD; ++i) {
             const int p = threadIdx.x + i * kLdsThreads;
             if (k <= n - 2 && p < H) {
                 ahead[i] = table[(long long)k * H + p];
@@ -156,17 +159,17 @@ __global__ __launch_bounds__(kLdsThreads) void lds_backward_kernel(
     };
     fetch(0);
     for (int k = 0; k <= n - 2; ++k) {                      // blocks b_1, b_2, ... in order
-        typename Pair2<T>::type cur[kLdsAhead];
-        int mark[kLdsAhead];
+        typename Pair2<T>::type cur[AHEAD > 0 ? AHEAD : 1];
+        int mark[AHEAD > 0 ? AHEAD : 1];
 #pragma unroll
-        for (int i = 0; i < kLdsAhead; ++i) { cur[i] = ahead[i]; mark[i] = mark_ahead[i]; }
+        for (int i = 0; i < AHEAD; ++i) { cur[i] = ahead[i]; mark[i] = mark_ahead[i]; }
         fetch(k + 1);
 #pragma unroll
-        for (int i = 0; i < kLdsAhead; ++i) {
+        for (int i = 0; i < AHEAD; ++i) {
             const int p = threadIdx.x + i * kLdsThreads;
             if (p < H) undo(k, p, cur[i], mark[i] < 0);
         }
-        for (int p = threadIdx.x + kLdsAhead * kLdsThreads; p < H; p += kLdsThreads) {
+        for (int p = threadIdx.x + AHEAD * kLdsThreads; p < H; p += kLdsThreads) {
             const bool bypass = map && map[(long long)k * H + p] < 0;
             if (!bypass) undo(k, p, table[(long long)k * H + p], false);
         }

@@ -18,6 +18,7 @@ template <> struct Cplx<float> { using type = float2; using quad = float4; };
 template <> struct Cplx<double> { using type = double2; using quad = double4; };
 
 constexpr int kUnitaryThreads = 256;
+constexpr int kUnitaryAhead = 8;   // AHEAD of the large-strip instances (see lds_kernels.hpp): n <= 4096: all pairs
 
 template <typename T>
 __global__ void unitary_table_kernel(int n, const T *__restrict__ theta, const T *__restrict__ phi,
@@ -44,7 +45,7 @@ __device__ __forceinline__ typename Cplx<T>::type cmul(T wr, T wi, typename Cplx
     return r;
 }
 
-template <typename T>
+template <typename T, int AHEAD>
 __global__ __launch_bounds__(kUnitaryThreads) void unitary_forward_kernel(
     int n, long long B, int w, const typename Cplx<T>::quad *__restrict__ table,
     const typename Cplx<T>::type *X, typename Cplx<T>::type *Y, int identity)
@@ -68,22 +69,43 @@ __global__ __launch_bounds__(kUnitaryThreads) void unitary_forward_kernel(
     }
     __syncthreads();
 
-    for (int k = n - 2; k >= 0; --k) {                       // reversed(B)
-        for (int p = threadIdx.x; p < H; p += blockDim.x) {
-            const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-            const int i = a < b ? a : b, j = a < b ? b : a;
-            const auto q = table[(long long)k * H + p];
-            C *ri = strip + i * w, *rj = strip + j * w;
-            for (int c = 0; c < w; ++c) {
-                const C ui = cmul<T>(q.z, q.w, ri[c]);      // exp(i phi) U_i
-                const C uj = rj[c];
-                C ni, nj;
-                ni.x = q.x * ui.x - q.y * uj.x; ni.y = q.x * ui.y - q.y * uj.y;
-                nj.x = q.y * ui.x + q.x * uj.x; nj.y = q.y * ui.y + q.x * uj.y;
-                ri[c] = ni;
-                rj[c] = nj;
-            }
+    auto update = [&](int k, int p, typename Cplx<T>::quad q) {
+        const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+        const int i = a < b ? a : b, j = a < b ? b : a;
+        C *ri = strip + i * w, *rj = strip + j * w;
+        for (int c = 0; c < w; ++c) {
+            const C ui = cmul<T>(q.z, q.w, ri[c]);      // exp(i phi) U_i
+            const C uj = rj[c];
+            C ni, nj;
+            ni.x = q.x * ui.x - q.y * uj.x; ni.y = q.x * ui.y - q.y * uj.y;
+            nj.x = q.y * ui.x + q.x * uj.x; nj.y = q.y * ui.y + q.x * uj.y;
+            ri[c] = ni;
+            rj[c] = nj;
         }
+    };
+    // a thread's first kUnitaryAhead pairs of a block get their coefficients a block ahead, in registers (a block
+    // is short and ends in a barrier, so a load issued inside it is waited for in full)
+    typename Cplx<T>::quad ahead[AHEAD > 0 ? AHEAD : 1];
+    auto fetch = [&](int k) {
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) {
+            const int p = threadIdx.x + i * kUnitaryThreads;
+            if (k >= 0 && p < H) ahead[i] = table[(long long)k * H + p];
+        }
+    };
+    fetch(n - 2);
+    for (int k = n - 2; k >= 0; --k) {                       // the blocks in reverse order (appendix, forward algorithm)
+        typename Cplx<T>::quad cur[AHEAD > 0 ? AHEAD : 1];
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) cur[i] = ahead[i];
+        fetch(k - 1);
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) {
+            const int p = threadIdx.x + i * kUnitaryThreads;
+            if (p < H) update(k, p, cur[i]);
+        }
+        for (int p = threadIdx.x + AHEAD * kUnitaryThreads; p < H; p += kUnitaryThreads)
+            update(k, p, table[(long long)k * H + p]);
         __syncthreads();
     }
 
@@ -100,7 +122,7 @@ __global__ __launch_bounds__(kUnitaryThreads) void unitary_forward_kernel(
 //   z, gbar <- G^dagger z, G^dagger gbar:  row i <- conj(w) (c row_i + s row_j),  row j <- -s row_i + c row_j
 //   dphi   = -Im sum_b conj(gbar_i) z_i                                   (after: P_e z = i (c, s)^T (c z_i + s z_j)
 //            and c z_i + s z_j = w z_i', c gbar_i + s gbar_j = w gbar_i', so the phases cancel)
-template <typename T>
+template <typename T, int AHEAD>
 __global__ __launch_bounds__(kUnitaryThreads) void unitary_backward_kernel(
     int n, long long B, int w, long long strip0, const typename Cplx<T>::quad *__restrict__ table,
     const typename Cplx<T>::type *Yin, const typename Cplx<T>::type *G, typename Cplx<T>::type *dX,
@@ -129,31 +151,50 @@ __global__ __launch_bounds__(kUnitaryThreads) void unitary_backward_kernel(
     }
     __syncthreads();
 
-    for (int k = 0; k <= n - 2; ++k) {
-        for (int p = threadIdx.x; p < H; p += blockDim.x) {
-            const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
-            const int i = a < b ? a : b, j = a < b ? b : a;
-            const auto q = table[(long long)k * H + p];
-            C *zi = z + i * w, *zj = z + j * w, *gi = gb + i * w, *gj = gb + j * w;
-            T sum_t = T(0), sum_p = T(0);
-            for (int c = 0; c < w; ++c) {
-                const C a_i = zi[c], a_j = zj[c], u_i = gi[c], u_j = gj[c];
-                sum_t += (u_j.x * a_i.x + u_j.y * a_i.y) - (u_i.x * a_j.x + u_i.y * a_j.y);
-                C t;
-                t.x = q.x * a_i.x + q.y * a_j.x; t.y = q.x * a_i.y + q.y * a_j.y;
-                const C nz_i = cmul<T>(q.z, -q.w, t);       // conj(w) (c z_i + s z_j)
-                C nz_j;
-                nz_j.x = q.x * a_j.x - q.y * a_i.x; nz_j.y = q.x * a_j.y - q.y * a_i.y;
-                t.x = q.x * u_i.x + q.y * u_j.x; t.y = q.x * u_i.y + q.y * u_j.y;
-                const C ng_i = cmul<T>(q.z, -q.w, t);
-                C ng_j;
-                ng_j.x = q.x * u_j.x - q.y * u_i.x; ng_j.y = q.x * u_j.y - q.y * u_i.y;
-                sum_p += ng_i.y * nz_i.x - ng_i.x * nz_i.y; // -Im( conj(gbar_i') z_i' )
-                zi[c] = nz_i; zj[c] = nz_j; gi[c] = ng_i; gj[c] = ng_j;
-            }
-            mine[(long long)k * H + p] = sum_t;
-            mine[N + (long long)k * H + p] = sum_p;
+    auto undo = [&](int k, int p, typename Cplx<T>::quad q) {
+        const int a = rr_label(n, k, p), b = rr_label(n, k, n - 1 - p);
+        const int i = a < b ? a : b, j = a < b ? b : a;
+        C *zi = z + i * w, *zj = z + j * w, *gi = gb + i * w, *gj = gb + j * w;
+        T sum_t = T(0), sum_p = T(0);
+        for (int c = 0; c < w; ++c) {
+            const C a_i = zi[c], a_j = zj[c], u_i = gi[c], u_j = gj[c];
+            sum_t += (u_j.x * a_i.x + u_j.y * a_i.y) - (u_i.x * a_j.x + u_i.y * a_j.y);
+            C t;
+            t.x = q.x * a_i.x + q.y * a_j.x; t.y = q.x * a_i.y + q.y * a_j.y;
+            const C nz_i = cmul<T>(q.z, -q.w, t);       // conj(w) (c z_i + s z_j)
+            C nz_j;
+            nz_j.x = q.x * a_j.x - q.y * a_i.x; nz_j.y = q.x * a_j.y - q.y * a_i.y;
+            t.x = q.x * u_i.x + q.y * u_j.x; t.y = q.x * u_i.y + q.y * u_j.y;
+            const C ng_i = cmul<T>(q.z, -q.w, t);
+            C ng_j;
+            ng_j.x = q.x * u_j.x - q.y * u_i.x; ng_j.y = q.x * u_j.y - q.y * u_i.y;
+            sum_p += ng_i.y * nz_i.x - ng_i.x * nz_i.y; // -Im( conj(gbar_i') z_i' )
+            zi[c] = nz_i; zj[c] = nz_j; gi[c] = ng_i; gj[c] = ng_j;
         }
+        mine[(long long)k * H + p] = sum_t;
+        mine[N + (long long)k * H + p] = sum_p;
+    };
+    typename Cplx<T>::quad ahead[AHEAD > 0 ? AHEAD : 1];   // coefficients a block ahead, as in the forward kernel
+    auto fetch = [&](int k) {
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) {
+            const int p = threadIdx.x + i * kUnitaryThreads;
+            if (k <= n - 2 && p < H) ahead[i] = table[(long long)k * H + p];
+        }
+    };
+    fetch(0);
+    for (int k = 0; k <= n - 2; ++k) {
+        typename Cplx<T>::quad cur[AHEAD > 0 ? AHEAD : 1];
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) cur[i] = ahead[i];
+        fetch(k + 1);
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) {
+            const int p = threadIdx.x + i * kUnitaryThreads;
+            if (p < H) undo(k, p, cur[i]);
+        }
+        for (int p = threadIdx.x + AHEAD * kUnitaryThreads; p < H; p += kUnitaryThreads)
+            undo(k, p, table[(long long)k * H + p]);
         __syncthreads();
     }
 
@@ -172,8 +213,16 @@ __global__ void sum_rows_kernel(long long count, long long rows, long long strid
 {
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= count) return;
-    T acc = T(0);
-    for (long long r = 0; r < rows; ++r) acc += partial[r * stride + e];
+    T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
+    long long r = 0;
+    for (; r + 4 <= rows; r += 4) {             // four loads in flight; the order of additions is fixed
+        a0 += partial[r * stride + e];
+        a1 += partial[(r + 1) * stride + e];
+        a2 += partial[(r + 2) * stride + e];
+        a3 += partial[(r + 3) * stride + e];
+    }
+    for (; r < rows; ++r) a0 += partial[r * stride + e];
+    const T acc = (a0 + a1) + (a2 + a3);
     out[e] = accumulate ? out[e] + acc : acc;
 }
 
