@@ -31,18 +31,26 @@ struct CarouselCoefs {
 // family takes every n that is a multiple of 4 from kCarouselMinN up to 2048 (M = 2), of 8 up to 4096 and
 // of 16 up to 8192.  The most slots per lane that fit are preferred: fewer of a lane's slots take part in
 // the exchange.  Below kCarouselMinN a workgroup would be mostly idle lanes.
+// The remaining multiples of 4 up to 4096 and of 8 up to 8192 run with 513 to 1024 lanes (2 or 4 slots per lane,
+// an even number of wavefronts from 10 to 16, one workgroup per compute unit): slower per update than the shapes
+// above, but several times faster than the LDS family they would otherwise fall to.
 constexpr int kCarouselMinN = 132;
-inline bool carousel_shape_with(int n, std::initializer_list<int> slots, CarouselShape *out)
+inline bool carousel_shape_with(int n, std::initializer_list<int> slots, CarouselShape *out, int max_lanes = 512)
 {
     if (n < kCarouselMinN) return false;
     for (int m : slots)
-        if (n % (2 * m) == 0 && n / (2 * m) <= 512) {
-            *out = {m, (n / (2 * m) + 63) / 64};
+        if (n % (2 * m) == 0 && n / (2 * m) <= max_lanes) {
+            int waves = (n / (2 * m) + 63) / 64;
+            if (waves > 8) waves += waves & 1;      // compiled: 10, 12, 14, 16
+            *out = {m, waves};
             return true;
         }
     return false;
 }
-inline bool carousel_shape_for(int n, CarouselShape *out) { return carousel_shape_with(n, {8, 4, 2}, out); }
+inline bool carousel_shape_for(int n, CarouselShape *out)
+{
+    return carousel_shape_with(n, {8, 4, 2}, out) || carousel_shape_with(n, {4, 2}, out, 1024);
+}
 
 template <typename T>
 inline bool carousel_supported(int n, long long B)
@@ -58,7 +66,8 @@ inline bool carousel_supported(int n, long long B)
 inline bool carousel_bwd_shape_for(int n, CarouselShape *out)
 {
     if (carousel_shape_with(n, {4, 2}, out)) return true;
-    return n > 4096 && carousel_shape_with(n, {8}, out);
+    if (n > 4096 && carousel_shape_with(n, {8}, out)) return true;
+    return carousel_shape_with(n, {4, 2}, out, 1024);
 }
 
 template <typename T>
@@ -155,6 +164,9 @@ int carousel_forward_m2(const CarouselFwdArgs &a, int waves, int W);
 int carousel_backward_m4(const CarouselBwdArgs &a, int waves, int W);
 int carousel_backward_m2(const CarouselBwdArgs &a, int waves, int W);
 int carousel_backward_m8(const CarouselBwdArgs &a, int waves, int W);
+// carousel_fwd_wide.hip / carousel_bwd_wide.hip: more than 8 wavefronts (M in {4, 2})
+int carousel_forward_wide(const CarouselFwdArgs &a, int M, int waves, int W);
+int carousel_backward_wide(const CarouselBwdArgs &a, int M, int waves, int W);
 
 inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
                             int identity, int mirror, hipStream_t stream)
@@ -165,6 +177,7 @@ inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &c
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
     const CarouselFwdArgs a{n, rows, B, coefs, X, Y, identity, aligned ? 1 : 0, mirror, stream};
+    if (s.WAVES > 8) return carousel_forward_wide(a, s.M, s.WAVES, W);
     switch (s.M) {
     case 8: return carousel_forward_m8(a, s.WAVES, W);
     case 4: return carousel_forward_m4(a, s.WAVES, W);
@@ -182,7 +195,8 @@ inline int carousel_bwd_width(int n, long long B)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return 0;
-    const int widest = s.M == 8 ? 4 : 8;       // 8 slots per lane: strips of at most 4 columns (registers)
+    // 8 slots per lane, or more than 8 wavefronts: strips of at most 4 columns (registers, LDS)
+    const int widest = (s.M == 8 || s.WAVES > 8) ? 4 : 8;
     for (int w = widest; w > 2; w >>= 1)
         if (((B + w - 1) / w) * s.WAVES >= 512) return w;
     return B > 1 ? 2 : 1;
@@ -213,6 +227,7 @@ inline int carousel_backward_strips(int n, int rows, long long B, int W, long lo
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
     const CarouselBwdArgs a{n,  rows,    B,     strip0, nstrips,         groups,     coefs, Y, G,
                             dX, partial, zeros, sink,   aligned ? 1 : 0, g_identity, stream};
+    if (s.WAVES > 8) return carousel_backward_wide(a, s.M, s.WAVES, W);
     switch (s.M) {
     case 8: return carousel_backward_m8(a, s.WAVES, W);
     case 4: return carousel_backward_m4(a, s.WAVES, W);

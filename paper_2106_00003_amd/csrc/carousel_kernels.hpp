@@ -402,7 +402,7 @@ __device__ __forceinline__ void carousel_forward_body(CarouselExchange<W, WAVES>
 // One launch per call: the rotation form is read from the device flag (nullptr: standard) and the
 // matching copy of the sweep runs; `table` holds that form's coefficients (coef_table_kernel).
 template <int M, int W, int WAVES>
-__global__ __launch_bounds__(64 * WAVES, 2) void carousel_forward_kernel(
+__global__ __launch_bounds__(64 * WAVES, WAVES > 8 ? 1 : 2) void carousel_forward_kernel(
     int n, int rows, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
     const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok, int mirror)
 {
@@ -757,7 +757,7 @@ __device__ __forceinline__ void carousel_backward_body(CarouselExchangeBwd<W, WA
 }
 
 template <int M, int W, int WAVES>
-__global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_kernel(
+__global__ __launch_bounds__(64 * WAVES, WAVES > 8 ? 1 : 2) void carousel_backward_kernel(
     int n, int rows, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
     const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
     float *dX, float *partial, const float *__restrict__ zeros, float *sink, int vec_ok, int g_identity)

@@ -221,6 +221,22 @@ def test_carousel_sizes_above_4096(n, B, seed, dist):
     binding.release()
 
 
+@pytest.mark.parametrize("n,B,seed,dist", [(2052, 24, 32, "uniform"), (4092, 12, 33, "normal0.1"),
+                                           (3004, 40, 34, "uniform"), (4104, 16, 35, "uniform"),
+                                           (6152, 8, 36, "normal0.1"), (8184, 8, 37, "uniform"),
+                                           (2060, 2200, 38, "normal0.1")])
+def test_carousel_shapes_with_more_than_512_lanes(n, B, seed, dist):
+    """Multiples of 4 beyond 2048 that are not multiples of 8 (2 slots per lane) and multiples of 8 beyond 4096 that
+    are not multiples of 16 (4 slots per lane): 513 to 1024 lanes, 10 to 16 wavefronts, both sweeps; 2060 x 2200
+    gives the reverse sweep's persistent workgroups (one per compute unit here) a second strip."""
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    print(f"[parity] n={n} B={B} seed={seed} {dist}", flush=True)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
+                           binding.KERNEL_CAROUSEL)
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL      # the reverse sweep too
+    binding.release()
+
+
 # ---------------------------------------------------------------- scaled rotation form (near-identity angles)
 @pytest.mark.parametrize("n,B,seed", [(256, 64, 51), (512, 100, 52), (1024, 67, 53), (2048, 130, 54)])
 def test_scaled_form_is_used_for_small_angles_and_matches_the_oracle(n, B, seed):
