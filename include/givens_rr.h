@@ -52,7 +52,8 @@ extern "C" {
 #define GIVENS_KERNEL_AUTO 0     /* column kernels for n <= 128, register carousel where the  */
                                  /* shape allows, else LDS strip                              */
 #define GIVENS_KERNEL_LDS 1      /* strip of the operand held in LDS; any even n that fits   */
-#define GIVENS_KERNEL_CAROUSEL 2 /* strip held in VGPRs in circle-method position order      */
+#define GIVENS_KERNEL_CAROUSEL 2 /* strip held in VGPRs in circle-method position order: float, */
+                                 /* n from 132, a multiple of 4 up to 4096 or of 8 up to 8192   */
 #define GIVENS_KERNEL_COLUMN 3   /* float, n <= 128: one lane per column, all rows in its VGPRs */
 
 /* Rotation forms of the float carousel kernels (givens_set_rotation_form). */
