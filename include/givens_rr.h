@@ -53,7 +53,9 @@ extern "C" {
                                  /* shape allows, else LDS strip                              */
 #define GIVENS_KERNEL_LDS 1      /* strip of the operand held in LDS; any even n that fits   */
 #define GIVENS_KERNEL_CAROUSEL 2 /* strip held in VGPRs in circle-method position order: float, */
-                                 /* n from 132, a multiple of 4 up to 4096 or of 8 up to 8192   */
+                                 /* n from 132, a multiple of 4 up to 4096 or of 8 up to 8192,  */
+                                 /* or n = 2 M L with M in {7, 5, 3} and L <= 1024 (standard    */
+                                 /* rotation form only, whatever givens_set_rotation_form says) */
 #define GIVENS_KERNEL_COLUMN 3   /* float, n <= 128: one lane per column, all rows in its VGPRs */
 
 /* Rotation forms of the float carousel kernels (givens_set_rotation_form). */

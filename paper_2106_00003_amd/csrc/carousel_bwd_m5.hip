@@ -1,0 +1,7 @@
+// Reverse-sweep carousel kernels with 5 slots per lane (n = 10 L, up to 1024 lanes), standard rotation form,
+// strips of at most 4 columns.
+#include "carousel_kernels.hpp"
+
+namespace givens {
+int carousel_backward_m5(const CarouselBwdArgs &a, int waves, int W) { return carousel_backward_odd_slots<5>(a, waves, W); }
+} // namespace givens

@@ -26,7 +26,8 @@ struct CarouselCoefs {
     float scaled_max; // threshold of the scaled form (negative: never), see form_for_range
 };
 
-// n = 2 * M * L: M slots per lane in {8, 4, 2} (the renormalisation period must be a multiple of M) and
+// n = 2 * M * L: M slots per lane in {8, 4, 2} (the scaled and lifted forms need a slot count that divides the
+// renormalisation period) and
 // L <= 512 lanes, run by a workgroup of WAVES = ceil(L / 64) wavefronts whose spare lanes idle.  So the
 // family takes every n that is a multiple of 4 from kCarouselMinN up to 2048 (M = 2), of 8 up to 4096 and
 // of 16 up to 8192.  The most slots per lane that fit are preferred: fewer of a lane's slots take part in
@@ -47,9 +48,17 @@ inline bool carousel_shape_with(int n, std::initializer_list<int> slots, Carouse
         }
     return false;
 }
+// What is left of the even n (n = 2 (mod 4), and multiples of 4 or 8 too large for the shapes above) runs with
+// 7, 5 or 3 slots per lane where n / 2 has such a factor and n / (2 M) <= 1024: about half of those sizes, among
+// them the padded sizes of half of the odd n.  Standard rotation form only (carousel_has_forms).
+inline bool carousel_odd_shape_for(int n, CarouselShape *out)
+{
+    return carousel_shape_with(n, {7, 5, 3}, out) || carousel_shape_with(n, {7, 5, 3}, out, 1024);
+}
 inline bool carousel_shape_for(int n, CarouselShape *out)
 {
-    return carousel_shape_with(n, {8, 4, 2}, out) || carousel_shape_with(n, {4, 2}, out, 1024);
+    return carousel_shape_with(n, {8, 4, 2}, out) || carousel_shape_with(n, {4, 2}, out, 1024) ||
+           carousel_odd_shape_for(n, out);
 }
 
 template <typename T>
@@ -67,7 +76,14 @@ inline bool carousel_bwd_shape_for(int n, CarouselShape *out)
 {
     if (carousel_shape_with(n, {4, 2}, out)) return true;
     if (n > 4096 && carousel_shape_with(n, {8}, out)) return true;
-    return carousel_shape_with(n, {4, 2}, out, 1024);
+    return carousel_shape_with(n, {4, 2}, out, 1024) || carousel_odd_shape_for(n, out);
+}
+// The scaled and lifted rotation forms renormalise on the last copy of an unrolled group of blocks, which needs a
+// slot count that divides the renormalisation period: the shapes with 2, 4 or 8 slots per lane.
+inline bool carousel_has_forms(int n)
+{
+    CarouselShape f, b;
+    return carousel_shape_for(n, &f) && carousel_bwd_shape_for(n, &b) && f.M % 2 == 0 && b.M % 2 == 0;
 }
 
 template <typename T>
@@ -81,12 +97,28 @@ inline bool carousel_backward_supported(int n, long long B)
 // Columns per lane of the forward sweep: the widest of {8,4,2,1} that still gives the chip about one wavefront
 // per SIMD (measured at n = 256 .. 2048, B = 256 .. 2048: at two per SIMD, the earlier rule, n = 2048 ran
 // 1.4 to 1.9 times slower; large batches reach 8 columns either way).
-inline int carousel_width(long long B, int waves)
+// `widest`: what the shape's registers allow (carousel_fwd_widest).
+inline int carousel_width(long long B, int waves, int widest = 8)
 {
     const long long want_waves = 1024; // 256 CUs x 4 SIMDs
-    for (int w = 8; w > 1; w >>= 1)
+    for (int w = widest; w > 1; w >>= 1)
         if (((B + w - 1) / w) * waves >= want_waves) return w;
     return 1;
+}
+// Widest strips whose block loop compiles without register spills.  Workgroups of more than 8 wavefronts have
+// 168 (10, 12) or 128 (14, 16) registers per lane instead of 256, which the 7- and 5-slot shapes feel first.
+inline int carousel_fwd_widest(const CarouselShape &s)
+{
+    if (s.M == 7 && s.WAVES > 8) return 4;
+    if (s.M == 5 && s.WAVES > 12) return 4;
+    return 8;
+}
+inline int carousel_bwd_widest(const CarouselShape &s)
+{
+    if (s.M == 7 && s.WAVES > 8) return 2;
+    if (s.M == 5 && s.WAVES > 12) return 2;
+    // 5 or more slots per lane, an odd number of them, or more than 8 wavefronts: strips of at most 4 columns
+    return (s.M > 4 || s.M % 2 || s.WAVES > 8) ? 4 : 8;
 }
 
 struct CarouselFwdArgs {
@@ -167,16 +199,29 @@ int carousel_backward_m8(const CarouselBwdArgs &a, int waves, int W);
 // carousel_fwd_wide.hip / carousel_bwd_wide.hip: more than 8 wavefronts (M in {4, 2})
 int carousel_forward_wide(const CarouselFwdArgs &a, int M, int waves, int W);
 int carousel_backward_wide(const CarouselBwdArgs &a, int M, int waves, int W);
+// odd slot counts: any compiled number of wavefronts, 1 to 8 and 10 to 16
+int carousel_forward_m7(const CarouselFwdArgs &a, int waves, int W);
+int carousel_forward_m5(const CarouselFwdArgs &a, int waves, int W);
+int carousel_forward_m3(const CarouselFwdArgs &a, int waves, int W);
+int carousel_backward_m7(const CarouselBwdArgs &a, int waves, int W);
+int carousel_backward_m5(const CarouselBwdArgs &a, int waves, int W);
+int carousel_backward_m3(const CarouselBwdArgs &a, int waves, int W);
 
 inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
                             int identity, int mirror, hipStream_t stream)
 {
     CarouselShape s;
     if (!carousel_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
-    const int W = carousel_width(B, s.WAVES);
+    const int W = carousel_width(B, s.WAVES, carousel_fwd_widest(s));
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
     const CarouselFwdArgs a{n, rows, B, coefs, X, Y, identity, aligned ? 1 : 0, mirror, stream};
+    switch (s.M) {
+    case 7: return carousel_forward_m7(a, s.WAVES, W);
+    case 5: return carousel_forward_m5(a, s.WAVES, W);
+    case 3: return carousel_forward_m3(a, s.WAVES, W);
+    default: break;
+    }
     if (s.WAVES > 8) return carousel_forward_wide(a, s.M, s.WAVES, W);
     switch (s.M) {
     case 8: return carousel_forward_m8(a, s.WAVES, W);
@@ -195,9 +240,7 @@ inline int carousel_bwd_width(int n, long long B)
 {
     CarouselShape s;
     if (!carousel_bwd_shape_for(n, &s)) return 0;
-    // 8 slots per lane, or more than 8 wavefronts: strips of at most 4 columns (registers, LDS)
-    const int widest = (s.M == 8 || s.WAVES > 8) ? 4 : 8;
-    for (int w = widest; w > 2; w >>= 1)
+    for (int w = carousel_bwd_widest(s); w > 2; w >>= 1)
         if (((B + w - 1) / w) * s.WAVES >= 512) return w;
     return B > 1 ? 2 : 1;
 }
@@ -227,6 +270,12 @@ inline int carousel_backward_strips(int n, int rows, long long B, int W, long lo
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
     const CarouselBwdArgs a{n,  rows,    B,     strip0, nstrips,         groups,     coefs, Y, G,
                             dX, partial, zeros, sink,   aligned ? 1 : 0, g_identity, stream};
+    switch (s.M) {
+    case 7: return carousel_backward_m7(a, s.WAVES, W);
+    case 5: return carousel_backward_m5(a, s.WAVES, W);
+    case 3: return carousel_backward_m3(a, s.WAVES, W);
+    default: break;
+    }
     if (s.WAVES > 8) return carousel_backward_wide(a, s.M, s.WAVES, W);
     switch (s.M) {
     case 8: return carousel_backward_m8(a, s.WAVES, W);

@@ -111,7 +111,11 @@ __device__ __forceinline__ void lds_load_row(float (&dst)[W], const float *src)
 //         sin(theta') with the carried signs folded in; same renormalisation points, factors +-1).
 template <int M, int W, int WAVES, int FORM>
 struct CarouselFwd {
-    static_assert(kRenormPeriod % M == 0, "renormalisation must fall on the last copy of an unrolled group");
+    // copies of the block body in one unrolled group: a multiple of M (static register map) and even (the
+    // coefficient and exchange buffers alternate by block parity), so an odd M unrolls 2 M times
+    static constexpr int kUnroll = (M % 2) ? 2 * M : M;
+    static_assert(FORM == 0 || kRenormPeriod % kUnroll == 0,
+                  "renormalisation must fall on the last copy of an unrolled group");
     static constexpr int kLastU = (2 * M - 2) % M; // register rotation after the n-2 moves (n is a multiple of M)
 
     float top[M][W];
@@ -191,7 +195,7 @@ struct CarouselFwd {
         (rotate_slot<U, FIRST + Rs, RN>(cur, rn), ...);
     }
 
-    // One block of Algorithm 2 with the slot <-> register map of unrolled copy U, then the move.
+    // One block of Algorithm 2 as unrolled copy C (register map C mod M, buffers C mod 2), then the move.
     // LAST marks the very last block (k = 0): nothing to prefetch and no move after it.
     // RENORM (scaled form): this block closes a renormalisation period; the rows are multiplied back
     // by their factors (compile-time variant: a run-time branch around 2*M*W multiplies made the
@@ -200,12 +204,14 @@ struct CarouselFwd {
     // position, 1) need what the previous block's exchange delivers and feed this block's exchange;
     // the other slots are rotated around them, so that both LDS latencies and the barrier overlap
     // with arithmetic.
-    template <int U, bool LAST, bool RENORM>
+    template <int C, bool LAST, bool RENORM>
     __device__ __forceinline__ void step(int k)
     {
+        constexpr int U = C % M;
+        constexpr int par = C & 1;
         constexpr bool RN = FORM != 0 && (LAST || RENORM);
-        float2(&cur)[M] = cs[U & 1];
-        if constexpr (!LAST) load_coefs(k - 1, cs[(U + 1) & 1]);
+        float2(&cur)[M] = cs[par];
+        if constexpr (!LAST) load_coefs(k - 1, cs[par ^ 1]);
         float2 rn[M];
         if constexpr (RN) load_row_of(rn_lane, (n - 2 - k) / kRenormPeriod, rn);
 
@@ -227,7 +233,6 @@ struct CarouselFwd {
         constexpr int q = U % M;                // top slot 0: leaves towards the previous lane
         constexpr int qb = (M - 1 - U + M) % M; // bottom slot M-1: leaves towards the next lane
         constexpr int q1 = (1 + U) % M;         // top slot 1 (matters in lane 0 of wavefront 0)
-        constexpr int par = U & 1;
         if constexpr (!LAST) {
             lds_store_row<W, WAVES>(out_top + par * kBufFloats, top[q]);
             lds_store_row<W, WAVES>(out_bot + par * kBufFloats, bot[qb]);
@@ -253,38 +258,39 @@ struct CarouselFwd {
         }
     }
 
-    // M consecutive blocks starting at block index k_first (going down), none of them the last;
+    // kUnroll consecutive blocks starting at block index k_first (going down), none of them the last;
     // RENORM: the group's last block closes a renormalisation period
-    template <bool RENORM, int... Us>
-    __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Us...>)
+    template <bool RENORM, int... Cs>
+    __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Cs...>)
     {
-        (step<Us, false, RENORM && Us == M - 1>(k_first - Us), ...);
+        (step<Cs, false, RENORM && Cs == kUnroll - 1>(k_first - Cs), ...);
     }
-    // the closing M-1 blocks k = M-2 .. 0 (n-1 = -1 mod M, so the tail always has M-1 blocks)
-    template <int... Us>
-    __device__ __forceinline__ void tail_group(std::integer_sequence<int, Us...>)
+    // the closing kUnroll-1 blocks k = kUnroll-2 .. 0 (n is a multiple of kUnroll, so n-1 blocks always leave
+    // a tail of kUnroll-1)
+    template <int... Cs>
+    __device__ __forceinline__ void tail_group(std::integer_sequence<int, Cs...>)
     {
-        (step<Us, Us == M - 2, false>(M - 2 - Us), ...);
+        (step<Cs, Cs == kUnroll - 2, false>(kUnroll - 2 - Cs), ...);
     }
 
-    // all n-1 blocks: n/M - 1 full groups of M, then the tail of M - 1
+    // all n-1 blocks: n/kUnroll - 1 full groups, then the tail of kUnroll - 1
     __device__ __forceinline__ void sweep()
     {
-        constexpr auto seq = std::make_integer_sequence<int, M>{};
+        constexpr auto seq = std::make_integer_sequence<int, kUnroll>{};
         int k = n - 2;
         if constexpr (FORM == 0) {
-            for (; k >= M - 1; k -= M) full_group<false>(k, seq);
+            for (; k >= kUnroll - 1; k -= kUnroll) full_group<false>(k, seq);
         } else {
-            constexpr int per = kRenormPeriod / M;         // groups per renormalisation period
-            const int groups = n / M - 1;
+            constexpr int per = kRenormPeriod / kUnroll;   // groups per renormalisation period
+            const int groups = n / kUnroll - 1;
             for (int pd = 0; pd < groups / per; ++pd) {
-                for (int g = 0; g < per - 1; ++g, k -= M) full_group<false>(k, seq);
+                for (int g = 0; g < per - 1; ++g, k -= kUnroll) full_group<false>(k, seq);
                 full_group<true>(k, seq);
-                k -= M;
+                k -= kUnroll;
             }
-            for (int g = 0; g < groups % per; ++g, k -= M) full_group<false>(k, seq);
+            for (int g = 0; g < groups % per; ++g, k -= kUnroll) full_group<false>(k, seq);
         }
-        tail_group(std::make_integer_sequence<int, M - 1>{});
+        tail_group(std::make_integer_sequence<int, kUnroll - 1>{});
     }
 };
 
@@ -407,13 +413,21 @@ __global__ __launch_bounds__(64 * WAVES, WAVES > 8 ? 1 : 2) void carousel_forwar
     const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok, int mirror)
 {
     __shared__ CarouselExchange<W, WAVES> sh;
-    const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
-    if (form == kFormScaled)
-        carousel_forward_body<M, W, WAVES, kFormScaled>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok, mirror);
-    else if (form == kFormLifted)
-        carousel_forward_body<M, W, WAVES, kFormLifted>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok, mirror);
-    else
+    if constexpr (kRenormPeriod % M != 0) {
+        // slot counts that do not divide the renormalisation period: standard form only (the host passes no flag)
         carousel_forward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok, mirror);
+    } else {
+        const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
+        if (form == kFormScaled)
+            carousel_forward_body<M, W, WAVES, kFormScaled>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok,
+                                                            mirror);
+        else if (form == kFormLifted)
+            carousel_forward_body<M, W, WAVES, kFormLifted>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok,
+                                                            mirror);
+        else
+            carousel_forward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok,
+                                                              mirror);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -444,7 +458,9 @@ struct CarouselExchangeBwd {
 
 template <int M, int W, int WAVES, int FORM>
 struct CarouselBwd {
-    static_assert(kRenormPeriod % M == 0, "renormalisation must fall on the last copy of an unrolled group");
+    static constexpr int kUnroll = (M % 2) ? 2 * M : M; // as in the forward kernel
+    static_assert(FORM == 0 || kRenormPeriod % kUnroll == 0,
+                  "renormalisation must fall on the last copy of an unrolled group");
     static constexpr int kLastU = (2 * M - 2) % M;
 
     float zt[M][W], zb[M][W], gt[M][W], gb[M][W];
@@ -506,25 +522,25 @@ struct CarouselBwd {
         }
     }
 
-    // carousel move of one strip (top line `t`, bottom line `b`), reverse direction
-    template <int U, int WHICH>
+    // carousel move of one strip (top line `t`, bottom line `b`), reverse direction; register map U, buffer PAR
+    template <int U, int PAR, int WHICH>
     __device__ __forceinline__ void publish(float (&t)[M][W], float (&b)[M][W])
     {
         constexpr int qt = (M - 1 - U + M) % M; // top slot M-1: leaves towards the next lane
         constexpr int qb = U % M;               // bottom slot 0: leaves towards the previous lane
         constexpr int pf = (M - U) % M;         // top slot 0 (the held position, in lane 0 of wavefront 0)
-        constexpr int off = (U & 1) * kBufFloats + WHICH * kStripFloats;
+        constexpr int off = PAR * kBufFloats + WHICH * kStripFloats;
         lds_store_row<W, WAVES>(out_top + off, t[qt]);
         lds_store_row<W, WAVES>(out_bot + off, b[qb]);
         if (wave == 0 && lane == 0) lds_store_row<W, WAVES>(hold + off, t[pf]);
     }
-    template <int U, int WHICH>
+    template <int U, int PAR, int WHICH>
     __device__ __forceinline__ void receive(float (&t)[M][W], float (&b)[M][W])
     {
         constexpr int qt = (M - 1 - U + M) % M;
         constexpr int qb = U % M;
         constexpr int pf = (M - U) % M;
-        constexpr int off = (U & 1) * kBufFloats + WHICH * kStripFloats;
+        constexpr int off = PAR * kBufFloats + WHICH * kStripFloats;
         if (wave == 0) {
             // lane 0: bot[0] turns round into top[1], i.e. into the register the held row leaves
 #pragma unroll
@@ -597,18 +613,20 @@ struct CarouselBwd {
 
     // One block of the reverse sweep.  The slots whose rows leave the lane (0 and M-1) go first and
     // are published to LDS; the inner slots run while those writes and the barrier are in flight.
-    template <int U, bool LAST, bool RENORM>
+    template <int C, bool LAST, bool RENORM>
     __device__ __forceinline__ void step(int k)
     {
+        constexpr int U = C % M;      // register map of this unrolled copy
+        constexpr int PAR = C & 1;    // its coefficient / prior-sum / exchange buffers
         constexpr bool RN = FORM != 0 && (LAST || RENORM);
-        float2(&cur)[M] = cs[U & 1];
-        if constexpr (!LAST) load_coefs(k + 1, cs[(U + 1) & 1]);
+        float2(&cur)[M] = cs[PAR];
+        if constexpr (!LAST) load_coefs(k + 1, cs[PAR ^ 1]);
         float2 rn[M];
         if constexpr (RN) load_row_of(rn_lane, k / kRenormPeriod, rn);
         // what this workgroup's earlier strips have summed for the NEXT block: fetched a block ahead,
         // like cos/sin, and before this block's store, so that waiting for it never waits for a store
-        float(&earlier)[M] = prior[U & 1];
-        if constexpr (!LAST) load_prior(k + 1, prior[(U + 1) & 1]);
+        float(&earlier)[M] = prior[PAR];
+        if constexpr (!LAST) load_prior(k + 1, prior[PAR ^ 1]);
 
         float sums[M];
         // the inner slots all run after the exchange slots here: splitting them around the exchange as
@@ -618,8 +636,8 @@ struct CarouselBwd {
         sums[0] = sweep_slot<U, 0, RN>(cur, rn);
         if constexpr (M > 1) sums[M - 1] = sweep_slot<U, M - 1, RN>(cur, rn);
         if constexpr (!LAST) {
-            publish<U, 0>(zt, zb);
-            publish<U, 1>(gt, gb);
+            publish<U, PAR, 0>(zt, zb);
+            publish<U, PAR, 1>(gt, gb);
         }
         __builtin_amdgcn_s_setprio(0);
         if constexpr (kInner > 0) sweep_inner<U, RN, 1>(cur, rn, sums, std::make_integer_sequence<int, kInner>{});
@@ -643,41 +661,41 @@ struct CarouselBwd {
         }
         if constexpr (!LAST) {
             __syncthreads();
-            receive<U, 0>(zt, zb);
-            receive<U, 1>(gt, gb);
+            receive<U, PAR, 0>(zt, zb);
+            receive<U, PAR, 1>(gt, gb);
         }
     }
 
-    template <bool RENORM, int... Us>
-    __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Us...>)
+    template <bool RENORM, int... Cs>
+    __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Cs...>)
     {
-        (step<Us, false, RENORM && Us == M - 1>(k_first + Us), ...);
+        (step<Cs, false, RENORM && Cs == kUnroll - 1>(k_first + Cs), ...);
     }
-    template <int... Us>
-    __device__ __forceinline__ void tail_group(int k_first, std::integer_sequence<int, Us...>)
+    template <int... Cs>
+    __device__ __forceinline__ void tail_group(int k_first, std::integer_sequence<int, Cs...>)
     {
-        (step<Us, Us == M - 2, false>(k_first + Us), ...);
+        (step<Cs, Cs == kUnroll - 2, false>(k_first + Cs), ...);
     }
 
-    // all n-1 blocks in the order b_1, b_2, ...: n/M - 1 full groups of M, then the tail of M - 1
+    // all n-1 blocks in the order b_1, b_2, ...: n/kUnroll - 1 full groups, then the tail of kUnroll - 1
     __device__ __forceinline__ void sweep()
     {
-        constexpr auto seq = std::make_integer_sequence<int, M>{};
+        constexpr auto seq = std::make_integer_sequence<int, kUnroll>{};
         load_prior(0, prior[0]);
         int k = 0;
         if constexpr (FORM == 0) {
-            for (; k + M <= n - 1; k += M) full_group<false>(k, seq);
+            for (; k + kUnroll <= n - 1; k += kUnroll) full_group<false>(k, seq);
         } else {
-            constexpr int per = kRenormPeriod / M;
-            const int groups = n / M - 1;
+            constexpr int per = kRenormPeriod / kUnroll;
+            const int groups = n / kUnroll - 1;
             for (int pd = 0; pd < groups / per; ++pd) {
-                for (int g = 0; g < per - 1; ++g, k += M) full_group<false>(k, seq);
+                for (int g = 0; g < per - 1; ++g, k += kUnroll) full_group<false>(k, seq);
                 full_group<true>(k, seq);
-                k += M;
+                k += kUnroll;
             }
-            for (int g = 0; g < groups % per; ++g, k += M) full_group<false>(k, seq);
+            for (int g = 0; g < groups % per; ++g, k += kUnroll) full_group<false>(k, seq);
         }
-        tail_group(k, std::make_integer_sequence<int, M - 1>{});
+        tail_group(k, std::make_integer_sequence<int, kUnroll - 1>{});
     }
 };
 
@@ -763,20 +781,26 @@ __global__ __launch_bounds__(64 * WAVES, WAVES > 8 ? 1 : 2) void carousel_backwa
     float *dX, float *partial, const float *__restrict__ zeros, float *sink, int vec_ok, int g_identity)
 {
     __shared__ CarouselExchangeBwd<W, WAVES> sh;
-    const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
-    if (form == kFormScaled)
-        carousel_backward_body<M, W, WAVES, kFormScaled>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G, dX,
-                                                         partial, zeros, sink, vec_ok, g_identity);
-    else if (form == kFormLifted)
-        carousel_backward_body<M, W, WAVES, kFormLifted>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G, dX,
-                                                         partial, zeros, sink, vec_ok, g_identity);
-    else
+    if constexpr (kRenormPeriod % M != 0) {
         carousel_backward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G, dX,
                                                            partial, zeros, sink, vec_ok, g_identity);
+    } else {
+        const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
+        if (form == kFormScaled)
+            carousel_backward_body<M, W, WAVES, kFormScaled>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G,
+                                                             dX, partial, zeros, sink, vec_ok, g_identity);
+        else if (form == kFormLifted)
+            carousel_backward_body<M, W, WAVES, kFormLifted>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G,
+                                                             dX, partial, zeros, sink, vec_ok, g_identity);
+        else
+            carousel_backward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G,
+                                                               dX, partial, zeros, sink, vec_ok, g_identity);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
-// launches (instantiated per number of slots per lane by carousel_fwd_m*.hip / carousel_bwd_m*.hip)
+// launches (instantiated per number of slots per lane by carousel_fwd_m*.hip / carousel_bwd_m*.hip, and for more
+// than 8 wavefronts by carousel_fwd_wide.hip / carousel_bwd_wide.hip)
 // ---------------------------------------------------------------------------------------------
 template <int M, int W, int WAVES>
 inline void carousel_launch_fwd(const CarouselFwdArgs &a)
@@ -848,6 +872,53 @@ inline int carousel_backward_slots(const CarouselBwdArgs &a, int waves, int W)
     case 6: return carousel_bwd_widths<M, 6>(W, a);
     case 7: return carousel_bwd_widths<M, 7>(W, a);
     case 8: return carousel_bwd_widths<M, 8>(W, a);
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+
+// Shapes with an odd number of slots per lane (standard rotation form only, reverse-sweep strips of at most 4
+// columns): every compiled number of wavefronts, up to 1024 lanes.
+template <int M>
+inline int carousel_forward_odd_slots(const CarouselFwdArgs &a, int waves, int W)
+{
+    static_assert(M % 2 == 1, "the even slot counts have their own translation units");
+    switch (waves) {
+    case 10: return carousel_fwd_widths<M, 10>(W, a);
+    case 12: return carousel_fwd_widths<M, 12>(W, a);
+    case 14: return carousel_fwd_widths<M, 14>(W, a);
+    case 16: return carousel_fwd_widths<M, 16>(W, a);
+    default: return carousel_forward_slots<M>(a, waves, W);
+    }
+}
+
+template <int M, int WAVES>
+inline int carousel_bwd_narrow_widths(int W, const CarouselBwdArgs &a)
+{
+    switch (W) {
+    case 4: carousel_launch_bwd<M, 4, WAVES>(a); return GIVENS_OK;
+    case 2: carousel_launch_bwd<M, 2, WAVES>(a); return GIVENS_OK;
+    case 1: carousel_launch_bwd<M, 1, WAVES>(a); return GIVENS_OK;
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+
+template <int M>
+inline int carousel_backward_odd_slots(const CarouselBwdArgs &a, int waves, int W)
+{
+    static_assert(M % 2 == 1, "the even slot counts have their own translation units");
+    switch (waves) {
+    case 1: return carousel_bwd_narrow_widths<M, 1>(W, a);
+    case 2: return carousel_bwd_narrow_widths<M, 2>(W, a);
+    case 3: return carousel_bwd_narrow_widths<M, 3>(W, a);
+    case 4: return carousel_bwd_narrow_widths<M, 4>(W, a);
+    case 5: return carousel_bwd_narrow_widths<M, 5>(W, a);
+    case 6: return carousel_bwd_narrow_widths<M, 6>(W, a);
+    case 7: return carousel_bwd_narrow_widths<M, 7>(W, a);
+    case 8: return carousel_bwd_narrow_widths<M, 8>(W, a);
+    case 10: return carousel_bwd_narrow_widths<M, 10>(W, a);
+    case 12: return carousel_bwd_narrow_widths<M, 12>(W, a);
+    case 14: return carousel_bwd_narrow_widths<M, 14>(W, a);
+    case 16: return carousel_bwd_narrow_widths<M, 16>(W, a);
     default: return GIVENS_ERR_UNSUPPORTED;
     }
 }

@@ -341,9 +341,10 @@ struct FormPolicy {
 // it: measured, they pay from about n = B = 2048 (4.3e9 updates; 2.97 against 3.08 ms per step) and lose below
 // (n = B = 1024, 5.4e8: 0.98 against 0.92 ms; n = B = 256: 0.20 against 0.14 ms).
 constexpr double kFormsMinUpdates = 1.0e9;
-FormPolicy form_policy(bool float_carousel, int form_choice, double updates)
+FormPolicy form_policy(bool float_carousel, int n, int form_choice, double updates)
 {
-    if (!float_carousel || form_choice == GIVENS_FORM_STANDARD) return {false, 0.f};
+    // a carousel shape with an odd number of slots per lane has the standard form only
+    if (!float_carousel || !carousel_has_forms(n) || form_choice == GIVENS_FORM_STANDARD) return {false, 0.f};
     if (form_choice == GIVENS_FORM_LIFTED) return {true, -1.f};
     if (form_choice == GIVENS_FORM_AUTO && updates < kFormsMinUpdates) return {false, 0.f};
     return {true, kScaledMaxAbsTheta};
@@ -729,7 +730,7 @@ int forward_impl(int rows, int m, long long B, const T *theta, const T *X, T *Y,
     Families fam;
     if (int rc = pick_forward_family<T>(n, B, opt.kernel, &fam)) return rc;
     Coefs<T> coefs;
-    const FormPolicy policy = form_policy(fam.carousel && std::is_same<T, float>::value, opt.form, sweep_updates(n, B));
+    const FormPolicy policy = form_policy(fam.carousel && std::is_same<T, float>::value, n, opt.form, sweep_updates(n, B));
     if (no_alloc) {
         if constexpr (std::is_same<T, float>::value) {
             CoefStorage<float> st;
@@ -812,12 +813,12 @@ int backward_impl(int rows, int m, long long B, const T *theta, const T *Y, cons
     invalidate_prepared(*ws, false, true);
     Coefs<T> coefs;
     if (int rc = build_coefs<T>(*ws, ws->rev, pb, theta, false,
-                                form_policy(fam.carousel && std::is_same<T, float>::value, opt.form, sweep_updates(n, B)),
+                                form_policy(fam.carousel && std::is_same<T, float>::value, n, opt.form, sweep_updates(n, B)),
                                 stream, &coefs))
         return rc;
     auto mirrored_for_dx = [&](Families dx_fam, Coefs<T> *out) {
         return build_coefs<T>(*ws, ws->mirrored, pb, theta, true,
-                              form_policy(dx_fam.carousel && std::is_same<T, float>::value, opt.form, sweep_updates(n, B)),
+                              form_policy(dx_fam.carousel && std::is_same<T, float>::value, n, opt.form, sweep_updates(n, B)),
                               stream, out, 1);
     };
     return run_backward<T>(*ws, dev, pb, B, coefs, fam, opt, Y, G, dX, dtheta, stream, mirrored_for_dx);
@@ -855,7 +856,7 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
     bool range_known = false, mirrored_forms = false;
     // without a hint the batch is not known here and AUTO means GIVENS_FORM_RANGE
     const double kAnyBatch = batch_hint > 0 ? sweep_updates(n, batch_hint) : 1.0e300;
-    const FormPolicy fpol = form_policy(ffam.carousel, opt.form, kAnyBatch), bpol = form_policy(bfam.carousel, opt.form, kAnyBatch);
+    const FormPolicy fpol = form_policy(ffam.carousel, n, opt.form, kAnyBatch), bpol = form_policy(bfam.carousel, n, opt.form, kAnyBatch);
     // one range check for all the sets, into the flag word that belongs to givens_prepare
     auto build = [&](CoefSet &set, bool forward, FormPolicy pol, int mirror) {
         if (pol.try_forms && !range_known) {
@@ -880,7 +881,7 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
         Families dx_fam;
         dx_fam.column = bfam.column;
         dx_fam.carousel = !bfam.column && bfam.carousel;
-        const FormPolicy mpol = form_policy(dx_fam.carousel, opt.form, kAnyBatch);
+        const FormPolicy mpol = form_policy(dx_fam.carousel, n, opt.form, kAnyBatch);
         if (int rc = build(ws->mirrored, true, mpol, 1)) return rc;
         mirrored_forms = mpol.try_forms;
     }
@@ -894,7 +895,7 @@ int64_t prepare_impl(int rows, int m, const float *theta, int directions, void *
     p.fwd_forms = fwd && fpol.try_forms;
     p.rev_forms = rev && bpol.try_forms;
     p.mirrored_forms = wide && mirrored_forms;
-    p.scaled_max = form_policy(true, opt.form, kAnyBatch).scaled_max;
+    p.scaled_max = form_policy(true, n, opt.form, kAnyBatch).scaled_max;
     return p.token;
 }
 

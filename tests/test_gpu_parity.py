@@ -237,6 +237,32 @@ def test_carousel_shapes_with_more_than_512_lanes(n, B, seed, dist):
     binding.release()
 
 
+@pytest.mark.parametrize("n,B,seed,dist", [(210, 33, 41, "uniform"), (1002, 70, 42, "uniform"),
+                                           (1010, 2100, 43, "normal0.1"), (2114, 40, 44, "uniform"),
+                                           (2050, 600, 45, "uniform"), (4098, 16, 46, "normal0.1"),
+                                           (6126, 8, 47, "uniform"), (8400, 8, 48, "uniform"),
+                                           (9010, 6, 49, "normal0.1"), (4100, 24, 50, "uniform")])
+def test_carousel_shapes_with_an_odd_number_of_slots_per_lane(n, B, seed, dist):
+    """Even n that no shape with 2, 4 or 8 slots per lane covers (n = 2 mod 4, and multiples of 4 or 8 too large
+    for 1024 lanes), with a factor 7, 5 or 3 in n / 2: 7 slots (210, 2114, 8400), 5 (1010, 2050, 4100, 9010) and
+    3 (1002, 4098, 6126) per lane, 1 to 16 wavefronts; standard rotation form whatever the angles, both sweeps;
+    1010 x 2100 takes the Gram form, 2050 x 600 gives persistent workgroups a second strip."""
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    print(f"[parity] n={n} B={B} seed={seed} {dist}", flush=True)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
+                           binding.KERNEL_CAROUSEL)
+    assert binding.last_kernel() == binding.KERNEL_CAROUSEL      # the reverse sweep too
+    assert binding.last_rotation_form() == binding.FORM_STANDARD
+    binding.release()
+
+
+def test_sizes_whose_half_is_a_prime_stay_in_the_lds_family():
+    """n = 2 p with p prime has no carousel shape (the slot count must divide n / 2)."""
+    data = inputs.make_custom(1006, 40, seed=39)
+    check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G, binding.KERNEL_LDS)
+    assert binding.last_kernel() == binding.KERNEL_LDS
+
+
 # ---------------------------------------------------------------- scaled rotation form (near-identity angles)
 @pytest.mark.parametrize("n,B,seed", [(256, 64, 51), (512, 100, 52), (1024, 67, 53), (2048, 130, 54)])
 def test_scaled_form_is_used_for_small_angles_and_matches_the_oracle(n, B, seed):
@@ -410,7 +436,7 @@ def test_gram_reduction_can_be_forced_on_a_narrow_batch_in_both_families():
         binding.set_kernel(binding.KERNEL_AUTO)
 
 
-@pytest.mark.parametrize("n,B,seed", [(202, 900, 111), (302, 700, 112), (1002, 2100, 113)])
+@pytest.mark.parametrize("n,B,seed", [(202, 900, 111), (302, 700, 112), (1006, 2100, 113)])
 def test_lds_family_wide_batches_use_the_gram_form(n, B, seed):
     data = inputs.make_custom(n, B, seed=seed)
     binding.set_kernel(binding.KERNEL_AUTO)

@@ -107,6 +107,13 @@ def test_carousel_family_restricted_and_odd_small_angles_use_the_scaled_form(n, 
           expect_form=binding.FORM_SCALED)
 
 
+@pytest.mark.parametrize("n,m,B,seed", [(1001, 1000, 48, 345), (2049, 700, 40, 346), (4097, 512, 24, 347)])
+def test_odd_sizes_that_pad_to_an_odd_slot_count_shape(n, m, B, seed):
+    """1002 = 6 x 167, 2050 = 10 x 205, 4098 = 6 x 683: padded sizes with 3 or 5 slots per lane (standard form)."""
+    check(n, m, B, seed, kernel=binding.KERNEL_AUTO, expect_kernel=binding.KERNEL_CAROUSEL,
+          expect_form=binding.FORM_STANDARD)
+
+
 def test_standard_form_and_forced_two_stage_reduction_with_a_restricted_problem():
     try:
         binding.set_rotation_form(binding.FORM_STANDARD)
