@@ -256,6 +256,38 @@ def test_carousel_shapes_with_an_odd_number_of_slots_per_lane(n, B, seed, dist):
     binding.release()
 
 
+@pytest.mark.parametrize("slots", [3, 5, 7])
+def test_every_workgroup_size_of_the_odd_slot_count_shapes(slots):
+    """n = 2 M L with L = 64 w - 3 lanes for every compiled number of wavefronts w (1..8, 10, 12, 14, 16): n / 2 is
+    odd, so only a shape with an odd slot count applies (M itself, or another odd factor of L with fewer lanes);
+    narrow batch, so the narrow strip widths are the ones that run, with a ragged last strip."""
+    for w in (1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16):
+        n = 2 * slots * (64 * w - 3)
+        if n < 132:
+            continue
+        B = 3 if n > 6000 else 7
+        data = inputs.make_custom(n, B, seed=7000 + n)
+        print(f"[parity] slots={slots} wavefronts={w} n={n} B={B}", flush=True)
+        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
+                               binding.KERNEL_CAROUSEL)
+        assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+        binding.release()
+
+
+def test_every_even_size_up_to_700_matches_the_oracle_in_its_default_family():
+    """All even n from 130 to 700 (carousel shapes with 8, 4, 2, 7, 5 or 3 slots per lane, LDS family where n / 2 is
+    a prime), forward and reverse sweeps, B = 5."""
+    families = set()
+    for n in range(130, 701, 2):
+        data = inputs.make_custom(n, 5, seed=9000 + n)
+        if n % 50 == 0:
+            print(f"[parity] n={n}", flush=True)
+        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G)
+        families.add(binding.last_kernel())
+    assert families == {binding.KERNEL_CAROUSEL, binding.KERNEL_LDS}
+    binding.release()
+
+
 def test_sizes_whose_half_is_a_prime_stay_in_the_lds_family():
     """n = 2 p with p prime has no carousel shape (the slot count must divide n / 2)."""
     data = inputs.make_custom(1006, 40, seed=39)
