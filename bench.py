@@ -137,6 +137,9 @@ def main() -> int:
                          "only enqueues (no wait between calls); the per-kernel figures then come from a second, "
                          "untimed pass of at most 20 steps.  For the small workloads, where the host's wait after "
                          "every call is a visible part of the step")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step into a HIP graph after the warm-up and time replays of it (the launch-bound "
+                         "small workloads); implies --enqueue-only for the per-kernel figures")
     ap.add_argument("--build", type=int, default=None, metavar="N",
                     help="the paper's own experiment at size N: build U(theta) from N(N-1)/2 uniform random angles "
                          "(givens_build) and take the gradient of a loss on U (dtheta-only givens_backward with a "
@@ -171,6 +174,11 @@ def main() -> int:
 
     if args.unitary:
         return _bench_unitary(args, binding, torch, np)
+    if args.graph:
+        # graphs are recorded on a stream other than the null stream (default priority); the whole run uses it, so
+        # that the workspace and any prepared coefficients belong to it
+        side = torch.cuda.Stream()
+        torch.cuda.set_stream(side)
 
     wl = inputs.WORKLOADS[args.workload]
     if args.build:
@@ -240,15 +248,31 @@ def main() -> int:
         binding.givens_backward(th_d, y_d, g_d, dX=dx_d, dtheta=dth_d, want_dx=not identity)
         return t_f, last_timing()
 
+    args.enqueue_only = args.enqueue_only or args.graph
     timing_on[0] = not args.enqueue_only
     binding.set_timing(timing_on[0])
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    kernel_times = [step() for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    if args.graph:
+        # the stream's workspace is warm, so a step allocates nothing: record it and replay it
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(3):
+            graph.replay()
+        side.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        side.synchronize()
+        elapsed = time.perf_counter() - t0
+        kernel_times = []
+    else:
+        t0 = time.perf_counter()
+        kernel_times = [step() for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     if args.enqueue_only:
         timing_on[0] = True
         binding.set_timing(True)
@@ -303,7 +327,8 @@ def main() -> int:
                             else "givens_forward_prepared + givens_backward_prepared (token prepared once)"
                             if prepared == "frozen"
                             else ("givens_build" if identity else "givens_forward") + " + givens_backward"),
-                   "host": ("enqueues only; kernel_ms from a second pass" if args.enqueue_only
+                   "host": ("replays a HIP graph of one step; kernel_ms from a second, eager pass" if args.graph
+                            else "enqueues only; kernel_ms from a second pass" if args.enqueue_only
                             else "waits for each call's timing events"),
                    "kernel_family": family_name,
                    "rotation_form": {binding.FORM_STANDARD: "standard", binding.FORM_SCALED: "scaled",
