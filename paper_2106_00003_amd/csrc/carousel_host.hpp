@@ -86,6 +86,29 @@ inline bool carousel_has_forms(int n)
     return carousel_shape_for(n, &f) && carousel_bwd_shape_for(n, &b) && f.M % 2 == 0 && b.M % 2 == 0;
 }
 
+// One-wavefront shapes whose exchange stays inside the wavefront (DPP shifts, no LDS, no barrier): the fewest slots
+// per lane in {2, 4, 8} with at most 64 lanes, so multiples of 8 up to 256, 512 and 1024.  A lane then has the least
+// work per block, and the block-to-block chain is what bounds the small sweeps these shapes are for.  max_slots: 8
+// for the forward sweep, 4 for the reverse sweep (with 8 slots and two strips per lane it does not beat the LDS
+// exchange).
+inline bool carousel_wave_shape_for(int n, int max_slots, CarouselShape *out)
+{
+    if (n < kCarouselMinN) return false;
+    if (n % 8) return false;   // the kernels unroll 8 blocks (ring of prefetched coefficients)
+    for (int m : {2, 4, 8})
+        if (m <= max_slots && n % (2 * m) == 0 && n / (2 * m) <= 64) {
+            *out = {m, 1};
+            return true;
+        }
+    return false;
+}
+
+// What a sweep runs with: shape, columns per lane, and whether the exchange stays inside the wavefront.
+struct CarouselPlan {
+    CarouselShape s;
+    int W;
+    bool wave;
+};
 template <typename T>
 inline bool carousel_backward_supported(int n, long long B)
 {
@@ -207,15 +230,41 @@ int carousel_backward_m7(const CarouselBwdArgs &a, int waves, int W);
 int carousel_backward_m5(const CarouselBwdArgs &a, int waves, int W);
 int carousel_backward_m3(const CarouselBwdArgs &a, int waves, int W);
 
+int carousel_forward_wave(const CarouselFwdArgs &a, int M, int W);
+int carousel_backward_wave(const CarouselBwdArgs &a, int M, int W);
+
+// Forward sweep.  The wavefront exchange is taken where it was measured faster than the LDS exchange (n = 256 ..
+// 1024, B = 64 .. 16384): batches up to 16384 columns with 2 or 4 slots per lane (1.5 to 3.2 times faster), up to
+// 8192 with 8 (1.05 to 1.7 times).  Its strips are single columns while the batch gives each SIMD at most one
+// wavefront, then 2 and 4 columns: every wavefront reads the whole coefficient table, and beyond about a thousand
+// wavefronts that traffic (L2) sets the time.
+inline bool carousel_fwd_plan(int n, long long B, CarouselPlan *p)
+{
+    if (!carousel_shape_for(n, &p->s)) return false;
+    p->W = carousel_width(B, p->s.WAVES, carousel_fwd_widest(p->s));
+    p->wave = false;
+    CarouselShape ws;
+    if (carousel_wave_shape_for(n, 8, &ws)) {
+        const bool eight = ws.M == 8;
+        if (B <= (eight ? 8192 : 16384)) {
+            const int w = B <= (eight ? 512 : 1024) ? 1 : B <= (eight ? 2048 : 4096) ? 2 : 4;
+            *p = {ws, w, true};
+        }
+    }
+    return true;
+}
+
 inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &coefs, const float *X, float *Y,
                             int identity, int mirror, hipStream_t stream)
 {
-    CarouselShape s;
-    if (!carousel_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
-    const int W = carousel_width(B, s.WAVES, carousel_fwd_widest(s));
+    CarouselPlan plan;
+    if (!carousel_fwd_plan(n, B, &plan)) return GIVENS_ERR_UNSUPPORTED;
+    const CarouselShape s = plan.s;
+    const int W = plan.W;
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (identity || reinterpret_cast<uintptr_t>(X) % 16 == 0);
     const CarouselFwdArgs a{n, rows, B, coefs, X, Y, identity, aligned ? 1 : 0, mirror, stream};
+    if (plan.wave) return carousel_forward_wave(a, s.M, W);
     switch (s.M) {
     case 7: return carousel_forward_m7(a, s.WAVES, W);
     case 5: return carousel_forward_m5(a, s.WAVES, W);
@@ -236,21 +285,35 @@ inline int carousel_forward(int n, int rows, long long B, const CarouselCoefs &c
 // by the latency of its exchange, not by arithmetic): the widest of {8, 4, 2} that still gives the chip 512
 // wavefronts, and 2 below that (measured at n = 256 .. 2048, B = 256 .. 2048: 1.1 to 1.8 times faster than
 // the forward sweep's rule).
+inline bool carousel_bwd_plan(int n, long long B, CarouselPlan *p)
+{
+    if (!carousel_bwd_shape_for(n, &p->s)) return false;
+    p->wave = false;
+    p->W = B > 1 ? 2 : 1;
+    for (int w = carousel_bwd_widest(p->s); w > 2; w >>= 1)
+        if (((B + w - 1) / w) * p->s.WAVES >= 512) {
+            p->W = w;
+            break;
+        }
+    // wavefront exchange: n up to 512 and batches up to 4096 columns (measured 1.2 to 2.1 times faster, sweep and
+    // second stage together; each strip costs a row of partial sums, hence wider strips sooner than forward)
+    CarouselShape ws;
+    if (B <= 4096 && carousel_wave_shape_for(n, 4, &ws)) *p = {ws, B <= 256 ? 1 : B <= 1024 ? 2 : 4, true};
+    return true;
+}
 inline int carousel_bwd_width(int n, long long B)
 {
-    CarouselShape s;
-    if (!carousel_bwd_shape_for(n, &s)) return 0;
-    for (int w = carousel_bwd_widest(s); w > 2; w >>= 1)
-        if (((B + w - 1) / w) * s.WAVES >= 512) return w;
-    return B > 1 ? 2 : 1;
+    CarouselPlan p;
+    return carousel_bwd_plan(n, B, &p) ? p.W : 0;
 }
 
 // Number of persistent workgroups the reverse sweep runs with: what the chip holds at once (the
 // kernel is limited to two wavefronts per SIMD by its registers), or one per strip if that is fewer.
-inline long long carousel_bwd_groups(int n, long long nstrips, int compute_units)
+inline long long carousel_bwd_groups(int n, long long B, long long nstrips, int compute_units)
 {
-    CarouselShape s;
-    if (!carousel_bwd_shape_for(n, &s)) return 0;
+    CarouselPlan p;
+    if (!carousel_bwd_plan(n, B, &p)) return 0;
+    const CarouselShape s = p.s;
     const long long resident = (long long)compute_units * (8 / s.WAVES > 0 ? 8 / s.WAVES : 1);
     return nstrips < resident ? nstrips : resident;
 }
@@ -263,13 +326,15 @@ inline int carousel_backward_strips(int n, int rows, long long B, int W, long lo
                                     float *dX, float *partial, const float *zeros, float *sink, int g_identity,
                                     hipStream_t stream)
 {
-    CarouselShape s;
-    if (!carousel_bwd_shape_for(n, &s)) return GIVENS_ERR_UNSUPPORTED;
+    CarouselPlan plan;
+    if (!carousel_bwd_plan(n, B, &plan) || plan.W != W) return GIVENS_ERR_UNSUPPORTED;
+    const CarouselShape s = plan.s;
     const bool aligned = (B % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0) &&
                          (g_identity || reinterpret_cast<uintptr_t>(G) % 16 == 0) &&
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
     const CarouselBwdArgs a{n,  rows,    B,     strip0, nstrips,         groups,     coefs, Y, G,
                             dX, partial, zeros, sink,   aligned ? 1 : 0, g_identity, stream};
+    if (plan.wave) return carousel_backward_wave(a, s.M, W);
     switch (s.M) {
     case 7: return carousel_backward_m7(a, s.WAVES, W);
     case 5: return carousel_backward_m5(a, s.WAVES, W);

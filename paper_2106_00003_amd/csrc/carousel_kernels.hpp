@@ -38,6 +38,40 @@
 
 namespace givens {
 
+// How the slots that leave a lane reach the neighbouring lane.
+//   kExchangeLds:  through LDS, for every lane (any number of wavefronts); one barrier per block.
+//   kExchangeWave: with DPP wavefront shifts, for workgroups of one wavefront.  No LDS, no barrier, and a chain of
+//                  a few cycles from one block to the next instead of an LDS write, a barrier and an LDS read.
+//                  Each move costs VALU issue slots (two shifts and one or two selects per column), so it is
+//                  the choice where a sweep is bound by that chain and not by arithmetic: few, narrow strips.
+enum { kExchangeLds = 0, kExchangeWave = 1 };
+// Coefficients (and the reverse sweep's earlier sums) are fetched ahead into a ring of registers: one block ahead
+// where the LDS exchange sets the pace of a block anyway, three or seven blocks ahead with the wavefront exchange,
+// whose blocks are shorter than a load's latency (a ring of 2 left those sweeps at one L2 latency per block: n = 256,
+// 64 columns, forward 38 us; ring of 4: 22 us; ring of 8: 15 us).
+// (ring slots are static, so the unrolled group has lcm(M, depth) copies and n must be a multiple of that: 8 here)
+constexpr int wave_ring_depth_fwd(int M) { return M == 8 ? 4 : 8; }
+constexpr int wave_ring_depth_bwd(int M) { return M == 2 ? 8 : 4; }
+constexpr int carousel_lcm(int a, int b)
+{
+    int x = a, y = b;
+    while (y) { const int t = x % y; x = y; y = t; }
+    return a / x * b;
+}
+
+// lane l receives the value of lane l+1; lane 63 (no source) keeps `incoming`
+__device__ __forceinline__ float lane_from_next(float incoming, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(incoming), __float_as_int(v),
+                                                      0x130 /* wave_shl:1 */, 0xf, 0xf, false));
+}
+// lane l receives the value of lane l-1; lane 0 (no source) keeps `incoming`
+__device__ __forceinline__ float lane_from_prev(float incoming, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(incoming), __float_as_int(v),
+                                                      0x138 /* wave_shr:1 */, 0xf, 0xf, false));
+}
+
 // The carousel move goes through LDS for every lane: each lane writes the slot that leaves its top
 // line and the slot that leaves its bottom line, and after the barrier reads its neighbours'.  This
 // costs LDS bandwidth (2*W floats written and read per lane per block), which is otherwise idle,
@@ -109,19 +143,22 @@ __device__ __forceinline__ void lds_load_row(float (&dst)[W], const float *src)
 //         table holds alpha and beta, renormalisation every kRenormPeriod blocks; coef_kernels.hpp).
 // FORM 2: lifted rotation (3 dependent FMA per update: three shears; table holds tan(theta'/2) and
 //         sin(theta') with the carried signs folded in; same renormalisation points, factors +-1).
-template <int M, int W, int WAVES, int FORM>
+template <int M, int W, int WAVES, int FORM, int EX = kExchangeLds>
 struct CarouselFwd {
-    // copies of the block body in one unrolled group: a multiple of M (static register map) and even (the
-    // coefficient and exchange buffers alternate by block parity), so an odd M unrolls 2 M times
-    static constexpr int kUnroll = (M % 2) ? 2 * M : M;
+    static_assert(EX == kExchangeLds || WAVES == 1, "the DPP exchange stays inside one wavefront");
+    // copies of the block body in one unrolled group: a multiple of M (static register map) and of the ring depth
+    // (static ring slot; the LDS exchange buffers alternate by block parity), so an odd M unrolls 2 M times
+    static constexpr int kDepth = EX == kExchangeWave ? wave_ring_depth_fwd(M) : 2;
+    static constexpr int kUnroll = carousel_lcm(M, kDepth);
     static_assert(FORM == 0 || kRenormPeriod % kUnroll == 0,
                   "renormalisation must fall on the last copy of an unrolled group");
     static constexpr int kLastU = (2 * M - 2) % M; // register rotation after the n-2 moves (n is a multiple of M)
 
     float top[M][W];
     float bot[M][W];
-    float2 cs[2][M];
+    float2 cs[kDepth][M];
     int n, H, lane, wave, tid;
+    int lanes;              // L = n / (2 M): lanes that hold slots (wavefront exchange: where the far end is)
     const float2 *tab_lane; // table + tid*M
     const float2 *rn_lane;  // renormalisation factors + tid*M (scaled form)
     // this lane's LDS addresses in exchange buffer 0 (buffer 1 is at a compile-time offset)
@@ -195,8 +232,8 @@ struct CarouselFwd {
         (rotate_slot<U, FIRST + Rs, RN>(cur, rn), ...);
     }
 
-    // One block of Algorithm 2 as unrolled copy C (register map C mod M, buffers C mod 2), then the move.
-    // LAST marks the very last block (k = 0): nothing to prefetch and no move after it.
+    // One block of Algorithm 2 as unrolled copy C (register map C mod M, ring slot C mod kDepth), then the move.
+    // LAST marks the very last block (k = 0): no move after it.  PF: block k - (kDepth - 1) exists and is fetched.
     // RENORM (scaled form): this block closes a renormalisation period; the rows are multiplied back
     // by their factors (compile-time variant: a run-time branch around 2*M*W multiplies made the
     // register allocator spill).
@@ -204,14 +241,14 @@ struct CarouselFwd {
     // position, 1) need what the previous block's exchange delivers and feed this block's exchange;
     // the other slots are rotated around them, so that both LDS latencies and the barrier overlap
     // with arithmetic.
-    template <int C, bool LAST, bool RENORM>
+    template <int C, bool LAST, bool RENORM, bool PF>
     __device__ __forceinline__ void step(int k)
     {
         constexpr int U = C % M;
         constexpr int par = C & 1;
         constexpr bool RN = FORM != 0 && (LAST || RENORM);
-        float2(&cur)[M] = cs[par];
-        if constexpr (!LAST) load_coefs(k - 1, cs[par ^ 1]);
+        float2(&cur)[M] = cs[C % kDepth];
+        if constexpr (PF) load_coefs(k - (kDepth - 1), cs[(C + kDepth - 1) % kDepth]);
         float2 rn[M];
         if constexpr (RN) load_row_of(rn_lane, (n - 2 - k) / kRenormPeriod, rn);
 
@@ -233,7 +270,7 @@ struct CarouselFwd {
         constexpr int q = U % M;                // top slot 0: leaves towards the previous lane
         constexpr int qb = (M - 1 - U + M) % M; // bottom slot M-1: leaves towards the next lane
         constexpr int q1 = (1 + U) % M;         // top slot 1 (matters in lane 0 of wavefront 0)
-        if constexpr (!LAST) {
+        if constexpr (!LAST && EX == kExchangeLds) {
             lds_store_row<W, WAVES>(out_top + par * kBufFloats, top[q]);
             lds_store_row<W, WAVES>(out_bot + par * kBufFloats, bot[qb]);
             if (wave == 0) {
@@ -246,12 +283,26 @@ struct CarouselFwd {
                 }
             }
         }
+        if constexpr (!LAST && EX == kExchangeWave) {
+            // the whole move inside the wavefront: the top slot that leaves comes from the next lane (at the far
+            // end, lane L-1, it is the lane's own leaving bottom slot), the bottom slot from the previous lane (in
+            // lane 0 it is the lane's own top slot 1, and the held row hops into that register)
+            const bool far = lane == lanes - 1;
+#pragma unroll
+            for (int x = 0; x < W; ++x) {
+                const float t_out = top[q][x], b_out = bot[qb][x], t_one = top[q1][x];
+                const float t_in = lane_from_next(b_out, t_out);
+                bot[qb][x] = lane_from_prev(t_one, b_out);
+                top[q][x] = far ? b_out : t_in;
+                top[q1][x] = (lane == 0) ? t_out : top[q1][x];
+            }
+        }
 
         __builtin_amdgcn_s_setprio(0);
         if constexpr (kInner - kInnerA > 0)
             rotate_inner<U, RN, 2 + kInnerA>(cur, rn, std::make_integer_sequence<int, kInner - kInnerA>{});
 
-        if constexpr (!LAST) {
+        if constexpr (!LAST && EX == kExchangeLds) {
             __syncthreads();
             lds_load_row<W, WAVES>(top[q], in_top + par * kBufFloats);
             lds_load_row<W, WAVES>(bot[qb], in_bot + par * kBufFloats);
@@ -263,14 +314,14 @@ struct CarouselFwd {
     template <bool RENORM, int... Cs>
     __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Cs...>)
     {
-        (step<Cs, false, RENORM && Cs == kUnroll - 1>(k_first - Cs), ...);
+        (step<Cs, false, RENORM && Cs == kUnroll - 1, true>(k_first - Cs), ...);
     }
     // the closing kUnroll-1 blocks k = kUnroll-2 .. 0 (n is a multiple of kUnroll, so n-1 blocks always leave
     // a tail of kUnroll-1)
     template <int... Cs>
     __device__ __forceinline__ void tail_group(std::integer_sequence<int, Cs...>)
     {
-        (step<Cs, Cs == kUnroll - 2, false>(kUnroll - 2 - Cs), ...);
+        (step<Cs, Cs == kUnroll - 2, false, (kUnroll - 2 - Cs >= kDepth - 1)>(kUnroll - 2 - Cs), ...);
     }
 
     // all n-1 blocks: n/kUnroll - 1 full groups, then the tail of kUnroll - 1
@@ -349,15 +400,16 @@ __device__ __forceinline__ void store_row(const float (&src)[W], float *Y, long 
 // coefficient tables (theta_at in coef_kernels.hpp) the launch then computes U(theta)^T X.
 __device__ __forceinline__ int mirrored_row(int n, int r, int mirror) { return (mirror && r) ? n - r : r; }
 
-template <int M, int W, int WAVES, int FORM>
-__device__ __forceinline__ void carousel_forward_body(CarouselExchange<W, WAVES> &sh, int n, int rows, long long B,
+template <int M, int W, int WAVES, int FORM, int EX, typename Exchange>
+__device__ __forceinline__ void carousel_forward_body(Exchange &sh, int n, int rows, long long B,
                                                       const float2 *__restrict__ table,
                                                       const float2 *__restrict__ renorm, const float *X, float *Y,
                                                       int identity, int vec_ok, int mirror)
 {
-    using State = CarouselFwd<M, W, WAVES, FORM>;
+    using State = CarouselFwd<M, W, WAVES, FORM, EX>;
     State st;
     const int L = n / (2 * M);                  // lanes that hold slots; the rest of the last wavefront idles
+    st.lanes = L;
     const bool idle = (int)threadIdx.x >= L;
     const int coef_lane = idle ? 0 : (int)threadIdx.x;
     const int my_rows = idle ? 0 : rows;        // an idle lane loads zeros and stores nothing
@@ -368,7 +420,7 @@ __device__ __forceinline__ void carousel_forward_body(CarouselExchange<W, WAVES>
     st.lane = threadIdx.x & 63;
     st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     st.tab_lane = table + (long long)coef_lane * M;
-    {
+    if constexpr (EX == kExchangeLds) {
         constexpr int LMAX = 64 * WAVES;
         auto &b = sh.buf[0];
         const int t = threadIdx.x;
@@ -391,7 +443,8 @@ __device__ __forceinline__ void carousel_forward_body(CarouselExchange<W, WAVES>
         load_row<W>(st.bot[r], X, B, mirrored_row(n, rr_label(n, n - 2, n - 1 - p), mirror), my_rows, b0, wv, vec,
                     identity);
     }
-    st.load_coefs(n - 2, st.cs[0]);
+#pragma unroll
+    for (int d = 0; d < State::kDepth - 1; ++d) st.load_coefs(n - 2 - d, st.cs[d]);
 
     st.sweep();
 
@@ -407,26 +460,29 @@ __device__ __forceinline__ void carousel_forward_body(CarouselExchange<W, WAVES>
 
 // One launch per call: the rotation form is read from the device flag (nullptr: standard) and the
 // matching copy of the sweep runs; `table` holds that form's coefficients (coef_table_kernel).
-template <int M, int W, int WAVES>
+struct NoExchange {};   // the wavefront exchange needs no LDS
+template <int M, int W, int WAVES, int EX = kExchangeLds>
 __global__ __launch_bounds__(64 * WAVES, WAVES > 8 ? 1 : 2) void carousel_forward_kernel(
     int n, int rows, long long B, const float2 *__restrict__ table, const float2 *__restrict__ renorm,
     const unsigned *flag, float scaled_max, const float *X, float *Y, int identity, int vec_ok, int mirror)
 {
-    __shared__ CarouselExchange<W, WAVES> sh;
+    using Exchange = std::conditional_t<EX == kExchangeLds, CarouselExchange<W, WAVES>, NoExchange>;
+    __shared__ Exchange sh;
     if constexpr (kRenormPeriod % M != 0) {
         // slot counts that do not divide the renormalisation period: standard form only (the host passes no flag)
-        carousel_forward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok, mirror);
+        carousel_forward_body<M, W, WAVES, kFormStandard, EX>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok,
+                                                              mirror);
     } else {
         const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
         if (form == kFormScaled)
-            carousel_forward_body<M, W, WAVES, kFormScaled>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok,
-                                                            mirror);
+            carousel_forward_body<M, W, WAVES, kFormScaled, EX>(sh, n, rows, B, table, renorm, X, Y, identity,
+                                                                vec_ok, mirror);
         else if (form == kFormLifted)
-            carousel_forward_body<M, W, WAVES, kFormLifted>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok,
-                                                            mirror);
+            carousel_forward_body<M, W, WAVES, kFormLifted, EX>(sh, n, rows, B, table, renorm, X, Y, identity,
+                                                                vec_ok, mirror);
         else
-            carousel_forward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, table, renorm, X, Y, identity, vec_ok,
-                                                              mirror);
+            carousel_forward_body<M, W, WAVES, kFormStandard, EX>(sh, n, rows, B, table, renorm, X, Y, identity,
+                                                                  vec_ok, mirror);
     }
 }
 
@@ -456,16 +512,18 @@ struct CarouselExchangeBwd {
     Buf buf[2];
 };
 
-template <int M, int W, int WAVES, int FORM>
+template <int M, int W, int WAVES, int FORM, int EX = kExchangeLds>
 struct CarouselBwd {
-    static constexpr int kUnroll = (M % 2) ? 2 * M : M; // as in the forward kernel
+    static_assert(EX == kExchangeLds || WAVES == 1, "the DPP exchange stays inside one wavefront");
+    static constexpr int kDepth = EX == kExchangeWave ? wave_ring_depth_bwd(M) : 2; // as in the forward kernel
+    static constexpr int kUnroll = carousel_lcm(M, kDepth);
     static_assert(FORM == 0 || kRenormPeriod % kUnroll == 0,
                   "renormalisation must fall on the last copy of an unrolled group");
     static constexpr int kLastU = (2 * M - 2) % M;
 
     float zt[M][W], zb[M][W], gt[M][W], gb[M][W];
-    float2 cs[2][M];
-    float prior[2][M]; // sums of this workgroup's earlier strips for the current / next block
+    float2 cs[kDepth][M];
+    float prior[kDepth][M]; // sums of this workgroup's earlier strips for the current and the next blocks
     int n, H, lane, wave, tid;
     int lanes;               // L = n / (2 M): lanes that hold slots
     const float2 *tab_lane;  // table + tid*M
@@ -552,6 +610,25 @@ struct CarouselBwd {
         lds_load_row<W, WAVES>(t[qt], in_top + off);
         lds_load_row<W, WAVES>(b[qb], in_bot + off);
     }
+    // the same move inside one wavefront: the top slot that leaves comes from the previous lane (lane 0 keeps the
+    // held row there, and its bottom slot 0 turns round into the register the held row leaves), the bottom slot
+    // from the next lane (at the far end, lane L-1, it is the lane's own leaving top slot)
+    template <int U>
+    __device__ __forceinline__ void move_in_wavefront(float (&t)[M][W], float (&b)[M][W])
+    {
+        constexpr int qt = (M - 1 - U + M) % M;
+        constexpr int qb = U % M;
+        constexpr int pf = (M - U) % M;
+        const bool far = lane == lanes - 1;
+#pragma unroll
+        for (int x = 0; x < W; ++x) {
+            const float t_out = t[qt][x], b_out = b[qb][x], held = t[pf][x];
+            const float b_in = lane_from_next(t_out, b_out);
+            t[qt][x] = lane_from_prev(held, t_out);
+            b[qb][x] = far ? t_out : b_in;
+            t[pf][x] = (lane == 0) ? b_out : held;
+        }
+    }
 
     // Logical slot R of one block: the strip's share of the pair's gradient, then the transposed
     // rotation on both strips (RN: then the renormalisation multiply), then the pin (see the forward
@@ -613,20 +690,21 @@ struct CarouselBwd {
 
     // One block of the reverse sweep.  The slots whose rows leave the lane (0 and M-1) go first and
     // are published to LDS; the inner slots run while those writes and the barrier are in flight.
-    template <int C, bool LAST, bool RENORM>
+    template <int C, bool LAST, bool RENORM, bool PF>
     __device__ __forceinline__ void step(int k)
     {
         constexpr int U = C % M;      // register map of this unrolled copy
-        constexpr int PAR = C & 1;    // its coefficient / prior-sum / exchange buffers
+        constexpr int PAR = C & 1;    // its exchange buffers
+        constexpr int SLOT = C % kDepth, FREE = (C + kDepth - 1) % kDepth;   // ring of coefficients and prior sums
         constexpr bool RN = FORM != 0 && (LAST || RENORM);
-        float2(&cur)[M] = cs[PAR];
-        if constexpr (!LAST) load_coefs(k + 1, cs[PAR ^ 1]);
+        float2(&cur)[M] = cs[SLOT];
+        if constexpr (PF) load_coefs(k + (kDepth - 1), cs[FREE]);
         float2 rn[M];
         if constexpr (RN) load_row_of(rn_lane, k / kRenormPeriod, rn);
-        // what this workgroup's earlier strips have summed for the NEXT block: fetched a block ahead,
-        // like cos/sin, and before this block's store, so that waiting for it never waits for a store
-        float(&earlier)[M] = prior[PAR];
-        if constexpr (!LAST) load_prior(k + 1, prior[PAR ^ 1]);
+        // what this workgroup's earlier strips have summed for a LATER block: fetched ahead, like cos/sin, and
+        // before this block's store, so that waiting for it never waits for a store
+        float(&earlier)[M] = prior[SLOT];
+        if constexpr (PF) load_prior(k + (kDepth - 1), prior[FREE]);
 
         float sums[M];
         // the inner slots all run after the exchange slots here: splitting them around the exchange as
@@ -635,9 +713,13 @@ struct CarouselBwd {
         __builtin_amdgcn_s_setprio(2);   // the exchange slots are the block's critical path (see the forward kernel)
         sums[0] = sweep_slot<U, 0, RN>(cur, rn);
         if constexpr (M > 1) sums[M - 1] = sweep_slot<U, M - 1, RN>(cur, rn);
-        if constexpr (!LAST) {
+        if constexpr (!LAST && EX == kExchangeLds) {
             publish<U, PAR, 0>(zt, zb);
             publish<U, PAR, 1>(gt, gb);
+        }
+        if constexpr (!LAST && EX == kExchangeWave) {
+            move_in_wavefront<U>(zt, zb);
+            move_in_wavefront<U>(gt, gb);
         }
         __builtin_amdgcn_s_setprio(0);
         if constexpr (kInner > 0) sweep_inner<U, RN, 1>(cur, rn, sums, std::make_integer_sequence<int, kInner>{});
@@ -659,7 +741,7 @@ struct CarouselBwd {
                 for (int r = 0; r < M; ++r) dst[r] = sums[r];
             }
         }
-        if constexpr (!LAST) {
+        if constexpr (!LAST && EX == kExchangeLds) {
             __syncthreads();
             receive<U, PAR, 0>(zt, zb);
             receive<U, PAR, 1>(gt, gb);
@@ -669,19 +751,20 @@ struct CarouselBwd {
     template <bool RENORM, int... Cs>
     __device__ __forceinline__ void full_group(int k_first, std::integer_sequence<int, Cs...>)
     {
-        (step<Cs, false, RENORM && Cs == kUnroll - 1>(k_first + Cs), ...);
+        (step<Cs, false, RENORM && Cs == kUnroll - 1, true>(k_first + Cs), ...);
     }
     template <int... Cs>
     __device__ __forceinline__ void tail_group(int k_first, std::integer_sequence<int, Cs...>)
     {
-        (step<Cs, Cs == kUnroll - 2, false>(k_first + Cs), ...);
+        (step<Cs, Cs == kUnroll - 2, false, (kUnroll - 2 - Cs >= kDepth - 1)>(k_first + Cs), ...);
     }
 
     // all n-1 blocks in the order b_1, b_2, ...: n/kUnroll - 1 full groups, then the tail of kUnroll - 1
     __device__ __forceinline__ void sweep()
     {
         constexpr auto seq = std::make_integer_sequence<int, kUnroll>{};
-        load_prior(0, prior[0]);
+#pragma unroll
+        for (int d = 0; d < kDepth - 1; ++d) load_prior(d, prior[d]);
         int k = 0;
         if constexpr (FORM == 0) {
             for (; k + kUnroll <= n - 1; k += kUnroll) full_group<false>(k, seq);
@@ -699,8 +782,8 @@ struct CarouselBwd {
     }
 };
 
-template <int M, int W, int WAVES, int FORM>
-__device__ __forceinline__ void carousel_backward_body(CarouselExchangeBwd<W, WAVES> &sh, int n, int rows, long long B,
+template <int M, int W, int WAVES, int FORM, int EX, typename Exchange>
+__device__ __forceinline__ void carousel_backward_body(Exchange &sh, int n, int rows, long long B,
                                                        long long strip0, long long nstrips,
                                                        const float2 *__restrict__ table,
                                                        const float2 *__restrict__ renorm, const float *Yin,
@@ -708,7 +791,7 @@ __device__ __forceinline__ void carousel_backward_body(CarouselExchangeBwd<W, WA
                                                        const float *__restrict__ zeros, float *sink, int vec_ok,
                                                        int g_identity)
 {
-    using State = CarouselBwd<M, W, WAVES, FORM>;
+    using State = CarouselBwd<M, W, WAVES, FORM, EX>;
     State st;
     const int L = n / (2 * M);                  // lanes that hold slots; the rest of the last wavefront idles
     const bool idle = (int)threadIdx.x >= L;
@@ -726,7 +809,7 @@ __device__ __forceinline__ void carousel_backward_body(CarouselExchangeBwd<W, WA
     st.part_lane = idle ? sink + (long long)threadIdx.x * M
                         : partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) +
                               (long long)threadIdx.x * M;
-    {
+    if constexpr (EX == kExchangeLds) {
         constexpr int LMAX = 64 * WAVES;
         auto &z = sh.buf[0].strip[0];
         const int t = threadIdx.x;
@@ -757,7 +840,8 @@ __device__ __forceinline__ void carousel_backward_body(CarouselExchangeBwd<W, WA
             load_row<W>(st.gt[r], G, B, p, my_rows, b0, wv, vec, g_identity);   // g_identity: G = I_n, not read
             load_row<W>(st.gb[r], G, B, n - 1 - p, my_rows, b0, wv, vec, g_identity);
         }
-        st.load_coefs(0, st.cs[0]);
+#pragma unroll
+        for (int d = 0; d < State::kDepth - 1; ++d) st.load_coefs(d, st.cs[d]);
 
         st.sweep();
 
@@ -770,31 +854,33 @@ __device__ __forceinline__ void carousel_backward_body(CarouselExchangeBwd<W, WA
                 store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), my_rows, b0, wv, vec);
             }
         }
-        __syncthreads(); // the next strip reuses the exchange buffers
+        if constexpr (EX == kExchangeLds) __syncthreads(); // the next strip reuses the exchange buffers
     }
 }
 
-template <int M, int W, int WAVES>
+template <int M, int W, int WAVES, int EX = kExchangeLds>
 __global__ __launch_bounds__(64 * WAVES, WAVES > 8 ? 1 : 2) void carousel_backward_kernel(
     int n, int rows, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
     const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
     float *dX, float *partial, const float *__restrict__ zeros, float *sink, int vec_ok, int g_identity)
 {
-    __shared__ CarouselExchangeBwd<W, WAVES> sh;
+    using Exchange = std::conditional_t<EX == kExchangeLds, CarouselExchangeBwd<W, WAVES>, NoExchange>;
+    __shared__ Exchange sh;
     if constexpr (kRenormPeriod % M != 0) {
-        carousel_backward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G, dX,
-                                                           partial, zeros, sink, vec_ok, g_identity);
+        carousel_backward_body<M, W, WAVES, kFormStandard, EX>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G,
+                                                               dX, partial, zeros, sink, vec_ok, g_identity);
     } else {
         const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
         if (form == kFormScaled)
-            carousel_backward_body<M, W, WAVES, kFormScaled>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G,
-                                                             dX, partial, zeros, sink, vec_ok, g_identity);
+            carousel_backward_body<M, W, WAVES, kFormScaled, EX>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin,
+                                                                 G, dX, partial, zeros, sink, vec_ok, g_identity);
         else if (form == kFormLifted)
-            carousel_backward_body<M, W, WAVES, kFormLifted>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G,
-                                                             dX, partial, zeros, sink, vec_ok, g_identity);
+            carousel_backward_body<M, W, WAVES, kFormLifted, EX>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin,
+                                                                 G, dX, partial, zeros, sink, vec_ok, g_identity);
         else
-            carousel_backward_body<M, W, WAVES, kFormStandard>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G,
-                                                               dX, partial, zeros, sink, vec_ok, g_identity);
+            carousel_backward_body<M, W, WAVES, kFormStandard, EX>(sh, n, rows, B, strip0, nstrips, table, renorm,
+                                                                   Yin, G, dX, partial, zeros, sink, vec_ok,
+                                                                   g_identity);
     }
 }
 
@@ -872,6 +958,44 @@ inline int carousel_backward_slots(const CarouselBwdArgs &a, int waves, int W)
     case 6: return carousel_bwd_widths<M, 6>(W, a);
     case 7: return carousel_bwd_widths<M, 7>(W, a);
     case 8: return carousel_bwd_widths<M, 8>(W, a);
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+
+// One-wavefront shapes with the exchange inside the wavefront (carousel_fwd_wave.hip / carousel_bwd_wave.hip):
+// strips of at most 4 columns.
+template <int M, int W>
+inline void carousel_launch_fwd_wave(const CarouselFwdArgs &a)
+{
+    const long long strips = (a.B + W - 1) / W;
+    hipLaunchKernelGGL((carousel_forward_kernel<M, W, 1, kExchangeWave>), dim3((unsigned)strips), dim3(64), 0,
+                       a.stream, a.n, a.rows, a.B, a.coefs.table, a.coefs.renorm, a.coefs.flag, a.coefs.scaled_max,
+                       a.X, a.Y, a.identity, a.vec_ok, a.mirror);
+}
+template <int M>
+inline int carousel_forward_wave_slots(const CarouselFwdArgs &a, int W)
+{
+    switch (W) {
+    case 4: carousel_launch_fwd_wave<M, 4>(a); return GIVENS_OK;
+    case 2: carousel_launch_fwd_wave<M, 2>(a); return GIVENS_OK;
+    case 1: carousel_launch_fwd_wave<M, 1>(a); return GIVENS_OK;
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+template <int M, int W>
+inline void carousel_launch_bwd_wave(const CarouselBwdArgs &a)
+{
+    hipLaunchKernelGGL((carousel_backward_kernel<M, W, 1, kExchangeWave>), dim3((unsigned)a.groups), dim3(64), 0,
+                       a.stream, a.n, a.rows, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
+                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.sink, a.vec_ok, a.g_identity);
+}
+template <int M>
+inline int carousel_backward_wave_slots(const CarouselBwdArgs &a, int W)
+{
+    switch (W) {
+    case 4: carousel_launch_bwd_wave<M, 4>(a); return GIVENS_OK;
+    case 2: carousel_launch_bwd_wave<M, 2>(a); return GIVENS_OK;
+    case 1: carousel_launch_bwd_wave<M, 1>(a); return GIVENS_OK;
     default: return GIVENS_ERR_UNSUPPORTED;
     }
 }

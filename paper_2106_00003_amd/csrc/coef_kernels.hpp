@@ -393,6 +393,41 @@ __global__ void reduce_partials_kernel(int n, long long nstrips, const T *__rest
     dtheta[out] = accumulate ? dtheta[out] + acc : acc;
 }
 
+// The same sum for small problems, where one thread per angle leaves most of the chip idle behind a long chain of
+// dependent loads (n = 256: 128 workgroups, 256 rows each): a workgroup takes 64 angles, its kReduceSplit groups of
+// 64 threads each sum every kReduceSplit-th row, and the first group adds the group sums in a fixed order.
+constexpr int kReduceSplit = 8;
+template <typename T>
+__global__ __launch_bounds__(64 * kReduceSplit) void reduce_partials_split_kernel(
+    int n, long long nstrips, const T *__restrict__ partial, const T *__restrict__ factor,
+    const int *__restrict__ map, T *dtheta, int accumulate)
+{
+    __shared__ T sums[kReduceSplit][64];
+    const int H = n >> 1;
+    const long long N = (long long)(n - 1) * H;
+    const int lane = threadIdx.x & 63, group = threadIdx.x >> 6;
+    const long long e = (long long)blockIdx.x * 64 + lane;
+    T a0 = T(0), a1 = T(0);
+    if (e < N) {
+        long long s = group;
+        for (; s + kReduceSplit < nstrips; s += 2 * kReduceSplit) {
+            a0 += partial[s * N + e];
+            a1 += partial[(s + kReduceSplit) * N + e];
+        }
+        if (s < nstrips) a0 += partial[s * N + e];
+    }
+    sums[group][lane] = a0 + a1;
+    __syncthreads();
+    if (group != 0 || e >= N) return;
+    const long long out = map ? (long long)map[e] : e;
+    if (out < 0) return;
+    T acc = sums[0][lane];
+#pragma unroll
+    for (int g = 1; g < kReduceSplit; ++g) acc += sums[g][lane];
+    acc *= factor ? factor[e] : T(1);
+    dtheta[out] = accumulate ? dtheta[out] + acc : acc;
+}
+
 __global__ void fill_zero_kernel(long long count, float *__restrict__ dst)
 {
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count;

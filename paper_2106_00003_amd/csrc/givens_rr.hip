@@ -24,6 +24,7 @@ namespace {
 constexpr int kMaxDevices = 64;
 constexpr int kMaxWorkspacesPerDevice = 8;                     // streams with a workspace of their own, per device
 constexpr size_t kLdsBudgetBytes = 144 * 1024;                 // of the 160 KB per CU on gfx950
+constexpr long long kReduceSplitMaxAngles = 1 << 18;           // below this the second stage splits the rows too
 constexpr size_t kPartialCapBytes = size_t(24) << 30;          // cap on one chunk of strip partials
 constexpr int kMaxRows = 36864;                                // largest n any kernel family takes (one float column in LDS)
 constexpr size_t kFlagBytes = 256;                             // the flag words of a workspace
@@ -639,7 +640,7 @@ int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, lo
     // Two-stage reduction.  LDS family: one row of partial sums per strip, in chunks of strips that fit
     // the workspace cap.  Carousel family: one row per persistent workgroup (at most what the chip
     // holds at once), whatever the number of strips.
-    const long long rows_wanted = carousel ? carousel_bwd_groups(n, strips, cus) : strips;
+    const long long rows_wanted = carousel ? carousel_bwd_groups(n, B, strips, cus) : strips;
     long long prows = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
     prows = std::max<long long>(1, std::min(prows, rows_wanted));
     if (int rc = grow(ws.partial, (size_t)prows * N * sizeof(T))) return rc;
@@ -665,9 +666,14 @@ int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, lo
         {
             Span span(2, stream);
             const int threads = 256;
-            hipLaunchKernelGGL(reduce_partials_kernel<T>, dim3((unsigned)((N + threads - 1) / threads)),
-                               dim3(threads), 0, stream, n, nrows, partial, coefs.factor, map, dtheta,
-                               s0 > 0 ? 1 : 0);
+            if (N <= kReduceSplitMaxAngles && nrows >= 4 * kReduceSplit)
+                hipLaunchKernelGGL(reduce_partials_split_kernel<T>, dim3((unsigned)((N + 63) / 64)),
+                                   dim3(64 * kReduceSplit), 0, stream, n, nrows, partial, coefs.factor, map, dtheta,
+                                   s0 > 0 ? 1 : 0);
+            else
+                hipLaunchKernelGGL(reduce_partials_kernel<T>, dim3((unsigned)((N + threads - 1) / threads)),
+                                   dim3(threads), 0, stream, n, nrows, partial, coefs.factor, map, dtheta,
+                                   s0 > 0 ? 1 : 0);
             GIVENS_HIP(hipGetLastError());
         }
     }

@@ -288,6 +288,33 @@ def test_every_even_size_up_to_700_matches_the_oracle_in_its_default_family():
     binding.release()
 
 
+@pytest.mark.parametrize("n,B,seed,dist", [(136, 5, 61, "uniform"), (200, 64, 62, "normal0.1"),
+                                           (256, 256, 63, "uniform"), (256, 1030, 64, "uniform"),
+                                           (256, 4100, 65, "normal0.1"), (384, 300, 66, "uniform"),
+                                           (512, 1024, 67, "uniform"), (512, 2500, 68, "normal0.1"),
+                                           (768, 40, 69, "uniform"), (768, 600, 70, "uniform"),
+                                           (1024, 512, 71, "normal0.1"), (1024, 2048, 72, "uniform"),
+                                           (1024, 2052, 73, "uniform"), (140, 9, 74, "uniform")])
+def test_one_wavefront_shapes_with_the_exchange_inside_the_wavefront(n, B, seed, dist):
+    """Multiples of 8 up to 1024 with small and medium batches run one wavefront per strip and move the slots with
+    wavefront shifts: 2, 4 and 8 slots per lane, fewer than 64 lanes (136, 200, 384, 768), strips of 1, 2 and 4
+    columns on both sides of the batch sizes where the width changes, ragged last strips, all three rotation
+    forms (the angles decide); 140 is not a multiple of 8 and keeps the LDS exchange."""
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    print(f"[parity] n={n} B={B} seed={seed} {dist}", flush=True)
+    binding.set_reduction(binding.REDUCTION_TWO_STAGE)       # the reverse sweep over all B columns
+    try:
+        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G,
+                               binding.KERNEL_CAROUSEL)
+        assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+        binding.set_rotation_form(binding.FORM_STANDARD)
+        check_forward_backward(data["theta"], data["X"], data["G"], binding.KERNEL_AUTO, TOL_Y, TOL_G)
+    finally:
+        binding.set_rotation_form(binding.FORM_RANGE)
+        binding.set_reduction(binding.REDUCTION_AUTO)
+    binding.release()
+
+
 def test_sizes_whose_half_is_a_prime_stay_in_the_lds_family():
     """n = 2 p with p prime has no carousel shape (the slot count must divide n / 2)."""
     data = inputs.make_custom(1006, 40, seed=39)
