@@ -909,21 +909,34 @@ inline int carousel_fwd_widths(int W, const CarouselFwdArgs &a)
     }
 }
 
-// every number of wavefronts carousel_shape_for can return for M slots per lane
+// every number of wavefronts carousel_shape_for can return for M slots per lane, in two halves so that a slot
+// count whose kernels take long to compile can spread them over two translation units
 template <int M>
-inline int carousel_forward_slots(const CarouselFwdArgs &a, int waves, int W)
+inline int carousel_forward_slots_1to4(const CarouselFwdArgs &a, int waves, int W)
 {
     switch (waves) {
     case 1: return carousel_fwd_widths<M, 1>(W, a);
     case 2: return carousel_fwd_widths<M, 2>(W, a);
     case 3: return carousel_fwd_widths<M, 3>(W, a);
     case 4: return carousel_fwd_widths<M, 4>(W, a);
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+template <int M>
+inline int carousel_forward_slots_5to8(const CarouselFwdArgs &a, int waves, int W)
+{
+    switch (waves) {
     case 5: return carousel_fwd_widths<M, 5>(W, a);
     case 6: return carousel_fwd_widths<M, 6>(W, a);
     case 7: return carousel_fwd_widths<M, 7>(W, a);
     case 8: return carousel_fwd_widths<M, 8>(W, a);
     default: return GIVENS_ERR_UNSUPPORTED;
     }
+}
+template <int M>
+inline int carousel_forward_slots(const CarouselFwdArgs &a, int waves, int W)
+{
+    return waves <= 4 ? carousel_forward_slots_1to4<M>(a, waves, W) : carousel_forward_slots_5to8<M>(a, waves, W);
 }
 
 template <int M, int W, int WAVES>
