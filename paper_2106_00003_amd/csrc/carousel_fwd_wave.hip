@@ -1,6 +1,7 @@
 // Forward carousel kernels for workgroups of one wavefront that exchange slots with DPP wavefront shifts instead
-// of LDS (n = 2 M L with L <= 64: up to 1024 with 8 slots per lane, 512 with 4, 256 with 2), strips of 1, 2 or 4
-// columns: the shapes of small problems, whose sweeps are bound by the block-to-block chain.
+// of LDS (n = 2 M L with L <= 64: up to 1024 with 8 slots per lane, 512 with 4, 256 with 2), strips of 1 to 8
+// columns: the shapes of small problems, whose sweeps are bound by the block-to-block chain when the batch is small
+// and whose LDS-exchange shapes would leave lanes idle when it is large.
 #include "carousel_kernels.hpp"
 
 namespace givens {

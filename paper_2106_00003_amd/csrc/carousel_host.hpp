@@ -233,11 +233,11 @@ int carousel_backward_m3(const CarouselBwdArgs &a, int waves, int W);
 int carousel_forward_wave(const CarouselFwdArgs &a, int M, int W);
 int carousel_backward_wave(const CarouselBwdArgs &a, int M, int W);
 
-// Forward sweep.  The wavefront exchange is taken where it was measured faster than the LDS exchange (n = 256 ..
-// 1024, B = 64 .. 16384): batches up to 16384 columns with 2 or 4 slots per lane (1.5 to 3.2 times faster), up to
-// 8192 with 8 (1.05 to 1.7 times).  Its strips are single columns while the batch gives each SIMD at most one
-// wavefront, then 2 and 4 columns: every wavefront reads the whole coefficient table, and beyond about a thousand
-// wavefronts that traffic (L2) sets the time.
+// Forward sweep.  A size with a one-wavefront shape always takes the wavefront exchange: measured against the LDS
+// exchange over n = 256 .. 1024 and B = 64 .. 262144 it is 1.5 to 3.2 times faster with 2 or 4 slots per lane (the
+// LDS shapes of those n leave lanes idle) and 1.0 to 1.7 times with 8.  Its strips are single columns while the
+// batch gives each SIMD at most one wavefront, then 2, 4 and 8 columns: every wavefront reads the whole coefficient
+// table, and beyond about a thousand wavefronts that traffic (L2) sets the time.
 inline bool carousel_fwd_plan(int n, long long B, CarouselPlan *p)
 {
     if (!carousel_shape_for(n, &p->s)) return false;
@@ -245,11 +245,8 @@ inline bool carousel_fwd_plan(int n, long long B, CarouselPlan *p)
     p->wave = false;
     CarouselShape ws;
     if (carousel_wave_shape_for(n, 8, &ws)) {
-        const bool eight = ws.M == 8;
-        if (B <= (eight ? 8192 : 16384)) {
-            const int w = B <= (eight ? 512 : 1024) ? 1 : B <= (eight ? 2048 : 4096) ? 2 : 4;
-            *p = {ws, w, true};
-        }
+        const long long single = ws.M == 8 ? 512 : 1024;     // widest batch of single-column strips
+        *p = {ws, B <= single ? 1 : B <= 4 * single ? 2 : B <= 16 * single ? 4 : 8, true};
     }
     return true;
 }

@@ -976,7 +976,7 @@ inline int carousel_backward_slots(const CarouselBwdArgs &a, int waves, int W)
 }
 
 // One-wavefront shapes with the exchange inside the wavefront (carousel_fwd_wave.hip / carousel_bwd_wave.hip):
-// strips of at most 4 columns.
+// forward strips of up to 8 columns, reverse strips of up to 4.
 template <int M, int W>
 inline void carousel_launch_fwd_wave(const CarouselFwdArgs &a)
 {
@@ -989,6 +989,7 @@ template <int M>
 inline int carousel_forward_wave_slots(const CarouselFwdArgs &a, int W)
 {
     switch (W) {
+    case 8: carousel_launch_fwd_wave<M, 8>(a); return GIVENS_OK;
     case 4: carousel_launch_fwd_wave<M, 4>(a); return GIVENS_OK;
     case 2: carousel_launch_fwd_wave<M, 2>(a); return GIVENS_OK;
     case 1: carousel_launch_fwd_wave<M, 1>(a); return GIVENS_OK;

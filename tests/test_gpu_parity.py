@@ -294,10 +294,11 @@ def test_every_even_size_up_to_700_matches_the_oracle_in_its_default_family():
                                            (512, 1024, 67, "uniform"), (512, 2500, 68, "normal0.1"),
                                            (768, 40, 69, "uniform"), (768, 600, 70, "uniform"),
                                            (1024, 512, 71, "normal0.1"), (1024, 2048, 72, "uniform"),
-                                           (1024, 2052, 73, "uniform"), (140, 9, 74, "uniform")])
+                                           (1024, 2052, 73, "uniform"), (140, 9, 74, "uniform"),
+                                           (256, 16400, 75, "uniform"), (1024, 8200, 76, "normal0.1")])
 def test_one_wavefront_shapes_with_the_exchange_inside_the_wavefront(n, B, seed, dist):
     """Multiples of 8 up to 1024 with small and medium batches run one wavefront per strip and move the slots with
-    wavefront shifts: 2, 4 and 8 slots per lane, fewer than 64 lanes (136, 200, 384, 768), strips of 1, 2 and 4
+    wavefront shifts: 2, 4 and 8 slots per lane, fewer than 64 lanes (136, 200, 384, 768), strips of 1, 2, 4 and 8
     columns on both sides of the batch sizes where the width changes, ragged last strips, all three rotation
     forms (the angles decide); 140 is not a multiple of 8 and keeps the LDS exchange."""
     data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
