@@ -168,6 +168,26 @@ struct CarouselBwdArgs {
     hipStream_t stream;
 };
 
+// Chained rows of partial sums in the reverse sweep (see carousel_backward_body for what the kernel does).
+constexpr int kChainLength = 8;      // workgroups per chain (measured at n = B = 4096: 4 and 8 tie, 16 and 32 are slower)
+constexpr int kChainMaxPasses = 8;   // strips per workgroup beyond which the rows would outgrow their use
+constexpr int kFlagStride = 32;      // words between progress flags: a 128-byte cache line each
+struct CarouselChainArgs {
+    unsigned *flags;      // [grid][n-1] cache lines of 32 words: word 0 = tag of the launch and pass that finished the block
+    unsigned *xcd_of;     // [grid], zero at launch; 1 + XCD number once the workgroup has started
+    unsigned *error;      // one word, zero at launch
+    const unsigned *epoch; // one word: number of this launch (counted on the device, so that a replayed graph counts
+                           // too); the tags of a launch are epoch * (kChainMaxPasses + 1) + pass
+    int chains;
+};
+// Number of chains the reverse sweep of (n, B) links its `groups` persistent workgroups into, or 0 for separate
+// rows.  Chains need: the 4-slot LDS-exchange shape with 5 to 8 wavefronts (n from 2112 to 4096) and strips of 8 or 4
+// columns; n a multiple of 64; a grid that is a multiple of
+// 8 chains of kChainLength (chain members then differ by multiples of 8 and share an XCD); a first pass in which
+// every workgroup has a strip; and enough partial sums for their traffic to matter (0.5 GB of separate rows).
+inline int carousel_bwd_chains(int n, long long B, long long nstrips, long long groups);
+int carousel_backward_chain(const CarouselBwdArgs &a, const CarouselChainArgs &c, int M, int waves, int W);
+
 // Unitary extension in the carousel family (unitary_carousel_kernels.hpp): complex64 operands seen as real
 // n x Breal arrays (Breal = 2 B), W real columns per lane (even).  Even n that is a multiple of 16, from
 // kUnitaryCarouselMinN up to 4096 (8 slots per lane forward, 4 reverse; the phase pass keeps n float64 in LDS).
@@ -315,13 +335,27 @@ inline long long carousel_bwd_groups(int n, long long B, long long nstrips, int 
     return nstrips < resident ? nstrips : resident;
 }
 
+inline int carousel_bwd_chains(int n, long long B, long long nstrips, long long groups)
+{
+    CarouselPlan p;
+    if (!carousel_bwd_plan(n, B, &p) || p.wave || p.s.M != 4 || (p.W != 8 && p.W != 4)) return 0;
+    if (p.s.WAVES < 5 || p.s.WAVES > 8) return 0;   // one workgroup per compute unit (see CarouselBwd)
+    // (a row's blocks must start on cache-line boundaries: a line that straddles two blocks could be read into a
+    // successor's L1 before the predecessor has written its second half)
+    if (n % 64 != 0 || groups % (8 * kChainLength) != 0 || nstrips < groups) return 0;
+    if ((nstrips + groups - 1) / groups > kChainMaxPasses) return 0;
+    const long long N = (long long)n * (n - 1) / 2;
+    if (N * groups * 4 < (512ll << 20)) return 0;
+    return (int)(groups / kChainLength);
+}
+
 // Launches the reverse sweep on strips [strip0, strip0 + nstrips) with `groups` persistent workgroups.
 // partial is [groups][N]: workgroup g stores the sums of its first strip in row g and adds those of its later
 // strips to them.  zeros: N floats that stay zero.
 inline int carousel_backward_strips(int n, int rows, long long B, int W, long long strip0, long long nstrips,
                                     long long groups, const CarouselCoefs &coefs, const float *Y, const float *G,
                                     float *dX, float *partial, const float *zeros, float *sink, int g_identity,
-                                    hipStream_t stream)
+                                    hipStream_t stream, const CarouselChainArgs *chain = nullptr)
 {
     CarouselPlan plan;
     if (!carousel_bwd_plan(n, B, &plan) || plan.W != W) return GIVENS_ERR_UNSUPPORTED;
@@ -331,6 +365,7 @@ inline int carousel_backward_strips(int n, int rows, long long B, int W, long lo
                          (!dX || reinterpret_cast<uintptr_t>(dX) % 16 == 0);
     const CarouselBwdArgs a{n,  rows,    B,     strip0, nstrips,         groups,     coefs, Y, G,
                             dX, partial, zeros, sink,   aligned ? 1 : 0, g_identity, stream};
+    if (chain) return carousel_backward_chain(a, *chain, s.M, s.WAVES, W);
     if (plan.wave) return carousel_backward_wave(a, s.M, W);
     switch (s.M) {
     case 7: return carousel_backward_m7(a, s.WAVES, W);

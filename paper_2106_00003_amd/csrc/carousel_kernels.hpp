@@ -512,9 +512,25 @@ struct CarouselExchangeBwd {
     Buf buf[2];
 };
 
-template <int M, int W, int WAVES, int FORM, int EX = kExchangeLds>
+// CHAIN: the persistent workgroups are linked into chains that share one row of partial sums (see
+// carousel_backward_body): a workgroup adds its sums to what its predecessor in the chain has left in the row, so
+// the row lives in the L2 of the chain's XCD while the chain works its way through it.
+// Progress is published as one flag per workgroup and block, each in a cache line of its own (kFlagStride words),
+// holding the tag of the launch and pass that last finished the block.
+constexpr int kChainSpinLimit = 1 << 23;   // polls (some seconds) before a workgroup gives up waiting
+constexpr int kChainSlack = 3;
+// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; others: no wait)
+constexpr int waitcnt_vm(int vmcnt) { return (vmcnt & 15) | ((vmcnt >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+template <int M, int W, int WAVES, int FORM, int EX = kExchangeLds, int CHAIN = 0>
 struct CarouselBwd {
     static_assert(EX == kExchangeLds || WAVES == 1, "the DPP exchange stays inside one wavefront");
+    static_assert(!CHAIN || (EX == kExchangeLds && M % 4 == 0), "chained rows: LDS exchange, 4 or 8 slots per lane");
+    // Two workgroups of a chain must never share a compute unit: a store does not update a line that the unit's
+    // L1 holds, so the second would read the row as the first found it (seen with one-wavefront workgroups: sums
+    // off by a strip's share; invalidating the L1 every block, buffer_inv sc1, made the sweep 13 times slower).
+    // From 5 wavefronts on a workgroup has its compute unit to itself (registers and LDS leave no room for two).
+    static_assert(!CHAIN || WAVES >= 5, "chained rows: one workgroup per compute unit");
     static constexpr int kDepth = EX == kExchangeWave ? wave_ring_depth_bwd(M) : 2; // as in the forward kernel
     static constexpr int kUnroll = carousel_lcm(M, kDepth);
     static_assert(FORM == 0 || kRenormPeriod % kUnroll == 0,
@@ -530,6 +546,13 @@ struct CarouselBwd {
     const float2 *rn_lane;   // renormalisation factors + tid*M (scaled form)
     float *part_lane;        // this workgroup's row of partial sums + tid*M (idle lanes: the sink)
     const float *prior_lane; // what load_prior reads: this workgroup's row, or zeros for its first strip
+    // chained rows: the predecessor's flags and this workgroup's own (one per block), the error word, the tag of
+    // this launch and pass, the predecessor's flag read ahead for the next block, and whether this wavefront waits
+    // for nobody (the head of a chain, or a wavefront that has given up waiting)
+    const unsigned *pred_flags;
+    unsigned *my_flags, *chain_error;
+    unsigned chain_tag, polled;
+    int unlinked;
     // this lane's LDS addresses for strip z in exchange buffer 0 (strip g and buffer 1 are at
     // compile-time offsets)
     float *out_top, *out_bot, *hold;
@@ -553,6 +576,58 @@ struct CarouselBwd {
         } else {
 #pragma unroll
             for (int r = 0; r < M; ++r) dst[r] = src[r];
+        }
+    }
+
+    // A counter of another workgroup, read through the scalar unit with the cache-bypass bit: the read is served by
+    // the L2, which the workgroups of a chain share, and it does not queue with the wavefront's vector loads (those
+    // return in order, so one slow read among them would hold up every coefficient fetch behind it: counters read
+    // and written with agent-scope vector accesses, which go to memory, cost 3.5 us per block).
+    __device__ __forceinline__ static unsigned read_counter(const unsigned *p)
+    {
+        // (the address is the same in every lane; the two halves are made scalar explicitly)
+        const unsigned long long a = reinterpret_cast<unsigned long long>(p);
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+        const unsigned long long q = ((unsigned long long)hi << 32) | lo;
+        unsigned v;
+        asm volatile("s_load_dword %0, %1, 0x0 glc\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(q) : "memory");
+        return v;
+    }
+    // A flag is written with an ordinary store (through the write-through L1 into the L2); "atomic" only keeps
+    // the compiler from merging or dropping it, and wavefront scope keeps it free of cache-policy bits and waits.
+    __device__ __forceinline__ static void publish_counter(unsigned *p, unsigned value)
+    {
+        __hip_atomic_store(p, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    }
+    // The predecessor's flag for block k as an ordinary vector load, issued one block before it is looked at.  Every
+    // flag has a cache line of its own and is read this way once per launch, so the load cannot be served by a
+    // stale line of this compute unit's L1: it comes from the L2 like the coefficient loads around it.
+    __device__ __forceinline__ unsigned flag_ahead(int k) const
+    {
+        const int kk = k < n - 1 ? k : n - 2;
+        return __hip_atomic_load(pred_flags + (long long)kk * kFlagStride, __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_WAVEFRONT);
+    }
+    // Returns once the predecessor has finished block k of this pass.  Normally `polled` (flag_ahead of the block
+    // before) already says so.  If not, the wavefront reads flags through the scalar unit until the predecessor is
+    // kChainSlack blocks further (while the pass has that many left): workgroups run at the same pace, so the
+    // distance gained lasts and the flags read ahead from then on are found set.  A wait that does not end within
+    // the spin limit marks the call as failed (the second stage then writes NaN) and stops this wavefront from
+    // waiting again, so every wavefront reaches the end of the kernel whatever happens to its predecessor.
+    __device__ __forceinline__ void wait_for_predecessor(int k)
+    {
+        if (unlinked || __builtin_amdgcn_readfirstlane(polled) >= chain_tag) return;
+        const int far = k + kChainSlack < n - 1 ? k + kChainSlack : n - 2;
+        const unsigned *flag = pred_flags + (long long)far * kFlagStride;
+        int budget = kChainSpinLimit;
+        while (read_counter(flag) < chain_tag) {
+            if (--budget <= 0) break;
+            __builtin_amdgcn_s_sleep(4);
+        }
+        if (budget <= 0) {
+            unlinked = 1;
+            if (lane == 0) atomicOr(chain_error, 1u);
         }
     }
 
@@ -704,6 +779,11 @@ struct CarouselBwd {
         // what this workgroup's earlier strips have summed for a LATER block: fetched ahead, like cos/sin, and
         // before this block's store, so that waiting for it never waits for a store
         float(&earlier)[M] = prior[SLOT];
+        if constexpr (CHAIN && PF) {
+            // the row's block k+1 is fetched now: the predecessor must have finished it
+            wait_for_predecessor(k + 1);
+            polled = flag_ahead(k + 2);   // looked at in the next block: nothing waits for this load here
+        }
         if constexpr (PF) load_prior(k + (kDepth - 1), prior[FREE]);
 
         float sums[M];
@@ -742,7 +822,15 @@ struct CarouselBwd {
             }
         }
         if constexpr (!LAST && EX == kExchangeLds) {
+            // chained rows: this wavefront's store of the previous block has reached L2 once at most the memory
+            // operations of this block are outstanding (they complete in order; a block issues at least five:
+            // two coefficient loads, the flag read ahead, the earlier sums, this store), and after the barrier that
+            // holds for all wavefronts, so block k-1 can be flagged as being in the row
+            if constexpr (CHAIN) __builtin_amdgcn_s_waitcnt(waitcnt_vm(4));
             __syncthreads();
+            if constexpr (CHAIN) {
+                if (tid == 0 && k > 0) publish_counter(my_flags + (long long)(k - 1) * kFlagStride, chain_tag);
+            }
             receive<U, PAR, 0>(zt, zb);
             receive<U, PAR, 1>(gt, gb);
         }
@@ -763,6 +851,11 @@ struct CarouselBwd {
     __device__ __forceinline__ void sweep()
     {
         constexpr auto seq = std::make_integer_sequence<int, kUnroll>{};
+        if constexpr (CHAIN) {
+            polled = 0u;
+            wait_for_predecessor(0);      // block 0 of the row
+            polled = flag_ahead(1);
+        }
 #pragma unroll
         for (int d = 0; d < kDepth - 1; ++d) load_prior(d, prior[d]);
         int k = 0;
@@ -782,16 +875,28 @@ struct CarouselBwd {
     }
 };
 
-template <int M, int W, int WAVES, int FORM, int EX, typename Exchange>
+// Chained rows (CHAIN).  Workgroup g of the grid belongs to chain c = g mod `chains` at place j = g / chains
+// (kChainLength places; the grid is chains * kChainLength workgroups, `chains` a multiple of 8, so that the
+// workgroups of a chain differ by multiples of 8 and, workgroups being dealt to the XCDs in turn, share an L2).  In
+// pass t (the workgroup's t-th strip) the chain sums into row t * chains + c: the head stores its sums, every other
+// place adds its own to what the place before it has left there, one block behind it at the earliest, and the last
+// place leaves the chain's total.  Only the head's lines ever come from HBM-side zeros and only the finished row
+// goes back to HBM; in between the row's active part sits in L2.  What tells a workgroup that its predecessor is
+// done with a block is that predecessor's progress counter (wait_for_predecessor).  At the start every workgroup
+// records which XCD it runs on and checks that its predecessor runs on the same one: if not (or if a wait runs
+// out), the error word is set and the second stage poisons the result instead of returning sums that may have
+// been read from a stale L2.
+
+template <int M, int W, int WAVES, int FORM, int EX, int CHAIN, typename Exchange>
 __device__ __forceinline__ void carousel_backward_body(Exchange &sh, int n, int rows, long long B,
                                                        long long strip0, long long nstrips,
                                                        const float2 *__restrict__ table,
                                                        const float2 *__restrict__ renorm, const float *Yin,
                                                        const float *G, float *dX, float *partial,
                                                        const float *__restrict__ zeros, float *sink, int vec_ok,
-                                                       int g_identity)
+                                                       int g_identity, const CarouselChainArgs &chain)
 {
-    using State = CarouselBwd<M, W, WAVES, FORM, EX>;
+    using State = CarouselBwd<M, W, WAVES, FORM, EX, CHAIN>;
     State st;
     const int L = n / (2 * M);                  // lanes that hold slots; the rest of the last wavefront idles
     const bool idle = (int)threadIdx.x >= L;
@@ -806,9 +911,41 @@ __device__ __forceinline__ void carousel_backward_body(Exchange &sh, int n, int 
     st.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     st.tab_lane = table + (long long)coef_lane * M;
     // an idle lane's sums (all zero) go to the sink: N + 8192 floats nobody reads
+    const long long N = (long long)(n - 1) * (n >> 1);
     st.part_lane = idle ? sink + (long long)threadIdx.x * M
-                        : partial + (long long)blockIdx.x * ((long long)(n - 1) * (n >> 1)) +
-                              (long long)threadIdx.x * M;
+                        : partial + (long long)blockIdx.x * N + (long long)threadIdx.x * M;
+    int place = 0, chain_id = 0;
+    unsigned tag_base = 0u;
+    if constexpr (CHAIN) {
+        chain_id = (int)blockIdx.x % chain.chains;
+        place = (int)blockIdx.x / chain.chains;
+        const long long flags_per_group = (long long)(n - 1) * kFlagStride;
+        st.my_flags = chain.flags + (long long)blockIdx.x * flags_per_group;
+        st.pred_flags = place ? chain.flags + (long long)(blockIdx.x - chain.chains) * flags_per_group : st.my_flags;
+        st.chain_error = chain.error;
+        tag_base = State::read_counter(chain.epoch) * (unsigned)(kChainMaxPasses + 1);
+        st.chain_tag = 0u;
+        st.polled = 0u;
+        st.unlinked = place ? 0 : 1;
+        unsigned xcd;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcd));
+        xcd = (xcd & 15u) + 1u;
+        if (threadIdx.x == 0) State::publish_counter(chain.xcd_of + blockIdx.x, xcd);
+        if (place) {
+            // the predecessor has a lower number and was dealt out earlier; wait (bounded) until it has started
+            const unsigned *theirs = chain.xcd_of + (blockIdx.x - chain.chains);
+            unsigned v = 0;
+            int budget = kChainSpinLimit;
+            do {
+                v = State::read_counter(theirs);
+                if (v == 0) __builtin_amdgcn_s_sleep(4);
+            } while (v == 0 && --budget > 0);
+            if (v != xcd) {
+                st.unlinked = 1;
+                if (st.lane == 0) atomicOr(chain.error, v ? 2u : 1u);
+            }
+        }
+    }
     if constexpr (EX == kExchangeLds) {
         constexpr int LMAX = 64 * WAVES;
         auto &z = sh.buf[0].strip[0];
@@ -824,9 +961,18 @@ __device__ __forceinline__ void carousel_backward_body(Exchange &sh, int n, int 
     // Persistent workgroup: strips strip0 + blockIdx.x, + gridDim.x, ... of the nstrips of this launch.
     // Its row of partial sums is written by the first strip and added to by the others, in program
     // order, so the result does not depend on scheduling.
-    for (long long s = blockIdx.x; s < nstrips; s += gridDim.x) {
+    int pass = 0;
+    for (long long s = blockIdx.x; s < nstrips; s += gridDim.x, ++pass) {
         const bool first_strip = (s == (long long)blockIdx.x);
-        st.prior_lane = first_strip ? zeros + (long long)coef_lane * M : st.part_lane;
+        if constexpr (CHAIN) {
+            // this pass's row of the chain; the head starts it from zeros
+            float *row = partial + ((long long)pass * chain.chains + chain_id) * N + (long long)threadIdx.x * M;
+            if (!idle) st.part_lane = row;
+            st.prior_lane = (place && !idle) ? row : zeros + (long long)coef_lane * M;
+            st.chain_tag = tag_base + (unsigned)pass;
+        } else {
+            st.prior_lane = first_strip ? zeros + (long long)coef_lane * M : st.part_lane;
+        }
         const long long b0 = (strip0 + s) * W;
         const int wv = (B - b0) < W ? (int)(B - b0) : W;
         const bool vec = vec_ok && wv == W;
@@ -854,7 +1000,15 @@ __device__ __forceinline__ void carousel_backward_body(Exchange &sh, int n, int 
                 store_row<W>(st.gb[(r + UL) % M], dX, B, rr_label(n, n - 2, n - 1 - p), my_rows, b0, wv, vec);
             }
         }
+        if constexpr (CHAIN) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // this pass's sums have reached L2
         if constexpr (EX == kExchangeLds) __syncthreads(); // the next strip reuses the exchange buffers
+        if constexpr (CHAIN) {
+            // (everything up to the last block at once: the per-block flags of the last blocks trail by one)
+            if (threadIdx.x == 0) {
+                State::publish_counter(st.my_flags + (long long)(n - 3) * kFlagStride, st.chain_tag);
+                State::publish_counter(st.my_flags + (long long)(n - 2) * kFlagStride, st.chain_tag);
+            }
+        }
     }
 }
 
@@ -867,21 +1021,49 @@ __global__ __launch_bounds__(64 * WAVES, WAVES > 8 ? 1 : 2) void carousel_backwa
     using Exchange = std::conditional_t<EX == kExchangeLds, CarouselExchangeBwd<W, WAVES>, NoExchange>;
     __shared__ Exchange sh;
     if constexpr (kRenormPeriod % M != 0) {
-        carousel_backward_body<M, W, WAVES, kFormStandard, EX>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin, G,
-                                                               dX, partial, zeros, sink, vec_ok, g_identity);
+        carousel_backward_body<M, W, WAVES, kFormStandard, EX, 0>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin,
+                                                                  G, dX, partial, zeros, sink, vec_ok, g_identity,
+                                                                  CarouselChainArgs{});
     } else {
         const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
         if (form == kFormScaled)
-            carousel_backward_body<M, W, WAVES, kFormScaled, EX>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin,
-                                                                 G, dX, partial, zeros, sink, vec_ok, g_identity);
+            carousel_backward_body<M, W, WAVES, kFormScaled, EX, 0>(sh, n, rows, B, strip0, nstrips, table, renorm,
+                                                                    Yin, G, dX, partial, zeros, sink, vec_ok,
+                                                                    g_identity, CarouselChainArgs{});
         else if (form == kFormLifted)
-            carousel_backward_body<M, W, WAVES, kFormLifted, EX>(sh, n, rows, B, strip0, nstrips, table, renorm, Yin,
-                                                                 G, dX, partial, zeros, sink, vec_ok, g_identity);
+            carousel_backward_body<M, W, WAVES, kFormLifted, EX, 0>(sh, n, rows, B, strip0, nstrips, table, renorm,
+                                                                    Yin, G, dX, partial, zeros, sink, vec_ok,
+                                                                    g_identity, CarouselChainArgs{});
         else
-            carousel_backward_body<M, W, WAVES, kFormStandard, EX>(sh, n, rows, B, strip0, nstrips, table, renorm,
-                                                                   Yin, G, dX, partial, zeros, sink, vec_ok,
-                                                                   g_identity);
+            carousel_backward_body<M, W, WAVES, kFormStandard, EX, 0>(sh, n, rows, B, strip0, nstrips, table, renorm,
+                                                                      Yin, G, dX, partial, zeros, sink, vec_ok,
+                                                                      g_identity, CarouselChainArgs{});
     }
+}
+
+// The reverse sweep with chained rows of partial sums (carousel_backward_body): same arguments plus the chain's
+// counters; `partial` holds passes * chains rows.
+template <int M, int W, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 2) void carousel_backward_chain_kernel(
+    int n, int rows, long long B, long long strip0, long long nstrips, const float2 *__restrict__ table,
+    const float2 *__restrict__ renorm, const unsigned *flag, float scaled_max, const float *Yin, const float *G,
+    float *dX, float *partial, const float *__restrict__ zeros, float *sink, int vec_ok, int g_identity,
+    CarouselChainArgs chain)
+{
+    __shared__ CarouselExchangeBwd<W, WAVES> sh;
+    const int form = __builtin_amdgcn_readfirstlane(selected_form(flag, scaled_max));
+    if (form == kFormScaled)
+        carousel_backward_body<M, W, WAVES, kFormScaled, kExchangeLds, 1>(sh, n, rows, B, strip0, nstrips, table,
+                                                                          renorm, Yin, G, dX, partial, zeros, sink,
+                                                                          vec_ok, g_identity, chain);
+    else if (form == kFormLifted)
+        carousel_backward_body<M, W, WAVES, kFormLifted, kExchangeLds, 1>(sh, n, rows, B, strip0, nstrips, table,
+                                                                          renorm, Yin, G, dX, partial, zeros, sink,
+                                                                          vec_ok, g_identity, chain);
+    else
+        carousel_backward_body<M, W, WAVES, kFormStandard, kExchangeLds, 1>(sh, n, rows, B, strip0, nstrips, table,
+                                                                            renorm, Yin, G, dX, partial, zeros,
+                                                                            sink, vec_ok, g_identity, chain);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -971,6 +1153,35 @@ inline int carousel_backward_slots(const CarouselBwdArgs &a, int waves, int W)
     case 6: return carousel_bwd_widths<M, 6>(W, a);
     case 7: return carousel_bwd_widths<M, 7>(W, a);
     case 8: return carousel_bwd_widths<M, 8>(W, a);
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+
+// Chained rows (carousel_bwd_chain.hip): 4 slots per lane, strips of 8 or 4 columns.
+template <int M, int W, int WAVES>
+inline void carousel_launch_bwd_chain(const CarouselBwdArgs &a, const CarouselChainArgs &c)
+{
+    hipLaunchKernelGGL((carousel_backward_chain_kernel<M, W, WAVES>), dim3((unsigned)a.groups), dim3(64 * WAVES), 0,
+                       a.stream, a.n, a.rows, a.B, a.strip0, a.nstrips, a.coefs.table, a.coefs.renorm, a.coefs.flag,
+                       a.coefs.scaled_max, a.Y, a.G, a.dX, a.partial, a.zeros, a.sink, a.vec_ok, a.g_identity, c);
+}
+template <int M, int WAVES>
+inline int carousel_bwd_chain_widths(int W, const CarouselBwdArgs &a, const CarouselChainArgs &c)
+{
+    switch (W) {
+    case 8: carousel_launch_bwd_chain<M, 8, WAVES>(a, c); return GIVENS_OK;
+    case 4: carousel_launch_bwd_chain<M, 4, WAVES>(a, c); return GIVENS_OK;
+    default: return GIVENS_ERR_UNSUPPORTED;
+    }
+}
+template <int M>
+inline int carousel_backward_chain_slots(const CarouselBwdArgs &a, const CarouselChainArgs &c, int waves, int W)
+{
+    switch (waves) {
+    case 5: return carousel_bwd_chain_widths<M, 5>(W, a, c);
+    case 6: return carousel_bwd_chain_widths<M, 6>(W, a, c);
+    case 7: return carousel_bwd_chain_widths<M, 7>(W, a, c);
+    case 8: return carousel_bwd_chain_widths<M, 8>(W, a, c);
     default: return GIVENS_ERR_UNSUPPORTED;
     }
 }

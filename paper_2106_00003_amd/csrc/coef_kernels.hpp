@@ -369,10 +369,11 @@ __global__ __launch_bounds__(kMapThreads) void map_fill_kernel(int n, int rows, 
 // sum_b (g_bot z_top - g_top z_bot) of their stored values; `factor` carries the orientation sign
 // (with i < j the paper's term is gbar_j z_i - gbar_i z_j) and, in the scaled form, d_top * d_bot.
 // (factor == nullptr: 1).  `map` (see theta_at): dtheta lists the free angles only; sums of bypassed pairs are dropped.
+// `poison` (may be null): a word the sweep sets when its chained rows could not be trusted; the result is then NaN.
 template <typename T>
 __global__ void reduce_partials_kernel(int n, long long nstrips, const T *__restrict__ partial,
                                        const T *__restrict__ factor, const int *__restrict__ map, T *dtheta,
-                                       int accumulate)
+                                       int accumulate, const unsigned *__restrict__ poison = nullptr)
 {
     const int H = n >> 1;
     const long long N = (long long)(n - 1) * H;
@@ -389,8 +390,27 @@ __global__ void reduce_partials_kernel(int n, long long nstrips, const T *__rest
         a3 += partial[(s + 3) * N + e];
     }
     for (; s < nstrips; ++s) a0 += partial[s * N + e];
-    const T acc = ((a0 + a1) + (a2 + a3)) * (factor ? factor[e] : T(1));
+    T acc = ((a0 + a1) + (a2 + a3)) * (factor ? factor[e] : T(1));
+    if (poison && *poison) acc = T(__builtin_nanf(""));
     dtheta[out] = accumulate ? dtheta[out] + acc : acc;
+}
+
+// Before a reverse sweep with chained rows: the launch counter goes up by one and the per-launch words (XCD
+// numbers, error word) go to zero.  kChainEpochLimit launches after the flags were last cleared the counter starts
+// again at 1 and chain_flags_wrap_kernel, which runs just before, clears the flags (their tags would wrap).
+constexpr unsigned kChainEpochLimit = 1u << 27;
+__global__ void chain_flags_wrap_kernel(const unsigned *__restrict__ epoch, unsigned *__restrict__ flags, long long words)
+{
+    if (*epoch < kChainEpochLimit) return;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < words;
+         i += (long long)gridDim.x * blockDim.x)
+        flags[i] = 0u;
+}
+__global__ void chain_reset_kernel(unsigned *words, int count, unsigned *epoch)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) words[i] = 0u;
+    if (i == 0) *epoch = (*epoch >= kChainEpochLimit) ? 1u : *epoch + 1u;
 }
 
 // The same sum for small problems, where one thread per angle leaves most of the chip idle behind a long chain of

@@ -66,6 +66,9 @@ struct Workspace {
     Buffer partial;     // per-workgroup (carousel) or per-strip (LDS family) dtheta partial sums
     Buffer zeros;       // N floats that are zeroed when allocated and never written again
     Buffer sink;        // N + 8192 floats: where idle lanes of the carousel reverse sweep put their sums
+    Buffer chain;       // reverse sweep's chained rows: XCD numbers and the error word (reset by every launch)
+    Buffer chain_flags; // one cache line per workgroup and block: tag of the launch and pass that finished it;
+                        // last word: the launch counter
     Buffer gram;        // Gram form: slices of C = Y G^T, rows x rows floats each
     Buffer map;         // restricted parametrisation / odd n: index in theta of every entry of E, or -1
     Buffer map_counts;  // free pairs per block (scratch of the map kernels)
@@ -74,9 +77,9 @@ struct Workspace {
     Buffer u_q, u_psi, u_sgn, u_rot, u_phs, u_orient, u_fin;
     int map_rows = 0, map_m = 0; // the (row count, m) the map was built for
     Prepared prepared;
-    Buffer *all[23] = {&flag, &scale, &fwd.table, &fwd.renorm, &fwd.factor, &rev.table, &rev.renorm, &rev.factor,
+    Buffer *all[25] = {&flag, &scale, &fwd.table, &fwd.renorm, &fwd.factor, &rev.table, &rev.renorm, &rev.factor,
                        &mirrored.table, &mirrored.renorm, &mirrored.factor, &partial, &zeros, &sink, &gram, &map,
-                       &u_q, &u_psi, &u_sgn, &u_rot, &u_phs, &u_orient, &u_fin};
+                       &u_q, &u_psi, &u_sgn, &u_rot, &u_phs, &u_orient, &u_fin, &chain, &chain_flags};
 };
 
 // One call's problem: `rows` coordinates of which the first m may rotate with every other one
@@ -643,12 +646,46 @@ int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, lo
     const long long rows_wanted = carousel ? carousel_bwd_groups(n, B, strips, cus) : strips;
     long long prows = (long long)(kPartialCapBytes / ((size_t)N * sizeof(T)));
     prows = std::max<long long>(1, std::min(prows, rows_wanted));
+    // Large carousel sweeps link their persistent workgroups into chains that share rows (fewer rows, and rows
+    // that stay in L2 while they are summed): needs the full grid and its rows within the cap
+    int chains = 0;
+    long long passes = 1;
+    if constexpr (std::is_same<T, float>::value) {
+        if (carousel && prows == rows_wanted) {
+            chains = carousel_bwd_chains(n, B, strips, rows_wanted);
+            passes = (strips + rows_wanted - 1) / rows_wanted;
+            if (chains && passes * chains > prows) chains = 0;
+        }
+    }
+    CarouselChainArgs chain{};
+    if (chains) {
+        // one flag line per workgroup and block, and the launch counter: zeroed when (re)allocated; after that
+        // every launch writes tags larger than all earlier ones
+        const size_t flag_words = (size_t)rows_wanted * (size_t)(n - 1) * kFlagStride + 1;
+        if (ws.chain_flags.bytes < flag_words * sizeof(unsigned)) {
+            if (int rc = grow(ws.chain_flags, flag_words * sizeof(unsigned))) return rc;
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, stream,
+                               (long long)(ws.chain_flags.bytes / sizeof(float)),
+                               reinterpret_cast<float *>(ws.chain_flags.ptr));
+            GIVENS_HIP(hipGetLastError());
+        }
+        unsigned *flags = reinterpret_cast<unsigned *>(ws.chain_flags.ptr);
+        unsigned *epoch = flags + (ws.chain_flags.bytes / sizeof(unsigned) - 1);    // the buffer's last word
+        const int words = (int)rows_wanted + 1;               // xcd_of, error
+        if (int rc = grow(ws.chain, (size_t)words * sizeof(unsigned))) return rc;
+        unsigned *cw = reinterpret_cast<unsigned *>(ws.chain.ptr);
+        hipLaunchKernelGGL(chain_flags_wrap_kernel, dim3(1024), dim3(256), 0, stream, epoch, flags,
+                           (long long)(ws.chain_flags.bytes / sizeof(unsigned) - 1));
+        hipLaunchKernelGGL(chain_reset_kernel, dim3((words + 255) / 256), dim3(256), 0, stream, cw, words, epoch);
+        GIVENS_HIP(hipGetLastError());
+        chain = CarouselChainArgs{flags, cw, cw + rows_wanted, epoch, chains};
+    }
     if (int rc = grow(ws.partial, (size_t)prows * N * sizeof(T))) return rc;
     T *partial = reinterpret_cast<T *>(ws.partial.ptr);
     const long long chunk = carousel ? strips : prows;     // strips per launch
     for (long long s0 = 0; s0 < strips; s0 += chunk) {
         const long long ns = std::min(chunk, strips - s0);
-        const long long nrows = carousel ? std::min(prows, ns) : ns;
+        long long nrows = carousel ? std::min(prows, ns) : ns;
         {
             Span span(1, stream);
             if (!carousel) {
@@ -656,8 +693,13 @@ int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, lo
                                    coefs.table, Y, G, dX, partial, g_identity, map);
             } else if constexpr (std::is_same<T, float>::value) {
                 if (int rc = carousel_backward_strips(n, rows, B, w, s0, ns, nrows, coefs.carousel(), Y, G, dX, partial,
-                                                      zeros, sink, g_identity, stream))
+                                                      zeros, sink, g_identity, stream, chains ? &chain : nullptr))
                     return rc;
+                if (chains) {
+                    // rows of the chains: all of them in every full pass, the heads that still had a strip in the last
+                    const long long last = strips - (passes - 1) * rows_wanted;
+                    nrows = (passes - 1) * chains + std::min<long long>(chains, last);
+                }
             } else {
                 return GIVENS_ERR_UNSUPPORTED;
             }
@@ -673,7 +715,7 @@ int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, lo
             else
                 hipLaunchKernelGGL(reduce_partials_kernel<T>, dim3((unsigned)((N + threads - 1) / threads)),
                                    dim3(threads), 0, stream, n, nrows, partial, coefs.factor, map, dtheta,
-                                   s0 > 0 ? 1 : 0);
+                                   s0 > 0 ? 1 : 0, chains ? (const unsigned *)chain.error : nullptr);
             GIVENS_HIP(hipGetLastError());
         }
     }

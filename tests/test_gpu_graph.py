@@ -23,7 +23,8 @@ def _gpu():
 
 
 @pytest.mark.parametrize("n,B,dist,reduction", [(1024, 256, "normal0.1", "two_stage"), (512, 200, "uniform", "two_stage"),
-                                                (256, 2048, "uniform", "gram"), (64, 4096, "uniform", "gram")])
+                                                (256, 2048, "uniform", "gram"), (64, 4096, "uniform", "gram"),
+                                                (2560, 2056, "normal0.1", "two_stage")])
 def test_forward_and_backward_replay_from_a_graph(n, B, dist, reduction):
     mode = {"two_stage": binding.REDUCTION_TWO_STAGE, "gram": binding.REDUCTION_GRAM}[reduction]
     binding.set_reduction(mode)

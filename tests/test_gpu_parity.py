@@ -316,6 +316,39 @@ def test_one_wavefront_shapes_with_the_exchange_inside_the_wavefront(n, B, seed,
     binding.release()
 
 
+@pytest.mark.parametrize("n,B,seed,dist", [(2112, 2056, 81, "uniform"), (2560, 4100, 82, "normal0.1"),
+                                           (3072, 2048, 83, "uniform"), (3584, 4104, 84, "normal0.1"),
+                                           (4096, 2056, 85, "uniform"), (2048, 4100, 86, "uniform")])
+def test_reverse_sweep_with_chained_rows_of_partial_sums(n, B, seed, dist):
+    """Large two-stage reverse sweeps (n = 2112 .. 4096, a multiple of 64: workgroups of 5 to 8 wavefronts, one per
+    compute unit) link their 256 persistent workgroups into chains that share rows of partial sums: exactly one pass
+    (3072 x 2048), one pass plus a ragged second one (257 strips), two passes plus a ragged third (513 strips:
+    2560 x 4100, 3584 x 4104); 2048 x 4100 has 4 wavefronts per workgroup and keeps separate rows.  Every component
+    against the oracle, and twice: the result must be the same bit for bit."""
+    data = inputs.make_custom(n, B, seed=seed, theta_dist=dist)
+    print(f"[parity] n={n} B={B} seed={seed} {dist}", flush=True)
+    binding.set_kernel(binding.KERNEL_AUTO)
+    binding.set_reduction(binding.REDUCTION_TWO_STAGE)
+    try:
+        th_d, g_d = dev(data["theta"]), dev(data["G"])
+        y_d = binding.givens_forward(th_d, dev(data["X"]))
+        dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
+        assert binding.last_kernel() == binding.KERNEL_CAROUSEL
+        assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+        want_y = C.forward(data["theta"], data["X"])
+        want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
+        got_dth = host(dth_d)
+        assert np.isfinite(got_dth).all()
+        assert O.rel_fro(host(dx_d), want_dx) <= TOL_G
+        assert O.rel_fro(got_dth, want_dth) <= TOL_G
+        assert float(np.abs(got_dth - want_dth).max()) <= 1e-3 * float(np.abs(want_dth).max())
+        dx2_d, dth2_d = binding.givens_backward(th_d, y_d, g_d)
+        assert np.array_equal(host(dth2_d), got_dth) and np.array_equal(host(dx2_d), host(dx_d))
+    finally:
+        binding.set_reduction(binding.REDUCTION_AUTO)
+    binding.release()
+
+
 def test_sizes_whose_half_is_a_prime_stay_in_the_lds_family():
     """n = 2 p with p prime has no carousel shape (the slot count must divide n / 2)."""
     data = inputs.make_custom(1006, 40, seed=39)
