@@ -299,6 +299,8 @@ def main() -> int:
     fwd_kernel = {"lds": "lds_forward_kernel", "carousel": "carousel_forward_kernel",
                   "column": "column_forward_kernel"}[family_name]
     bwd_kernel = "lds_backward_kernel" if family_name == "lds" else "carousel_backward_kernel"
+    # (large two-stage carousel sweeps run the variant of that kernel with chained rows of partial sums,
+    # carousel_backward_chain_kernel; the label names the family)
 
     fwd_tflops = FWD_FLOP_PER_UPDATE * updates / (fwd_sweep * 1e-3) / 1e12
     gram = reduction == binding.REDUCTION_GRAM
