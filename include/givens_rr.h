@@ -71,6 +71,10 @@ extern "C" {
 /* How givens_backward sums the per-strip shares of dtheta (givens_set_reduction). */
 #define GIVENS_REDUCTION_AUTO 0      /* the library's default for the kernel family in use                     */
 #define GIVENS_REDUCTION_TWO_STAGE 1 /* one partial sum per (strip, angle), then a fixed-order pass: reproducible */
+                                     /* (large float sweeps, n = 2112 .. 4096: the sweep's persistent workgroups */
+                                     /* are chained and add their sums into shared rows, in a fixed order too;   */
+                                     /* should a workgroup's bounded wait for its predecessor ever run out, the  */
+                                     /* call cannot report it, being asynchronous: dtheta is then all NaN)       */
 #define GIVENS_REDUCTION_GRAM 3      /* C = Y G^T by the library's float32 MFMA kernel, then the sweep on the    */
                                      /* n x n operand C; dX by a forward-type sweep (float entry points)        */
 
