@@ -204,10 +204,11 @@ def test_per_call_options():
     assert binding.last_kernel() == binding.KERNEL_CAROUSEL
 
 
-def test_calls_on_two_streams_overlap_without_sharing_tables():
+@pytest.mark.parametrize("n,B", [(1024, 512), (2560, 2056)])
+def test_calls_on_two_streams_overlap_without_sharing_tables(n, B):
     """Two problems with different angles, each on a stream of its own, launched alternately without waiting:
-    every result must equal what the same call gives alone."""
-    n, B = 1024, 512
+    every result must equal what the same call gives alone.  2560 x 2056: reverse sweeps whose workgroups are
+    chained (each stream has its own rows and flags; the two grids share the compute units)."""
     a, b = inputs.make_custom(n, B, seed=641, theta_dist="uniform"), inputs.make_custom(n, B, seed=642, theta_dist="normal0.1")
     tha, xa, ga = dev(a["theta"]), dev(a["X"]), dev(a["G"])
     thb, xb, gb = dev(b["theta"]), dev(b["X"]), dev(b["G"])
