@@ -518,7 +518,10 @@ struct CarouselExchangeBwd {
 // Progress is published as one flag per workgroup and block, each in a cache line of its own (kFlagStride words),
 // holding the tag of the launch and pass that last finished the block.
 constexpr int kChainSpinLimit = 1 << 23;   // polls (some seconds) before a workgroup gives up waiting
-constexpr int kChainSlack = 3;
+// Blocks a place lets its predecessor get ahead, beyond the one it needs, whenever it has to wait.  Measured at
+// n = B = 4096 (reverse sweep, ms): 0: 8.58, 1: 8.66, 2: 8.87, 3 (with the row fetched a block ahead): 9.2.  The
+// closer a place follows, the more of the row it finds in the L2 where its predecessor left it.
+constexpr int kChainSlack = 0;
 // s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; others: no wait)
 constexpr int waitcnt_vm(int vmcnt) { return (vmcnt & 15) | ((vmcnt >> 4) << 14) | (7 << 4) | (15 << 8); }
 
@@ -610,9 +613,8 @@ struct CarouselBwd {
                                  __HIP_MEMORY_SCOPE_WAVEFRONT);
     }
     // Returns once the predecessor has finished block k of this pass.  Normally `polled` (flag_ahead of the block
-    // before) already says so.  If not, the wavefront reads flags through the scalar unit until the predecessor is
-    // kChainSlack blocks further (while the pass has that many left): workgroups run at the same pace, so the
-    // distance gained lasts and the flags read ahead from then on are found set.  A wait that does not end within
+    // before) already says so.  If not, the wavefront reads the flag (of the block kChainSlack further on, while
+    // the pass has that many left) through the scalar unit until it is set.  A wait that does not end within
     // the spin limit marks the call as failed (the second stage then writes NaN) and stops this wavefront from
     // waiting again, so every wavefront reaches the end of the kernel whatever happens to its predecessor.
     __device__ __forceinline__ void wait_for_predecessor(int k)
@@ -779,12 +781,16 @@ struct CarouselBwd {
         // what this workgroup's earlier strips have summed for a LATER block: fetched ahead, like cos/sin, and
         // before this block's store, so that waiting for it never waits for a store
         float(&earlier)[M] = prior[SLOT];
-        if constexpr (CHAIN && PF) {
-            // the row's block k+1 is fetched now: the predecessor must have finished it
-            wait_for_predecessor(k + 1);
-            polled = flag_ahead(k + 2);   // looked at in the next block: nothing waits for this load here
+        if constexpr (CHAIN) {
+            // chained rows: this block's part of the row is fetched in the block itself (it is needed only at the
+            // block's end), so that a place runs as close behind its predecessor as the flags allow and finds the
+            // lines its predecessor stored still in the L2
+            wait_for_predecessor(k);
+            polled = flag_ahead(k + 1);   // looked at in the next block: nothing waits for this load here
+            load_prior(k, prior[SLOT]);
+        } else {
+            if constexpr (PF) load_prior(k + (kDepth - 1), prior[FREE]);
         }
-        if constexpr (PF) load_prior(k + (kDepth - 1), prior[FREE]);
 
         float sums[M];
         // the inner slots all run after the exchange slots here: splitting them around the exchange as
@@ -853,11 +859,10 @@ struct CarouselBwd {
         constexpr auto seq = std::make_integer_sequence<int, kUnroll>{};
         if constexpr (CHAIN) {
             polled = 0u;
-            wait_for_predecessor(0);      // block 0 of the row
-            polled = flag_ahead(1);
-        }
+        } else {
 #pragma unroll
-        for (int d = 0; d < kDepth - 1; ++d) load_prior(d, prior[d]);
+            for (int d = 0; d < kDepth - 1; ++d) load_prior(d, prior[d]);
+        }
         int k = 0;
         if constexpr (FORM == 0) {
             for (; k + kUnroll <= n - 1; k += kUnroll) full_group<false>(k, seq);
