@@ -81,8 +81,8 @@ extern "C" {
 /*
  * rr_schedule -- the round-robin sequence by the circle method (Section 3; the worked n = 6
  * example is Eq. (3), the dimension sequences are the left column of Figure 1).
- * Start from (0, 1, ..., n-1); block k pairs the elements at equal distance from the two ends,
- * outermost arc first; then element 0 is held and the last element moves to position 1.
+ * Start from (0, 1, ..., n-1); block k pairs position p with position n-1-p of the current sequence,
+ * p = 0 (the outermost arc) first; then element 0 is held and the last element moves to position 1.
  *   pairs : HOST buffer of (n-1)*(n/2)*2 int32, written as pairs[k][p][0] = i, pairs[k][p][1] = j.
  * Pure host integer work; bit-exact by definition.
  */

@@ -64,7 +64,7 @@ def restricted_blocks(n: int, m=None):
     for _ in range(size - 1):
         block = []
         for p in range(size // 2):
-            a, b = seq[p], seq[size - 1 - p]      # equal distance from the endpoints
+            a, b = seq[p], seq[size - 1 - p]      # position p with its mirror position
             i, j = (a, b) if a < b else (b, a)
             if j >= n:                            # the added dimension: bypass (odd n)
                 continue
