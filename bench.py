@@ -113,6 +113,8 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--settle", type=int, default=25,
+                    help="untimed steps before the warm-up steps, so that a short --warmup still times the steady state")
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed steps first (the shader clock and the caches need some tens of launches to settle)")
     ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5],
@@ -251,7 +253,10 @@ def main() -> int:
     args.enqueue_only = args.enqueue_only or args.graph
     timing_on[0] = not args.enqueue_only
     binding.set_timing(timing_on[0])
-    for _ in range(args.warmup):
+    # the shader clock and the caches take some 25 launches to reach their steady state; a short --warmup would time
+    # that ramp instead of the kernels, so the same untimed steps run first whatever --warmup says (reported as
+    # config.settle_steps)
+    for _ in range(args.settle + args.warmup):
         step()
     torch.cuda.synchronize()
     if args.graph:
@@ -298,9 +303,9 @@ def main() -> int:
     family_name = {binding.KERNEL_LDS: "lds", binding.KERNEL_CAROUSEL: "carousel", binding.KERNEL_COLUMN: "column"}[family]
     fwd_kernel = {"lds": "lds_forward_kernel", "carousel": "carousel_forward_kernel",
                   "column": "column_forward_kernel"}[family_name]
-    bwd_kernel = "lds_backward_kernel" if family_name == "lds" else "carousel_backward_kernel"
-    # (large two-stage carousel sweeps run the variant of that kernel with chained rows of partial sums,
-    # carousel_backward_chain_kernel; the label names the family)
+    chains = binding.last_chains() if family_name == "carousel" and wl.dtype == "f32" else 0
+    bwd_kernel = ("lds_backward_kernel" if family_name == "lds"
+                  else "carousel_backward_chain_kernel" if chains else "carousel_backward_kernel")
 
     fwd_tflops = FWD_FLOP_PER_UPDATE * updates / (fwd_sweep * 1e-3) / 1e12
     gram = reduction == binding.REDUCTION_GRAM
@@ -325,6 +330,7 @@ def main() -> int:
         "dtype": wl.dtype,
         "data": "synthetic",
         "config": {"workload": name, "n": n, "B": B, "angles": N, "theta": theta_dist,
+                   "settle_steps": args.settle,
                    "step": ("givens_prepare + givens_forward_prepared + givens_backward_prepared" if prepared == "step"
                             else "givens_forward_prepared + givens_backward_prepared (token prepared once)"
                             if prepared == "frozen"
@@ -349,7 +355,8 @@ def main() -> int:
                                                  else (" (on C = Y G^T)" if gram else "")),
                          "bound": "alu", "achieved": bwd_tflops, "peak": peak, "unit": "TFLOP/s",
                          "frac": bwd_tflops / peak,
-                         "traffic": _traffic_from_profiles(f"{bwd_kernel.replace('_kernel', '')}_{name}")},
+                         "traffic": _traffic_from_profiles(
+                             f"{bwd_kernel.replace('_chain', '').replace('_kernel', '')}_{name}")},
     }
     if gram and bwd_gram > 0:
         gram_tflops = 2.0 * n * n * B / (bwd_gram * 1e-3) / 1e12

@@ -316,6 +316,14 @@ int givens_set_reduction(int which);
 int givens_last_reduction(void);
 
 /*
+ * givens_last_chains() -- how the last two-stage reverse sweep on this thread laid out its partial sums: the number
+ * of chains its persistent workgroups were linked into (each chain sums into one shared row per pass; the kernel is
+ * then carousel_backward_chain_kernel), or 0 when every workgroup or strip kept a row of its own.  Section 4.2
+ * (the row sums across columns); reporting only.
+ */
+int givens_last_chains(void);
+
+/*
  * Per-kernel timing.  givens_set_timing(1) makes every subsequent call record HIP events on the
  * caller's stream around each group of kernels it launches.  givens_last_timing() waits for the events of
  * the last call on this thread and writes milliseconds: ms[0] = coefficient kernels (range check, tables),

@@ -36,7 +36,8 @@ Pins (tests/test_oracle_unitary.py): phi = 0 gives the real oracle; n = 2 closed
 factor and of Q_e, P_e against differences of the explicit factor; dense product = forward algorithm;
 U^dagger U = I and det U = exp(i sum phi); per-parameter central differences of the loss; adjoint
 identity for dX; G = Y gives dtheta = 0 and dphi = 0 (the loss is then the constant ||X||^2).
-The gradient sweep has no printed algorithm to compare with: beyond these pins it is "parity unpinned".
+The appendix prints no gradient algorithm to compare the sweep with: the per-parameter central differences of
+the loss through the explicit product (every theta and phi at small n) are what pins it.
 """
 from __future__ import annotations
 

@@ -30,7 +30,7 @@ EXPORTS = [
     "givens_release", "givens_last_hip_error", "givens_error_string",
     "givens_set_kernel", "givens_last_kernel", "givens_set_timing", "givens_last_timing",
     "givens_set_rotation_form", "givens_last_rotation_form",
-    "givens_set_reduction", "givens_last_reduction",
+    "givens_set_reduction", "givens_last_reduction", "givens_last_chains",
     "givens_num_angles", "rr_schedule_restricted",
     "givens_forward_restricted", "givens_build_restricted", "givens_backward_restricted",
     "givens_forward_restricted_f64", "givens_build_restricted_f64", "givens_backward_restricted_f64",
@@ -477,6 +477,10 @@ def set_reduction(which: int) -> int:
 
 def last_reduction() -> int:
     return lib().givens_last_reduction()
+
+
+def last_chains() -> int:
+    return lib().givens_last_chains()
 
 
 def set_timing(on: bool) -> int:

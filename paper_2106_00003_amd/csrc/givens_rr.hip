@@ -115,6 +115,7 @@ struct ThreadState {
     int last_hip_error = 0;
     int last_kernel = 0;
     int last_reduction = 0;
+    int last_chains = 0;                 // chains of workgroups in the last two-stage carousel reverse sweep (0: none)
     const unsigned *last_flag = nullptr; // device flag of the last call when the form was chosen on the device
     float last_scaled_max = 0.f;         // that call's threshold for the scaled form
     hipStream_t last_stream = nullptr;
@@ -657,6 +658,7 @@ int backward_chunks(Workspace &ws, int dev, bool carousel, const Problem &pb, lo
             if (chains && passes * chains > prows) chains = 0;
         }
     }
+    t_state.last_chains = chains;
     CarouselChainArgs chain{};
     if (chains) {
         // one flag line per workgroup and block, and the launch counter: zeroed when (re)allocated; after that
@@ -1175,6 +1177,7 @@ int unitary_carousel_backward(Workspace &ws, int dev, int n, long long B, const 
     }
     t_state.last_kernel = GIVENS_KERNEL_CAROUSEL;
     t_state.last_reduction = GIVENS_REDUCTION_TWO_STAGE;
+    t_state.last_chains = 0;
     t_state.last_flag = nullptr;
     return GIVENS_OK;
 }
@@ -1277,6 +1280,7 @@ int unitary_backward_impl(int n, long long B, const T *theta, const T *phi, cons
     }
     t_state.last_kernel = GIVENS_KERNEL_LDS;
     t_state.last_reduction = GIVENS_REDUCTION_TWO_STAGE;
+    t_state.last_chains = 0;
     t_state.last_flag = nullptr;
     return GIVENS_OK;
 }
@@ -1537,6 +1541,8 @@ int givens_set_reduction(int which)
 }
 
 int givens_last_reduction(void) { return givens::t_state.last_reduction; }
+int givens_last_chains(void) { return givens::t_state.last_chains; }
+
 
 int givens_set_rotation_form(int which)
 {

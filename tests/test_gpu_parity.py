@@ -335,6 +335,7 @@ def test_reverse_sweep_with_chained_rows_of_partial_sums(n, B, seed, dist):
         dx_d, dth_d = binding.givens_backward(th_d, y_d, g_d)
         assert binding.last_kernel() == binding.KERNEL_CAROUSEL
         assert binding.last_reduction() == binding.REDUCTION_TWO_STAGE
+        assert binding.last_chains() == (0 if n == 2048 else 32)   # 256 workgroups in chains of 8, or separate rows
         want_y = C.forward(data["theta"], data["X"])
         want_dth, want_dx, _ = C.reverse_sweep(data["theta"], want_y, data["G"])
         got_dth = host(dth_d)
